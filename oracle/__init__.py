@@ -1,0 +1,165 @@
+"""CPU checker for the Sequoia tree-verify step.  TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the benchmark's CPU-baseline leg may import this package.
+It wraps the plain-C fp64 routines in this directory with ctypes; it shares no code with the
+HIP library and never imports it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+_LIB: Optional[C.CDLL] = None
+_f32p = np.ctypeslib.ndpointer(dtype=np.float32, flags="C_CONTIGUOUS")
+_i32p = np.ctypeslib.ndpointer(dtype=np.int32, flags="C_CONTIGUOUS")
+_f64p = np.ctypeslib.ndpointer(dtype=np.float64, flags="C_CONTIGUOUS")
+
+
+def lib() -> C.CDLL:
+    global _LIB
+    if _LIB is None:
+        path = _build.build(force=False)
+        _LIB = C.CDLL(path)
+        _LIB.oracle_tree_attn_row.restype = C.c_int
+        _LIB.oracle_tree_attn.restype = C.c_int
+        _LIB.oracle_verify.restype = C.c_int
+        _LIB.oracle_verify_trials.restype = C.c_int
+    return _LIB
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def tree_attn(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len: int) -> np.ndarray:
+    """All rows.  q [n,H,d]; k_cache/v_cache [Hk,cap,d]; k_tree/v_tree [n,Hk,d] -> fp64 [n,H,d]."""
+    q, k_cache, v_cache, k_tree, v_tree = map(_f32, (q, k_cache, v_cache, k_tree, v_tree))
+    parent = _i32(parent)
+    n, H, d = q.shape
+    Hk, cap, _ = k_cache.shape
+    out = np.zeros((n, H, d), dtype=np.float64)
+    rc = lib().oracle_tree_attn(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree), _ptr(v_tree),
+                                _ptr(parent), C.c_int32(prefix_len), C.c_int32(cap), C.c_int32(n),
+                                C.c_int32(H), C.c_int32(Hk), C.c_int32(d), _ptr(out))
+    if rc:
+        raise ValueError(f"oracle_tree_attn rc={rc}")
+    return out
+
+
+def tree_attn_row(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len: int, i: int, h: int,
+                  want_weights: bool = False):
+    """One output row (node i, head h) -> fp64 [d] (and the softmax weights if asked)."""
+    q, k_cache, v_cache, k_tree, v_tree = map(_f32, (q, k_cache, v_cache, k_tree, v_tree))
+    parent = _i32(parent)
+    n, H, d = q.shape
+    Hk, cap, _ = k_cache.shape
+    out = np.zeros(d, dtype=np.float64)
+    wp = np.zeros(max(prefix_len, 1), dtype=np.float64) if want_weights else None
+    wt = np.zeros(n, dtype=np.float64) if want_weights else None
+    rc = lib().oracle_tree_attn_row(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree),
+                                    _ptr(v_tree), _ptr(parent), C.c_int32(prefix_len),
+                                    C.c_int32(cap), C.c_int32(n), C.c_int32(H), C.c_int32(Hk),
+                                    C.c_int32(d), C.c_int32(i), C.c_int32(h), _ptr(out),
+                                    _ptr(wp), _ptr(wt))
+    if rc:
+        raise ValueError(f"oracle_tree_attn_row rc={rc}")
+    if want_weights:
+        return out, wp[:prefix_len], wt
+    return out
+
+
+@dataclass
+class Decision:
+    node: int
+    token: int
+    u: float
+    R_s: float
+    D_s: float
+    ratio: float
+    accepted: bool
+    parent: int
+
+    @property
+    def margin(self) -> float:
+        return abs(self.u - self.ratio)
+
+
+@dataclass
+class VerifyResult:
+    accepted_path: np.ndarray  # [n] int32, -1 terminated
+    bonus_token: int
+    decisions: List[Decision]
+    stop_node: int
+    bonus_u: float
+    bonus_total: float
+    bonus_cdf_lo: float
+    bonus_cdf_hi: float
+    bonus_margin: float        # distance of u*sum(R) to the nearer CDF edge, relative to sum(R)
+    final_R: Optional[np.ndarray]
+    final_D: Optional[np.ndarray]
+    degenerate: int
+    fallbacks: int
+
+    @property
+    def path(self) -> List[int]:
+        return [int(x) for x in self.accepted_path if x >= 0]
+
+
+def verify(target_logits, draft_logits, tree_tokens, parent, temperature: float, uniforms,
+           want_final: bool = False) -> VerifyResult:
+    tl, dl, un = _f32(target_logits), _f32(draft_logits), _f32(uniforms)
+    tok, par = _i32(tree_tokens), _i32(parent)
+    n, V = tl.shape
+    path = np.full(n, -1, dtype=np.int32)
+    bonus = np.zeros(1, dtype=np.int32)
+    dec = np.zeros((max(n - 1, 1), 8), dtype=np.float64)
+    ndec = np.zeros(1, dtype=np.int32)
+    binfo = np.zeros(8, dtype=np.float64)
+    fR = np.zeros(V, dtype=np.float64) if want_final else None
+    fD = np.zeros(V, dtype=np.float64) if want_final else None
+    counters = np.zeros(2, dtype=np.int32)
+    rc = lib().oracle_verify(_ptr(tl), _ptr(dl), _ptr(tok), _ptr(par), C.c_double(temperature),
+                             _ptr(un), C.c_int32(n), C.c_int32(V), _ptr(path), _ptr(bonus),
+                             _ptr(dec), _ptr(ndec), _ptr(binfo), _ptr(fR), _ptr(fD), _ptr(counters))
+    if rc:
+        raise ValueError(f"oracle_verify rc={rc}")
+    decisions = [Decision(int(r[0]), int(r[1]), float(r[2]), float(r[3]), float(r[4]), float(r[5]),
+                          bool(r[6]), int(r[7])) for r in dec[: int(ndec[0])]]
+    return VerifyResult(path, int(bonus[0]), decisions, int(binfo[0]), float(binfo[1]),
+                        float(binfo[2]), float(binfo[3]), float(binfo[4]), float(binfo[5]),
+                        fR, fD, int(counters[0]), int(counters[1]))
+
+
+def verify_trials(target_logits, draft_logits, tree_tokens, parent, temperature: float, uniforms
+                  ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Independent walks.  tree_tokens, uniforms [trials, n]; logits [n,V] (shared) or
+    [trials,n,V].  Returns (path_len, first_token, bonus) per trial."""
+    tl, dl, un = _f32(target_logits), _f32(draft_logits), _f32(uniforms)
+    tok, par = _i32(tree_tokens), _i32(parent)
+    trials, n = tok.shape
+    shared = tl.ndim == 2
+    V = tl.shape[-1]
+    plen = np.zeros(trials, dtype=np.int32)
+    first = np.zeros(trials, dtype=np.int32)
+    bonus = np.zeros(trials, dtype=np.int32)
+    rc = lib().oracle_verify_trials(C.c_int64(trials), C.c_int32(1 if shared else 0), _ptr(tl),
+                                    _ptr(dl), _ptr(tok), _ptr(par), C.c_double(temperature),
+                                    _ptr(un), C.c_int32(n), C.c_int32(V), _ptr(plen), _ptr(first),
+                                    _ptr(bonus))
+    if rc:
+        raise ValueError(f"oracle_verify_trials rc={rc}")
+    return plen, first, bonus
