@@ -385,3 +385,16 @@ def test_temperature_tempers_both_models():
             res = oracle.verify(tl, dl, np.array([0, s], np.int32), parent, T,
                                 np.array([0.5, 0.5], np.float32))
             assert abs(res.decisions[0].ratio - p[s] / q[s]) < 1e-12 * max(1.0, p[s] / q[s])
+
+
+def test_bonus_draw_never_emits_a_zero_probability_token():
+    # u = 0 with a leading zero-mass token: the first token whose cumulative mass EXCEEDS 0
+    tl = logits_of([0.0, 0.5, 0.5])[None, :]
+    res = oracle.verify(tl, tl, np.zeros(1, np.int32), np.array([-1], np.int32), 1.0,
+                        np.array([0.0], np.float32))
+    assert res.bonus_token == 1
+    # u at an interior CDF edge belongs to the next token (half-open intervals [lo, hi))
+    tl = np.zeros((1, 2), np.float32)  # P = [0.5, 0.5] exactly
+    res = oracle.verify(tl, tl, np.zeros(1, np.int32), np.array([-1], np.int32), 1.0,
+                        np.array([0.5], np.float32))
+    assert res.bonus_token == 1
