@@ -1,0 +1,159 @@
+/*
+ * seqtree -- the target model's verification step over a speculated token tree
+ * (Sequoia, arxiv 2402.12374), as a C-ABI library for AMD MI355X (gfx950).
+ *
+ * Two operations make up the step:
+ *   seq_tree_attn   one attention layer of the single target forward pass that scores every
+ *                   token of the tree at once (Sec. 1: the tree is "verified in parallel
+ *                   through a single forward pass"; Sec. 2.1: the root stands for the current
+ *                   prefix): tree token i attends to the prefix KV cache, to its ancestors in
+ *                   the tree and to itself.
+ *   seq_verify      Algorithm 2 (Sec. 3.2.1, "Sequoia Sampling and Verification") applied
+ *                   recursively from the root (Sec. 2.2), on caller-supplied uniforms.
+ *
+ * Conventions for every entry point
+ *   - Tensors are row-major and contiguous.  Pointers are DEVICE pointers unless marked HOST.
+ *   - The caller owns every buffer.  Inputs are never written.  The library keeps, per
+ *     process, a small cache of tree plans (device copies of the ancestor bitset and the
+ *     child lists, keyed by the contents of parent[]) and one small synchronisation area;
+ *     both are created on first use and released by seq_shutdown().  A call whose tree is
+ *     already cached allocates nothing, copies nothing and never synchronises with the host.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
+ *     stream); outputs are valid once the caller has synchronised that stream.
+ *   - Return value: SEQ_OK (0) or a negative SEQ_ERR_* code.  Nothing is thrown or printed.
+ *     All argument checks happen on the host before any GPU call, so invalid arguments are
+ *     reported even on a machine without a GPU.
+ *   - Two calls that overlap in time on the same GPU (different streams or threads) race on
+ *     the library's synchronisation area; serialise them.
+ */
+#ifndef SEQTREE_H
+#define SEQTREE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element types of q/k/v/out and of the logits */
+#define SEQ_BF16 1
+#define SEQ_F32 2
+
+#define SEQ_OK 0
+#define SEQ_ERR_NULL (-1)        /* a required pointer is NULL */
+#define SEQ_ERR_SHAPE (-2)       /* n_tree < 1 or > SEQ_MAX_TREE, head_dim not 64/128, heads % kv_heads != 0,
+                                    prefix_len < 0 or > prefix_cap, vocab < 2 or > SEQ_MAX_VOCAB */
+#define SEQ_ERR_TREE (-3)        /* parent[0] != -1 or parent[i] not in [0, i) */
+#define SEQ_ERR_DTYPE (-4)       /* dtype is neither SEQ_BF16 nor SEQ_F32 */
+#define SEQ_ERR_TEMPERATURE (-5) /* temperature negative, NaN or infinite */
+#define SEQ_ERR_WORKSPACE (-6)   /* workspace NULL or smaller than the matching *_workspace() */
+#define SEQ_ERR_HIP (-7)         /* a HIP runtime call failed (no device, launch failure, ...) */
+
+#define SEQ_MAX_TREE 1024
+#define SEQ_MAX_VOCAB 524288
+
+/*
+ * Tree-masked attention with grouped-query heads (one layer).
+ *
+ * For query head h (KV head g = h / (heads / kv_heads)) and tree token i:
+ *     keys(i)      = cache rows 0..prefix_len-1  u  tree rows j with j == i or j an ancestor of i
+ *     out[i,h,:]   = softmax_x( <q[i,h,:], k_x[g,:]> / sqrt(head_dim) ) . v_x[g,:]   over x in keys(i)
+ * Every other key has weight exactly zero (its K/V rows may hold anything, NaN included).
+ * Positional encodings, if any, are applied by the caller beforehand.
+ *
+ *   q        [n_tree, heads, head_dim]
+ *   k_cache  [kv_heads, prefix_cap, head_dim]   first prefix_len rows of each head are valid
+ *   v_cache  same layout
+ *   k_tree   [n_tree, kv_heads, head_dim]       row 0 belongs to the root (the last accepted
+ *   v_tree   same layout                         token, whose K/V is not yet in the cache)
+ *   parent   HOST [n_tree]; parent[0] = -1; 0 <= parent[i] < i
+ *   out      [n_tree, heads, head_dim], same dtype as the inputs
+ *   dtype    SEQ_BF16 (bf16 MFMA, fp32 accumulation) or SEQ_F32 (fp32 throughout)
+ *   workspace, workspace_bytes   scratch of at least seq_tree_attn_workspace(...) bytes
+ *
+ * prefix_len = 0 (tree only) and n_tree = 1 (plain decode attention) are legal.
+ */
+int seq_tree_attn(const void* q, const void* k_cache, const void* v_cache,
+                  const void* k_tree, const void* v_tree, const int32_t* parent,
+                  int32_t prefix_len, int32_t n_tree, int32_t heads, int32_t kv_heads,
+                  int32_t head_dim, void* out,
+                  int32_t prefix_cap, int32_t dtype,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Verification walk (Algorithm 2 at every node on the way down, Sec. 3.2.1 / Sec. 2.2).
+ *
+ * With P_v = softmax(target_logits[v,:] / T) and Q_v = softmax(draft_logits[v,:] / T):
+ *     v = root;  loop:
+ *       R = P_v, D = Q_v, S = {}
+ *       for each child c of v in ascending node id (the order the drafter sampled them):
+ *           s = tree_tokens[c];  accept c iff uniforms[c] < R[s] / D[s]   (strict)
+ *           accepted: append c to accepted_path, v = c, restart the loop
+ *           rejected: R = norm(max(R - D, 0));  D[s] = 0;  S += s;
+ *                     if sum(D) == 0: D = uniform over tokens not in S;  D = norm(D)
+ *       no child accepted: bonus_token ~ R by inverse CDF over ascending token id using
+ *           uniforms[0] (first x with inclusive cumulative mass > u * sum(R));  stop.
+ * T = 0 is greedy: P and Q are one-hot at the arg-max (lowest index on ties), which reduces
+ * the walk to "accept c iff tree_tokens[c] == argmax target_logits[v]".
+ * A token with D[s] = 0 is accepted iff R[s] > 0.
+ *
+ *   target_logits  [n_tree, vocab]   row v: the target's next-token logits after node v
+ *   draft_logits   [n_tree, vocab]   row v: the draft logits v's children were sampled from
+ *   tree_tokens    [n_tree] int32    token id of node i, in [0, vocab); entry 0 is ignored
+ *   parent         HOST [n_tree]
+ *   temperature    >= 0, finite
+ *   uniforms       [n_tree] float in [0,1): [i >= 1] decides node i, [0] draws the bonus token
+ *   accepted_path  [n_tree] int32 out: accepted node ids from the root's child downwards,
+ *                  every remaining entry -1
+ *   bonus_token    [1] int32 out
+ *   workspace      at least seq_verify_workspace(...) bytes; on return it starts with a trace
+ *                  (see seq_verify_trace below) that tests and debuggers may read
+ */
+int seq_verify(const void* target_logits, const void* draft_logits,
+               const int32_t* tree_tokens, const int32_t* parent, float temperature,
+               const float* uniforms, int32_t* accepted_path, int32_t* bonus_token,
+               int32_t n_tree, int32_t vocab, int32_t dtype,
+               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Trace left at the start of the seq_verify workspace.  Header of 8 int32:
+ *   [0] number of accept tests recorded   [1] status: 0 ok, 1 = the cooperating workgroups
+ *   timed out waiting for each other (outputs invalid)   [2] node the bonus token was drawn at
+ *   [3] number of uniform fallbacks   [4] number of degenerate residual updates   [5..7] zero
+ * followed by one record of 4 x 32 bit per accept test, in order:
+ *   int32 node, int32 accepted (0/1), float ratio R[s]/D[s], float uniform
+ * and after SEQ_MAX_TREE such records 4 floats about the bonus draw:
+ *   u, sum(R) before normalisation by the residual mass, cumulative mass below the drawn
+ *   token, cumulative mass including it (the last three relative to sum(R) = 1).
+ */
+#define SEQ_TRACE_HEADER_INTS 8
+#define SEQ_TRACE_RECORD_WORDS 4
+
+/* Scratch sizes in bytes for the two calls above (0 is never returned; at least 256). */
+size_t seq_tree_attn_workspace(int32_t prefix_len, int32_t n_tree, int32_t heads,
+                               int32_t kv_heads, int32_t head_dim, int32_t dtype);
+size_t seq_verify_workspace(int32_t n_tree, int32_t vocab, int32_t dtype);
+
+/*
+ * Host-only helper: the tree plan both calls derive from parent[] (no GPU involved).
+ *   depth        [n_tree]      depth[0] = 0
+ *   child_start  [n_tree + 1]  children of v are child_list[child_start[v] .. child_start[v+1])
+ *   child_list   [n_tree - 1]  ascending node id within each sibling list = drafting order
+ *   anc_words    [n_tree * words_per_row] uint32, words_per_row = 2 * ceil(n_tree / 64):
+ *                bit j of row i is set iff j == i or j is an ancestor of i
+ * Any output pointer may be NULL.  Returns SEQ_OK, SEQ_ERR_SHAPE or SEQ_ERR_TREE.
+ */
+int seq_tree_plan_host(const int32_t* parent, int32_t n_tree, int32_t* depth,
+                       int32_t* child_start, int32_t* child_list, uint32_t* anc_words);
+
+/* Releases the plan cache and the synchronisation area of every device.  Safe to call twice. */
+int seq_shutdown(void);
+
+const char* seq_strerror(int code);
+int seq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEQTREE_H */

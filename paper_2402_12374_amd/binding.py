@@ -1,0 +1,186 @@
+"""Thin ctypes binding of libseqtree.so: argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels; PyTorch is used for device
+memory and for the stream the work is enqueued on.  There is no CPU fallback: if the library
+has not been built, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libseqtree.so")
+
+SEQ_BF16, SEQ_F32 = 1, 2
+SEQ_OK = 0
+SEQ_ERR_NULL, SEQ_ERR_SHAPE, SEQ_ERR_TREE, SEQ_ERR_DTYPE = -1, -2, -3, -4
+SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE, SEQ_ERR_HIP = -5, -6, -7
+SEQ_MAX_TREE = 1024
+TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
+
+EXPORTS = ("seq_tree_attn", "seq_verify", "seq_tree_attn_workspace", "seq_verify_workspace",
+           "seq_tree_plan_host", "seq_shutdown", "seq_strerror", "seq_version")
+
+_lib: Optional[C.CDLL] = None
+
+
+class SeqTreeError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (code {code})")
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'"
+                " or python paper_2402_12374_amd/build.py); there is no fallback path")
+        l = C.CDLL(LIB_PATH)
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        l.seq_tree_attn.restype = C.c_int
+        l.seq_tree_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, i32, vp, sz, vp]
+        l.seq_verify.restype = C.c_int
+        l.seq_verify.argtypes = [vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
+        l.seq_tree_attn_workspace.restype = sz
+        l.seq_tree_attn_workspace.argtypes = [i32] * 6
+        l.seq_verify_workspace.restype = sz
+        l.seq_verify_workspace.argtypes = [i32] * 3
+        l.seq_tree_plan_host.restype = C.c_int
+        l.seq_tree_plan_host.argtypes = [vp, i32, vp, vp, vp, vp]
+        l.seq_shutdown.restype = C.c_int
+        l.seq_strerror.restype = C.c_char_p
+        l.seq_strerror.argtypes = [C.c_int]
+        l.seq_version.restype = C.c_int
+        _lib = l
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().seq_strerror(code).decode()
+
+
+def version() -> int:
+    return lib().seq_version()
+
+
+def shutdown() -> None:
+    lib().seq_shutdown()
+
+
+def _parent_array(parent) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(parent), dtype=np.int32)
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return SEQ_BF16
+    if t.dtype == torch.float32:
+        return SEQ_F32
+    raise SeqTreeError(SEQ_ERR_DTYPE, "dtype")
+
+
+def _stream_ptr(stream=None) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def seq_tree_plan_host(parent):
+    """(depth, child_start, child_list, anc_words[n, words_per_row]) computed on the host."""
+    par = _parent_array(parent)
+    n = len(par)
+    wpr = 2 * ((n + 63) // 64)
+    depth = np.zeros(n, np.int32)
+    cstart = np.zeros(n + 1, np.int32)
+    clist = np.zeros(max(n - 1, 1), np.int32)
+    anc = np.zeros((n, wpr), np.uint32)
+    rc = lib().seq_tree_plan_host(par.ctypes.data, n, depth.ctypes.data, cstart.ctypes.data,
+                                  clist.ctypes.data, anc.ctypes.data)
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_tree_plan_host")
+    return depth, cstart, clist[: n - 1], anc
+
+
+def seq_tree_attn_workspace(prefix_len, n_tree, heads, kv_heads, head_dim, dtype_code) -> int:
+    return int(lib().seq_tree_attn_workspace(prefix_len, n_tree, heads, kv_heads, head_dim, dtype_code))
+
+
+def seq_verify_workspace(n_tree, vocab, dtype_code) -> int:
+    return int(lib().seq_verify_workspace(n_tree, vocab, dtype_code))
+
+
+def seq_tree_attn(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len: int, out=None,
+                  workspace=None, stream=None):
+    """q [n,H,d]; k_cache/v_cache [Hk,cap,d]; k_tree/v_tree [n,Hk,d] (torch, on the GPU);
+    parent: host int array.  Returns out [n,H,d].  Asynchronous on the current stream."""
+    import torch
+    par = _parent_array(parent)
+    n, H, d = q.shape
+    Hk, cap = k_cache.shape[0], k_cache.shape[1]
+    code = _dtype_code(q)
+    for t in (q, k_cache, v_cache, k_tree, v_tree):
+        if not t.is_contiguous() or not t.is_cuda or t.dtype != q.dtype:
+            raise SeqTreeError(SEQ_ERR_SHAPE, "seq_tree_attn (tensors must be contiguous GPU tensors of one dtype)")
+    if out is None:
+        out = torch.empty_like(q)
+    need = seq_tree_attn_workspace(prefix_len, n, H, Hk, d, code)
+    if workspace is None or workspace.numel() * workspace.element_size() < need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = lib().seq_tree_attn(q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), k_tree.data_ptr(),
+                             v_tree.data_ptr(), par.ctypes.data, int(prefix_len), n, H, Hk, d,
+                             out.data_ptr(), cap, code, workspace.data_ptr(),
+                             workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_tree_attn")
+    return out
+
+
+def seq_verify(target_logits, draft_logits, tree_tokens, parent, temperature: float, uniforms,
+               accepted_path=None, bonus_token=None, workspace=None, stream=None):
+    """Logits [n,V] (bf16 or fp32), tree_tokens int32 [n], uniforms float32 [n] on the GPU; parent
+    on the host.  Returns (accepted_path int32 [n], bonus_token int32 [1], workspace) -- device
+    tensors, valid after the stream has been synchronised."""
+    import torch
+    par = _parent_array(parent)
+    n, V = target_logits.shape
+    code = _dtype_code(target_logits)
+    if accepted_path is None:
+        accepted_path = torch.empty(n, dtype=torch.int32, device=target_logits.device)
+    if bonus_token is None:
+        bonus_token = torch.empty(1, dtype=torch.int32, device=target_logits.device)
+    need = seq_verify_workspace(n, V, code)
+    if workspace is None or workspace.numel() * workspace.element_size() < need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=target_logits.device)
+    for t in (target_logits, draft_logits, tree_tokens, uniforms):
+        if not t.is_contiguous() or not t.is_cuda:
+            raise SeqTreeError(SEQ_ERR_SHAPE, "seq_verify (tensors must be contiguous GPU tensors)")
+    rc = lib().seq_verify(target_logits.data_ptr(), draft_logits.data_ptr(), tree_tokens.data_ptr(),
+                          par.ctypes.data, float(temperature), uniforms.data_ptr(),
+                          accepted_path.data_ptr(), bonus_token.data_ptr(), n, V, code,
+                          workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                          _stream_ptr(stream))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_verify")
+    return accepted_path, bonus_token, workspace
+
+
+def read_verify_trace(workspace) -> dict:
+    """Decode the trace seq_verify leaves at the start of its workspace (synchronises)."""
+    raw = workspace.cpu().numpy().view(np.int32)
+    n_dec, status, stop, fallbacks, degenerate = (int(x) for x in raw[:5])
+    rec = raw[TRACE_HEADER_INTS: TRACE_HEADER_INTS + n_dec * TRACE_RECORD_WORDS].reshape(-1, 4)
+    binfo = raw[TRACE_HEADER_INTS + SEQ_MAX_TREE * TRACE_RECORD_WORDS:][:4].view(np.float32)
+    return {
+        "status": status, "stop_node": stop, "fallbacks": fallbacks, "degenerate": degenerate,
+        "nodes": rec[:, 0].copy(), "accepted": rec[:, 1].astype(bool),
+        "ratios": rec[:, 2].copy().view(np.float32), "uniforms": rec[:, 3].copy().view(np.float32),
+        "bonus_u": float(binfo[0]), "bonus_total": float(binfo[1]),
+        "bonus_cdf_lo": float(binfo[2]), "bonus_cdf_hi": float(binfo[3]),
+    }

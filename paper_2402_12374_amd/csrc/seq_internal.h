@@ -1,0 +1,48 @@
+// Internal declarations shared by the translation units of libseqtree (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "seqtree.h"
+
+namespace seqtree {
+
+// Device-side copy of what both calls derive from parent[]: the ancestor-or-self bitset that
+// masks the tree part of the attention scores, and the sibling lists the verification walk
+// follows (ascending node id within a list = the order the drafter sampled the children).
+struct TreePlan {
+    int32_t n = 0;
+    int32_t words_per_row = 0;          // 32-bit words per bitset row = 2 * ceil(n / 64)
+    uint32_t* anc_words = nullptr;      // [n][words_per_row]
+    int32_t* child_start = nullptr;     // [n + 1]
+    int32_t* child_list = nullptr;      // [max(n - 1, 1)]
+    int32_t max_children = 0;
+};
+
+// Per-device area the kernels use to hand partial results between workgroups.  Zeroed once
+// when created; the kernels leave it in a reusable state (arrival counters return to zero,
+// exchange slots carry ever-increasing tags).
+struct SyncArea {
+    unsigned long long* verify_slots = nullptr;  // [2][kVerifyMaxGroups][kVerifySlotWords]
+    uint32_t* attn_counters = nullptr;           // [kAttnMaxCounters]
+    uint32_t next_tag = 1;                       // host-side: first tag block of the next verify call
+};
+
+constexpr int kVerifyMaxGroups = 64;
+constexpr int kVerifySlotWords = 4;
+constexpr int kVerifyTagsPerCall = 4096;
+constexpr int kAttnMaxCounters = 16384;
+
+// Looks up (or builds and uploads) the plan for this parent array on the current device.
+// Returns SEQ_OK or an error code; *plan receives a copy whose device pointers stay owned by
+// the cache.
+int get_tree_plan(const int32_t* parent, int32_t n, TreePlan* plan);
+int get_sync_area(SyncArea** area);
+int release_all();
+
+// Host-side plan construction (no GPU).  Vectors are sized by the callee.
+int validate_parent(const int32_t* parent, int32_t n);
+
+}  // namespace seqtree

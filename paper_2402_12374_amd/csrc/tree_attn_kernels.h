@@ -1,0 +1,32 @@
+// Launchers of the tree-attention kernels (internal).
+#pragma once
+
+#include "seq_internal.h"
+
+namespace seqtree {
+
+int launch_tree_attn_rowwise_f32(const float* q, const float* k_cache, const float* v_cache,
+                                 const float* k_tree, const float* v_tree, const TreePlan& plan,
+                                 int P, int cap, int n, int H, int Hk, int D, float* out,
+                                 hipStream_t stream);
+
+// How the bf16 kernel cuts the work: query rows of one KV head (all G = H/Hk heads of the
+// group times n tree tokens) in blocks of kQueryBlock, the key axis in `splits` contiguous
+// ranges of 64-key tiles whose partial results are merged by the last workgroup to finish.
+struct AttnSchedule {
+    int query_blocks;   // per KV head
+    int splits;
+    size_t workspace_bytes;
+};
+constexpr int kQueryBlock = 128;
+constexpr int kKeyTile = 64;
+
+AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D);
+
+int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v_cache,
+                               const void* k_tree, const void* v_tree, const TreePlan& plan,
+                               int P, int cap, int n, int H, int Hk, int D, void* out,
+                               const AttnSchedule& sched, float* workspace, uint32_t* counters,
+                               hipStream_t stream);
+
+}  // namespace seqtree

@@ -1,0 +1,200 @@
+// Tree plan: everything both calls derive from parent[] before any arithmetic happens.
+// The tree is fixed ahead of time (Sec. 3.1: the structure is found offline; Sec. 4.1
+// "Implementation Details": because it is known in advance the step can be captured as a
+// graph), so the plan is built once per tree shape and cached.
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "seq_internal.h"
+
+namespace seqtree {
+
+int validate_parent(const int32_t* parent, int32_t n) {
+    if (n < 1 || n > SEQ_MAX_TREE) return SEQ_ERR_SHAPE;
+    if (parent[0] != -1) return SEQ_ERR_TREE;
+    for (int32_t i = 1; i < n; ++i)
+        if (parent[i] < 0 || parent[i] >= i) return SEQ_ERR_TREE;
+    return SEQ_OK;
+}
+
+static int words_per_row(int32_t n) { return 2 * ((n + 63) / 64); }
+
+static void build_host(const int32_t* parent, int32_t n, std::vector<int32_t>* depth,
+                       std::vector<int32_t>* child_start, std::vector<int32_t>* child_list,
+                       std::vector<uint32_t>* anc) {
+    const int wpr = words_per_row(n);
+    depth->assign(n, 0);
+    child_start->assign(n + 1, 0);
+    child_list->assign(n > 1 ? n - 1 : 1, 0);
+    anc->assign((size_t)n * wpr, 0u);
+    for (int32_t i = 1; i < n; ++i) {
+        (*depth)[i] = (*depth)[parent[i]] + 1;
+        (*child_start)[parent[i] + 1] += 1;
+    }
+    for (int32_t v = 0; v < n; ++v) (*child_start)[v + 1] += (*child_start)[v];
+    std::vector<int32_t> fill(child_start->begin(), child_start->end() - 1);
+    for (int32_t i = 1; i < n; ++i) (*child_list)[fill[parent[i]]++] = i;  // ascending id per list
+    for (int32_t i = 0; i < n; ++i) {
+        uint32_t* row = anc->data() + (size_t)i * wpr;
+        if (i > 0) std::memcpy(row, anc->data() + (size_t)parent[i] * wpr, sizeof(uint32_t) * wpr);
+        row[i >> 5] |= 1u << (i & 31);
+    }
+}
+
+namespace {
+struct CacheEntry {
+    int device;
+    std::vector<int32_t> parent;
+    TreePlan plan;
+    uint64_t last_use;
+};
+struct DeviceSync {
+    int device;
+    SyncArea area;
+};
+std::mutex g_mutex;
+std::vector<CacheEntry> g_cache;
+std::vector<DeviceSync> g_sync;
+uint64_t g_clock = 0;
+constexpr size_t kMaxPlans = 32;
+
+void free_plan(TreePlan& p) {
+    if (p.anc_words) (void)hipFree(p.anc_words);
+    if (p.child_start) (void)hipFree(p.child_start);
+    if (p.child_list) (void)hipFree(p.child_list);
+    p = TreePlan{};
+}
+}  // namespace
+
+int get_tree_plan(const int32_t* parent, int32_t n, TreePlan* out) {
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return SEQ_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (auto& e : g_cache) {
+        if (e.device == device && (int32_t)e.parent.size() == n &&
+            std::memcmp(e.parent.data(), parent, sizeof(int32_t) * n) == 0) {
+            e.last_use = ++g_clock;
+            *out = e.plan;
+            return SEQ_OK;
+        }
+    }
+    if (g_cache.size() >= kMaxPlans) {  // evict the least recently used (hipFree waits for the GPU)
+        size_t victim = 0;
+        for (size_t i = 1; i < g_cache.size(); ++i)
+            if (g_cache[i].last_use < g_cache[victim].last_use) victim = i;
+        free_plan(g_cache[victim].plan);
+        g_cache.erase(g_cache.begin() + victim);
+    }
+    std::vector<int32_t> depth, cstart, clist;
+    std::vector<uint32_t> anc;
+    build_host(parent, n, &depth, &cstart, &clist, &anc);
+    CacheEntry e;
+    e.device = device;
+    e.parent.assign(parent, parent + n);
+    e.plan.n = n;
+    e.plan.words_per_row = words_per_row(n);
+    for (int32_t v = 0; v < n; ++v)
+        e.plan.max_children = std::max(e.plan.max_children, cstart[v + 1] - cstart[v]);
+    bool ok = hipMalloc(&e.plan.anc_words, anc.size() * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&e.plan.child_start, cstart.size() * sizeof(int32_t)) == hipSuccess &&
+              hipMalloc(&e.plan.child_list, clist.size() * sizeof(int32_t)) == hipSuccess;
+    ok = ok && hipMemcpy(e.plan.anc_words, anc.data(), anc.size() * sizeof(uint32_t),
+                         hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(e.plan.child_start, cstart.data(), cstart.size() * sizeof(int32_t),
+                         hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(e.plan.child_list, clist.data(), clist.size() * sizeof(int32_t),
+                         hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) {
+        free_plan(e.plan);
+        (void)hipGetLastError();
+        return SEQ_ERR_HIP;
+    }
+    e.last_use = ++g_clock;
+    g_cache.push_back(std::move(e));
+    *out = g_cache.back().plan;
+    return SEQ_OK;
+}
+
+int get_sync_area(SyncArea** out) {
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return SEQ_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (auto& s : g_sync)
+        if (s.device == device) { *out = &s.area; return SEQ_OK; }
+    // g_sync never reallocates below its reserved size, so returned pointers stay valid
+    if (g_sync.capacity() < 64) g_sync.reserve(64);
+    DeviceSync s;
+    s.device = device;
+    const size_t slot_bytes = sizeof(unsigned long long) * 2 * kVerifyMaxGroups * kVerifySlotWords;
+    const size_t ctr_bytes = sizeof(uint32_t) * kAttnMaxCounters;
+    bool ok = hipMalloc(&s.area.verify_slots, slot_bytes) == hipSuccess &&
+              hipMalloc(&s.area.attn_counters, ctr_bytes) == hipSuccess &&
+              hipMemset(s.area.verify_slots, 0, slot_bytes) == hipSuccess &&
+              hipMemset(s.area.attn_counters, 0, ctr_bytes) == hipSuccess &&
+              hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        if (s.area.verify_slots) (void)hipFree(s.area.verify_slots);
+        if (s.area.attn_counters) (void)hipFree(s.area.attn_counters);
+        (void)hipGetLastError();
+        return SEQ_ERR_HIP;
+    }
+    g_sync.push_back(s);
+    *out = &g_sync.back().area;
+    return SEQ_OK;
+}
+
+int release_all() {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int current = 0;
+    const bool have_dev = hipGetDevice(&current) == hipSuccess;
+    for (auto& e : g_cache) {
+        if (have_dev) (void)hipSetDevice(e.device);
+        free_plan(e.plan);
+    }
+    g_cache.clear();
+    for (auto& s : g_sync) {
+        if (have_dev) (void)hipSetDevice(s.device);
+        if (s.area.verify_slots) (void)hipFree(s.area.verify_slots);
+        if (s.area.attn_counters) (void)hipFree(s.area.attn_counters);
+    }
+    g_sync.clear();
+    if (have_dev) (void)hipSetDevice(current);
+    return SEQ_OK;
+}
+
+}  // namespace seqtree
+
+extern "C" int seq_tree_plan_host(const int32_t* parent, int32_t n_tree, int32_t* depth,
+                                  int32_t* child_start, int32_t* child_list, uint32_t* anc_words) {
+    if (!parent) return SEQ_ERR_NULL;
+    if (n_tree < 1 || n_tree > SEQ_MAX_TREE) return SEQ_ERR_SHAPE;
+    int rc = seqtree::validate_parent(parent, n_tree);
+    if (rc != SEQ_OK) return rc;
+    std::vector<int32_t> d, cs, cl;
+    std::vector<uint32_t> anc;
+    seqtree::build_host(parent, n_tree, &d, &cs, &cl, &anc);
+    if (depth) std::memcpy(depth, d.data(), sizeof(int32_t) * n_tree);
+    if (child_start) std::memcpy(child_start, cs.data(), sizeof(int32_t) * (n_tree + 1));
+    if (child_list && n_tree > 1) std::memcpy(child_list, cl.data(), sizeof(int32_t) * (n_tree - 1));
+    if (anc_words) std::memcpy(anc_words, anc.data(), sizeof(uint32_t) * anc.size());
+    return SEQ_OK;
+}
+
+extern "C" int seq_shutdown(void) { return seqtree::release_all(); }
+
+extern "C" const char* seq_strerror(int code) {
+    switch (code) {
+        case SEQ_OK: return "ok";
+        case SEQ_ERR_NULL: return "a required pointer is NULL";
+        case SEQ_ERR_SHAPE: return "unsupported or inconsistent sizes";
+        case SEQ_ERR_TREE: return "parent[] is not a tree in topological order";
+        case SEQ_ERR_DTYPE: return "dtype must be SEQ_BF16 or SEQ_F32";
+        case SEQ_ERR_TEMPERATURE: return "temperature must be finite and >= 0";
+        case SEQ_ERR_WORKSPACE: return "workspace missing or too small";
+        case SEQ_ERR_HIP: return "HIP runtime error";
+        default: return "unknown seqtree error code";
+    }
+}
+
+extern "C" int seq_version(void) { return 100; }

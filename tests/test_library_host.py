@@ -1,0 +1,145 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares, rejects
+bad arguments before touching a GPU, and builds the tree plan correctly."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2402_12374_amd as S
+from paper_2402_12374_amd import binding as B
+from paper_2402_12374_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "seqtree.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(seq_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    lib = S.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_strerror():
+    assert S.version() >= 100
+    assert S.strerror(0) == "ok"
+    for code in range(-7, 0):
+        assert "unknown" not in S.strerror(code)
+    assert "unknown" in S.strerror(-99)
+
+
+def _attn(parent, prefix_len=4, n=None, heads=2, kv_heads=2, head_dim=64, cap=8, dtype=B.SEQ_F32,
+          ptr=0x1000, ws=0x1000, ws_bytes=1 << 30, q=0x1000, out=0x1000):
+    par = np.asarray(parent, np.int32)
+    n = len(par) if n is None else n
+    return S.lib().seq_tree_attn(q, ptr, ptr, ptr, ptr, par.ctypes.data, prefix_len, n, heads, kv_heads,
+                                 head_dim, out, cap, dtype, ws, ws_bytes, None)
+
+
+def test_attn_argument_errors_need_no_gpu():
+    good = [-1, 0, 0, 1]
+    assert _attn(good, q=None) == B.SEQ_ERR_NULL
+    assert _attn(good, out=None) == B.SEQ_ERR_NULL
+    assert _attn(good, head_dim=96) == B.SEQ_ERR_SHAPE
+    assert _attn(good, heads=3, kv_heads=2) == B.SEQ_ERR_SHAPE
+    assert _attn(good, prefix_len=9, cap=8) == B.SEQ_ERR_SHAPE
+    assert _attn(good, prefix_len=-1) == B.SEQ_ERR_SHAPE
+    assert _attn(good, n=0) == B.SEQ_ERR_SHAPE
+    assert _attn(good, n=B.SEQ_MAX_TREE + 1) == B.SEQ_ERR_SHAPE
+    assert _attn(good, dtype=7) == B.SEQ_ERR_DTYPE
+    assert _attn([0, 0, 0, 1]) == B.SEQ_ERR_TREE
+    assert _attn([-1, 0, 2, 1]) == B.SEQ_ERR_TREE
+    assert _attn([-1, 0, -1, 1]) == B.SEQ_ERR_TREE
+    # bf16 with a split key axis needs the workspace it asks for
+    par = W.geometric_tree(64, 8)
+    need = S.seq_tree_attn_workspace(1024, 64, 32, 32, 128, B.SEQ_BF16)
+    assert need > 256
+    assert _attn(par, prefix_len=1024, cap=1024, heads=32, kv_heads=32, head_dim=128, dtype=B.SEQ_BF16,
+                 ws_bytes=need - 1) == B.SEQ_ERR_WORKSPACE
+    assert _attn(par, prefix_len=1024, cap=1024, heads=32, kv_heads=32, head_dim=128, dtype=B.SEQ_BF16,
+                 ws=None) == B.SEQ_ERR_WORKSPACE
+
+
+def _verify(parent, n=None, vocab=64, dtype=B.SEQ_F32, temperature=1.0, ptr=0x1000, ws=0x1000,
+            ws_bytes=1 << 20, tl=0x1000):
+    par = np.asarray(parent, np.int32)
+    n = len(par) if n is None else n
+    return S.lib().seq_verify(tl, ptr, ptr, par.ctypes.data, temperature, ptr, ptr, ptr, n, vocab, dtype,
+                              ws, ws_bytes, None)
+
+
+def test_verify_argument_errors_need_no_gpu():
+    good = [-1, 0, 0]
+    assert _verify(good, tl=None) == B.SEQ_ERR_NULL
+    assert _verify(good, vocab=1) == B.SEQ_ERR_SHAPE
+    assert _verify(good, vocab=(1 << 19) + 1) == B.SEQ_ERR_SHAPE
+    assert _verify(good, n=0) == B.SEQ_ERR_SHAPE
+    assert _verify(good, dtype=0) == B.SEQ_ERR_DTYPE
+    assert _verify(good, temperature=-0.5) == B.SEQ_ERR_TEMPERATURE
+    assert _verify(good, temperature=float("nan")) == B.SEQ_ERR_TEMPERATURE
+    assert _verify(good, temperature=float("inf")) == B.SEQ_ERR_TEMPERATURE
+    assert _verify([-1, 1, 0]) == B.SEQ_ERR_TREE
+    assert _verify(good, ws=None) == B.SEQ_ERR_WORKSPACE
+    assert _verify(good, ws_bytes=S.seq_verify_workspace(3, 64, B.SEQ_F32) - 1) == B.SEQ_ERR_WORKSPACE
+
+
+def test_workspace_sizes():
+    assert S.seq_tree_attn_workspace(256, 16, 2, 2, 64, B.SEQ_F32) >= 256
+    assert S.seq_verify_workspace(768, 128256, B.SEQ_BF16) >= 4 * (8 + 4 * 1024 + 4)
+    # bigger trees never need less attention scratch at the same head shape
+    a = S.seq_tree_attn_workspace(8192, 768, 64, 8, 128, B.SEQ_BF16)
+    assert a >= 256
+
+
+@pytest.mark.parametrize("n,seed", [(1, 0), (2, 1), (17, 2), (64, 3), (65, 4), (200, 5), (1024, 6)])
+def test_tree_plan_against_direct_definitions(n, seed):
+    rng = np.random.default_rng(seed)
+    parent = W.random_topological_tree(n, rng) if seed % 2 else W.geometric_tree(n, 12)
+    depth, cstart, clist, anc = S.seq_tree_plan_host(parent)
+    assert anc.shape == (n, 2 * ((n + 63) // 64))
+    for i in range(n):
+        # walk to the root
+        want_bits = np.zeros(anc.shape[1] * 32, dtype=bool)
+        j, dep = i, 0
+        while j >= 0:
+            want_bits[j] = True
+            j = int(parent[j])
+            dep += 1
+        assert depth[i] == dep - 1
+        got_bits = np.unpackbits(anc[i].view(np.uint8), bitorder="little").astype(bool)
+        assert np.array_equal(got_bits, want_bits)
+        kids = [c for c in range(n) if parent[c] == i]
+        assert list(clist[cstart[i]:cstart[i + 1]]) == kids  # ascending id = drafting order
+    assert cstart[0] == 0 and cstart[n] == n - 1
+
+
+def test_tree_plan_rejects_bad_trees():
+    with pytest.raises(S.SeqTreeError) as e:
+        S.seq_tree_plan_host([-1, 0, 5])
+    assert e.value.code == B.SEQ_ERR_TREE
+    with pytest.raises(S.SeqTreeError):
+        S.seq_tree_plan_host([0])
+
+
+def test_workload_generators_are_seeded_and_shaped():
+    a1, a2 = W.attn_inputs_for("C1"), W.attn_inputs_for("C1")
+    assert np.array_equal(a1.q, a2.q) and np.array_equal(a1.parent, a2.parent)
+    assert a1.q.shape == (16, 2, 64) and a1.k_cache.shape == (2, 256, 64)
+    assert W.depths(a1.parent).max() <= 4
+    for key in ("C2", "C3", "C4", "C5"):
+        cfg = W.CONFIGS[key]
+        par = W.make_tree(cfg, 0)
+        assert len(par) == cfg.n_tree and W.depths(par).max() <= cfg.max_depth
+        assert all(par[i] < i for i in range(1, len(par)))
+    v = W.verify_inputs_for("C2", n_tree=16, vocab=512)
+    # siblings carry distinct tokens (sampling without replacement)
+    for ch in W.children_lists(v.parent):
+        toks = v.tree_tokens[ch]
+        assert len(set(toks.tolist())) == len(ch)
+    # bf16 storage: values survive a bf16 round trip exactly
+    assert np.array_equal(W.quantize(v.target_logits, W.BF16), v.target_logits)
+    assert (v.uniforms >= 0).all() and (v.uniforms < 1).all()
