@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verify step on one MI355X.
+
+A step is one pass of the hot path over one set of synthetic inputs: one seq_tree_attn call
+(one attention layer of the target's forward pass over the tree) followed by one seq_verify
+call (the verification walk).  Consecutive steps use different input sets (as many K/V sets as
+the model has layers), so no step finds its K/V or logits in a cache left by the previous one.
+All inputs are in HBM before the timed region starts.
+
+Prints ONE JSON line (see the design doc for how each figure is formed).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def attn_alg_bytes(cfg, n=None, P=None):
+    e = 2 if cfg.dtype == "bf16" else 4
+    n = cfg.n_tree if n is None else n
+    P = cfg.prefix_len if P is None else P
+    H, Hk, d = cfg.heads, cfg.kv_heads, cfg.head_dim
+    return 2 * Hk * P * d * e + 2 * n * Hk * d * e + 2 * n * H * d * e + n * ((n + 63) // 64) * 8
+
+
+def attn_alg_flops(cfg, parent):
+    from paper_2402_12374_amd import workloads as W
+    visible = int((W.depths(parent) + 1).sum())
+    return 4 * cfg.head_dim * cfg.heads * (len(parent) * cfg.prefix_len + visible)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4000)
+    ap.add_argument("--warmup", type=int, default=400)
+    ap.add_argument("--config", default="C2", help="workload (C2 is the one the metric is quoted on)")
+    ap.add_argument("--sets", type=int, default=0, help="distinct input sets to rotate over (0 = layer count)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of a HIP graph")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2402_12374_amd as S
+    from paper_2402_12374_amd import workloads as W
+
+    cfg = W.CONFIGS[args.config]
+    cfg_index = list(W.CONFIGS).index(args.config) + 1
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    tdt = torch.bfloat16 if cfg.dtype == W.BF16 else torch.float32
+    T = cfg.temperatures[0]
+    sets = args.sets or cfg.layers
+    parent = W.make_tree(cfg, W.seed_for(cfg_index))
+    n, H, Hk, d, P, V = cfg.n_tree, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.prefix_len, cfg.vocab
+
+    # ---- inputs, resident in HBM ---------------------------------------------------------
+    g = torch.Generator(device=dev)
+    g.manual_seed(W.seed_for(cfg_index))
+
+    def randn(*shape, scale=1.0):
+        return (torch.randn(*shape, generator=g, device=dev, dtype=torch.float32) * scale).to(tdt).contiguous()
+
+    attn_sets, verify_sets = [], []
+    host0 = W.verify_inputs_for(args.config)  # set 0 comes from the seeded host generator
+    for s in range(sets):
+        attn_sets.append(dict(q=randn(n, H, d), kc=randn(Hk, P, d), vc=randn(Hk, P, d),
+                              kt=randn(n, Hk, d), vt=randn(n, Hk, d), out=torch.empty(n, H, d, device=dev, dtype=tdt)))
+    per_set_bytes = 2 * n * V * (2 if tdt == torch.bfloat16 else 4)
+    n_vsets = max(1, min(sets, 32, (2 << 30) // per_set_bytes))
+    for s in range(n_vsets):
+        if s == 0:
+            tl = torch.from_numpy(host0.target_logits).to(dev).to(tdt)
+            dl = torch.from_numpy(host0.draft_logits).to(dev).to(tdt)
+            tok = torch.from_numpy(host0.tree_tokens).to(dev)
+            un = torch.from_numpy(host0.uniforms).to(dev)
+        else:
+            tl = randn(n, V, scale=cfg.sigma_target)
+            dl = (tl.float() + torch.randn(n, V, generator=g, device=dev) * cfg.sigma_draft).to(tdt)
+            # ordered children without replacement: Gumbel-top-k on the tempered draft logits
+            tok = torch.zeros(n, dtype=torch.int32, device=dev)
+            for node, ch in enumerate(W.children_lists(parent)):
+                if ch:
+                    u = torch.rand(V, generator=g, device=dev).clamp_(1e-20, 1.0)
+                    key = dl[node].float() / max(T, 1e-6) - torch.log(-torch.log(u))
+                    tok[torch.tensor(ch, device=dev)] = torch.topk(key, len(ch)).indices.to(torch.int32)
+            un = torch.rand(n, generator=g, device=dev, dtype=torch.float32).clamp_(0.0, 1.0 - 2.0 ** -24)
+        verify_sets.append(dict(tl=tl.contiguous(), dl=dl.contiguous(), tok=tok, un=un,
+                                path=torch.empty(n, dtype=torch.int32, device=dev),
+                                bonus=torch.empty(1, dtype=torch.int32, device=dev),
+                                ws=torch.empty(S.seq_verify_workspace(n, V, 1), dtype=torch.uint8, device=dev)))
+    code = 1 if tdt == torch.bfloat16 else 2
+    attn_ws = torch.empty(S.seq_tree_attn_workspace(P, n, H, Hk, d, code), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    def attn_call(i):
+        a = attn_sets[i % sets]
+        S.seq_tree_attn(a["q"], a["kc"], a["vc"], a["kt"], a["vt"], parent, P, out=a["out"], workspace=attn_ws)
+
+    def verify_call(i):
+        v = verify_sets[i % n_vsets]
+        S.seq_verify(v["tl"], v["dl"], v["tok"], parent, T, v["un"], accepted_path=v["path"],
+                     bonus_token=v["bonus"], workspace=v["ws"])
+
+    def step(i):
+        attn_call(i)
+        verify_call(i)
+
+    # one eager pass builds the tree plan and the library's sync area (the only allocations)
+    step(0)
+    torch.cuda.synchronize()
+
+    # ---- the step, captured once as a HIP graph of `sets` consecutive steps --------------
+    use_graph = not args.no_graph
+
+    def capture(fn, count):
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for i in range(count):
+                fn(i)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(count):
+                fn(i)
+        return graph
+
+    def timed(run_block, blocks):
+        """HIP events on the launching stream around `blocks` executions of run_block."""
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        start.record()
+        for b in range(blocks):
+            run_block(b)
+        stop.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return start.elapsed_time(stop) * 1e-3, wall
+
+    if use_graph:
+        g_step = capture(step, sets)
+        g_attn = capture(attn_call, sets)
+        g_verify = capture(verify_call, sets)
+        per_block = sets
+        run_step = lambda b: g_step.replay()
+        run_attn = lambda b: g_attn.replay()
+        run_verify = lambda b: g_verify.replay()
+    else:
+        per_block = 1
+        run_step, run_attn, run_verify = step, attn_call, verify_call
+
+    warm_blocks = max(1, -(-args.warmup // per_block))
+    blocks = max(1, -(-args.steps // per_block))
+    steps = blocks * per_block
+    for b in range(warm_blocks):
+        run_step(b)
+    torch.cuda.synchronize()
+    ev_s, wall_s = timed(run_step, blocks)
+    step_us = wall_s / steps * 1e6
+    # per-kernel durations over the same number of launches, each kernel alone on the stream
+    attn_ev_s, _ = timed(run_attn, blocks)
+    verify_ev_s, _ = timed(run_verify, blocks)
+    attn_us = attn_ev_s / steps * 1e6
+    verify_us = verify_ev_s / steps * 1e6
+
+    # ---- results still right?  (set 0 is the seeded host-generated one) -------------------
+    v0 = verify_sets[0]
+    path0 = [int(x) for x in v0["path"].cpu().numpy() if x >= 0]
+    trace0 = S.read_verify_trace(v0["ws"])
+    assert trace0["status"] == 0
+
+    bytes_alg = attn_alg_bytes(cfg)
+    flops_alg = attn_alg_flops(cfg, parent)
+    gbs = bytes_alg / (attn_us * 1e-6) / 1e9
+    tflops = flops_alg / (attn_us * 1e-6) / 1e12
+    hbm_bound = bytes_alg / (HBM_PEAK_GBS * 1e9) >= flops_alg / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if hbm_bound:
+        roofline = {"kernel": "tree_attn_mfma_kernel" if code == 1 else "tree_attn_rowwise_f32",
+                    "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                    "alg_bytes_per_launch": bytes_alg, "avg_launch_us": round(attn_us, 3)}
+    else:
+        roofline = {"kernel": "tree_attn_mfma_kernel", "bound": "mfma", "achieved": round(tflops, 1),
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "alg_flops_per_launch": flops_alg, "avg_launch_us": round(attn_us, 3)}
+    e = 2 if tdt == torch.bfloat16 else 4
+    verify_bytes = (len(path0) + 1) * 2 * V * e
+    verify_info = {"kernel": "verify_walk_kernel", "avg_launch_us": round(verify_us, 3),
+                   "accepted_path_len_set0": len(path0), "alg_bytes_lazy_set0": verify_bytes,
+                   "hbm_frac_lazy_set0": round(verify_bytes / (verify_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 5),
+                   "note": "latency-bound: reads only the rows of visited nodes"}
+
+    # ---- CPU baseline: the checker as it stands, one thread, same workload ----------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        a0 = W.attn_inputs_for(args.config)
+        done, t0 = 0, time.perf_counter()
+        rows_per_step = n * H
+        # whole steps if they are short; otherwise a bounded sample of attention rows
+        t_probe = time.perf_counter()
+        oracle.tree_attn_row(a0.q, a0.k_cache, a0.v_cache, a0.k_tree, a0.v_tree, a0.parent, P, 0, 0)
+        row_s = time.perf_counter() - t_probe
+        sample_rows = int(min(rows_per_step, max(8, args.cpu_seconds * 0.8 / max(row_s, 1e-6))))
+        rng = np.random.default_rng(0)
+        t_a = time.perf_counter()
+        for r in range(sample_rows):
+            i, h = (r // H, r % H) if sample_rows == rows_per_step else (int(rng.integers(n)), int(rng.integers(H)))
+            oracle.tree_attn_row(a0.q, a0.k_cache, a0.v_cache, a0.k_tree, a0.v_tree, a0.parent, P, i, h)
+        attn_cpu_s = (time.perf_counter() - t_a) * rows_per_step / sample_rows
+        t_v = time.perf_counter()
+        reps = 0
+        while reps < 3 or (time.perf_counter() - t_v < args.cpu_seconds * 0.2 and reps < 50):
+            oracle.verify(host0.target_logits, host0.draft_logits, host0.tree_tokens, host0.parent, T, host0.uniforms)
+            reps += 1
+        verify_cpu_s = (time.perf_counter() - t_v) / reps
+        cpu = {"value": round((attn_cpu_s + verify_cpu_s) * 1e6, 1), "unit": "us/step", "cores": 1,
+               "kind": "oracle",
+               "sample": f"{sample_rows} of {rows_per_step} attention rows of {cfg.name} (scaled to all rows) + "
+                         f"{reps} full verification walks; fp64, single thread; host has {os.cpu_count()} cpus",
+               "attn_us": round(attn_cpu_s * 1e6, 1), "verify_us": round(verify_cpu_s * 1e6, 1)}
+
+    line = {
+        "metric": "tree-verify step latency", "value": round(step_us, 3), "unit": "us",
+        "n_gpus": 1, "steps": steps, "warmup": warm_blocks * per_block, "ms_per_step": round(step_us * 1e-3, 6),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if code == 1 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: H{H}/Hk{Hk}/d{d} {cfg.dtype}, prefix {P}, tree {n} "
+                               f"(geometric, depth {int(W.depths(parent).max())}), vocab {V}, T={T}",
+                   "step": "1 x seq_tree_attn (one layer) + 1 x seq_verify", "input_sets": sets,
+                   "launch": "HIP graph of %d steps" % sets if use_graph else "eager from Python"},
+        "tree_tokens_per_s": round(n / (step_us * 1e-6), 1),
+        "attn_us_per_layer": round(attn_us, 3), "verify_us": round(verify_us, 3),
+        "gpu_event_us_per_step": round(ev_s / steps * 1e6, 3),
+        "roofline": roofline, "verify": verify_info, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    S.shutdown()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

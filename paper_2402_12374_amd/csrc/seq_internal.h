@@ -26,8 +26,8 @@ struct TreePlan {
 // exchange slots carry ever-increasing tags).
 struct SyncArea {
     unsigned long long* verify_slots = nullptr;  // [2][kVerifyMaxGroups][kVerifySlotWords]
+    uint32_t* verify_epoch = nullptr;            // [1] tag base of the next verify launch
     uint32_t* attn_counters = nullptr;           // [kAttnMaxCounters]
-    uint32_t next_tag = 1;                       // host-side: first tag block of the next verify call
 };
 
 constexpr int kVerifyMaxGroups = 64;

@@ -126,7 +126,9 @@ int get_sync_area(SyncArea** out) {
     if (g_sync.capacity() < 64) g_sync.reserve(64);
     DeviceSync s;
     s.device = device;
-    const size_t slot_bytes = sizeof(unsigned long long) * 2 * kVerifyMaxGroups * kVerifySlotWords;
+    // the exchange slots, then one 64-bit cell whose low half is the tag epoch
+    const size_t slot_words = (size_t)2 * kVerifyMaxGroups * kVerifySlotWords;
+    const size_t slot_bytes = sizeof(unsigned long long) * (slot_words + 1);
     const size_t ctr_bytes = sizeof(uint32_t) * kAttnMaxCounters;
     bool ok = hipMalloc(&s.area.verify_slots, slot_bytes) == hipSuccess &&
               hipMalloc(&s.area.attn_counters, ctr_bytes) == hipSuccess &&
@@ -139,6 +141,7 @@ int get_sync_area(SyncArea** out) {
         (void)hipGetLastError();
         return SEQ_ERR_HIP;
     }
+    s.area.verify_epoch = reinterpret_cast<uint32_t*>(s.area.verify_slots + slot_words);
     g_sync.push_back(s);
     *out = &g_sync.back().area;
     return SEQ_OK;

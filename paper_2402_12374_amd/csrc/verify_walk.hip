@@ -45,7 +45,7 @@ struct VerifyParams {
     int32_t* bonus;
     int32_t* trace;
     unsigned long long* slots;
-    uint32_t tag_base;
+    uint32_t* epoch;
     uint32_t spin_limit;
     int n, V, W;
     float inv_T;
@@ -96,9 +96,9 @@ __device__ __forceinline__ double block_sum(double v, Shared& sh) {
 // most one round ahead of the slowest one, because it cannot finish a round without that
 // workgroup's contribution.
 template <int K>
-__device__ __forceinline__ bool exchange(const VerifyParams& p, uint32_t round, float v0, float v1,
-                                         float v2, float v3, Shared& sh) {
-    const uint32_t tag = p.tag_base + round;
+__device__ __forceinline__ bool exchange(const VerifyParams& p, uint32_t tag_base, uint32_t round,
+                                         float v0, float v1, float v2, float v3, Shared& sh) {
+    const uint32_t tag = tag_base + round;
     unsigned long long* buf = p.slots + (size_t)(round & 1u) * kVerifyMaxGroups * kVerifySlotWords;
     const int tid = threadIdx.x;
     __syncthreads();  // everyone is done reading sh.gath of the previous exchange
@@ -141,6 +141,18 @@ __device__ __forceinline__ bool exchange(const VerifyParams& p, uint32_t round, 
     return sh.fail == 0;
 }
 
+
+// Tags must differ from launch to launch (also when a captured graph replays the same kernel
+// arguments) and agree between the workgroups of one launch.  Every launch has exactly
+// kVerifyMaxGroups workgroups and each takes one ticket from a device counter, so
+// ticket / kVerifyMaxGroups numbers the launch whatever happened to earlier ones.
+__device__ __forceinline__ uint32_t launch_tag_base(const VerifyParams& p, Shared& sh) {
+    if (threadIdx.x == 0) sh.res_i[0] = (int)atomicAdd(p.epoch, 1u);
+    __syncthreads();
+    const uint32_t ticket = (uint32_t)sh.res_i[0];
+    __syncthreads();
+    return (ticket / (uint32_t)kVerifyMaxGroups) * (uint32_t)kVerifyTagsPerCall;
+}
 
 __device__ __forceinline__ double wave_sum(double v) {
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
@@ -247,6 +259,8 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
     const LT* draft = static_cast<const LT*>(p.draft);
     const int V = p.V;
 
+    const uint32_t tag_base = launch_tag_base(p, sh);
+    if ((int)blockIdx.x >= p.W) return;
     float pr[EPT], qr[EPT];
     uint32_t round = 0;
     int v = 0, path_len = 0, n_dec = 0, fallbacks = 0, degenerate = 0;
@@ -274,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
         }
         const float zt_blk = (float)block_sum(zt_loc, sh);
         const float zd_blk = (float)block_sum(zd_loc, sh);
-        if (!exchange<4>(p, ++round, mt_blk, zt_blk, md_blk, zd_blk, sh)) {
+        if (!exchange<4>(p, tag_base, ++round, mt_blk, zt_blk, md_blk, zd_blk, sh)) {
             finish(p, path_len, n_dec, 1, v, fallbacks, degenerate);
             return;
         }
@@ -333,7 +347,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
             }
             const float r_blk = (float)block_sum(r_loc, sh);
             const float q_blk = (float)block_sum(q_loc, sh);
-            if (!exchange<2>(p, ++round, r_blk, q_blk, 0.f, 0.f, sh)) {
+            if (!exchange<2>(p, tag_base, ++round, r_blk, q_blk, 0.f, 0.f, sh)) {
                 finish(p, path_len, n_dec, 1, v, fallbacks, degenerate);
                 return;
             }
@@ -358,7 +372,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
 #pragma unroll
             for (int e = 0; e < EPT; ++e) r_loc += (double)residual_of(pr[e], qr[e], af, bf);
             const float r_blk = (float)block_sum(r_loc, sh);
-            if (!exchange<1>(p, ++round, r_blk, 0.f, 0.f, 0.f, sh)) {
+            if (!exchange<1>(p, tag_base, ++round, r_blk, 0.f, 0.f, 0.f, sh)) {
                 finish(p, path_len, n_dec, 1, v, fallbacks, degenerate);
                 return;
             }
@@ -426,6 +440,8 @@ __global__ __launch_bounds__(kThreads) void verify_greedy_kernel(const VerifyPar
     const int base = ((int)blockIdx.x * kThreads + tid) * EPT;
     const LT* target = static_cast<const LT*>(p.target);
     const int V = p.V;
+    const uint32_t tag_base = launch_tag_base(p, sh);
+    if ((int)blockIdx.x >= p.W) return;
     uint32_t round = 0;
     int v = 0, path_len = 0, n_dec = 0;
     for (;;) {
@@ -453,7 +469,7 @@ __global__ __launch_bounds__(kThreads) void verify_greedy_kernel(const VerifyPar
             if (sh.red_f[w] > best || (sh.red_f[w] == best && sh.red_i[w] < best_x)) {
                 best = sh.red_f[w]; best_x = sh.red_i[w];
             }
-        if (!exchange<2>(p, ++round, best, __int_as_float(best_x), 0.f, 0.f, sh)) {
+        if (!exchange<2>(p, tag_base, ++round, best, __int_as_float(best_x), 0.f, 0.f, sh)) {
             finish(p, path_len, n_dec, 1, v, 0, 0);
             return;
         }
@@ -490,7 +506,7 @@ uint32_t g_spin_limit = 1u << 22;
 
 template <typename LT>
 void launch_verify(const VerifyParams& p, bool greedy, int ept, hipStream_t stream) {
-    const dim3 grid((unsigned)p.W), block(kThreads);
+    const dim3 grid((unsigned)kVerifyMaxGroups), block(kThreads);  // workgroups >= W only take a ticket
 #define SEQ_LAUNCH(E)                                                                          \
     do {                                                                                       \
         if (greedy) hipLaunchKernelGGL((verify_greedy_kernel<LT, E>), grid, block, 0, stream, p); \
@@ -553,8 +569,7 @@ extern "C" int seq_verify(const void* target_logits, const void* draft_logits,
     p.bonus = bonus_token;
     p.trace = static_cast<int32_t*>(workspace);
     p.slots = sync->verify_slots;
-    if (sync->next_tag >= (1u << 20)) sync->next_tag = 1;
-    p.tag_base = sync->next_tag++ * (uint32_t)kVerifyTagsPerCall;
+    p.epoch = sync->verify_epoch;
     p.spin_limit = g_spin_limit;
     p.n = n_tree;
     p.V = vocab;

@@ -111,7 +111,9 @@ def test_uniform_fallback_and_zero_draft_probability():
         tok = np.zeros(n, np.int32)
         tok[1:] = order
         for u in (0.9999, 0.5):
-            v = W.VerifyInputs(tl, dl, tok, W.star_tree(n), np.full(n, u, np.float32), 1.0, W.F32)
+            un = np.full(n, u, np.float32)
+            un[0] = 0.37  # bonus draw away from the CDF edges of this hand-made target
+            v = W.VerifyInputs(tl, dl, tok, W.star_tree(n), un, 1.0, W.F32)
             got = run_verify(v)
             assert check_verify(v, got) == "exact"
             ref = oracle.verify(tl, dl, tok, v.parent, 1.0, v.uniforms)
@@ -122,8 +124,10 @@ def test_uniform_fallback_and_zero_draft_probability():
         n = len(toks) + 1
         tok = np.zeros(n, np.int32)
         tok[1:] = toks
+        un = np.full(n, 0.9999, np.float32)
+        un[0] = 0.37
         v = W.VerifyInputs(np.tile(logits_of(P_), (n, 1)), np.tile(logits_of(Q_), (n, 1)), tok,
-                           W.star_tree(n), np.full(n, 0.9999, np.float32), 1.0, W.F32)
+                           W.star_tree(n), un, 1.0, W.F32)
         assert check_verify(v) == "exact"
 
 
