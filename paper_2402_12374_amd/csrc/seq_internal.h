@@ -26,7 +26,7 @@ struct TreePlan {
 // exchange slots carry ever-increasing tags).
 struct SyncArea {
     unsigned long long* verify_slots = nullptr;  // [2][kVerifyMaxGroups][kVerifySlotWords]
-    uint32_t* verify_epoch = nullptr;            // [1] tag base of the next verify launch
+    uint32_t* verify_epoch = nullptr;            // [2] tag base of the next verify launch, poison flag
     uint32_t* attn_counters = nullptr;           // [kAttnMaxCounters]
 };
 

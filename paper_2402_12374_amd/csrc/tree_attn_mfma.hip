@@ -353,6 +353,8 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(const MfmaP
 
 }  // namespace
 
+int g_splits_override = 0;  // tuning hook, 0 = automatic
+
 AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     AttnSchedule s;
     const int G = H / Hk;
@@ -361,6 +363,7 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     const int units = Hk * s.query_blocks;
     const int prefix_tiles = (P + kKeyTile - 1) / kKeyTile;
     int splits = 256 / (units > 0 ? units : 1);
+    if (g_splits_override > 0) splits = g_splits_override;
     if (splits > prefix_tiles + 1) splits = prefix_tiles + 1;
     if (splits > 32) splits = 32;
     if (splits < 1) splits = 1;
@@ -404,3 +407,6 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
 }
 
 }  // namespace seqtree
+
+// Tuning hook (not part of the public header): force the number of key-axis ranges.
+extern "C" void seqtree_internal_set_attn_splits(int splits) { seqtree::g_splits_override = splits; }

@@ -126,7 +126,7 @@ int get_sync_area(SyncArea** out) {
     if (g_sync.capacity() < 64) g_sync.reserve(64);
     DeviceSync s;
     s.device = device;
-    // the exchange slots, then one 64-bit cell whose low half is the tag epoch
+    // the exchange slots, then one 64-bit cell: tag epoch (low half), poison flag (high half)
     const size_t slot_words = (size_t)2 * kVerifyMaxGroups * kVerifySlotWords;
     const size_t slot_bytes = sizeof(unsigned long long) * (slot_words + 1);
     const size_t ctr_bytes = sizeof(uint32_t) * kAttnMaxCounters;

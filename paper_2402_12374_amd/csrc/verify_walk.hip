@@ -9,11 +9,13 @@
 // consecutive tokens of the current node's target and draft rows in registers, first as tempered
 // logits, then as probabilities p[x], q[x].  Every step of the algorithm that needs a
 // vocabulary-wide number (softmax max/normaliser, the mass of the new residual, the mass of
-// the remaining draft) is one block reduction per workgroup followed by one all-to-all exchange
-// of the per-workgroup partials through tagged 64-bit slots in global memory; every workgroup
-// then combines the same partials in the same order, so all of them take identical decisions
-// without a leader.  Waiting is bounded: a workgroup that does not see its peers within
-// `spin_limit` polls records status 1 in the trace and leaves.
+// the remaining draft) is one reduction per workgroup followed by one all-to-all exchange of the
+// per-workgroup partials through tagged 64-bit slots in global memory; the first wavefront of
+// every workgroup then combines the same partials in the same order and its first lane takes
+// the next step of the algorithm, so all workgroups reach identical decisions without a leader
+// workgroup.  A step costs two workgroup barriers and one exchange.  Waiting is bounded: a
+// workgroup that does not see its peers within `spin_limit` polls records status 1 in the trace
+// and leaves.
 //
 // Residual and draft are never rewritten.  After j rejections at a node, with S the rejected
 // tokens (whose p and q registers are set to zero when they are rejected):
@@ -31,8 +33,9 @@
 namespace seqtree {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWavesPerBlock = kThreads / 64;
+constexpr int kThreads = 1024;  // few, fat workgroups: an exchange costs more the more take part
+constexpr int kWaves = kThreads / 64;
+static_assert(kWaves <= 16, "the first wavefront folds the per-wave partials within one 16-lane row");
 
 struct VerifyParams {
     const void* target;
@@ -57,167 +60,188 @@ template <> __device__ __forceinline__ float load_logit<uint16_t>(const uint16_t
     return __uint_as_float((uint32_t)row[x] << 16);
 }
 
+__device__ __forceinline__ int wg_rank() { return (int)blockIdx.x; }
+
+// Phase timestamps of workgroup 0 (100 MHz wall clock), compiled in with -DSEQTREE_STAMPS only.
+#ifdef SEQTREE_STAMPS
+__device__ long long g_stamps[64];
+__device__ int g_stamp_count;
+#define SEQ_STAMP_RESET() do { if (blockIdx.x == 0 && threadIdx.x == 0) g_stamp_count = 0; } while (0)
+#define SEQ_STAMP(id) do { if (blockIdx.x == 0 && threadIdx.x == 0 && g_stamp_count < 31) { \
+    g_stamps[2 * g_stamp_count] = (id); g_stamps[2 * g_stamp_count + 1] = wall_clock64(); ++g_stamp_count; } } while (0)
+#else
+#define SEQ_STAMP_RESET() do {} while (0)
+#define SEQ_STAMP(id) do {} while (0)
+#endif
+
+constexpr int kActPass = 0, kActAccepted = 1, kActExhausted = 2;
+
 struct Shared {
-    float gath[kVerifyMaxGroups][kVerifySlotWords];
-    double red_d[kWavesPerBlock];
-    float red_f[kWavesPerBlock];
-    int red_i[kWavesPerBlock];
-    double res_d[4];
-    float res_f[2];
-    int res_i[2];
+    float part[2][kWaves][4];           // per-wavefront partials, double-buffered by step parity
+    float stat[4];                      // max and 1/normaliser of the target and draft rows
+    double bonus_d[2];                  // total residual mass, mass before the owning workgroup
+    int bonus_i[2];                     // owning workgroup, 1 if rounding left no owner
+    double scan[kWaves];
+    float red_f[kWaves];
+    int red_i[kWaves];
     int fail;
     int cand_min;
     int cand_max;
-    int rejected[SEQ_MAX_TREE];
+    // the tree and the per-node draws, staged once so the walk never chases them through memory
+    int child_start[SEQ_MAX_TREE + 1];
+    int child_list[SEQ_MAX_TREE];
+    int token[SEQ_MAX_TREE];
+    float uniform[SEQ_MAX_TREE];
+    // the current node's rows at its children's tokens: tempered logits, then probabilities
+    float child_lt[SEQ_MAX_TREE];
+    float child_ld[SEQ_MAX_TREE];
+    unsigned char child_dup[SEQ_MAX_TREE];  // child's token already carried by an earlier sibling
+    // state of Algorithm 2 at the current node; written by thread 0 only, read after a barrier
+    struct {
+        double A, B, Wn, massQ, dA, dB;
+        float af, bf;
+        int action, next, zero_token, ci, n_rej, fallback, sums_valid;
+        int n_dec, fallbacks, degenerate;
+    } st;
 };
 
-__device__ __forceinline__ float block_max(float v, Shared& sh) {
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh.red_f[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float r = sh.red_f[0];
-    for (int w = 1; w < kWavesPerBlock; ++w) r = fmaxf(r, sh.red_f[w]);
-    return r;
+// ---- wavefront reductions on the data-parallel-primitive path (no LDS round trips) -----------
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
 }
-
-__device__ __forceinline__ double block_sum(double v, Shared& sh) {
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh.red_d[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double r = sh.red_d[0];
-    for (int w = 1; w < kWavesPerBlock; ++w) r += sh.red_d[w];
-    return r;
+__device__ __forceinline__ float lane_value(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
-
-// All-to-all of K floats per workgroup.  Afterwards sh.gath[w][k] holds workgroup w's k-th
-// value in every workgroup.  Two slot buffers alternate by round parity: a workgroup can be at
-// most one round ahead of the slowest one, because it cannot finish a round without that
-// workgroup's contribution.
-template <int K>
-__device__ __forceinline__ bool exchange(const VerifyParams& p, uint32_t tag_base, uint32_t round,
-                                         float v0, float v1, float v2, float v3, Shared& sh) {
-    const uint32_t tag = tag_base + round;
-    unsigned long long* buf = p.slots + (size_t)(round & 1u) * kVerifyMaxGroups * kVerifySlotWords;
-    const int tid = threadIdx.x;
-    __syncthreads();  // everyone is done reading sh.gath of the previous exchange
-    if (tid < K) {
-        const float mine = tid == 0 ? v0 : (tid == 1 ? v1 : (tid == 2 ? v2 : v3));
-        const unsigned long long word = ((unsigned long long)tag << 32) | __float_as_uint(mine);
-        __hip_atomic_store(&buf[blockIdx.x * kVerifySlotWords + tid], word, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-    }
-    if (tid < 64) {
-        bool done = tid >= p.W;
-        float got[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) got[k] = 0.f;
-        uint32_t spins = 0;
-        for (;;) {
-            if (!done) {
-                bool all = true;
-#pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    const unsigned long long word = __hip_atomic_load(
-                        &buf[tid * kVerifySlotWords + k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if ((uint32_t)(word >> 32) == tag) got[k] = __uint_as_float((uint32_t)word);
-                    else all = false;
-                }
-                done = all;
-            }
-            if (__all(done)) break;
-            if (++spins > p.spin_limit) break;   // bounded wait: every wave leaves this loop
-            __builtin_amdgcn_s_sleep(2);
-        }
-        const bool ok = __all(done);
-        if (tid < p.W) {
-#pragma unroll
-            for (int k = 0; k < K; ++k) sh.gath[tid][k] = got[k];
-        }
-        if (tid == 0) sh.fail = ok ? 0 : 1;
-    }
-    __syncthreads();
-    return sh.fail == 0;
+constexpr int kOpSum = 0, kOpMax = 1;
+template <int OP> __device__ __forceinline__ float combine(float a, float b) {
+    return OP == kOpSum ? a + b : fmaxf(a, b);
 }
-
-
-// Tags must differ from launch to launch (also when a captured graph replays the same kernel
-// arguments) and agree between the workgroups of one launch.  Every launch has exactly
-// kVerifyMaxGroups workgroups and each takes one ticket from a device counter, so
-// ticket / kVerifyMaxGroups numbers the launch whatever happened to earlier ones.
-__device__ __forceinline__ uint32_t launch_tag_base(const VerifyParams& p, Shared& sh) {
-    if (threadIdx.x == 0) sh.res_i[0] = (int)atomicAdd(p.epoch, 1u);
-    __syncthreads();
-    const uint32_t ticket = (uint32_t)sh.res_i[0];
-    __syncthreads();
-    return (ticket / (uint32_t)kVerifyMaxGroups) * (uint32_t)kVerifyTagsPerCall;
-}
-
-__device__ __forceinline__ double wave_sum(double v) {
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+// every lane of a 16-lane row ends with the row's result
+template <int OP> __device__ __forceinline__ float row_reduce(float v) {
+    v = combine<OP>(v, dpp<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = combine<OP>(v, dpp<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = combine<OP>(v, dpp<0x141>(v));  // row_half_mirror
+    v = combine<OP>(v, dpp<0x140>(v));  // row_mirror
     return v;
 }
-
-// The per-workgroup partials sit in sh.gath; the first wavefront folds them (lane w takes
-// workgroup w, butterfly order, identical in every workgroup) and leaves the results in shared
-// memory for the whole block.
-__device__ __forceinline__ void fold_softmax_stats(const VerifyParams& p, Shared& sh) {
-    const int tid = threadIdx.x;
-    if (tid < 64) {
-        const bool have = tid < p.W;
-        const float m_t = have ? sh.gath[tid][0] : -INFINITY, z_t = have ? sh.gath[tid][1] : 0.f;
-        const float m_d = have ? sh.gath[tid][2] : -INFINITY, z_d = have ? sh.gath[tid][3] : 0.f;
-        float mt = m_t, md = m_d;
-        for (int off = 32; off > 0; off >>= 1) {
-            mt = fmaxf(mt, __shfl_xor(mt, off));
-            md = fmaxf(md, __shfl_xor(md, off));
-        }
-        const double zt = wave_sum(z_t > 0.f ? (double)z_t * (double)expf(m_t - mt) : 0.0);
-        const double zd = wave_sum(z_d > 0.f ? (double)z_d * (double)expf(m_d - md) : 0.0);
-        if (tid == 0) { sh.res_f[0] = mt; sh.res_f[1] = md; sh.res_d[0] = zt; sh.res_d[1] = zd; }
-    }
-    __syncthreads();
+// wave-uniform result; all 64 lanes must be active
+template <int OP> __device__ __forceinline__ float wave_reduce(float v) {
+    v = row_reduce<OP>(v);
+    return combine<OP>(combine<OP>(lane_value(v, 0), lane_value(v, 16)),
+                       combine<OP>(lane_value(v, 32), lane_value(v, 48)));
 }
 
-__device__ __forceinline__ void fold_sums(const VerifyParams& p, Shared& sh) {
-    const int tid = threadIdx.x;
-    if (tid < 64) {
-        const bool have = tid < p.W;
-        const double a = wave_sum(have ? (double)sh.gath[tid][0] : 0.0);
-        const double b = wave_sum(have ? (double)sh.gath[tid][1] : 0.0);
-        if (tid == 0) { sh.res_d[0] = a; sh.res_d[1] = b; }
+// All-to-all of K floats per workgroup, run by the first wavefront only.  mine[k] is this
+// workgroup's value; afterwards lane w of the wavefront holds workgroup w's values in got[]
+// (lanes >= W keep `fill`).  Two slot buffers alternate by step parity: a workgroup can be at
+// most one step ahead of the slowest one, because it cannot finish a step without that
+// workgroup's contribution.
+template <int K>
+__device__ __forceinline__ bool exchange(const VerifyParams& p, uint32_t tag_base, uint32_t step,
+                                         const float (&mine)[K], float fill, float (&got)[K]) {
+    const int lane = threadIdx.x;  // first wavefront: 0..63
+#pragma unroll
+    for (int k = 0; k < K; ++k) got[k] = fill;
+    if (p.W == 1) {   // nobody to talk to
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < K; ++k) got[k] = mine[k];
+        }
+        return true;
     }
-    __syncthreads();
+    const uint32_t tag = tag_base + step;
+    unsigned long long* buf = p.slots + (size_t)(step & 1u) * kVerifyMaxGroups * kVerifySlotWords;
+    if (lane < K) {
+        float v = mine[0];
+#pragma unroll
+        for (int k = 1; k < K; ++k) v = lane == k ? mine[k] : v;
+        const unsigned long long word = ((unsigned long long)tag << 32) | __float_as_uint(v);
+        __hip_atomic_store(&buf[lane * kVerifyMaxGroups + wg_rank()], word, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    bool done = lane >= p.W;
+    uint32_t spins = 0;
+    for (;;) {
+        if (!done) {
+            bool all = true;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const unsigned long long word = __hip_atomic_load(
+                    &buf[k * kVerifyMaxGroups + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((uint32_t)(word >> 32) == tag) got[k] = __uint_as_float((uint32_t)word);
+                else all = false;
+            }
+            done = all;
+        }
+        if (__all(done)) return true;
+        if (++spins > p.spin_limit) return false;   // bounded wait: every wave leaves this loop
+        __builtin_amdgcn_s_sleep(1);
+    }
 }
 
-// Which workgroup holds the token at cumulative mass u * total?  res_d[0] = total,
-// res_d[1] = mass before the owner, res_i[0] = owner, res_i[1] = 1 if rounding left no owner
-// and the last workgroup with mass was taken instead.
-__device__ __forceinline__ void fold_bonus_owner(const VerifyParams& p, float u0, Shared& sh) {
-    const int tid = threadIdx.x;
-    if (tid < 64) {
-        const double sw = tid < p.W ? (double)sh.gath[tid][0] : 0.0;
-        double incl = sw;
-        for (int off = 1; off < 64; off <<= 1) {
-            const double t = __shfl_up(incl, off);
-            if (tid >= off) incl += t;
-        }
-        const double total = __shfl(incl, 63);
-        const double goal = (double)u0 * total;
-        const unsigned long long hit = __ballot(sw > 0.0 && incl > goal);
-        const unsigned long long pos = __ballot(sw > 0.0);
-        int owner, forced = 0;
-        if (hit) owner = __ffsll((long long)hit) - 1;
-        else { forced = 1; owner = pos ? 63 - __clzll((long long)pos) : p.W - 1; }
-        const double before = __shfl(incl - sw, owner);
-        if (tid == 0) { sh.res_d[0] = total; sh.res_d[1] = before; sh.res_i[0] = owner; sh.res_i[1] = forced; }
+// Tags must differ from launch to launch (also when a captured graph replays the same kernel
+// arguments) and agree between the workgroups of one launch.  epoch[0] is the tag base: every
+// workgroup reads it on entry and workgroup 0 moves it on when it leaves -- which it cannot do
+// before every workgroup has published, hence read the epoch, at least once.  That argument
+// fails only after a timed-out wait, so a timeout also sets epoch[1], and every later launch
+// refuses to run (status 1) until seq_shutdown() has discarded the area.
+__device__ __forceinline__ uint32_t launch_tag_base(const VerifyParams& p, bool* poisoned) {
+    *poisoned = __hip_atomic_load(p.epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+    return __hip_atomic_load(p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void stage_tree(const VerifyParams& p, Shared& sh) {
+    for (int i = threadIdx.x; i < p.n; i += kThreads) {
+        sh.child_start[i] = p.child_start[i];
+        sh.token[i] = min(max(p.tokens[i], 0), p.V - 1);  // stay inside the row whatever was sent
+        sh.uniform[i] = p.uniforms[i];
+        if (i < p.n - 1) sh.child_list[i] = p.child_list[i];
     }
-    __syncthreads();
+    if (threadIdx.x == 0) sh.child_start[p.n] = p.child_start[p.n];
+}
+
+// My EPT consecutive logits of one row, tempered; tokens past the vocabulary read as -inf.
+// 16-byte loads when the row start and EPT allow it.
+template <typename LT, int EPT>
+__device__ __forceinline__ void load_row_slice(const LT* row, int base, int V, float inv_T, bool vec_ok,
+                                               float (&x)[EPT]) {
+    constexpr int kPerVec = 16 / (int)sizeof(LT);
+    if (vec_ok && base + EPT <= V) {
+#pragma unroll
+        for (int c = 0; c < EPT / kPerVec; ++c) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(row + base + c * kPerVec);
+            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if constexpr (sizeof(LT) == 2) {
+                    x[c * 8 + 2 * k] = __uint_as_float(w[k] << 16) * inv_T;
+                    x[c * 8 + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u) * inv_T;
+                } else {
+                    x[c * 4 + k] = __uint_as_float(w[k]) * inv_T;
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) x[e] = base + e < V ? load_logit<LT>(row, base + e) * inv_T : -INFINITY;
+    }
+}
+
+// e^x on the hardware base-2 exponential, with the rounding error of x * log2(e) carried into
+// the result (about 2 ulp for the x <= 0 this file feeds it); e^-inf = 0.
+__device__ __forceinline__ float exp_fast(float x) {
+    constexpr float kLog2e = 1.44269504088896341f;
+    constexpr float kLog2eLo = 1.92596299112661746e-8f;  // log2(e) - float(log2(e))
+    constexpr float kLn2 = 0.693147180559945309f;
+    const float hi = x * kLog2e;
+    const float lo = fmaf(x, kLog2e, -hi) + x * kLog2eLo;
+    const float e = __builtin_amdgcn_exp2f(hi);
+    return x == -INFINITY ? 0.f : fmaf(e, lo * kLn2, e);
 }
 
 __device__ __forceinline__ float prob_of(float scaled_logit, float m, float inv_z) {
-    return scaled_logit == -INFINITY ? 0.f : expf(scaled_logit - m) * inv_z;
+    return scaled_logit == -INFINITY ? 0.f : exp_fast(scaled_logit - m) * inv_z;
 }
 
 __device__ __forceinline__ float residual_of(float p, float q, float a, float b) {
@@ -226,7 +250,7 @@ __device__ __forceinline__ float residual_of(float p, float q, float a, float b)
 
 __device__ __forceinline__ void finish(const VerifyParams& p, int path_len, int n_dec, int status,
                                        int stop_node, int fallbacks, int degenerate) {
-    if (blockIdx.x != 0) return;
+    if (wg_rank() != 0) return;
     for (int i = path_len + (int)threadIdx.x; i < p.n; i += kThreads) p.path[i] = -1;
     if (threadIdx.x == 0) {
         p.trace[0] = n_dec;
@@ -235,13 +259,17 @@ __device__ __forceinline__ void finish(const VerifyParams& p, int path_len, int 
         p.trace[3] = fallbacks;
         p.trace[4] = degenerate;
         p.trace[5] = p.trace[6] = p.trace[7] = 0;
-        if (status != 0) p.bonus[0] = -1;
+        if (status != 0) {
+            p.bonus[0] = -1;
+            __hip_atomic_store(p.epoch + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        atomicAdd(p.epoch, (uint32_t)kVerifyTagsPerCall);
     }
 }
 
 __device__ __forceinline__ void record(const VerifyParams& p, int n_dec, int node, bool accepted,
                                        float ratio, float u) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (wg_rank() == 0 && threadIdx.x == 0) {
         int32_t* rec = p.trace + SEQ_TRACE_HEADER_INTS + n_dec * SEQ_TRACE_RECORD_WORDS;
         rec[0] = node;
         rec[1] = accepted ? 1 : 0;
@@ -250,140 +278,271 @@ __device__ __forceinline__ void record(const VerifyParams& p, int n_dec, int nod
     }
 }
 
+// One step of Algorithm 2 at the current node, taken by thread 0 alone (a dependent chain of a
+// few dozen scalar operations; every other lane would only repeat it).  Applies the result of
+// the previous vocabulary pass if there was one, then tests the next child: accepted, or
+// rejected (a pass over the vocabulary is needed before the next test), or none is left.
+// The accept test u < (r/W) / (q/massQ) is evaluated as u * W * q < r * massQ: no division.
+__device__ void leader_step(const VerifyParams& p, Shared& sh, int c_begin, int c_end, int V,
+                            bool have_pass, double w_new, double q_new) {
+    auto& st = sh.st;
+    if (have_pass) {
+        if (w_new > 0.0) { st.Wn = w_new; st.sums_valid = 1; }
+        else { st.A -= st.dA; st.B -= st.dB; ++st.degenerate; st.sums_valid = 0; }  // R stays as it was
+        st.af = (float)st.A;
+        st.bf = (float)st.B;
+        st.massQ = q_new;
+        if (!st.fallback && !(q_new > 0.0)) { st.fallback = 1; ++st.fallbacks; }
+    }
+    if (st.ci == c_end) { st.action = kActExhausted; return; }
+    const int k = st.ci - c_begin;
+    const int c = sh.child_list[st.ci];
+    const float u = sh.uniform[c];
+    const bool in_s = sh.child_dup[k] != 0;
+    const float ps = sh.child_lt[k], qs = sh.child_ld[k];  // probabilities by now
+    const int left = V - st.n_rej;  // tokens not yet rejected
+    const float r_num = in_s ? 0.f : residual_of(ps, qs, st.af, st.bf);   // R[s] * W
+    // D[s]: q/massQ, or 1/left once the draft's support is exhausted, or 0 for a rejected token
+    bool accept;
+    float ratio;
+    if (in_s || (st.fallback ? left <= 0 : !(qs > 0.f))) {
+        accept = r_num > 0.f;
+        ratio = accept ? INFINITY : 0.f;
+    } else if (st.fallback) {
+        accept = (double)u * st.Wn < (double)r_num * (double)left;
+        ratio = r_num * (float)left / (float)st.Wn;
+    } else {
+        accept = (double)u * st.Wn * (double)qs < (double)r_num * st.massQ;
+        ratio = (r_num * (float)st.massQ) / ((float)st.Wn * qs);
+    }
+    record(p, st.n_dec, c, accept, ratio, u);
+    ++st.n_dec;
+    if (accept) { st.action = kActAccepted; st.next = c; return; }
+    // rejected: R <- norm(max(R - D, 0)), then D[s] <- 0 (and the uniform fallback)
+    st.dA = 0.0;
+    st.dB = 0.0;
+    if (st.fallback) { if (left > 0) st.dB = (double)((float)st.Wn / (float)left); }
+    else st.dA = (double)((float)st.Wn / (float)st.massQ);
+    st.A += st.dA;
+    st.B += st.dB;
+    st.af = (float)st.A;
+    st.bf = (float)st.B;
+    st.zero_token = in_s ? -1 : sh.token[c];
+    if (!in_s) ++st.n_rej;
+    ++st.ci;
+    st.action = kActPass;
+}
+
+// First wavefront: which workgroup holds the token at cumulative residual mass u * total?
+// `sw` is the mass of workgroup `lane`.
+__device__ __forceinline__ void find_bonus_owner(const VerifyParams& p, float u0, float sw_f, Shared& sh) {
+    const int lane = threadIdx.x;
+    const double sw = (double)sw_f;
+    double incl = sw;
+    for (int off = 1; off < 64; off <<= 1) {
+        const double t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    const double total = __shfl(incl, 63);
+    const double goal = (double)u0 * total;
+    const unsigned long long hit = __ballot(sw > 0.0 && incl > goal);
+    const unsigned long long pos = __ballot(sw > 0.0);
+    int owner, forced = 0;
+    if (hit) owner = __ffsll((long long)hit) - 1;
+    else { forced = 1; owner = pos ? 63 - __clzll((long long)pos) : p.W - 1; }
+    const double before = __shfl(incl - sw, owner);
+    if (lane == 0) { sh.bonus_d[0] = total; sh.bonus_d[1] = before; sh.bonus_i[0] = owner; sh.bonus_i[1] = forced; }
+}
+
+// Per-wavefront partials -> this workgroup's values, inside the first wavefront (lane w < kWaves
+// reads wavefront w's partial; kWaves <= 16, so one 16-lane row holds them all).
+template <int OP>
+__device__ __forceinline__ float fold_waves(const Shared& sh, int par, int k, float identity) {
+    const int lane = threadIdx.x;
+    const float v = lane < kWaves ? sh.part[par][lane][k] : identity;
+    return lane_value(row_reduce<OP>(v), 0);
+}
+
 template <typename LT, int EPT>
 __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParams p) {
     __shared__ Shared sh;
-    const int tid = threadIdx.x;
-    const int base = ((int)blockIdx.x * kThreads + tid) * EPT;  // my EPT consecutive tokens
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int base = (wg_rank() * kThreads + tid) * EPT;  // my EPT consecutive tokens
     const LT* target = static_cast<const LT*>(p.target);
     const LT* draft = static_cast<const LT*>(p.draft);
     const int V = p.V;
 
-    const uint32_t tag_base = launch_tag_base(p, sh);
-    if ((int)blockIdx.x >= p.W) return;
+    SEQ_STAMP_RESET();
+    SEQ_STAMP(0);
+    bool poisoned;
+    const uint32_t tag_base = launch_tag_base(p, &poisoned);
+    if (poisoned) { finish(p, 0, 0, 1, 0, 0, 0); return; }
+    stage_tree(p, sh);
+    const bool vec_ok = (V % (16 / (int)sizeof(LT)) == 0) &&
+                        ((reinterpret_cast<uintptr_t>(p.target) | reinterpret_cast<uintptr_t>(p.draft)) & 15) == 0;
     float pr[EPT], qr[EPT];
-    uint32_t round = 0;
-    int v = 0, path_len = 0, n_dec = 0, fallbacks = 0, degenerate = 0;
+    uint32_t step = 0;
+    int par = 0, v = 0, path_len = 0;
+    if (tid == 0) { sh.st.n_dec = 0; sh.st.fallbacks = 0; sh.st.degenerate = 0; }
+    __syncthreads();
 
     for (;;) {
         const LT* trow = target + (size_t)v * V;
         const LT* drow = draft + (size_t)v * V;
-        // tempered logits of my tokens, then the two softmax statistics
-        float mt_loc = -INFINITY, md_loc = -INFINITY;
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            const int x = base + e;
-            pr[e] = x < V ? load_logit<LT>(trow, x) * p.inv_T : -INFINITY;
-            qr[e] = x < V ? load_logit<LT>(drow, x) * p.inv_T : -INFINITY;
-            mt_loc = fmaxf(mt_loc, pr[e]);
-            md_loc = fmaxf(md_loc, qr[e]);
+        const int c_begin = sh.child_start[v], c_end = sh.child_start[v + 1];
+        // both rows at the children's tokens (needed for the accept tests), in flight together
+        // with the row slices themselves
+        for (int k = tid; k < c_end - c_begin; k += kThreads) {
+            const int s = sh.token[sh.child_list[c_begin + k]];
+            sh.child_lt[k] = load_logit<LT>(trow, s) * p.inv_T;
+            sh.child_ld[k] = load_logit<LT>(drow, s) * p.inv_T;
+            bool dup = false;
+            for (int j = 0; j < k; ++j) dup |= sh.token[sh.child_list[c_begin + j]] == s;
+            sh.child_dup[k] = dup ? 1 : 0;
         }
-        const float mt_blk = block_max(mt_loc, sh);
-        const float md_blk = block_max(md_loc, sh);
-        double zt_loc = 0.0, zd_loc = 0.0;
+        load_row_slice<LT, EPT>(trow, base, V, p.inv_T, vec_ok, pr);
+        load_row_slice<LT, EPT>(drow, base, V, p.inv_T, vec_ok, qr);
+        SEQ_STAMP(1);
+        // softmax statistics: per wavefront first (no barrier), then folded by the first wavefront.
+        // pr/qr become e^(x - wave max); one more factor per wavefront turns them into
+        // probabilities once the vocabulary-wide max and normaliser are known.
+        float mt_wave = -INFINITY, md_wave = -INFINITY;
+        {
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            zt_loc += (double)prob_of(pr[e], mt_blk, 1.0f);
-            zd_loc += (double)prob_of(qr[e], md_blk, 1.0f);
-        }
-        const float zt_blk = (float)block_sum(zt_loc, sh);
-        const float zd_blk = (float)block_sum(zd_loc, sh);
-        if (!exchange<4>(p, tag_base, ++round, mt_blk, zt_blk, md_blk, zd_blk, sh)) {
-            finish(p, path_len, n_dec, 1, v, fallbacks, degenerate);
-            return;
-        }
-        fold_softmax_stats(p, sh);
-        const float mt = sh.res_f[0], md = sh.res_f[1];
-        const double zt = sh.res_d[0], zd = sh.res_d[1];
-        const float inv_zt = (float)(1.0 / zt), inv_zd = (float)(1.0 / zd);
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            pr[e] = prob_of(pr[e], mt, inv_zt);
-            qr[e] = prob_of(qr[e], md, inv_zd);
-        }
-
-        // Algorithm 2 at node v
-        double A = 0.0, B = 0.0, Wn = 1.0, massQ = 1.0;
-        bool fallback = false, sums_valid = false;
-        int n_rej = 0, next = -1;
-        const int c_begin = p.child_start[v], c_end = p.child_start[v + 1];
-        for (int ci = c_begin; ci < c_end; ++ci) {
-            const int c = p.child_list[ci];
-            const int s = min(max(p.tokens[c], 0), V - 1);  // stay inside the row whatever the caller sent
-            const float u = p.uniforms[c];
-            const float ps = prob_of(load_logit<LT>(trow, s) * p.inv_T, mt, inv_zt);
-            const float qs = prob_of(load_logit<LT>(drow, s) * p.inv_T, md, inv_zd);
-            bool in_s = false;
-            for (int k = 0; k < n_rej; ++k) in_s |= (sh.rejected[k] == s);
-            const int left = V - n_rej;  // tokens not yet rejected
-            const double rs = in_s ? 0.0 : (double)residual_of(ps, qs, (float)A, (float)B) / Wn;
-            const double ds = in_s ? 0.0
-                                   : (fallback ? (left > 0 ? 1.0 / (double)left : 0.0) : (double)qs / massQ);
-            const double ratio = ds > 0.0 ? rs / ds : (rs > 0.0 ? (double)INFINITY : 0.0);
-            const bool accept = (double)u < ratio;
-            record(p, n_dec, c, accept, (float)ratio, u);
-            ++n_dec;
-            if (accept) { next = c; break; }
-
-            // rejected: R <- norm(max(R - D, 0)), then D[s] <- 0 (and the uniform fallback)
-            double dA = 0.0, dB = 0.0;
-            if (fallback) { if (left > 0) dB = Wn / (double)left; }
-            else dA = Wn / massQ;
-            A += dA;
-            B += dB;
-            if (!in_s) {
-#pragma unroll
-                for (int e = 0; e < EPT; ++e)
-                    if (base + e == s) { pr[e] = 0.f; qr[e] = 0.f; }
-                if (tid == 0) sh.rejected[n_rej] = s;
-                ++n_rej;
-            }
-            const float af = (float)A, bf = (float)B;
-            double r_loc = 0.0, q_loc = 0.0;
+            for (int e = 0; e < EPT; ++e) { mt_wave = fmaxf(mt_wave, pr[e]); md_wave = fmaxf(md_wave, qr[e]); }
+            mt_wave = wave_reduce<kOpMax>(mt_wave);
+            md_wave = wave_reduce<kOpMax>(md_wave);
+            float zt = 0.f, zd = 0.f;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
-                r_loc += (double)residual_of(pr[e], qr[e], af, bf);
-                q_loc += (double)qr[e];
+                pr[e] = prob_of(pr[e], mt_wave, 1.0f);
+                qr[e] = prob_of(qr[e], md_wave, 1.0f);
+                zt += pr[e];
+                zd += qr[e];
             }
-            const float r_blk = (float)block_sum(r_loc, sh);
-            const float q_blk = (float)block_sum(q_loc, sh);
-            if (!exchange<2>(p, tag_base, ++round, r_blk, q_blk, 0.f, 0.f, sh)) {
-                finish(p, path_len, n_dec, 1, v, fallbacks, degenerate);
-                return;
-            }
-            fold_sums(p, sh);
-            const double w_new = sh.res_d[0], q_new = sh.res_d[1];
-            if (w_new > 0.0) { Wn = w_new; sums_valid = true; }
-            else { A -= dA; B -= dB; ++degenerate; sums_valid = false; }  // R stays as it was
-            massQ = q_new;
-            if (!fallback && !(massQ > 0.0)) { fallback = true; ++fallbacks; }
+            zt = wave_reduce<kOpSum>(zt);
+            zd = wave_reduce<kOpSum>(zd);
+            if (lane == 0) { sh.part[par][wave][0] = mt_wave; sh.part[par][wave][1] = zt; sh.part[par][wave][2] = md_wave; sh.part[par][wave][3] = zd; }
         }
-        if (next >= 0) {
-            if (blockIdx.x == 0 && tid == 0) p.path[path_len] = next;
+        __syncthreads();
+        SEQ_STAMP(2);
+        if (wave == 0) {
+            float mine[4], got[4];
+            {
+                const bool have = lane < kWaves;
+                const float mt_w = have ? sh.part[par][lane][0] : -INFINITY, zt_w = have ? sh.part[par][lane][1] : 0.f;
+                const float md_w = have ? sh.part[par][lane][2] : -INFINITY, zd_w = have ? sh.part[par][lane][3] : 0.f;
+                mine[0] = lane_value(row_reduce<kOpMax>(mt_w), 0);
+                mine[2] = lane_value(row_reduce<kOpMax>(md_w), 0);
+                mine[1] = lane_value(row_reduce<kOpSum>(zt_w > 0.f ? zt_w * exp_fast(mt_w - mine[0]) : 0.f), 0);
+                mine[3] = lane_value(row_reduce<kOpSum>(zd_w > 0.f ? zd_w * exp_fast(md_w - mine[2]) : 0.f), 0);
+            }
+            const bool ok = exchange<4>(p, tag_base, ++step, mine, 0.f, got);
+            SEQ_STAMP(3);
+            const bool have = lane < p.W;
+            const float mt = wave_reduce<kOpMax>(have && got[1] > 0.f ? got[0] : -INFINITY);
+            const float md = wave_reduce<kOpMax>(have && got[3] > 0.f ? got[2] : -INFINITY);
+            const float zt = wave_reduce<kOpSum>(have && got[1] > 0.f ? got[1] * exp_fast(got[0] - mt) : 0.f);
+            const float zd = wave_reduce<kOpSum>(have && got[3] > 0.f ? got[3] * exp_fast(got[2] - md) : 0.f);
+            // the children's logits become probabilities, a lane per child
+            for (int k = lane; k < c_end - c_begin; k += 64) {
+                sh.child_lt[k] = prob_of(sh.child_lt[k], mt, 1.0f / zt);
+                sh.child_ld[k] = prob_of(sh.child_ld[k], md, 1.0f / zd);
+            }
+            if (lane == 0) {
+                sh.fail = ok ? 0 : 1;
+                sh.stat[0] = mt; sh.stat[1] = md; sh.stat[2] = 1.0f / zt; sh.stat[3] = 1.0f / zd;
+                auto& st = sh.st;
+                st.A = st.B = 0.0; st.Wn = st.massQ = 1.0; st.af = st.bf = 0.f; st.dA = st.dB = 0.0;
+                st.ci = c_begin; st.n_rej = 0; st.fallback = 0; st.sums_valid = 0; st.next = -1;
+                if (ok) leader_step(p, sh, c_begin, c_end, V, false, 0.0, 0.0);
+            }
+        } else {
+            ++step;
+        }
+        par ^= 1;
+        __syncthreads();
+        SEQ_STAMP(4);
+        if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
+        {
+            const float ft = mt_wave == -INFINITY ? 0.f : exp_fast(mt_wave - sh.stat[0]) * sh.stat[2];
+            const float fd = md_wave == -INFINITY ? 0.f : exp_fast(md_wave - sh.stat[1]) * sh.stat[3];
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) { pr[e] *= ft; qr[e] *= fd; }
+        }
+
+        // Algorithm 2 at node v: one vocabulary pass + exchange per rejection
+        while (sh.st.action == kActPass) {
+            const int zero_token = sh.st.zero_token;
+            const float af = sh.st.af, bf = sh.st.bf;
+            float r_loc = 0.f, q_loc = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                if (base + e == zero_token) { pr[e] = 0.f; qr[e] = 0.f; }
+                r_loc += residual_of(pr[e], qr[e], af, bf);
+                q_loc += qr[e];
+            }
+            r_loc = wave_reduce<kOpSum>(r_loc);
+            q_loc = wave_reduce<kOpSum>(q_loc);
+            if (lane == 0) { sh.part[par][wave][0] = r_loc; sh.part[par][wave][1] = q_loc; }
+            __syncthreads();
+            SEQ_STAMP(10);
+            if (wave == 0) {
+                float mine[2], got[2];
+                mine[0] = fold_waves<kOpSum>(sh, par, 0, 0.f);
+                mine[1] = fold_waves<kOpSum>(sh, par, 1, 0.f);
+                const bool ok = exchange<2>(p, tag_base, ++step, mine, 0.f, got);
+                SEQ_STAMP(11);
+                const float w_new = wave_reduce<kOpSum>(got[0]);
+                const float q_new = wave_reduce<kOpSum>(got[1]);
+                if (lane == 0) {
+                    sh.fail = ok ? 0 : 1;
+                    if (ok) leader_step(p, sh, c_begin, c_end, V, true, (double)w_new, (double)q_new);
+                }
+                if (ok && sh.st.action == kActExhausted && sh.st.sums_valid)
+                    find_bonus_owner(p, sh.uniform[0], got[0], sh);
+            } else {
+                ++step;
+            }
+            par ^= 1;
+            __syncthreads();
+            SEQ_STAMP(12);
+            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
+        }
+        if (sh.st.action == kActAccepted) {
+            const int next = sh.st.next;
+            if (wg_rank() == 0 && tid == 0) p.path[path_len] = next;
             ++path_len;
             v = next;
+            __syncthreads();  // everyone has read the state before the next node rewrites it
             continue;
         }
 
         // no child accepted: bonus token ~ R by inverse CDF with uniforms[0]
-        const float af = (float)A, bf = (float)B;
-        if (!sums_valid) {
-            double r_loc = 0.0;
+        const float af = sh.st.af, bf = sh.st.bf;
+        const float u0 = sh.uniform[0];
+        if (!sh.st.sums_valid) {   // no pass has left the workgroups' residual masses yet
+            float r_loc = 0.f;
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) r_loc += (double)residual_of(pr[e], qr[e], af, bf);
-            const float r_blk = (float)block_sum(r_loc, sh);
-            if (!exchange<1>(p, tag_base, ++round, r_blk, 0.f, 0.f, 0.f, sh)) {
-                finish(p, path_len, n_dec, 1, v, fallbacks, degenerate);
-                return;
+            for (int e = 0; e < EPT; ++e) r_loc += residual_of(pr[e], qr[e], af, bf);
+            r_loc = wave_reduce<kOpSum>(r_loc);
+            if (lane == 0) sh.part[par][wave][0] = r_loc;
+            __syncthreads();
+            if (wave == 0) {
+                float mine[1], got[1];
+                mine[0] = fold_waves<kOpSum>(sh, par, 0, 0.f);
+                const bool ok = exchange<1>(p, tag_base, ++step, mine, 0.f, got);
+                if (lane == 0) sh.fail = ok ? 0 : 1;
+                if (ok) find_bonus_owner(p, u0, got[0], sh);
             }
+            __syncthreads();
+            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
         }
-        const float u0 = p.uniforms[0];
-        fold_bonus_owner(p, u0, sh);
-        const double total = sh.res_d[0], before = sh.res_d[1];
+        const double total = sh.bonus_d[0], before = sh.bonus_d[1];
         const double goal = (double)u0 * total;
-        const int owner = sh.res_i[0];
-        const bool pick_last = sh.res_i[1] != 0;
-        if ((int)blockIdx.x == owner) {
+        const int owner = sh.bonus_i[0];
+        const bool pick_last = sh.bonus_i[1] != 0;
+        if (wg_rank() == owner) {
             if (tid == 0) { sh.cand_min = 0x7FFFFFFF; sh.cand_max = -1; }
             float r[EPT];
             double mine = 0.0;
@@ -393,29 +552,37 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
             double incl = mine;
             for (int off = 1; off < 64; off <<= 1) {
                 const double t = __shfl_up(incl, off);
-                if ((tid & 63) >= off) incl += t;
+                if (lane >= off) incl += t;
             }
-            __syncthreads();
-            if ((tid & 63) == 63) sh.red_d[tid >> 6] = incl;
+            if (lane == 63) sh.scan[wave] = incl;
             __syncthreads();
             double run = before + incl - mine;
-            for (int w = 0; w < (tid >> 6); ++w) run += sh.red_d[w];
-            int found = -1;
+            for (int w = 0; w < wave; ++w) run += sh.scan[w];
+            int found = 0x7FFFFFFF, last_pos = -1;
             double lo = 0.0, hi = 0.0;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
                 const double prev = run;
                 run += (double)r[e];
-                if (found < 0 && !pick_last && run > goal) { found = base + e; lo = prev; hi = run; }
-                if (r[e] > 0.f) atomicMax(&sh.cand_max, base + e);
+                if (found == 0x7FFFFFFF && !pick_last && run > goal) { found = base + e; lo = prev; hi = run; }
+                if (r[e] > 0.f) last_pos = base + e;
             }
-            if (found >= 0) atomicMin(&sh.cand_min, found);
+            // one shared-memory atomic per wavefront, not per element
+            int wave_found = found, wave_last = last_pos;
+            for (int off = 32; off > 0; off >>= 1) {
+                wave_found = min(wave_found, __shfl_xor(wave_found, off));
+                wave_last = max(wave_last, __shfl_xor(wave_last, off));
+            }
+            if (lane == 0) {
+                if (wave_found != 0x7FFFFFFF) atomicMin(&sh.cand_min, wave_found);
+                if (wave_last >= 0) atomicMax(&sh.cand_max, wave_last);
+            }
             __syncthreads();
             int pick = sh.cand_min;
             if (pick == 0x7FFFFFFF) pick = sh.cand_max >= 0 ? sh.cand_max : min(V - 1, base);
             float* binfo = reinterpret_cast<float*>(p.trace + SEQ_TRACE_HEADER_INTS +
                                                     SEQ_MAX_TREE * SEQ_TRACE_RECORD_WORDS);
-            if (found >= 0 && found == pick) {
+            if (found == pick) {
                 binfo[0] = u0; binfo[1] = (float)total;
                 binfo[2] = (float)(lo / total); binfo[3] = (float)(hi / total);
             } else if (sh.cand_min == 0x7FFFFFFF && tid == 0) {
@@ -423,7 +590,8 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
             }
             if (tid == 0) p.bonus[0] = pick;
         }
-        finish(p, path_len, n_dec, 0, v, fallbacks, degenerate);
+        SEQ_STAMP(20);
+        finish(p, path_len, sh.st.n_dec, 0, v, sh.st.fallbacks, sh.st.degenerate);
         return;
     }
 }
@@ -436,67 +604,77 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
 template <typename LT, int EPT>
 __global__ __launch_bounds__(kThreads) void verify_greedy_kernel(const VerifyParams p) {
     __shared__ Shared sh;
-    const int tid = threadIdx.x;
-    const int base = ((int)blockIdx.x * kThreads + tid) * EPT;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int base = (wg_rank() * kThreads + tid) * EPT;
     const LT* target = static_cast<const LT*>(p.target);
     const int V = p.V;
-    const uint32_t tag_base = launch_tag_base(p, sh);
-    if ((int)blockIdx.x >= p.W) return;
-    uint32_t round = 0;
+    constexpr int kNone = 0x7FFFFFFF;
+    bool poisoned;
+    const uint32_t tag_base = launch_tag_base(p, &poisoned);
+    if (poisoned) { finish(p, 0, 0, 1, 0, 0, 0); return; }
+    stage_tree(p, sh);
+    __syncthreads();
+    uint32_t step = 0;
     int v = 0, path_len = 0, n_dec = 0;
+    auto better = [](float ov, int ox, float bv, int bx) {   // larger value, lower index on ties
+        return ox != kNone && (bx == kNone || ov > bv || (ov == bv && ox < bx));
+    };
     for (;;) {
         const LT* trow = target + (size_t)v * V;
         float best = -INFINITY;
-        int best_x = 0x7FFFFFFF;
+        int best_x = kNone;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
             const int x = base + e;
             if (x < V) {
                 const float val = load_logit<LT>(trow, x);
-                if (val > best || best_x == 0x7FFFFFFF) { best = val; best_x = x; }
+                if (better(val, x, best, best_x)) { best = val; best_x = x; }
             }
         }
         for (int off = 32; off > 0; off >>= 1) {
             const float ov = __shfl_xor(best, off);
             const int ox = __shfl_xor(best_x, off);
-            if (ov > best || (ov == best && ox < best_x)) { best = ov; best_x = ox; }
+            if (better(ov, ox, best, best_x)) { best = ov; best_x = ox; }
         }
+        if (lane == 0) { sh.red_f[wave] = best; sh.red_i[wave] = best_x; }
         __syncthreads();
-        if ((tid & 63) == 0) { sh.red_f[tid >> 6] = best; sh.red_i[tid >> 6] = best_x; }
-        __syncthreads();
-        best = sh.red_f[0]; best_x = sh.red_i[0];
-        for (int w = 1; w < kWavesPerBlock; ++w)
-            if (sh.red_f[w] > best || (sh.red_f[w] == best && sh.red_i[w] < best_x)) {
-                best = sh.red_f[w]; best_x = sh.red_i[w];
+        if (wave == 0) {
+            best = sh.red_f[0]; best_x = sh.red_i[0];
+            for (int w = 1; w < kWaves; ++w)
+                if (better(sh.red_f[w], sh.red_i[w], best, best_x)) { best = sh.red_f[w]; best_x = sh.red_i[w]; }
+            float mine[2] = {best, __int_as_float(best_x)}, got[2];
+            const bool ok = exchange<2>(p, tag_base, ++step, mine, __int_as_float(kNone), got);
+            float top = lane < p.W ? got[0] : -INFINITY;
+            int top_x = lane < p.W ? __float_as_int(got[1]) : kNone;
+            for (int off = 32; off > 0; off >>= 1) {
+                const float ov = __shfl_xor(top, off);
+                const int ox = __shfl_xor(top_x, off);
+                if (better(ov, ox, top, top_x)) { top = ov; top_x = ox; }
             }
-        if (!exchange<2>(p, tag_base, ++round, best, __int_as_float(best_x), 0.f, 0.f, sh)) {
-            finish(p, path_len, n_dec, 1, v, 0, 0);
-            return;
+            if (lane == 0) { sh.fail = ok ? 0 : 1; sh.cand_min = top_x; }
+        } else {
+            ++step;
         }
-        float top = -INFINITY;
-        int top_x = 0x7FFFFFFF;
-        for (int w = 0; w < p.W; ++w) {
-            const float ov = sh.gath[w][0];
-            const int ox = __float_as_int(sh.gath[w][1]);
-            if (ox == 0x7FFFFFFF) continue;  // workgroup owns no token
-            if (top_x == 0x7FFFFFFF || ov > top || (ov == top && ox < top_x)) { top = ov; top_x = ox; }
-        }
+        __syncthreads();
+        if (sh.fail) { finish(p, path_len, n_dec, 1, v, 0, 0); return; }
+        const int top_x = sh.cand_min;
         int next = -1;
-        const int c_begin = p.child_start[v], c_end = p.child_start[v + 1];
+        const int c_begin = sh.child_start[v], c_end = sh.child_start[v + 1];
         for (int ci = c_begin; ci < c_end; ++ci) {
-            const int c = p.child_list[ci];
-            const bool accept = p.tokens[c] == top_x;
-            record(p, n_dec, c, accept, accept ? 1.f : 0.f, p.uniforms[c]);
+            const int c = sh.child_list[ci];
+            const bool accept = sh.token[c] == top_x;
+            record(p, n_dec, c, accept, accept ? 1.f : 0.f, sh.uniform[c]);
             ++n_dec;
             if (accept) { next = c; break; }
         }
         if (next >= 0) {
-            if (blockIdx.x == 0 && tid == 0) p.path[path_len] = next;
+            if (wg_rank() == 0 && tid == 0) p.path[path_len] = next;
             ++path_len;
             v = next;
+            __syncthreads();  // sh.cand_min and the wave partials are rewritten at the next node
             continue;
         }
-        if (blockIdx.x == 0 && tid == 0) p.bonus[0] = top_x;
+        if (wg_rank() == 0 && tid == 0) p.bonus[0] = top_x;
         finish(p, path_len, n_dec, 0, v, 0, 0);
         return;
     }
@@ -506,15 +684,14 @@ uint32_t g_spin_limit = 1u << 22;
 
 template <typename LT>
 void launch_verify(const VerifyParams& p, bool greedy, int ept, hipStream_t stream) {
-    const dim3 grid((unsigned)kVerifyMaxGroups), block(kThreads);  // workgroups >= W only take a ticket
+    const dim3 grid((unsigned)p.W), block(kThreads);
 #define SEQ_LAUNCH(E)                                                                          \
     do {                                                                                       \
         if (greedy) hipLaunchKernelGGL((verify_greedy_kernel<LT, E>), grid, block, 0, stream, p); \
         else hipLaunchKernelGGL((verify_walk_kernel<LT, E>), grid, block, 0, stream, p);       \
     } while (0)
-    if (ept == 8) SEQ_LAUNCH(8);
-    else if (ept == 16) SEQ_LAUNCH(16);
-    else SEQ_LAUNCH(32);
+    (void)ept;
+    SEQ_LAUNCH(8);
 #undef SEQ_LAUNCH
 }
 
@@ -527,6 +704,14 @@ constexpr size_t kTraceBytes =
 using namespace seqtree;
 
 // Test hook (not part of the public header): bound of the inter-workgroup wait, in polls.
+#ifdef SEQTREE_STAMPS
+extern "C" int seqtree_internal_read_stamps(long long* out) {
+    int count = 0;
+    (void)hipMemcpyFromSymbol(&count, HIP_SYMBOL(g_stamp_count), sizeof(int));
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_stamps), sizeof(long long) * 64);
+    return count;
+}
+#endif
 extern "C" void seqtree_internal_set_spin_limit(uint32_t polls) { g_spin_limit = polls; }
 
 extern "C" size_t seq_verify_workspace(int32_t n_tree, int32_t vocab, int32_t dtype) {
@@ -556,8 +741,8 @@ extern "C" int seq_verify(const void* target_logits, const void* draft_logits,
     rc = get_sync_area(&sync);
     if (rc != SEQ_OK) return rc;
 
-    int ept = 8;
-    while ((long long)kVerifyMaxGroups * kThreads * ept < vocab) ept *= 2;  // <= 32 by SEQ_MAX_VOCAB
+    const int ept = 8;  // kVerifyMaxGroups * kThreads * 8 = SEQ_MAX_VOCAB
+    static_assert((long long)kVerifyMaxGroups * kThreads * 8 >= SEQ_MAX_VOCAB, "vocabulary limit");
     VerifyParams p;
     p.target = target_logits;
     p.draft = draft_logits;

@@ -151,14 +151,20 @@ def test_outputs_are_deterministic_and_trace_ratios_match():
 
 def test_bounded_wait_always_terminates():
     """Force the inter-workgroup wait to give up after a single poll: the kernel must still end
-    normally, report status 1 (or succeed by luck), and the next call must work."""
+    normally and report status 1 (or succeed by luck).  After a timeout the library refuses
+    further walks until seq_shutdown() has discarded its synchronisation area."""
     v = W.verify_inputs_for("C2")
     S.lib().seqtree_internal_set_spin_limit(0)
     try:
         p, bonus, trace = run_verify(v)
         assert trace["status"] in (0, 1)
-        if trace["status"] == 1:
+        timed_out = trace["status"] == 1
+        if timed_out:
             assert bonus == -1
     finally:
         S.lib().seqtree_internal_set_spin_limit(1 << 22)
+    if timed_out:
+        _, bonus, trace = run_verify(v)
+        assert trace["status"] == 1 and bonus == -1
+        S.shutdown()
     assert check_verify(v) in ("exact", "flagged")
