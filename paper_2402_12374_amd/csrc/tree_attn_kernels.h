@@ -11,14 +11,15 @@ int launch_tree_attn_rowwise_f32(const float* q, const float* k_cache, const flo
                                  hipStream_t stream);
 
 // How the bf16 kernel cuts the work: query rows of one KV head (all G = H/Hk heads of the
-// group times n tree tokens) in blocks of kQueryBlock, the key axis in `splits` contiguous
-// ranges of 64-key tiles whose partial results are merged by the last workgroup to finish.
+// group times n tree tokens) in units of 128 * r_blocks rows, the key axis in `splits`
+// contiguous ranges of 64-key tiles whose partial results are merged by the last workgroup to
+// finish.
 struct AttnSchedule {
-    int query_blocks;   // per KV head
+    int r_blocks;       // 32-row query blocks per wavefront (1 or 2)
+    int query_blocks;   // units per KV head
     int splits;
     size_t workspace_bytes;
 };
-constexpr int kQueryBlock = 128;
 constexpr int kKeyTile = 64;
 
 AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D);
