@@ -58,5 +58,6 @@ extern "C" int seq_tree_attn(const void* q, const void* k_cache, const void* v_c
     if (rc != SEQ_OK) return rc;
     return launch_tree_attn_mfma_bf16(q, k_cache, v_cache, k_tree, v_tree, plan, prefix_len,
                                       prefix_cap, n_tree, heads, kv_heads, head_dim, out, sched,
-                                      static_cast<float*>(workspace), sync->attn_counters, stream);
+                                      static_cast<float*>(workspace), sync->attn_counters,
+                                      sync->round_robin_xcds, stream);
 }

@@ -11,16 +11,16 @@ int launch_tree_attn_rowwise_f32(const float* q, const float* k_cache, const flo
                                  hipStream_t stream);
 
 // How the bf16 kernel cuts the work: query rows of one KV head (all G = H/Hk heads of the
-// group times n tree tokens) in units of 128 * r_blocks rows, the key axis in `splits`
-// contiguous ranges of 64-key tiles whose partial results are merged by the last workgroup to
-// finish.
+// group times n tree tokens) in units of 32 * wq rows (one per workgroup; its 8 wavefronts form
+// a wq x 8/wq grid of query blocks x key groups), the key axis in `splits` contiguous ranges of
+// 32-key tiles whose partial results are merged by the last workgroup to finish.
 struct AttnSchedule {
-    int r_blocks;       // 32-row query blocks per wavefront (1 or 2)
+    int wq;             // query blocks per workgroup: 2, 4 or 8
     int query_blocks;   // units per KV head
     int splits;
     size_t workspace_bytes;
 };
-constexpr int kKeyTile = 64;
+constexpr int kKeyTile = 32;
 
 AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D);
 
@@ -28,6 +28,6 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
                                const void* k_tree, const void* v_tree, const TreePlan& plan,
                                int P, int cap, int n, int H, int Hk, int D, void* out,
                                const AttnSchedule& sched, float* workspace, uint32_t* counters,
-                               hipStream_t stream);
+                               bool units_share_l2, hipStream_t stream);
 
 }  // namespace seqtree

@@ -46,10 +46,9 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
-constexpr int kStages = 4;          // tile buffers in the LDS ring
-constexpr int kAhead = kStages - 1; // tiles in flight beyond the one being consumed
+constexpr int kWaves = 8;             // two wavefronts per SIMD: one computes while the other waits
+constexpr int kThreads = kWaves * 64;
+constexpr int kRing = 8;              // tile buffers in the LDS ring
 constexpr int kMaxSplits = 16;
 
 struct MfmaParams {
@@ -63,22 +62,13 @@ struct MfmaParams {
     int words_per_row;
     int P, cap, n, H, Hk, G;
     int query_blocks;     // units per KV head
-    int prefix_tiles;     // ceil(P / 64)
+    int prefix_tiles;     // ceil(P / 32)
     int splits;
     float* partials;
     uint32_t* counters;
     float scale_log2;     // log2(e) / sqrt(D)
+    int share_l2;         // all workgroups of a unit run on one XCD (checked once per device)
 };
-
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
-}
 
 // 16 bytes per lane from global memory into LDS at lds_base + lane * 16 (lds_base uniform).
 __device__ __forceinline__ void async_copy16(const void* gptr, uint32_t lds_base) {
@@ -123,20 +113,6 @@ template <int D> __device__ __forceinline__ int v_swizzle(int row) {
     return D == 128 ? (row & 3) << 2 : ((row >> 1) & 1) << 2;
 }
 
-template <int D>
-struct Smem {
-    static constexpr int kTileElems = kKeyTile * D;   // bf16 elements per K (or V) tile
-    uint16_t k[kStages][kTileElems];
-    uint16_t v[kStages][kTileElems];
-};
-
-// Visibility words of a tree tile travel through the same ring as K and V: lane l of a
-// wavefront fetches word (l / 32) of the tile for query (l % 32) of each of its R blocks.
-template <int R>
-struct MaskRing {
-    uint32_t w[kStages][kWaves][R][64];
-};
-
 // Phase timestamps of workgroup 0 (100 MHz wall clock), compiled in with -DSEQTREE_STAMPS only.
 #ifdef SEQTREE_STAMPS
 __device__ long long g_attn_stamps[128];
@@ -149,20 +125,50 @@ __device__ int g_attn_stamp_count;
 #define ATTN_STAMP(id) do {} while (0)
 #endif
 
-template <int D, int R>
-__global__ __launch_bounds__(kThreads, 1) void tree_attn_mfma_kernel(const MfmaParams p) {
+// LDS: a ring of kRing tile buffers (K and V of 32 keys each), and a ring of visibility words.
+// After the last tile the K ring is reused to merge the key groups of the workgroup.
+template <int D>
+struct Rings {
+    static constexpr int kTileElems = kKeyTile * D;   // bf16 elements per K (or V) tile
+    uint16_t k[kRing][kTileElems];
+    uint16_t v[kRing][kTileElems];
+    uint32_t mask[kRing][kWaves][64];
+};
+
+// Rows of the weight table of the epilogue: key groups of a workgroup, or key ranges of a unit.
+template <int WQ> constexpr int fac_rows() { return WQ == 8 ? 8 : kMaxSplits; }
+
+template <int D, int WQ>
+constexpr size_t epilogue_bytes() {
+    return sizeof(float) * ((size_t)kWaves * (D / 32) * 4 * 256 + kWaves * 128 + (size_t)fac_rows<WQ>() * WQ * 64 + 2 * WQ * 64);
+}
+
+template <int D, int WQ>
+union Smem {
+    Rings<D> r;
+    char epilogue[epilogue_bytes<D, WQ>()];
+};
+
+template <int D, int WQ, int WK>
+__global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaParams p) {
+    static_assert(WQ * WK == kWaves, "wavefront grid");
     constexpr int kKSteps = D / 16;        // contraction steps of Q K^T
     constexpr int kDBlocks = D / 32;       // 32-row blocks of O^T
     constexpr int kChunks = D / 8;         // 16-byte chunks per K/V row
     constexpr int kRowBytes = D * 2;
     constexpr int kRowsPerCopy = 64 / kChunks;               // rows one wave-wide copy covers
-    constexpr int kCopies = kKeyTile / kRowsPerCopy / kWaves; // copies per wavefront per tile
-    constexpr int kLoadsPerTile = 2 * kCopies + R;           // K, V and visibility words, per lane
-    constexpr int kPartialWords = kDBlocks * 16 + 2;
-    constexpr int kUnitRows = 128 * R;
-    using SM = Smem<D>;
-    __shared__ __attribute__((aligned(1024))) SM sm;
-    __shared__ __attribute__((aligned(256))) MaskRing<R> mr;
+    constexpr int kCopiesPerTile = kKeyTile / kRowsPerCopy;  // per K (or V) tile
+    constexpr int kCopiesPerRound = 2 * kCopiesPerTile * WK; // K and V of the WK tiles of a round
+    constexpr int kCopiesPerWave = kCopiesPerRound / kWaves;
+    constexpr int kLoadsPerRound = kCopiesPerWave + 1;       // + my visibility word
+    constexpr int kAheadRounds = kRing / WK - 1;             // rounds in flight beyond the current one
+    constexpr int kUnitRows = 32 * WQ;
+    constexpr uint32_t kTileBytes = kKeyTile * D * 2;
+    static_assert(kCopiesPerRound % kWaves == 0, "copies divide evenly among the wavefronts");
+    static_assert(kAheadRounds >= 1, "ring too small");
+    using SM = Smem<D, WQ>;
+    __shared__ __attribute__((aligned(1024))) SM sm_union;
+    Rings<D>& sm = sm_union.r;
     __shared__ int s_last;
 
     ATTN_STAMP_RESET();
@@ -181,20 +187,15 @@ __global__ __launch_bounds__(kThreads, 1) void tree_attn_mfma_kernel(const MfmaP
     const int g = unit / p.query_blocks, qb = unit % p.query_blocks;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wq = wave % WQ, wk = wave / WQ;      // query block and key group of this wavefront
     const int half = lane >> 5, col = lane & 31;
     const int rows = p.G * p.n;
-    int qi[R], qh[R];
-    bool qvalid[R], blk_valid[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int row0 = qb * kUnitRows + (wave * R + r) * 32;
-        blk_valid[r] = row0 < rows;
-        const int qrow = row0 + col;
-        qvalid[r] = qrow < rows;
-        qi[r] = qvalid[r] ? qrow / p.G : 0;
-        qh[r] = qvalid[r] ? g * p.G + qrow % p.G : 0;
-    }
-    const bool wave_valid = blk_valid[0];
+    const int row0 = qb * kUnitRows + wq * 32;
+    const bool blk_valid = row0 < rows;
+    const int qrow = row0 + col;
+    const bool qvalid = qrow < rows;
+    const int qi = qvalid ? qrow / p.G : 0;
+    const int qh = qvalid ? g * p.G + qrow % p.G : 0;
 
     // key tiles of this workgroup
     const int last_row = min(rows - 1, qb * kUnitRows + kUnitRows - 1);
@@ -203,75 +204,78 @@ __global__ __launch_bounds__(kThreads, 1) void tree_attn_mfma_kernel(const MfmaP
     const int total_tiles = p.prefix_tiles + tree_tiles;
     const int t_begin = (int)((long long)total_tiles * split / S);
     const int t_end = (int)((long long)total_tiles * (split + 1) / S);
+    const int n_rounds = (t_end - t_begin + WK - 1) / WK;
 
     const uint32_t k_lds = lds_address(&sm.k[0][0]);
     const uint32_t v_lds = lds_address(&sm.v[0][0]);
-    const uint32_t m_lds = lds_address(&mr.w[0][0][0][0]);
-    constexpr uint32_t kTileBytes = SM::kTileElems * 2;
+    const uint32_t m_lds = lds_address(&sm.mask[0][0][0]);
 
-    // one tile: every lane moves kCopies 16-byte chunks of K and of V (and R visibility words)
-    auto issue_tile = [&](int t) {
-        const int buf = (t - t_begin) % kStages;
-        const bool is_prefix = t < p.prefix_tiles;
-        const int key0 = is_prefix ? t * kKeyTile : (t - p.prefix_tiles) * kKeyTile;
-        const int limit = is_prefix ? p.P : p.n;
-        const uint16_t* kbase = is_prefix ? p.k_cache + (size_t)g * p.cap * D : p.k_tree + (size_t)g * D;
-        const uint16_t* vbase = is_prefix ? p.v_cache + (size_t)g * p.cap * D : p.v_tree + (size_t)g * D;
-        const size_t row_stride = is_prefix ? (size_t)D : (size_t)p.Hk * D;
+    // One round = the WK tiles t_begin + rho*WK .. +WK-1; tile j of the range lives in ring
+    // buffer j % kRing.  Every wavefront issues the same number of copies per round (the waits
+    // below count them), so tiles past the end of the range and rows past the valid keys fetch
+    // valid memory that is never used: the last valid row of the last tile.
+    auto issue_round = [&](int rho) {
 #pragma unroll
-        for (int j = 0; j < kCopies; ++j) {
-            const int copy = wave * kCopies + j;                 // 1 KB block of the tile
+        for (int c = 0; c < kCopiesPerWave; ++c) {
+            const int item = wave + c * kWaves;                   // (tile of the round, K|V, copy)
+            const int tr = item / (2 * kCopiesPerTile);
+            const int is_v = (item / kCopiesPerTile) & 1;
+            const int copy = item % kCopiesPerTile;
+            const int j = rho * WK + tr;
+            const int t = max(min(t_begin + j, t_end - 1), 0);
+            const bool is_prefix = t < p.prefix_tiles;
+            const int key0 = is_prefix ? t * kKeyTile : (t - p.prefix_tiles) * kKeyTile;
+            const int limit = is_prefix ? p.P : p.n;
+            const uint16_t* base = is_prefix ? (is_v ? p.v_cache : p.k_cache) + (size_t)g * p.cap * D
+                                             : (is_v ? p.v_tree : p.k_tree) + (size_t)g * D;
+            const size_t row_stride = is_prefix ? (size_t)D : (size_t)p.Hk * D;
             const int row = copy * kRowsPerCopy + lane / kChunks;
             const int slot = lane % kChunks;
-            // Rows past the valid keys fetch the last valid row instead: the copy count per tile
-            // stays the same for every wavefront (the waits below count copies), memory past the
-            // valid range is never touched, and those keys are masked anyway.
             const int key = min(key0 + row, limit - 1);
-            const uint32_t block_off = (uint32_t)buf * kTileBytes + (uint32_t)copy * 1024u;
-            async_copy16(kbase + (size_t)key * row_stride + ((slot ^ k_swizzle<D>(row)) * 8),
-                         __builtin_amdgcn_readfirstlane(k_lds + block_off));
-            async_copy16(vbase + (size_t)key * row_stride + ((slot ^ v_swizzle<D>(row)) * 8),
-                         __builtin_amdgcn_readfirstlane(v_lds + block_off));
+            const int swz = is_v ? v_swizzle<D>(row) : k_swizzle<D>(row);
+            const uint32_t dst = (is_v ? v_lds : k_lds) + (uint32_t)(j % kRing) * kTileBytes + (uint32_t)copy * 1024u;
+            async_copy16(base + (size_t)key * row_stride + ((slot ^ swz) * 8), __builtin_amdgcn_readfirstlane(dst));
         }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int word = is_prefix ? 0 : (t - p.prefix_tiles) * 2 + half;
-            const bool real = !is_prefix && qvalid[r] && word < p.words_per_row;
-            const uint32_t* src = p.anc + (real ? (size_t)qi[r] * p.words_per_row + word : 0);
-            async_copy4(src, __builtin_amdgcn_readfirstlane(m_lds + (uint32_t)(((buf * kWaves + wave) * R + r) * 256)));
+        {   // visibility word of my query for my tile of this round (tree tiles only; else unused)
+            const int j = rho * WK + wk;
+            const int t = max(min(t_begin + j, t_end - 1), 0);
+            const int word = t - p.prefix_tiles;
+            const bool real = word >= 0 && qvalid && word < p.words_per_row;
+            const uint32_t* src = p.anc + (real ? (size_t)qi * p.words_per_row + word : 0);
+            async_copy4(src, __builtin_amdgcn_readfirstlane(m_lds + (uint32_t)(((j % kRing) * kWaves + wave) * 256)));
         }
     };
 
-    // start the pipeline before anything else touches memory
-#pragma unroll
-    for (int a = 0; a < kAhead; ++a)
-        if (t_begin + a < t_end) issue_tile(t_begin + a);
-
-    ATTN_STAMP(1);
-    // Q fragments (B operand): lane holds query `col`, features ks*16 + half*8 .. +7
-    bf16x8_t qf[R][kKSteps];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const uint16_t* qp = p.q + ((size_t)qi[r] * p.H + qh[r]) * D + half * 8;
+    // Q fragments (B operand): lane holds query `col`, features ks*16 + half*8 .. +7.  Requested
+    // first, settled after the tile copies have been issued.
+    bf16x8_t qf[kKSteps];
+    {
+        const uint16_t* qp = p.q + ((size_t)qi * p.H + qh) * D + half * 8;
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (qvalid[r]) v = *reinterpret_cast<const uint4*>(qp + ks * 16);
-            qf[r][ks] = __builtin_bit_cast(bf16x8_t, v);
+            if (qvalid) v = *reinterpret_cast<const uint4*>(qp + ks * 16);
+            qf[ks] = __builtin_bit_cast(bf16x8_t, v);
         }
     }
+
+    // start the tile pipeline (a rolled loop: code that runs once is fetched cold, and slowly)
+#pragma unroll 1
+    for (int a = 0; a < kAheadRounds; ++a) issue_round(a);
+    ATTN_STAMP(1);
+
     // Make the compiler settle these loads here.  It cannot see the copies issued in assembly,
     // and a wait for the Q fragments placed at their first use inside the tile loop would also
-    // wait, on every iteration, for every copy in flight.
+    // wait, on every iteration, for every copy in flight.  (Loading Q in assembly as well, to
+    // count its wait exactly, is not an option: the compiler may move or reuse the destination
+    // registers of a load it does not know to be in flight.)
 #pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[r][ks]));
-
+    for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
     ATTN_STAMP(2);
+
     // Per-lane LDS byte offsets inside a tile, fixed for the whole kernel.  Everything else in
     // an address is a compile-time constant that goes into the instruction's offset field.
-    //   K (ds_read_b128): key row `col` (+32 for the second half), chunk (2*ks + half) ^ swizzle
+    //   K (ds_read_b128): key row `col`, chunk (2*ks + half) ^ swizzle
     //   V (transpose read): 16-lane group, lanes 4r..4r+3 address 16 features of key row r
     const int grp = lane >> 4, li = lane & 15;
     uint32_t koff[kKSteps], voff[kDBlocks];
@@ -280,7 +284,7 @@ __global__ __launch_bounds__(kThreads, 1) void tree_attn_mfma_kernel(const MfmaP
         koff[ks] = (uint32_t)(col * kRowBytes + (((ks * 2 + half) ^ k_swizzle<D>(col)) * 16));
 #pragma unroll
     for (int b = 0; b < kDBlocks; ++b) {
-        const int vrow = half * 4 + (li >> 2);                 // + kb*32 + (2m+a)*8, multiples of 8
+        const int vrow = half * 4 + (li >> 2);                    // + (2m+a)*8, multiples of 8
         const int feat = b * 32 + (grp & 1) * 16 + (li & 3) * 4;  // 4 features = 8 bytes
         voff[b] = (uint32_t)(vrow * kRowBytes + (((feat >> 3) ^ v_swizzle<D>(vrow)) * 16) + (feat & 7) * 2);
     }
@@ -288,188 +292,212 @@ __global__ __launch_bounds__(kThreads, 1) void tree_attn_mfma_kernel(const MfmaP
     const lds_cptr k_base = (lds_cptr)(lds_ptr_t)&sm.k[0][0];
     const lds_cptr v_base = (lds_cptr)(lds_ptr_t)&sm.v[0][0];
 
-    f32x16_t oacc[R][kDBlocks];
-    float m_run[R], l_run[R];
+    f32x16_t oacc[kDBlocks];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        m_run[r] = -INFINITY;
-        l_run[r] = 0.f;
+    for (int b = 0; b < kDBlocks; ++b)
 #pragma unroll
-        for (int b = 0; b < kDBlocks; ++b)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) oacc[r][b][x] = 0.f;
-    }
+        for (int x = 0; x < 16; ++x) oacc[b][x] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
 
-    for (int t = t_begin; t < t_end; ++t) {
-        const int buf = (t - t_begin) % kStages;
-        // my copies of tile t have landed once at most the copies of the tiles after it are
-        // still in flight (copies complete in order); near the end of the range wait for all
-        if (t + kAhead - 1 < t_end) wait_vmcnt<(kAhead - 1) * kLoadsPerTile>();
-        else wait_vmcnt<0>();
+    for (int rho = 0; rho < n_rounds; ++rho) {
+        // my copies of this round have landed once at most the copies of the kAheadRounds - 1
+        // rounds issued after it are in flight (copies complete in order)
+        wait_vmcnt<(kAheadRounds - 1) * kLoadsPerRound>();
         ATTN_STAMP(10);
-        __syncthreads();   // everybody's copies of tile t are in LDS; tile t-1's buffer is free
+        __syncthreads();   // everybody's copies of this round are in LDS; the previous round's buffers are free
         ATTN_STAMP(11);
-        if (t + kAhead < t_end) issue_tile(t + kAhead);
-        if (!wave_valid) continue;
-
+        issue_round(rho + kAheadRounds);
+        const int j = rho * WK + wk;
+        const int t = t_begin + j;
+        if (!blk_valid || t >= t_end) continue;
+        const int buf = j % kRing;
         const lds_cptr kt = k_base + buf * kTileBytes;
         const lds_cptr vt = v_base + buf * kTileBytes;
 
-        // S^T = K Q^T for the two 32-key halves of the tile
-        f32x16_t sacc[R][2];
+        // S^T = K Q^T (32 keys x 32 queries)
+        f32x16_t sacc;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int ks = 0; ks < kKSteps; ++ks) {
+            const bf16x8_t kf = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(kt + koff[ks]);
+            if (ks == 0) {
+                f32x16_t zero;
 #pragma unroll
-            for (int ks = 0; ks < kKSteps; ++ks) {
-                const bf16x8_t kf = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(
-                    kt + koff[ks] + kb * 32 * kRowBytes);
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    if (ks == 0) {
-                        f32x16_t zero;
-#pragma unroll
-                        for (int x = 0; x < 16; ++x) zero[x] = 0.f;
-                        sacc[r][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[r][ks], zero, 0, 0, 0);
-                    } else {
-                        sacc[r][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[r][ks], sacc[r][kb], 0, 0, 0);
-                    }
-                }
+                for (int x = 0; x < 16; ++x) zero[x] = 0.f;
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], zero, 0, 0, 0);
+            } else {
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
             }
         }
-
         ATTN_STAMP(12);
+
         // Tiles that lie wholly inside the prefix need no masking at all.
         const bool full = t < p.prefix_tiles && (t + 1) * kKeyTile <= p.P;
         if (!full) {
+            uint32_t m;   // bit x <=> key x of this tile is visible to my query
+            if (t < p.prefix_tiles) {
+                const int left = p.P - t * kKeyTile;
+                m = left >= 32 ? 0xFFFFFFFFu : (left <= 0 ? 0u : ((1u << left) - 1u));
+            } else {
+                const int word = t - p.prefix_tiles;
+                m = (qvalid && word < p.words_per_row) ? sm.mask[buf][wave][col] : 0u;
+            }
+            m >>= half * 4;
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    uint32_t m;   // bit x <=> key kb*32+x of this tile is visible to my query
-                    if (t < p.prefix_tiles) {
-                        const int left = p.P - (t * kKeyTile + kb * 32);
-                        m = left >= 32 ? 0xFFFFFFFFu : (left <= 0 ? 0u : ((1u << left) - 1u));
-                    } else {
-                        const int word = (t - p.prefix_tiles) * 2 + kb;
-                        m = (qvalid[r] && word < p.words_per_row) ? mr.w[buf][wave][r][kb * 32 + col] : 0u;
-                    }
-                    m >>= half * 4;
-#pragma unroll
-                    for (int x = 0; x < 16; ++x)   // accumulator element x holds key (x/4)*8 + half*4 + x%4
-                        sacc[r][kb][x] = ((m >> ((x >> 2) * 8 + (x & 3))) & 1u) ? sacc[r][kb][x] : -INFINITY;
-                }
+            for (int x = 0; x < 16; ++x)   // accumulator element x holds key (x/4)*8 + half*4 + x%4
+                sacc[x] = ((m >> ((x >> 2) * 8 + (x & 3))) & 1u) ? sacc[x] : -INFINITY;
         }
 
         // online softmax per query column (scores are scaled inside the exponential), and the
         // probabilities packed as the B operand of the second product
-        uint32_t pw[R][2][2][4];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
+        uint32_t pw[2][4];
+        {
             float mx = -INFINITY;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[r][kb][x]);
+            for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[x]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[r], mx * p.scale_log2);
+            const float m_new = fmaxf(m_run, mx * p.scale_log2);
             const float ref = (m_new == -INFINITY) ? 0.f : m_new;
-            const bool moved = m_new != m_run[r];
-            const float alpha = __builtin_amdgcn_exp2f(m_run[r] - ref);
-            m_run[r] = m_new;
+            const bool moved = m_new != m_run;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - ref);
+            m_run = m_new;
             float psum = 0.f;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int x = 0; x < 16; x += 2) {
-                    f32x2_t e;
-                    e[0] = __builtin_amdgcn_exp2f(fmaf(sacc[r][kb][x], p.scale_log2, -ref));
-                    e[1] = __builtin_amdgcn_exp2f(fmaf(sacc[r][kb][x + 1], p.scale_log2, -ref));
-                    psum += e[0] + e[1];
-                    pw[r][kb][x >> 3][(x & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(e, bf16x2_t));
-                }
-            l_run[r] = l_run[r] * alpha + psum;
+            for (int x = 0; x < 16; x += 2) {
+                f32x2_t e;
+                e[0] = __builtin_amdgcn_exp2f(fmaf(sacc[x], p.scale_log2, -ref));
+                e[1] = __builtin_amdgcn_exp2f(fmaf(sacc[x + 1], p.scale_log2, -ref));
+                psum += e[0] + e[1];
+                pw[x >> 3][(x & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(e, bf16x2_t));
+            }
+            l_run = l_run * alpha + psum;
             if (__any(moved)) {   // the running maximum of some column changed: rescale the output
 #pragma unroll
                 for (int b = 0; b < kDBlocks; ++b)
 #pragma unroll
-                    for (int x = 0; x < 16; ++x) oacc[r][b][x] *= alpha;
+                    for (int x = 0; x < 16; ++x) oacc[b][x] *= alpha;
             }
         }
-
         ATTN_STAMP(13);
-        // O^T += V^T P^T.  Matrix step (kb, m) contracts keys kb*32 + (2m+a)*8 + half*4 + 0..3,
-        // a = 0,1 -- the keys whose probabilities sit in accumulator elements 8m..8m+7.
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int m = 0; m < 2; ++m)
-#pragma unroll
-                for (int b = 0; b < kDBlocks; ++b) {
-                    v4i16 part[2];
-#pragma unroll
-                    for (int a = 0; a < 2; ++a)
-                        part[a] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (v4i16 __attribute__((address_space(3)))*)(vt + voff[b] +
-                                                                       (kb * 32 + (2 * m + a) * 8) * kRowBytes));
-                    uint4 vw;
-                    vw.x = __builtin_bit_cast(uint2, part[0]).x;
-                    vw.y = __builtin_bit_cast(uint2, part[0]).y;
-                    vw.z = __builtin_bit_cast(uint2, part[1]).x;
-                    vw.w = __builtin_bit_cast(uint2, part[1]).y;
-                    const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, vw);
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        uint4 pq;
-                        pq.x = pw[r][kb][m][0]; pq.y = pw[r][kb][m][1]; pq.z = pw[r][kb][m][2]; pq.w = pw[r][kb][m][3];
-                        oacc[r][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            vf, __builtin_bit_cast(bf16x8_t, pq), oacc[r][b], 0, 0, 0);
-                    }
-                }
-    }
 
-    ATTN_STAMP(20);
-    auto write_out = [&](auto rc, float l_lane) {
-        constexpr int r = decltype(rc)::value;
-        const float l_tot = l_lane + __shfl_xor(l_lane, 32);
-        if (!qvalid[r]) return;
-        const float inv = 1.0f / l_tot;
-        uint16_t* op = p.out + ((size_t)qi[r] * p.H + qh[r]) * D;
+        // O^T += V^T P^T.  Matrix step m contracts keys (2m+a)*8 + half*4 + 0..3, a = 0,1 -- the
+        // keys whose probabilities sit in accumulator elements 8m..8m+7.
 #pragma unroll
-        for (int b = 0; b < kDBlocks; ++b)
+        for (int m = 0; m < 2; ++m) {
+            uint4 pq;
+            pq.x = pw[m][0]; pq.y = pw[m][1]; pq.z = pw[m][2]; pq.w = pw[m][3];
+            const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, pq);
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                const int d0 = b * 32 + rq * 8 + half * 4;
-                f32x2_t lo = {oacc[r][b][rq * 4 + 0] * inv, oacc[r][b][rq * 4 + 1] * inv};
-                f32x2_t hi = {oacc[r][b][rq * 4 + 2] * inv, oacc[r][b][rq * 4 + 3] * inv};
-                uint2 w;
-                w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2_t));
-                w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
-                *reinterpret_cast<uint2*>(op + d0) = w;
+            for (int b = 0; b < kDBlocks; ++b) {
+                v4i16 part[2];
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+                    part[a] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (v4i16 __attribute__((address_space(3)))*)(vt + voff[b] + ((2 * m + a) * 8) * kRowBytes));
+                uint4 vw;
+                vw.x = __builtin_bit_cast(uint2, part[0]).x;
+                vw.y = __builtin_bit_cast(uint2, part[0]).y;
+                vw.z = __builtin_bit_cast(uint2, part[1]).x;
+                vw.w = __builtin_bit_cast(uint2, part[1]).y;
+                oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vw), pf, oacc[b], 0, 0, 0);
             }
-    };
+        }
+    }
+    wait_vmcnt<0>();   // nothing of mine may still be landing in LDS when the ring is reused below
+    ATTN_STAMP(20);
 
-    // one query block: either the final result, or a partial result left for the merge
-    const size_t block_words = (size_t)kPartialWords * 64;
-    const size_t split_stride = (size_t)kWaves * R * block_words;
-    auto leave = [&](auto rc) {
-        constexpr int r = decltype(rc)::value;
-        if (!blk_valid[r]) return;
-        if (S == 1) { write_out(rc, l_run[r]); return; }
-        float* dst = p.partials + ((size_t)unit * S + split) * split_stride + (size_t)(wave * R + r) * block_words + lane;
-        dst[0] = m_run[r];
-        dst[64] = l_run[r];
+    // ---- epilogue ---------------------------------------------------------------------------
+    // Code that runs once per workgroup is fetched cold, at a small fraction of the speed of a
+    // loop that sits in the instruction cache, and for short key ranges the epilogue is most of
+    // the kernel.  So every wavefront only drops its registers into LDS (a few wide stores) and
+    // all merging -- of the key groups of the workgroup, and of the key ranges of the unit --
+    // is done by tight loops over LDS / the workspace with all 512 threads.
+    //
+    // LDS scratch (the tile rings, free by now):
+    //   o[wave][k4][lane][4]   unnormalised output; k4 = b*4 + rq holds features
+    //                          b*32 + rq*8 + half*4 .. +3 of query (lane % 32), half = lane / 32
+    //   ml[wave][2][64]        running maximum and (per-lane part of the) normaliser
+    //   fac[*][WQ][64], big_m / big_l [WQ][64]   weights and merged statistics
+    constexpr int kK4 = kDBlocks * 4;
+    __syncthreads();
+    float* const lds_f = reinterpret_cast<float*>(&sm_union);
+    float* const o_s = lds_f;                                        // [kWaves][kK4][64][4]
+    float* const ml_s = o_s + (size_t)kWaves * kK4 * 256;            // [kWaves][2][64]
+    float* const fac_s = ml_s + kWaves * 128;                        // [fac_rows][WQ][64]
+    float* const bigm_s = fac_s + (size_t)fac_rows<WQ>() * WQ * 64;  // [WQ][64]
+    float* const bigl_s = bigm_s + WQ * 64;                          // [WQ][64]
+    static_assert(WK <= fac_rows<WQ>(), "weight table too small");
+    {
+        float4* dst = reinterpret_cast<float4*>(o_s) + (size_t)wave * kK4 * 64 + lane;
 #pragma unroll
         for (int b = 0; b < kDBlocks; ++b)
 #pragma unroll
-            for (int x = 0; x < 16; ++x) dst[(2 + b * 16 + x) * 64] = oacc[r][b][x];
-    };
-    leave(std::integral_constant<int, 0>{});
-    if constexpr (R == 2) leave(std::integral_constant<int, 1>{});
-    ATTN_STAMP(21);
-    if (S == 1) return;
+            for (int rq = 0; rq < 4; ++rq)
+                dst[(b * 4 + rq) * 64] = make_float4(oacc[b][rq * 4], oacc[b][rq * 4 + 1], oacc[b][rq * 4 + 2], oacc[b][rq * 4 + 3]);
+        ml_s[wave * 128 + lane] = m_run;
+        ml_s[wave * 128 + 64 + lane] = l_run;
+    }
+    __syncthreads();
+    // weights of the key groups: per (query block, lane)
+    for (int i = tid; i < WQ * 64; i += kThreads) {
+        const int q = i >> 6, l = i & 63;
+        float big = -INFINITY;
+#pragma unroll 1
+        for (int o = 0; o < WK; ++o) big = fmaxf(big, ml_s[(o * WQ + q) * 128 + l]);
+        const float ref = (big == -INFINITY) ? 0.f : big;
+        float lsum = 0.f;
+#pragma unroll 1
+        for (int o = 0; o < WK; ++o) {
+            const float f = __builtin_amdgcn_exp2f(ml_s[(o * WQ + q) * 128 + l] - ref);
+            fac_s[(o * WQ + q) * 64 + l] = f;
+            lsum = fmaf(ml_s[(o * WQ + q) * 128 + 64 + l], f, lsum);
+        }
+        bigm_s[i] = big;
+        bigl_s[i] = lsum;
+    }
+    __syncthreads();
 
-    // see whether we are the last range of this unit to finish
-    __threadfence();
+    const size_t block_words = (size_t)kK4 * 256 + 128;            // one (unit, range, query block)
+    float* const my_part = p.partials + ((size_t)unit * S + split) * WQ * block_words;
+    // 8-byte store of four consecutive output features of one query
+    auto store_out = [&](int q, int l, int k4, float4 acc, float inv) {
+        const int qr = qb * kUnitRows + q * 32 + (l & 31);
+        if (qr >= rows) return;
+        const int node = qr / p.G, head = g * p.G + qr % p.G;
+        const int d0 = (k4 >> 2) * 32 + (k4 & 3) * 8 + (l >> 5) * 4;
+        f32x2_t lo = {acc.x * inv, acc.y * inv}, hi = {acc.z * inv, acc.w * inv};
+        uint2 w;
+        w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2_t));
+        w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
+        *reinterpret_cast<uint2*>(p.out + ((size_t)node * p.H + head) * D + d0) = w;
+    };
+    // merged output of the workgroup: straight to `out` (single range) or to the workspace
+#pragma unroll 1
+    for (int i = tid; i < WQ * kK4 * 64; i += kThreads) {
+        const int l = i & 63, k4 = (i >> 6) % kK4, q = i / (64 * kK4);
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 1
+        for (int o = 0; o < WK; ++o) {
+            const float f = fac_s[(o * WQ + q) * 64 + l];
+            const float4 v = reinterpret_cast<const float4*>(o_s)[((size_t)(o * WQ + q) * kK4 + k4) * 64 + l];
+            acc.x = fmaf(v.x, f, acc.x); acc.y = fmaf(v.y, f, acc.y);
+            acc.z = fmaf(v.z, f, acc.z); acc.w = fmaf(v.w, f, acc.w);
+        }
+        if (S == 1) store_out(q, l, k4, acc, 1.0f / (bigl_s[q * 64 + l] + bigl_s[q * 64 + (l ^ 32)]));
+        else reinterpret_cast<float4*>(my_part + (size_t)q * block_words)[k4 * 64 + l] = acc;
+    }
+    if (S == 1) return;
+    for (int i = tid; i < WQ * 64; i += kThreads) {
+        float* ml = my_part + (size_t)(i >> 6) * block_words + (size_t)kK4 * 256;
+        ml[i & 63] = bigm_s[i];
+        ml[64 + (i & 63)] = bigl_s[i];
+    }
+    ATTN_STAMP(21);
+
+    // See whether we are the last range of this unit to finish.  The partial results must be
+    // visible to that workgroup.  When all ranges of a unit run on one XCD they meet in its L2:
+    // it is enough that my stores have completed.  Otherwise the L2 has to be written back.
+    if (p.share_l2) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    else __threadfence();
     __syncthreads();
     if (tid == 0) {
         const uint32_t arrived = atomicAdd(&p.counters[unit], 1u);
@@ -479,75 +507,69 @@ __global__ __launch_bounds__(kThreads, 1) void tree_attn_mfma_kernel(const MfmaP
     __syncthreads();
     ATTN_STAMP(22);
     if (!s_last) return;
-    __threadfence();
+    if (p.share_l2) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    else __threadfence();
     ATTN_STAMP(23);
 
-    auto merge = [&](auto rc) {
-        constexpr int r = decltype(rc)::value;
-        if (!blk_valid[r]) return;
-        const float* src0 = p.partials + (size_t)unit * S * split_stride + (size_t)(wave * R + r) * block_words + lane;
-        // weights of the ranges first, then the weighted sums; every load is unconditional (ranges
-        // past S re-read the last one with weight zero) so that they are all in flight together
-        float w[kMaxSplits], ls[kMaxSplits];
-        float m_all = -INFINITY;
-#pragma unroll
-        for (int s = 0; s < kMaxSplits; ++s) {
-            const float* src = src0 + (size_t)min(s, S - 1) * split_stride;
-            w[s] = src[0];
-            ls[s] = src[64];
+    // merge the ranges of the unit: weights first, then the weighted sums
+    const float* const unit_part = p.partials + (size_t)unit * S * WQ * block_words;
+    for (int i = tid; i < WQ * 64; i += kThreads) {
+        const float* ml = unit_part + (size_t)(i >> 6) * block_words + (size_t)kK4 * 256 + (i & 63);
+        float big = -INFINITY;
+#pragma unroll 4
+        for (int r = 0; r < S; ++r) big = fmaxf(big, ml[(size_t)r * WQ * block_words]);
+        const float ref = (big == -INFINITY) ? 0.f : big;
+        float lsum = 0.f;
+#pragma unroll 4
+        for (int r = 0; r < S; ++r) {
+            const float f = __builtin_amdgcn_exp2f(ml[(size_t)r * WQ * block_words] - ref);
+            fac_s[r * WQ * 64 + i] = f;
+            lsum = fmaf(ml[(size_t)r * WQ * block_words + 64], f, lsum);
         }
-#pragma unroll
-        for (int s = 0; s < kMaxSplits; ++s) {
-            if (s >= S) w[s] = -INFINITY;
-            m_all = fmaxf(m_all, w[s]);
+        bigl_s[i] = lsum;
+    }
+    __syncthreads();
+#pragma unroll 1
+    for (int i = tid; i < WQ * kK4 * 64; i += kThreads) {
+        const int l = i & 63, k4 = (i >> 6) % kK4, q = i / (64 * kK4);
+        const float4* src = reinterpret_cast<const float4*>(unit_part + (size_t)q * block_words) + k4 * 64 + l;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+        for (int r = 0; r < S; ++r) {
+            const float f = fac_s[r * WQ * 64 + q * 64 + l];
+            const float4 v = src[(size_t)r * WQ * block_words / 4];
+            acc.x = fmaf(v.x, f, acc.x); acc.y = fmaf(v.y, f, acc.y);
+            acc.z = fmaf(v.z, f, acc.z); acc.w = fmaf(v.w, f, acc.w);
         }
-        const float ref = (m_all == -INFINITY) ? 0.f : m_all;
-        float l_all = 0.f;
-#pragma unroll
-        for (int s = 0; s < kMaxSplits; ++s) {
-            w[s] = __builtin_amdgcn_exp2f(w[s] - ref);
-            l_all += ls[s] * w[s];
-        }
-#pragma unroll
-        for (int b = 0; b < kDBlocks; ++b)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) {
-                float acc = 0.f;
-#pragma unroll
-                for (int s = 0; s < kMaxSplits; ++s)
-                    acc = fmaf(src0[(size_t)min(s, S - 1) * split_stride + (2 + b * 16 + x) * 64], w[s], acc);
-                oacc[r][b][x] = acc;
-            }
-        write_out(rc, l_all);
-    };
-    merge(std::integral_constant<int, 0>{});
-    if constexpr (R == 2) merge(std::integral_constant<int, 1>{});
+        store_out(q, l, k4, acc, 1.0f / (bigl_s[q * 64 + l] + bigl_s[q * 64 + (l ^ 32)]));
+    }
     ATTN_STAMP(24);
 }
 
 }  // namespace
 
 int g_splits_override = 0;  // tuning hooks, 0 = automatic
-int g_rblocks_override = 0;
+int g_wq_override = 0;
 
 AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     AttnSchedule s;
     const int G = H / Hk;
     const int rows = G * n;
-    s.r_blocks = rows > 128 ? 2 : 1;
-    if (g_rblocks_override > 0) s.r_blocks = g_rblocks_override;
-    const int unit_rows = 128 * s.r_blocks;
+    s.wq = rows <= 64 ? 2 : (rows <= 128 ? 4 : 8);
+    if (g_wq_override > 0) s.wq = g_wq_override;
+    const int unit_rows = 32 * s.wq;
     s.query_blocks = (rows + unit_rows - 1) / unit_rows;
     const int units = Hk * s.query_blocks;
     const int prefix_tiles = (P + kKeyTile - 1) / kKeyTile;
+    const int wk = kWaves / s.wq;
     int splits = 256 / (units > 0 ? units : 1);
     if (g_splits_override > 0) splits = g_splits_override;
-    if (splits > prefix_tiles + 1) splits = prefix_tiles + 1;
-    if (splits > kMaxSplits) splits = kMaxSplits;
+    if (splits > (prefix_tiles + 1 + wk - 1) / wk) splits = (prefix_tiles + 1 + wk - 1) / wk;
+    if (splits > (s.wq == 8 ? 8 : kMaxSplits)) splits = s.wq == 8 ? 8 : kMaxSplits;   // weight table of the epilogue
     if (splits < 1) splits = 1;
     s.splits = splits;
-    const size_t words = (size_t)(D / 32) * 16 + 2;
-    s.workspace_bytes = splits > 1 ? (size_t)units * splits * kWaves * s.r_blocks * words * 64 * sizeof(float) : 0;
+    const size_t block_words = (size_t)(D / 32) * 4 * 256 + 128;   // one (unit, range, query block)
+    s.workspace_bytes = splits > 1 ? (size_t)units * splits * s.wq * block_words * sizeof(float) : 0;
     if (s.workspace_bytes < 256) s.workspace_bytes = 256;
     return s;
 }
@@ -556,7 +578,7 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
                                const void* k_tree, const void* v_tree, const TreePlan& plan,
                                int P, int cap, int n, int H, int Hk, int D, void* out,
                                const AttnSchedule& sched, float* workspace, uint32_t* counters,
-                               hipStream_t stream) {
+                               bool units_share_l2, hipStream_t stream) {
     MfmaParams p;
     p.q = static_cast<const uint16_t*>(q);
     p.k_cache = static_cast<const uint16_t*>(k_cache);
@@ -573,24 +595,30 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
     p.partials = workspace;
     p.counters = counters;
     p.scale_log2 = 1.4426950408889634f / sqrtf((float)D);
+    p.share_l2 = units_share_l2 ? 1 : 0;
     const int units = Hk * sched.query_blocks;
     if (units > kAttnMaxCounters) return SEQ_ERR_SHAPE;
     const int unit_groups = (units + 7) / 8;
     const dim3 grid((unsigned)(unit_groups * 8 * sched.splits)), block(kThreads);
+#define SEQ_ATTN_LAUNCH(DD, WQ_)                                                                  \
+    hipLaunchKernelGGL((tree_attn_mfma_kernel<DD, WQ_, kWaves / WQ_>), grid, block, 0, stream, p)
     if (D == 64) {
-        if (sched.r_blocks == 2) hipLaunchKernelGGL((tree_attn_mfma_kernel<64, 2>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((tree_attn_mfma_kernel<64, 1>), grid, block, 0, stream, p);
+        if (sched.wq == 2) SEQ_ATTN_LAUNCH(64, 2);
+        else if (sched.wq == 4) SEQ_ATTN_LAUNCH(64, 4);
+        else SEQ_ATTN_LAUNCH(64, 8);
     } else {
-        if (sched.r_blocks == 2) hipLaunchKernelGGL((tree_attn_mfma_kernel<128, 2>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((tree_attn_mfma_kernel<128, 1>), grid, block, 0, stream, p);
+        if (sched.wq == 2) SEQ_ATTN_LAUNCH(128, 2);
+        else if (sched.wq == 4) SEQ_ATTN_LAUNCH(128, 4);
+        else SEQ_ATTN_LAUNCH(128, 8);
     }
+#undef SEQ_ATTN_LAUNCH
     return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
 }
 
 }  // namespace seqtree
 
 // Tuning hooks (not part of the public header): force the number of key-axis ranges and the
-// number of 32-row query blocks per wavefront.
+// number of query blocks per workgroup (2, 4 or 8).
 #ifdef SEQTREE_STAMPS
 extern "C" int seqtree_internal_read_attn_stamps(long long* out) {
     int count = 0;
@@ -600,4 +628,4 @@ extern "C" int seqtree_internal_read_attn_stamps(long long* out) {
 }
 #endif
 extern "C" void seqtree_internal_set_attn_splits(int splits) { seqtree::g_splits_override = splits; }
-extern "C" void seqtree_internal_set_attn_rblocks(int r) { seqtree::g_rblocks_override = r; }
+extern "C" void seqtree_internal_set_attn_wq(int wq) { seqtree::g_wq_override = wq; }

@@ -10,6 +10,39 @@
 
 namespace seqtree {
 
+namespace {
+// Which XCD does each workgroup of a launch run on?
+__global__ void xcd_probe_kernel(int* out) {
+    if (threadIdx.x == 0) {
+        int id;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(id));
+        out[blockIdx.x] = id & 0xF;
+    }
+}
+
+// True iff workgroup b runs on the XCD of workgroup b % 8 and those eight are distinct.
+bool probe_round_robin_xcds() {
+    constexpr int kBlocks = 1024;
+    int* dev = nullptr;
+    if (hipMalloc(&dev, sizeof(int) * kBlocks) != hipSuccess) return false;
+    std::vector<int> host(kBlocks, -1);
+    bool ok = hipMemset(dev, 0xFF, sizeof(int) * kBlocks) == hipSuccess;
+    if (ok) {
+        hipLaunchKernelGGL(xcd_probe_kernel, dim3(kBlocks), dim3(64), 0, 0, dev);
+        ok = hipGetLastError() == hipSuccess &&
+             hipMemcpy(host.data(), dev, sizeof(int) * kBlocks, hipMemcpyDeviceToHost) == hipSuccess;
+    }
+    (void)hipFree(dev);
+    if (!ok) return false;
+    for (int b = 0; b < 8; ++b)
+        for (int c = 0; c < b; ++c)
+            if (host[b] == host[c]) return false;
+    for (int b = 8; b < kBlocks; ++b)
+        if (host[b] != host[b % 8]) return false;
+    return true;
+}
+}  // namespace
+
 int validate_parent(const int32_t* parent, int32_t n) {
     if (n < 1 || n > SEQ_MAX_TREE) return SEQ_ERR_SHAPE;
     if (parent[0] != -1) return SEQ_ERR_TREE;
@@ -142,6 +175,7 @@ int get_sync_area(SyncArea** out) {
         return SEQ_ERR_HIP;
     }
     s.area.verify_epoch = reinterpret_cast<uint32_t*>(s.area.verify_slots + slot_words);
+    s.area.round_robin_xcds = probe_round_robin_xcds();
     g_sync.push_back(s);
     *out = &g_sync.back().area;
     return SEQ_OK;
