@@ -30,6 +30,7 @@
 // When the key axis is cut into several ranges, every workgroup leaves (max, normaliser,
 // unnormalised output) in the workspace and the last one to arrive for a unit merges them by
 // log-sum-exp; no workgroup ever waits for another.
+#include <algorithm>
 #include <type_traits>
 
 #include "seq_internal.h"
@@ -181,9 +182,11 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
     const int xcd = bid & 7, idx = bid >> 3;
     const int total_units = p.Hk * p.query_blocks;
     const int units_per_xcd = (total_units + 7) >> 3;
-    const int local = idx / S, split = idx % S;
+    // Range-major within an XCD: the workgroups that run at the same time then mostly work on
+    // the same key range of their head and find its tiles in L2.
+    const int split = idx / units_per_xcd, local = idx % units_per_xcd;
     const int unit = xcd * units_per_xcd + local;
-    if (local >= units_per_xcd || unit >= total_units) return;
+    if (split >= S || unit >= total_units) return;
     const int g = unit / p.query_blocks, qb = unit % p.query_blocks;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -214,30 +217,48 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
     // buffer j % kRing.  Every wavefront issues the same number of copies per round (the waits
     // below count them), so tiles past the end of the range and rows past the valid keys fetch
     // valid memory that is never used: the last valid row of the last tile.
+    // What a copy of mine moves is fixed for the whole kernel (which tile of the round, K or V,
+    // which 1 KB block of the tile): its lane-dependent part is computed once, here.
+    int cp_tr[kCopiesPerWave], cp_row[kCopiesPerWave];
+    uint32_t cp_chunk[kCopiesPerWave], cp_dst[kCopiesPerWave];
+    const uint16_t* cp_prefix[kCopiesPerWave];   // address of my chunk in row 0 of cache tile 0
+#pragma unroll
+    for (int c = 0; c < kCopiesPerWave; ++c) {
+        const int item = wave + c * kWaves;                   // (tile of the round, K|V, copy)
+        const int is_v = (item / kCopiesPerTile) & 1, copy = item % kCopiesPerTile;
+        cp_tr[c] = item / (2 * kCopiesPerTile);
+        cp_row[c] = copy * kRowsPerCopy + lane / kChunks;
+        const int swz = is_v ? v_swizzle<D>(cp_row[c]) : k_swizzle<D>(cp_row[c]);
+        cp_chunk[c] = (uint32_t)(((lane % kChunks) ^ swz) * 8) | (is_v ? 0x80000000u : 0u);
+        cp_dst[c] = (is_v ? v_lds : k_lds) + (uint32_t)copy * 1024u;
+        cp_prefix[c] = (is_v ? p.v_cache : p.k_cache) + ((size_t)g * p.cap + cp_row[c]) * D + (cp_chunk[c] & 0xFFFFu);
+    }
     auto issue_round = [&](int rho) {
+        const int j0 = rho * WK;
+        const bool inside = (t_begin + j0 + WK) * kKeyTile <= p.P && t_begin + j0 + WK <= t_end;
 #pragma unroll
         for (int c = 0; c < kCopiesPerWave; ++c) {
-            const int item = wave + c * kWaves;                   // (tile of the round, K|V, copy)
-            const int tr = item / (2 * kCopiesPerTile);
-            const int is_v = (item / kCopiesPerTile) & 1;
-            const int copy = item % kCopiesPerTile;
-            const int j = rho * WK + tr;
-            const int t = max(min(t_begin + j, t_end - 1), 0);
-            const bool is_prefix = t < p.prefix_tiles;
-            const int key0 = is_prefix ? t * kKeyTile : (t - p.prefix_tiles) * kKeyTile;
-            const int limit = is_prefix ? p.P : p.n;
-            const uint16_t* base = is_prefix ? (is_v ? p.v_cache : p.k_cache) + (size_t)g * p.cap * D
-                                             : (is_v ? p.v_tree : p.k_tree) + (size_t)g * D;
-            const size_t row_stride = is_prefix ? (size_t)D : (size_t)p.Hk * D;
-            const int row = copy * kRowsPerCopy + lane / kChunks;
-            const int slot = lane % kChunks;
-            const int key = min(key0 + row, limit - 1);
-            const int swz = is_v ? v_swizzle<D>(row) : k_swizzle<D>(row);
-            const uint32_t dst = (is_v ? v_lds : k_lds) + (uint32_t)(j % kRing) * kTileBytes + (uint32_t)copy * 1024u;
-            async_copy16(base + (size_t)key * row_stride + ((slot ^ swz) * 8), __builtin_amdgcn_readfirstlane(dst));
+            const int j = j0 + cp_tr[c];
+            const uint32_t dst = cp_dst[c] + (uint32_t)(j % kRing) * kTileBytes;
+            const uint16_t* src;
+            if (inside) {   // every tile of the round lies wholly inside the prefix
+                src = cp_prefix[c] + (size_t)(t_begin + j) * (kKeyTile * D);
+            } else {
+                const int t = max(min(t_begin + j, t_end - 1), 0);
+                const bool is_prefix = t < p.prefix_tiles;
+                const bool is_v = (cp_chunk[c] >> 31) != 0;
+                const int key0 = is_prefix ? t * kKeyTile : (t - p.prefix_tiles) * kKeyTile;
+                const int limit = is_prefix ? p.P : p.n;
+                const uint16_t* base = is_prefix ? (is_v ? p.v_cache : p.k_cache) + (size_t)g * p.cap * D
+                                                 : (is_v ? p.v_tree : p.k_tree) + (size_t)g * D;
+                const size_t row_stride = is_prefix ? (size_t)D : (size_t)p.Hk * D;
+                const int key = min(key0 + cp_row[c], limit - 1);
+                src = base + (size_t)key * row_stride + (cp_chunk[c] & 0xFFFFu);
+            }
+            async_copy16(src, __builtin_amdgcn_readfirstlane(dst));
         }
         {   // visibility word of my query for my tile of this round (tree tiles only; else unused)
-            const int j = rho * WK + wk;
+            const int j = j0 + wk;
             const int t = max(min(t_begin + j, t_end - 1), 0);
             const int word = t - p.prefix_tiles;
             const bool real = word >= 0 && qvalid && word < p.words_per_row;
@@ -314,18 +335,23 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
         const lds_cptr kt = k_base + buf * kTileBytes;
         const lds_cptr vt = v_base + buf * kTileBytes;
 
-        // S^T = K Q^T (32 keys x 32 queries)
+        // S^T = K Q^T (32 keys x 32 queries): all K fragments are requested before the first
+        // matrix instruction, so that one LDS latency is paid per tile, not one per instruction
+        bf16x8_t kf[kKSteps];
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks)
+            kf[ks] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(kt + koff[ks]);
+        __builtin_amdgcn_sched_barrier(0);
         f32x16_t sacc;
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
-            const bf16x8_t kf = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(kt + koff[ks]);
             if (ks == 0) {
                 f32x16_t zero;
 #pragma unroll
                 for (int x = 0; x < 16; ++x) zero[x] = 0.f;
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], zero, 0, 0, 0);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], zero, 0, 0, 0);
             } else {
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
             }
         }
         ATTN_STAMP(12);
@@ -562,11 +588,20 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     const int units = Hk * s.query_blocks;
     const int prefix_tiles = (P + kKeyTile - 1) / kKeyTile;
     const int wk = kWaves / s.wq;
-    int splits = 256 / (units > 0 ? units : 1);
-    if (g_splits_override > 0) splits = g_splits_override;
-    if (splits > (prefix_tiles + 1 + wk - 1) / wk) splits = (prefix_tiles + 1 + wk - 1) / wk;
-    if (splits > (s.wq == 8 ? 8 : kMaxSplits)) splits = s.wq == 8 ? 8 : kMaxSplits;   // weight table of the epilogue
-    if (splits < 1) splits = 1;
+    // Key ranges per unit.  One workgroup fits on a CU at a time, so the launch runs in batches
+    // of 256 workgroups; a range costs its rounds plus a fixed prologue/epilogue (about a dozen
+    // rounds' worth, measured) plus the merge.  Take the cheapest count.
+    const int tiles = prefix_tiles + (n + kKeyTile - 1) / kKeyTile;
+    const int max_splits = std::min(s.wq == 8 ? 8 : kMaxSplits, std::max(1, tiles / wk));
+    int splits = 1;
+    long best = -1;
+    for (int cand = 1; cand <= max_splits; ++cand) {
+        const long batches = ((long)units * cand + 255) / 256;
+        const long rounds = (tiles + cand * wk - 1) / (cand * wk);
+        const long cost = batches * (rounds + 12 + (cand > 1 ? cand : 0));
+        if (best < 0 || cost < best) { best = cost; splits = cand; }
+    }
+    if (g_splits_override > 0) splits = std::min(g_splits_override, max_splits);
     s.splits = splits;
     const size_t block_words = (size_t)(D / 32) * 4 * 256 + 128;   // one (unit, range, query block)
     s.workspace_bytes = splits > 1 ? (size_t)units * splits * s.wq * block_words * sizeof(float) : 0;

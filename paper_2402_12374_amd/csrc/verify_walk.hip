@@ -374,13 +374,16 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
 
     SEQ_STAMP_RESET();
     SEQ_STAMP(0);
+    const bool vec_ok = (V % (16 / (int)sizeof(LT)) == 0) &&
+                        ((reinterpret_cast<uintptr_t>(p.target) | reinterpret_cast<uintptr_t>(p.draft)) & 15) == 0;
+    float pr[EPT], qr[EPT];
+    // the root's rows are needed whatever happens: ask for them before anything else
+    load_row_slice<LT, EPT>(target, base, V, p.inv_T, vec_ok, pr);
+    load_row_slice<LT, EPT>(draft, base, V, p.inv_T, vec_ok, qr);
     bool poisoned;
     const uint32_t tag_base = launch_tag_base(p, &poisoned);
     if (poisoned) { finish(p, 0, 0, 1, 0, 0, 0); return; }
     stage_tree(p, sh);
-    const bool vec_ok = (V % (16 / (int)sizeof(LT)) == 0) &&
-                        ((reinterpret_cast<uintptr_t>(p.target) | reinterpret_cast<uintptr_t>(p.draft)) & 15) == 0;
-    float pr[EPT], qr[EPT];
     uint32_t step = 0;
     int par = 0, v = 0, path_len = 0;
     if (tid == 0) { sh.st.n_dec = 0; sh.st.fallbacks = 0; sh.st.degenerate = 0; }
@@ -400,8 +403,10 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
             for (int j = 0; j < k; ++j) dup |= sh.token[sh.child_list[c_begin + j]] == s;
             sh.child_dup[k] = dup ? 1 : 0;
         }
-        load_row_slice<LT, EPT>(trow, base, V, p.inv_T, vec_ok, pr);
-        load_row_slice<LT, EPT>(drow, base, V, p.inv_T, vec_ok, qr);
+        if (v != 0) {
+            load_row_slice<LT, EPT>(trow, base, V, p.inv_T, vec_ok, pr);
+            load_row_slice<LT, EPT>(drow, base, V, p.inv_T, vec_ok, qr);
+        }
         SEQ_STAMP(1);
         // softmax statistics: per wavefront first (no barrier), then folded by the first wavefront.
         // pr/qr become e^(x - wave max); one more factor per wavefront turns them into
