@@ -49,6 +49,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of a HIP graph")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--yardstick-mib", type=int, default=0,
+                    help="after the timed region, also launch a plain copy kernel of this many MiB four times "
+                         "(the known-size reference for HBM traffic counters collected with rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -205,10 +208,18 @@ def main() -> int:
                     "alg_flops_per_launch": flops_alg, "avg_launch_us": round(attn_us, 3)}
     e = 2 if tdt == torch.bfloat16 else 4
     verify_bytes = (len(path0) + 1) * 2 * V * e
-    verify_info = {"kernel": "verify_walk_kernel", "avg_launch_us": round(verify_us, 3),
+    per_node = T > 0 and V <= 32768   # the library's own choice of kernel (see include/seqtree.h)
+    leaves = int(sum(1 for ch in W.children_lists(parent) if not ch))
+    moved = ((n - leaves) * 2 + leaves) * V * e if per_node else verify_bytes
+    verify_info = {"kernel": "verify_chains_kernel" if per_node else "verify_walk_kernel",
+                   "avg_launch_us": round(verify_us, 3),
                    "accepted_path_len_set0": len(path0), "alg_bytes_lazy_set0": verify_bytes,
                    "hbm_frac_lazy_set0": round(verify_bytes / (verify_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 5),
-                   "note": "latency-bound: reads only the rows of visited nodes"}
+                   "logit_bytes_read": moved,
+                   "hbm_frac_read": round(moved / (verify_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 5),
+                   "note": ("one workgroup per node reads every row the tree can visit; bound by one compute "
+                            "unit's ALU rate over its node's sibling chain, not by HBM") if per_node else
+                           "latency-bound: reads only the rows of visited nodes"}
 
     # ---- CPU baseline: the checker as it stands, one thread, same workload ----------------
     cpu = None
@@ -254,6 +265,18 @@ def main() -> int:
         "gpu_event_us_per_step": round(ev_s / steps * 1e6, 3),
         "roofline": roofline, "verify": verify_info, "cpu_baseline": cpu,
     }
+    if args.yardstick_mib > 0:
+        nbytes = args.yardstick_mib << 20
+        src = torch.full((nbytes,), 1, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(4):
+            rc = S.lib().seqtree_internal_copy_probe(src.data_ptr(), dst.data_ptr(), nbytes,
+                                                     torch.cuda.current_stream().cuda_stream)
+            assert rc == 0
+        torch.cuda.synchronize()
+        assert bool((dst == 1).all())
+        line["yardstick_copy_bytes"] = nbytes
     print(json.dumps(line))
     S.shutdown()
     return 0

@@ -47,7 +47,7 @@ extern "C" {
 #define SEQ_ERR_TREE (-3)        /* parent[0] != -1 or parent[i] not in [0, i) */
 #define SEQ_ERR_DTYPE (-4)       /* dtype is neither SEQ_BF16 nor SEQ_F32 */
 #define SEQ_ERR_TEMPERATURE (-5) /* temperature negative, NaN or infinite */
-#define SEQ_ERR_WORKSPACE (-6)   /* workspace NULL or smaller than the matching *_workspace() */
+#define SEQ_ERR_WORKSPACE (-6)   /* workspace NULL, smaller than the matching *_workspace(), or not 16-byte aligned */
 #define SEQ_ERR_HIP (-7)         /* a HIP runtime call failed (no device, launch failure, ...) */
 
 #define SEQ_MAX_TREE 1024
@@ -107,8 +107,16 @@ int seq_tree_attn(const void* q, const void* k_cache, const void* v_cache,
  *   accepted_path  [n_tree] int32 out: accepted node ids from the root's child downwards,
  *                  every remaining entry -1
  *   bonus_token    [1] int32 out
- *   workspace      at least seq_verify_workspace(...) bytes; on return it starts with a trace
- *                  (see seq_verify_trace below) that tests and debuggers may read
+ *   workspace      DEVICE, 16-byte aligned, at least seq_verify_workspace(...) bytes; on return it
+ *                  starts with a trace (see below) that tests and debuggers may read; the rest
+ *                  is scratch whose contents are unspecified
+ *
+ * Two kernels sit behind this call and give the same results.  For sampling (T > 0) over a
+ * vocabulary of at most 32768 tokens, every node's accept thresholds are computed at once,
+ * one workgroup per node (all 2 * n_tree * vocab logits are read), and a short walk follows;
+ * otherwise only the rows of the nodes the walk visits are read, by workgroups that share the
+ * vocabulary.  Calls that overlap in time on one device (different streams) are not supported:
+ * both kernels use a per-device synchronisation area.
  */
 int seq_verify(const void* target_logits, const void* draft_logits,
                const int32_t* tree_tokens, const int32_t* parent, float temperature,

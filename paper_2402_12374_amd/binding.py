@@ -57,6 +57,8 @@ def lib() -> C.CDLL:
         l.seq_strerror.restype = C.c_char_p
         l.seq_strerror.argtypes = [C.c_int]
         l.seq_version.restype = C.c_int
+        l.seqtree_internal_copy_probe.restype = C.c_int
+        l.seqtree_internal_copy_probe.argtypes = [vp, vp, sz, vp]
         _lib = l
     return _lib
 

@@ -27,6 +27,7 @@ struct TreePlan {
 struct SyncArea {
     unsigned long long* verify_slots = nullptr;  // [2][kVerifyMaxGroups][kVerifySlotWords]
     uint32_t* verify_epoch = nullptr;            // [2] tag base of the next verify launch, poison flag
+    uint32_t* verify_arrivals = nullptr;         // [1] workgroups of a per-node verify launch that are done
     uint32_t* attn_counters = nullptr;           // [kAttnMaxCounters]
     // Measured once per device: do workgroups whose ids are congruent mod 8 share an XCD (one
     // L2)?  The attention kernel then keeps all key ranges of a unit on one XCD and can hand

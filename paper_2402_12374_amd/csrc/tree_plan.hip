@@ -2,6 +2,7 @@
 // The tree is fixed ahead of time (Sec. 3.1: the structure is found offline; Sec. 4.1
 // "Implementation Details": because it is known in advance the step can be captured as a
 // graph), so the plan is built once per tree shape and cached.
+#include <algorithm>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -159,9 +160,9 @@ int get_sync_area(SyncArea** out) {
     if (g_sync.capacity() < 64) g_sync.reserve(64);
     DeviceSync s;
     s.device = device;
-    // the exchange slots, then one 64-bit cell: tag epoch (low half), poison flag (high half)
+    // the exchange slots, then two 64-bit cells: tag epoch and poison flag; arrival counter
     const size_t slot_words = (size_t)2 * kVerifyMaxGroups * kVerifySlotWords;
-    const size_t slot_bytes = sizeof(unsigned long long) * (slot_words + 1);
+    const size_t slot_bytes = sizeof(unsigned long long) * (slot_words + 2);
     const size_t ctr_bytes = sizeof(uint32_t) * kAttnMaxCounters;
     bool ok = hipMalloc(&s.area.verify_slots, slot_bytes) == hipSuccess &&
               hipMalloc(&s.area.attn_counters, ctr_bytes) == hipSuccess &&
@@ -175,6 +176,7 @@ int get_sync_area(SyncArea** out) {
         return SEQ_ERR_HIP;
     }
     s.area.verify_epoch = reinterpret_cast<uint32_t*>(s.area.verify_slots + slot_words);
+    s.area.verify_arrivals = s.area.verify_epoch + 2;
     s.area.round_robin_xcds = probe_round_robin_xcds();
     g_sync.push_back(s);
     *out = &g_sync.back().area;
@@ -235,3 +237,23 @@ extern "C" const char* seq_strerror(int code) {
 }
 
 extern "C" int seq_version(void) { return 100; }
+
+// A plain copy of a known size: the yardstick the benchmark puts beside its kernels when HBM
+// traffic counters are collected, so that the counters' unit can be checked against bytes
+// that are known exactly (16 bytes per lane, grid-stride, `bytes` a multiple of 16).
+__global__ void __launch_bounds__(256) seq_copy_probe_kernel(const uint4* __restrict__ src,
+                                                             uint4* __restrict__ dst, size_t count) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256)
+        dst[i] = src[i];
+}
+
+extern "C" int seqtree_internal_copy_probe(const void* src, void* dst, size_t bytes, void* hip_stream) {
+    if (!src || !dst) return SEQ_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return SEQ_ERR_SHAPE;
+    const size_t count = bytes / 16;
+    const unsigned blocks = (unsigned)std::min<size_t>(8192, (count + 255) / 256);
+    hipLaunchKernelGGL(seq_copy_probe_kernel, dim3(blocks), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), static_cast<const uint4*>(src),
+                       static_cast<uint4*>(dst), count);
+    return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
+}

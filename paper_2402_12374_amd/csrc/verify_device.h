@@ -1,0 +1,277 @@
+// Device-side pieces shared by the two kernels behind seq_verify (internal): row loads, the
+// exponential, wavefront reductions, and the scalar state of Algorithm 2 (Sec. 3.2.1) at one
+// tree node.
+//
+// Residual and draft are never rewritten.  After j rejections at a node, with S the rejected
+// tokens (whose p and q registers are set to zero when they are rejected):
+//     D_j[x] = q[x] / massQ,   massQ = sum_x q[x]                       (or 1/(V-|S|) off S once
+//                                                                        massQ has reached 0)
+//     R_j[x] = max(p[x] - A q[x] - B, 0) / W
+// where A (resp. B) accumulates W / massQ (resp. W / (V-|S|)) at every rejection and W is the
+// vocabulary sum of the numerator.  This is the update R <- norm(max(R - D, 0)) unrolled: the
+// nested max(., 0) collapse because the subtracted amounts never decrease.  A rejection thus
+// costs one read-only pass over the vocabulary.
+#pragma once
+
+#include <cmath>
+
+#include "seq_internal.h"
+
+namespace seqtree {
+namespace verify {
+
+constexpr int kThreads = 1024;  // few, fat workgroups
+constexpr int kWaves = kThreads / 64;
+static_assert(kWaves <= 16, "the first wavefront folds the per-wave partials within one 16-lane row");
+
+struct VerifyParams {
+    const void* target;
+    const void* draft;
+    const int32_t* tokens;
+    const float* uniforms;
+    const int32_t* child_start;
+    const int32_t* child_list;
+    int32_t* path;
+    int32_t* bonus;
+    int32_t* trace;
+    unsigned long long* records;   // per-node kernel: child records, then node records
+    unsigned long long* slots;
+    uint32_t* epoch;
+    uint32_t* arrivals;
+    uint32_t spin_limit;
+    int n, V, W;
+    float inv_T;
+};
+
+// verify_chains.hip: every node's sibling chain in parallel, then the walk over the results.
+// Vocabularies up to kChainsMaxVocab; dtype SEQ_BF16 or SEQ_F32.
+constexpr int kChainsMaxVocab = 32768;
+void launch_verify_chains(const VerifyParams& p, int dtype, hipStream_t stream);
+
+template <typename LT> __device__ __forceinline__ float load_logit(const LT* row, int x);
+template <> __device__ __forceinline__ float load_logit<float>(const float* row, int x) { return row[x]; }
+template <> __device__ __forceinline__ float load_logit<uint16_t>(const uint16_t* row, int x) {
+    return __uint_as_float((uint32_t)row[x] << 16);
+}
+
+// EPT consecutive logits of one row starting at `base`, tempered; tokens past the vocabulary
+// read as -inf.  16-byte loads when the row start and EPT allow it.
+template <typename LT, int EPT>
+__device__ __forceinline__ void load_row_slice(const LT* row, int base, int V, float inv_T, bool vec_ok,
+                                               float* x) {
+    constexpr int kPerVec = 16 / (int)sizeof(LT);
+    if (vec_ok && base + EPT <= V) {
+#pragma unroll
+        for (int c = 0; c < EPT / kPerVec; ++c) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(row + base + c * kPerVec);
+            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if constexpr (sizeof(LT) == 2) {
+                    x[c * 8 + 2 * k] = __uint_as_float(w[k] << 16) * inv_T;
+                    x[c * 8 + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u) * inv_T;
+                } else {
+                    x[c * 4 + k] = __uint_as_float(w[k]) * inv_T;
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) x[e] = base + e < V ? load_logit<LT>(row, base + e) * inv_T : -INFINITY;
+    }
+}
+
+// e^x on the hardware base-2 exponential, with the rounding error of x * log2(e) carried into
+// the result (about 2 ulp for the x <= 0 this file feeds it); e^-inf = 0.
+__device__ __forceinline__ float exp_fast(float x) {
+    constexpr float kLog2e = 1.44269504088896341f;
+    constexpr float kLog2eLo = 1.92596299112661746e-8f;  // log2(e) - float(log2(e))
+    constexpr float kLn2 = 0.693147180559945309f;
+    const float hi = x * kLog2e;
+    const float lo = fmaf(x, kLog2e, -hi) + x * kLog2eLo;
+    const float e = __builtin_amdgcn_exp2f(hi);
+    return x == -INFINITY ? 0.f : fmaf(e, lo * kLn2, e);
+}
+
+__device__ __forceinline__ float prob_of(float scaled_logit, float m, float inv_z) {
+    return scaled_logit == -INFINITY ? 0.f : exp_fast(scaled_logit - m) * inv_z;
+}
+
+__device__ __forceinline__ float residual_of(float p, float q, float a, float b) {
+    return fmaxf(fmaf(-a, q, p) - b, 0.f);
+}
+
+// ---- wavefront reductions on the data-parallel-primitive path (no LDS round trips) -----------
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float lane_value(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+constexpr int kOpSum = 0, kOpMax = 1;
+template <int OP> __device__ __forceinline__ float combine(float a, float b) {
+    return OP == kOpSum ? a + b : fmaxf(a, b);
+}
+// every lane of a 16-lane row ends with the row's result
+template <int OP> __device__ __forceinline__ float row_reduce(float v) {
+    v = combine<OP>(v, dpp<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = combine<OP>(v, dpp<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = combine<OP>(v, dpp<0x141>(v));  // row_half_mirror
+    v = combine<OP>(v, dpp<0x140>(v));  // row_mirror
+    return v;
+}
+// wave-uniform result; all 64 lanes must be active
+template <int OP> __device__ __forceinline__ float wave_reduce(float v) {
+    v = row_reduce<OP>(v);
+    return combine<OP>(combine<OP>(lane_value(v, 0), lane_value(v, 16)),
+                       combine<OP>(lane_value(v, 32), lane_value(v, 48)));
+}
+
+// ---- Algorithm 2 at one node: the scalar state and its three moves ---------------------------
+struct NodeState {
+    double A, B, Wn, massQ, dA, dB;
+    float af, bf;
+    int n_rej, fallback, sums_valid;
+    int fallbacks, degenerate;   // event counts (for the trace)
+};
+
+__device__ __forceinline__ void node_begin(NodeState& st) {
+    st.A = st.B = 0.0;
+    st.Wn = st.massQ = 1.0;
+    st.af = st.bf = 0.f;
+    st.dA = st.dB = 0.0;
+    st.n_rej = 0;
+    st.fallback = 0;
+    st.sums_valid = 0;
+}
+
+// The result of the vocabulary pass that follows a rejection: the mass of the new residual's
+// numerator and the draft mass that is left.
+__device__ __forceinline__ void node_apply_pass(NodeState& st, double w_new, double q_new) {
+    if (w_new > 0.0) { st.Wn = w_new; st.sums_valid = 1; }
+    else { st.A -= st.dA; st.B -= st.dB; ++st.degenerate; st.sums_valid = 0; }  // R stays as it was
+    st.af = (float)st.A;
+    st.bf = (float)st.B;
+    st.massQ = q_new;
+    if (!st.fallback && !(q_new > 0.0)) { st.fallback = 1; ++st.fallbacks; }
+}
+
+// The accept test of one child, u < R[s] / D[s], kept free of divisions: the child is accepted
+// iff u * lhs < rhs, both sides products of two floats taken in fp64.  ps, qs: target and draft probability of the child's token; in_s: the token
+// was already rejected at this node (an earlier sibling carried it).
+struct ChildTest {
+    float lhs_w, lhs_q, rhs_r, rhs_m;   // lhs = lhs_w * lhs_q, rhs = rhs_r * rhs_m, products in fp64
+    __device__ __forceinline__ bool accepts(float u) const {
+        return (double)u * (double)lhs_w * (double)lhs_q < (double)rhs_r * (double)rhs_m;
+    }
+    // R[s] / D[s] as a float, for the trace (infinite where D[s] = 0 < R[s])
+    __device__ __forceinline__ float ratio() const {
+        if (lhs_w == 0.f) return rhs_r > 0.f ? INFINITY : 0.f;
+        return (rhs_r * rhs_m) / (lhs_w * lhs_q);
+    }
+};
+__device__ __forceinline__ ChildTest node_test_child(const NodeState& st, float ps, float qs, bool in_s, int V) {
+    const int left = V - st.n_rej;  // tokens not yet rejected
+    const float r_num = in_s ? 0.f : residual_of(ps, qs, st.af, st.bf);   // R[s] * W
+    ChildTest t;
+    // D[s]: q/massQ, or 1/left once the draft's support is exhausted, or 0 for a rejected token
+    if (in_s || (st.fallback ? left <= 0 : !(qs > 0.f))) {
+        t.lhs_w = 0.f; t.lhs_q = 1.f;
+        t.rhs_r = r_num > 0.f ? 1.f : 0.f; t.rhs_m = 1.f;    // D[s] = 0: accepted iff R[s] > 0
+    } else if (st.fallback) {
+        t.lhs_w = (float)st.Wn; t.lhs_q = 1.f;
+        t.rhs_r = r_num; t.rhs_m = (float)left;              // vocabularies stay far below 2^24
+    } else {
+        t.lhs_w = (float)st.Wn; t.lhs_q = qs;
+        t.rhs_r = r_num; t.rhs_m = (float)st.massQ;
+    }
+    return t;
+}
+
+// Rejection: R <- norm(max(R - D, 0)), then D[s] <- 0 (uniform over what is left once the draft
+// has no mass).  Only the coefficients move here; the pass over the vocabulary follows.
+__device__ __forceinline__ void node_reject_child(NodeState& st, bool in_s, int V) {
+    const int left = V - st.n_rej;
+    st.dA = 0.0;
+    st.dB = 0.0;
+    if (st.fallback) { if (left > 0) st.dB = (double)((float)st.Wn / (float)left); }
+    else st.dA = (double)((float)st.Wn / (float)st.massQ);
+    st.A += st.dA;
+    st.B += st.dB;
+    st.af = (float)st.A;
+    st.bf = (float)st.B;
+    if (!in_s) ++st.n_rej;
+}
+
+// Inverse CDF over 64 consecutive blocks of the vocabulary, one per lane of a wavefront: which
+// block holds the cumulative residual mass u * total?  `sw_f` is the mass of block `lane`
+// (0 for lanes past `blocks`).  All lanes return the same answer.
+struct BlockPick {
+    double total, before;   // total mass; mass of the blocks before the owner
+    int owner, forced;      // forced: rounding left no block above the goal; take the last token with mass
+};
+
+// Cross-lane moves of doubles and ints without LDS round trips.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_or_zero(double v) {   // lanes the move does not reach read 0
+    const long long bits = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)bits, CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), CTRL, ROW_MASK, 0xF, false);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+// inclusive prefix sum over the 64 lanes of a wavefront (all lanes active)
+__device__ __forceinline__ double wave_scan(double v) {
+    v += dpp_or_zero<0x111, 0xF>(v);   // row_shr:1
+    v += dpp_or_zero<0x112, 0xF>(v);   // row_shr:2
+    v += dpp_or_zero<0x114, 0xF>(v);   // row_shr:4
+    v += dpp_or_zero<0x118, 0xF>(v);   // row_shr:8
+    v += dpp_or_zero<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_or_zero<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+__device__ __forceinline__ double lane_value(double v, int lane) {   // lane: wave-uniform
+    const long long bits = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_readlane((int)bits, lane);
+    const int hi = __builtin_amdgcn_readlane((int)(bits >> 32), lane);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_int(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+__device__ __forceinline__ int wave_min(int v) {   // wave-uniform result; all lanes active
+    v = min(v, dpp_int<0xB1>(v));
+    v = min(v, dpp_int<0x4E>(v));
+    v = min(v, dpp_int<0x141>(v));
+    v = min(v, dpp_int<0x140>(v));
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+__device__ __forceinline__ int wave_max(int v) { return -wave_min(-v); }
+
+__device__ __forceinline__ BlockPick pick_block(float u0, float sw_f, int blocks) {
+    const double sw = (double)sw_f;
+    const double incl = wave_scan(sw);
+    BlockPick r;
+    r.total = lane_value(incl, 63);
+    const double goal = (double)u0 * r.total;
+    const unsigned long long hit = __ballot(sw > 0.0 && incl > goal);
+    const unsigned long long pos = __ballot(sw > 0.0);
+    r.forced = 0;
+    if (hit) r.owner = __ffsll((long long)hit) - 1;
+    else { r.forced = 1; r.owner = pos ? 63 - __clzll((long long)pos) : blocks - 1; }
+    r.before = lane_value(incl - sw, __builtin_amdgcn_readfirstlane(r.owner));
+    return r;
+}
+
+// Layout of the caller's workspace: the trace first (header, one record per accept test, four
+// floats about the bonus draw), then what the per-node kernel leaves for the final walk.
+constexpr size_t kTraceBytes =
+    sizeof(int32_t) * (SEQ_TRACE_HEADER_INTS + (size_t)SEQ_MAX_TREE * SEQ_TRACE_RECORD_WORDS + 4);
+constexpr size_t kTraceBytesPadded = (kTraceBytes + 255) / 256 * 256;
+constexpr int kChildRecordWords = 5;   // tagged words per child: the four factors of the test, events
+constexpr int kNodeRecordWords = 4;    // tagged words per node: bonus token, total mass, CDF below / above
+
+}  // namespace verify
+}  // namespace seqtree

@@ -16,49 +16,18 @@
 // workgroup.  A step costs two workgroup barriers and one exchange.  Waiting is bounded: a
 // workgroup that does not see its peers within `spin_limit` polls records status 1 in the trace
 // and leaves.
-//
-// Residual and draft are never rewritten.  After j rejections at a node, with S the rejected
-// tokens (whose p and q registers are set to zero when they are rejected):
-//     D_j[x] = q[x] / massQ,   massQ = sum_x q[x]                       (or 1/(V-|S|) off S once
-//                                                                        massQ has reached 0)
-//     R_j[x] = max(p[x] - A q[x] - B, 0) / W
-// where A (resp. B) accumulates W / massQ (resp. W / (V-|S|)) at every rejection and W is the
-// vocabulary sum of the numerator.  This is the update R <- norm(max(R - D, 0)) unrolled: the
-// nested max(., 0) collapse because the subtracted amounts never decrease.  A rejection thus
-// costs one read-only pass over registers and one exchange.
 #include <cmath>
 
 #include "seq_internal.h"
+#include "verify_device.h"
 
 namespace seqtree {
+using namespace verify;
+
+
+
 namespace {
 
-constexpr int kThreads = 1024;  // few, fat workgroups: an exchange costs more the more take part
-constexpr int kWaves = kThreads / 64;
-static_assert(kWaves <= 16, "the first wavefront folds the per-wave partials within one 16-lane row");
-
-struct VerifyParams {
-    const void* target;
-    const void* draft;
-    const int32_t* tokens;
-    const float* uniforms;
-    const int32_t* child_start;
-    const int32_t* child_list;
-    int32_t* path;
-    int32_t* bonus;
-    int32_t* trace;
-    unsigned long long* slots;
-    uint32_t* epoch;
-    uint32_t spin_limit;
-    int n, V, W;
-    float inv_T;
-};
-
-template <typename LT> __device__ __forceinline__ float load_logit(const LT* row, int x);
-template <> __device__ __forceinline__ float load_logit<float>(const float* row, int x) { return row[x]; }
-template <> __device__ __forceinline__ float load_logit<uint16_t>(const uint16_t* row, int x) {
-    return __uint_as_float((uint32_t)row[x] << 16);
-}
 
 __device__ __forceinline__ int wg_rank() { return (int)blockIdx.x; }
 
@@ -98,39 +67,10 @@ struct Shared {
     unsigned char child_dup[SEQ_MAX_TREE];  // child's token already carried by an earlier sibling
     // state of Algorithm 2 at the current node; written by thread 0 only, read after a barrier
     struct {
-        double A, B, Wn, massQ, dA, dB;
-        float af, bf;
-        int action, next, zero_token, ci, n_rej, fallback, sums_valid;
-        int n_dec, fallbacks, degenerate;
+        NodeState ns;
+        int action, next, zero_token, ci, n_dec;
     } st;
 };
-
-// ---- wavefront reductions on the data-parallel-primitive path (no LDS round trips) -----------
-template <int CTRL>
-__device__ __forceinline__ float dpp(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
-}
-__device__ __forceinline__ float lane_value(float v, int lane) {
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
-}
-constexpr int kOpSum = 0, kOpMax = 1;
-template <int OP> __device__ __forceinline__ float combine(float a, float b) {
-    return OP == kOpSum ? a + b : fmaxf(a, b);
-}
-// every lane of a 16-lane row ends with the row's result
-template <int OP> __device__ __forceinline__ float row_reduce(float v) {
-    v = combine<OP>(v, dpp<0xB1>(v));   // quad_perm [1,0,3,2]
-    v = combine<OP>(v, dpp<0x4E>(v));   // quad_perm [2,3,0,1]
-    v = combine<OP>(v, dpp<0x141>(v));  // row_half_mirror
-    v = combine<OP>(v, dpp<0x140>(v));  // row_mirror
-    return v;
-}
-// wave-uniform result; all 64 lanes must be active
-template <int OP> __device__ __forceinline__ float wave_reduce(float v) {
-    v = row_reduce<OP>(v);
-    return combine<OP>(combine<OP>(lane_value(v, 0), lane_value(v, 16)),
-                       combine<OP>(lane_value(v, 32), lane_value(v, 48)));
-}
 
 // All-to-all of K floats per workgroup, run by the first wavefront only.  mine[k] is this
 // workgroup's value; afterwards lane w of the wavefront holds workgroup w's values in got[]
@@ -201,53 +141,6 @@ __device__ __forceinline__ void stage_tree(const VerifyParams& p, Shared& sh) {
     if (threadIdx.x == 0) sh.child_start[p.n] = p.child_start[p.n];
 }
 
-// My EPT consecutive logits of one row, tempered; tokens past the vocabulary read as -inf.
-// 16-byte loads when the row start and EPT allow it.
-template <typename LT, int EPT>
-__device__ __forceinline__ void load_row_slice(const LT* row, int base, int V, float inv_T, bool vec_ok,
-                                               float (&x)[EPT]) {
-    constexpr int kPerVec = 16 / (int)sizeof(LT);
-    if (vec_ok && base + EPT <= V) {
-#pragma unroll
-        for (int c = 0; c < EPT / kPerVec; ++c) {
-            const uint4 raw = *reinterpret_cast<const uint4*>(row + base + c * kPerVec);
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if constexpr (sizeof(LT) == 2) {
-                    x[c * 8 + 2 * k] = __uint_as_float(w[k] << 16) * inv_T;
-                    x[c * 8 + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u) * inv_T;
-                } else {
-                    x[c * 4 + k] = __uint_as_float(w[k]) * inv_T;
-                }
-            }
-        }
-    } else {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) x[e] = base + e < V ? load_logit<LT>(row, base + e) * inv_T : -INFINITY;
-    }
-}
-
-// e^x on the hardware base-2 exponential, with the rounding error of x * log2(e) carried into
-// the result (about 2 ulp for the x <= 0 this file feeds it); e^-inf = 0.
-__device__ __forceinline__ float exp_fast(float x) {
-    constexpr float kLog2e = 1.44269504088896341f;
-    constexpr float kLog2eLo = 1.92596299112661746e-8f;  // log2(e) - float(log2(e))
-    constexpr float kLn2 = 0.693147180559945309f;
-    const float hi = x * kLog2e;
-    const float lo = fmaf(x, kLog2e, -hi) + x * kLog2eLo;
-    const float e = __builtin_amdgcn_exp2f(hi);
-    return x == -INFINITY ? 0.f : fmaf(e, lo * kLn2, e);
-}
-
-__device__ __forceinline__ float prob_of(float scaled_logit, float m, float inv_z) {
-    return scaled_logit == -INFINITY ? 0.f : exp_fast(scaled_logit - m) * inv_z;
-}
-
-__device__ __forceinline__ float residual_of(float p, float q, float a, float b) {
-    return fmaxf(fmaf(-a, q, p) - b, 0.f);
-}
-
 __device__ __forceinline__ void finish(const VerifyParams& p, int path_len, int n_dec, int status,
                                        int stop_node, int fallbacks, int degenerate) {
     if (wg_rank() != 0) return;
@@ -282,76 +175,31 @@ __device__ __forceinline__ void record(const VerifyParams& p, int n_dec, int nod
 // few dozen scalar operations; every other lane would only repeat it).  Applies the result of
 // the previous vocabulary pass if there was one, then tests the next child: accepted, or
 // rejected (a pass over the vocabulary is needed before the next test), or none is left.
-// The accept test u < (r/W) / (q/massQ) is evaluated as u * W * q < r * massQ: no division.
 __device__ void leader_step(const VerifyParams& p, Shared& sh, int c_begin, int c_end, int V,
                             bool have_pass, double w_new, double q_new) {
     auto& st = sh.st;
-    if (have_pass) {
-        if (w_new > 0.0) { st.Wn = w_new; st.sums_valid = 1; }
-        else { st.A -= st.dA; st.B -= st.dB; ++st.degenerate; st.sums_valid = 0; }  // R stays as it was
-        st.af = (float)st.A;
-        st.bf = (float)st.B;
-        st.massQ = q_new;
-        if (!st.fallback && !(q_new > 0.0)) { st.fallback = 1; ++st.fallbacks; }
-    }
+    if (have_pass) node_apply_pass(st.ns, w_new, q_new);
     if (st.ci == c_end) { st.action = kActExhausted; return; }
     const int k = st.ci - c_begin;
     const int c = sh.child_list[st.ci];
     const float u = sh.uniform[c];
     const bool in_s = sh.child_dup[k] != 0;
-    const float ps = sh.child_lt[k], qs = sh.child_ld[k];  // probabilities by now
-    const int left = V - st.n_rej;  // tokens not yet rejected
-    const float r_num = in_s ? 0.f : residual_of(ps, qs, st.af, st.bf);   // R[s] * W
-    // D[s]: q/massQ, or 1/left once the draft's support is exhausted, or 0 for a rejected token
-    bool accept;
-    float ratio;
-    if (in_s || (st.fallback ? left <= 0 : !(qs > 0.f))) {
-        accept = r_num > 0.f;
-        ratio = accept ? INFINITY : 0.f;
-    } else if (st.fallback) {
-        accept = (double)u * st.Wn < (double)r_num * (double)left;
-        ratio = r_num * (float)left / (float)st.Wn;
-    } else {
-        accept = (double)u * st.Wn * (double)qs < (double)r_num * st.massQ;
-        ratio = (r_num * (float)st.massQ) / ((float)st.Wn * qs);
-    }
-    record(p, st.n_dec, c, accept, ratio, u);
+    const ChildTest t = node_test_child(st.ns, sh.child_lt[k], sh.child_ld[k], in_s, V);  // probabilities by now
+    const bool accept = t.accepts(u);
+    record(p, st.n_dec, c, accept, t.ratio(), u);
     ++st.n_dec;
     if (accept) { st.action = kActAccepted; st.next = c; return; }
-    // rejected: R <- norm(max(R - D, 0)), then D[s] <- 0 (and the uniform fallback)
-    st.dA = 0.0;
-    st.dB = 0.0;
-    if (st.fallback) { if (left > 0) st.dB = (double)((float)st.Wn / (float)left); }
-    else st.dA = (double)((float)st.Wn / (float)st.massQ);
-    st.A += st.dA;
-    st.B += st.dB;
-    st.af = (float)st.A;
-    st.bf = (float)st.B;
+    node_reject_child(st.ns, in_s, V);
     st.zero_token = in_s ? -1 : sh.token[c];
-    if (!in_s) ++st.n_rej;
     ++st.ci;
     st.action = kActPass;
 }
 
 // First wavefront: which workgroup holds the token at cumulative residual mass u * total?
-// `sw` is the mass of workgroup `lane`.
+// `sw_f` is the mass of workgroup `lane`.
 __device__ __forceinline__ void find_bonus_owner(const VerifyParams& p, float u0, float sw_f, Shared& sh) {
-    const int lane = threadIdx.x;
-    const double sw = (double)sw_f;
-    double incl = sw;
-    for (int off = 1; off < 64; off <<= 1) {
-        const double t = __shfl_up(incl, off);
-        if (lane >= off) incl += t;
-    }
-    const double total = __shfl(incl, 63);
-    const double goal = (double)u0 * total;
-    const unsigned long long hit = __ballot(sw > 0.0 && incl > goal);
-    const unsigned long long pos = __ballot(sw > 0.0);
-    int owner, forced = 0;
-    if (hit) owner = __ffsll((long long)hit) - 1;
-    else { forced = 1; owner = pos ? 63 - __clzll((long long)pos) : p.W - 1; }
-    const double before = __shfl(incl - sw, owner);
-    if (lane == 0) { sh.bonus_d[0] = total; sh.bonus_d[1] = before; sh.bonus_i[0] = owner; sh.bonus_i[1] = forced; }
+    const BlockPick b = pick_block(u0, sw_f, p.W);
+    if (threadIdx.x == 0) { sh.bonus_d[0] = b.total; sh.bonus_d[1] = b.before; sh.bonus_i[0] = b.owner; sh.bonus_i[1] = b.forced; }
 }
 
 // Per-wavefront partials -> this workgroup's values, inside the first wavefront (lane w < kWaves
@@ -386,7 +234,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
     stage_tree(p, sh);
     uint32_t step = 0;
     int par = 0, v = 0, path_len = 0;
-    if (tid == 0) { sh.st.n_dec = 0; sh.st.fallbacks = 0; sh.st.degenerate = 0; }
+    if (tid == 0) { sh.st.n_dec = 0; sh.st.ns.fallbacks = 0; sh.st.ns.degenerate = 0; }
     __syncthreads();
 
     for (;;) {
@@ -458,8 +306,8 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
                 sh.fail = ok ? 0 : 1;
                 sh.stat[0] = mt; sh.stat[1] = md; sh.stat[2] = 1.0f / zt; sh.stat[3] = 1.0f / zd;
                 auto& st = sh.st;
-                st.A = st.B = 0.0; st.Wn = st.massQ = 1.0; st.af = st.bf = 0.f; st.dA = st.dB = 0.0;
-                st.ci = c_begin; st.n_rej = 0; st.fallback = 0; st.sums_valid = 0; st.next = -1;
+                node_begin(st.ns);
+                st.ci = c_begin; st.next = -1;
                 if (ok) leader_step(p, sh, c_begin, c_end, V, false, 0.0, 0.0);
             }
         } else {
@@ -468,7 +316,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
         par ^= 1;
         __syncthreads();
         SEQ_STAMP(4);
-        if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
+        if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.ns.fallbacks, sh.st.ns.degenerate); return; }
         {
             const float ft = mt_wave == -INFINITY ? 0.f : exp_fast(mt_wave - sh.stat[0]) * sh.stat[2];
             const float fd = md_wave == -INFINITY ? 0.f : exp_fast(md_wave - sh.stat[1]) * sh.stat[3];
@@ -479,7 +327,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
         // Algorithm 2 at node v: one vocabulary pass + exchange per rejection
         while (sh.st.action == kActPass) {
             const int zero_token = sh.st.zero_token;
-            const float af = sh.st.af, bf = sh.st.bf;
+            const float af = sh.st.ns.af, bf = sh.st.ns.bf;
             float r_loc = 0.f, q_loc = 0.f;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
@@ -504,7 +352,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
                     sh.fail = ok ? 0 : 1;
                     if (ok) leader_step(p, sh, c_begin, c_end, V, true, (double)w_new, (double)q_new);
                 }
-                if (ok && sh.st.action == kActExhausted && sh.st.sums_valid)
+                if (ok && sh.st.action == kActExhausted && sh.st.ns.sums_valid)
                     find_bonus_owner(p, sh.uniform[0], got[0], sh);
             } else {
                 ++step;
@@ -512,7 +360,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
             par ^= 1;
             __syncthreads();
             SEQ_STAMP(12);
-            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
+            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.ns.fallbacks, sh.st.ns.degenerate); return; }
         }
         if (sh.st.action == kActAccepted) {
             const int next = sh.st.next;
@@ -524,9 +372,9 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
         }
 
         // no child accepted: bonus token ~ R by inverse CDF with uniforms[0]
-        const float af = sh.st.af, bf = sh.st.bf;
+        const float af = sh.st.ns.af, bf = sh.st.ns.bf;
         const float u0 = sh.uniform[0];
-        if (!sh.st.sums_valid) {   // no pass has left the workgroups' residual masses yet
+        if (!sh.st.ns.sums_valid) {   // no pass has left the workgroups' residual masses yet
             float r_loc = 0.f;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) r_loc += residual_of(pr[e], qr[e], af, bf);
@@ -541,7 +389,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
                 if (ok) find_bonus_owner(p, u0, got[0], sh);
             }
             __syncthreads();
-            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
+            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.ns.fallbacks, sh.st.ns.degenerate); return; }
         }
         const double total = sh.bonus_d[0], before = sh.bonus_d[1];
         const double goal = (double)u0 * total;
@@ -554,11 +402,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
 #pragma unroll
             for (int e = 0; e < EPT; ++e) { r[e] = residual_of(pr[e], qr[e], af, bf); mine += (double)r[e]; }
             // exclusive prefix of the per-thread masses over the block
-            double incl = mine;
-            for (int off = 1; off < 64; off <<= 1) {
-                const double t = __shfl_up(incl, off);
-                if (lane >= off) incl += t;
-            }
+            const double incl = wave_scan(mine);
             if (lane == 63) sh.scan[wave] = incl;
             __syncthreads();
             double run = before + incl - mine;
@@ -573,11 +417,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
                 if (r[e] > 0.f) last_pos = base + e;
             }
             // one shared-memory atomic per wavefront, not per element
-            int wave_found = found, wave_last = last_pos;
-            for (int off = 32; off > 0; off >>= 1) {
-                wave_found = min(wave_found, __shfl_xor(wave_found, off));
-                wave_last = max(wave_last, __shfl_xor(wave_last, off));
-            }
+            const int wave_found = wave_min(found), wave_last = wave_max(last_pos);
             if (lane == 0) {
                 if (wave_found != 0x7FFFFFFF) atomicMin(&sh.cand_min, wave_found);
                 if (wave_last >= 0) atomicMax(&sh.cand_max, wave_last);
@@ -596,7 +436,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
             if (tid == 0) p.bonus[0] = pick;
         }
         SEQ_STAMP(20);
-        finish(p, path_len, sh.st.n_dec, 0, v, sh.st.fallbacks, sh.st.degenerate);
+        finish(p, path_len, sh.st.n_dec, 0, v, sh.st.ns.fallbacks, sh.st.ns.degenerate);
         return;
     }
 }
@@ -700,9 +540,6 @@ void launch_verify(const VerifyParams& p, bool greedy, int ept, hipStream_t stre
 #undef SEQ_LAUNCH
 }
 
-constexpr size_t kTraceBytes =
-    sizeof(int32_t) * (SEQ_TRACE_HEADER_INTS + (size_t)SEQ_MAX_TREE * SEQ_TRACE_RECORD_WORDS + 4);
-
 }  // namespace
 }  // namespace seqtree
 
@@ -718,10 +555,15 @@ extern "C" int seqtree_internal_read_stamps(long long* out) {
 }
 #endif
 extern "C" void seqtree_internal_set_spin_limit(uint32_t polls) { g_spin_limit = polls; }
+// Test hook: 0 = choose by vocabulary size, 1 = always the lazy walk, 2 = the per-node kernel
+// wherever the vocabulary allows it.
+static int g_verify_mode = 0;
+extern "C" void seqtree_internal_set_verify_mode(int mode) { g_verify_mode = mode; }
 
 extern "C" size_t seq_verify_workspace(int32_t n_tree, int32_t vocab, int32_t dtype) {
     (void)n_tree; (void)vocab; (void)dtype;
-    return (kTraceBytes + 255) / 256 * 256;
+    return kTraceBytesPadded +
+           sizeof(unsigned long long) * (size_t)SEQ_MAX_TREE * (kChildRecordWords + kNodeRecordWords);
 }
 
 extern "C" int seq_verify(const void* target_logits, const void* draft_logits,
@@ -737,7 +579,9 @@ extern "C" int seq_verify(const void* target_logits, const void* draft_logits,
     if (!(temperature >= 0.0f) || std::isinf(temperature)) return SEQ_ERR_TEMPERATURE;
     int rc = validate_parent(parent, n_tree);
     if (rc != SEQ_OK) return rc;
-    if (!workspace || workspace_bytes < seq_verify_workspace(n_tree, vocab, dtype)) return SEQ_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < seq_verify_workspace(n_tree, vocab, dtype) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 15) != 0)
+        return SEQ_ERR_WORKSPACE;
 
     TreePlan plan;
     rc = get_tree_plan(parent, n_tree, &plan);
@@ -758,6 +602,8 @@ extern "C" int seq_verify(const void* target_logits, const void* draft_logits,
     p.path = accepted_path;
     p.bonus = bonus_token;
     p.trace = static_cast<int32_t*>(workspace);
+    p.records = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + kTraceBytesPadded);
+    p.arrivals = sync->verify_arrivals;
     p.slots = sync->verify_slots;
     p.epoch = sync->verify_epoch;
     p.spin_limit = g_spin_limit;
@@ -767,6 +613,12 @@ extern "C" int seq_verify(const void* target_logits, const void* draft_logits,
     const bool greedy = temperature == 0.0f;
     p.inv_T = greedy ? 1.0f : 1.0f / temperature;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // Sampling with a vocabulary one workgroup can hold: all nodes at once.  Otherwise (and for
+    // greedy decoding, which needs one arg-max per visited node) the lazy walk.
+    if (!greedy && vocab <= kChainsMaxVocab && g_verify_mode != 1) {
+        launch_verify_chains(p, dtype, stream);
+        return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
+    }
     if (dtype == SEQ_BF16) launch_verify<uint16_t>(p, greedy, ept, stream);
     else launch_verify<float>(p, greedy, ept, stream);
     return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;

@@ -14,6 +14,15 @@ from gpu_util import DEV, check_verify, run_verify
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["auto", "lazy"])
+def kernel_choice(request):
+    """Every case runs twice: with the library's own choice of kernel (the per-node kernel
+    wherever temperature and vocabulary allow it) and with the lazy walk forced."""
+    S.lib().seqtree_internal_set_verify_mode(0 if request.param == "auto" else 1)
+    yield request.param
+    S.lib().seqtree_internal_set_verify_mode(0)
+
+
 def logits_of(p):
     with np.errstate(divide="ignore"):
         return np.log(np.asarray(p, np.float64)).astype(np.float32)
@@ -149,10 +158,30 @@ def test_outputs_are_deterministic_and_trace_ratios_match():
     assert np.array_equal(a[2]["ratios"], b[2]["ratios"])
 
 
-def test_bounded_wait_always_terminates():
+def test_both_kernels_leave_the_same_trace():
+    for key, rep in (("C2", 0), ("C2", 1), ("C3", 0), ("C4", 0)):
+        v = W.verify_inputs_for(key, rep=rep)
+        got = []
+        for mode in (2, 1):
+            S.lib().seqtree_internal_set_verify_mode(mode)
+            got.append(run_verify(v))
+        (pa, ba, ta), (pb, bb, tb) = got
+        # the two kernels sum the vocabulary in different orders: compare decisions, and ratios
+        # to rounding
+        assert np.array_equal(ta["nodes"], tb["nodes"]) and np.array_equal(ta["accepted"], tb["accepted"])
+        assert np.allclose(ta["ratios"], tb["ratios"], rtol=1e-5, atol=1e-7)
+        assert np.array_equal(pa, pb) and ta["stop_node"] == tb["stop_node"]
+        assert (ta["fallbacks"], ta["degenerate"]) == (tb["fallbacks"], tb["degenerate"])
+        if abs(ta["bonus_cdf_lo"] - ta["bonus_u"]) > 1e-5 and abs(ta["bonus_cdf_hi"] - ta["bonus_u"]) > 1e-5:
+            assert ba == bb
+
+
+def test_bounded_wait_always_terminates(kernel_choice):
     """Force the inter-workgroup wait to give up after a single poll: the kernel must still end
     normally and report status 1 (or succeed by luck).  After a timeout the library refuses
     further walks until seq_shutdown() has discarded its synchronisation area."""
+    if kernel_choice != "lazy":
+        pytest.skip("only the lazy walk waits for other workgroups")
     v = W.verify_inputs_for("C2")
     S.lib().seqtree_internal_set_spin_limit(0)
     try:
