@@ -32,6 +32,7 @@
 // log-sum-exp; no workgroup ever waits for another.
 #include <algorithm>
 #include <type_traits>
+#include <utility>
 
 #include "seq_internal.h"
 #include "tree_attn_kernels.h"
@@ -47,8 +48,7 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-constexpr int kWaves = 8;             // two wavefronts per SIMD: one computes while the other waits
-constexpr int kThreads = kWaves * 64;
+constexpr int kCells = 8;             // (row block, key group) cells of a workgroup
 constexpr int kRing = 8;              // tile buffers in the LDS ring
 constexpr int kMaxSplits = 16;
 
@@ -71,31 +71,41 @@ struct MfmaParams {
     int share_l2;         // all workgroups of a unit run on one XCD (checked once per device)
 };
 
-// 16 bytes per lane from global memory into LDS at lds_base + lane * 16 (lds_base uniform).
-__device__ __forceinline__ void async_copy16(const void* gptr, uint32_t lds_base) {
+// A pointer that is the same in every lane, moved to scalar registers whatever the compiler
+// believes about it.
+__device__ __forceinline__ const void* scalar_pointer(const void* p) {
+    const uint64_t bits = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)bits);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(bits >> 32));
+    return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
+}
+
+// 16 bytes per lane from global memory (uniform base + per-lane byte offset) into LDS at
+// lds_base + lane * 16 (lds_base uniform).
+__device__ __forceinline__ void async_copy16(uint32_t lane_offset, const void* base, uint32_t lds_base) {
     uint32_t saved;
     asm volatile(
         "s_mov_b32 %0, m0\n\t"
-        "s_mov_b32 m0, %2\n\t"
+        "s_mov_b32 m0, %3\n\t"
         "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %1, off\n\t"
+        "global_load_lds_dwordx4 %1, %2\n\t"
         "s_mov_b32 m0, %0"
         : "=&s"(saved)
-        : "v"(gptr), "s"(lds_base)
+        : "v"(lane_offset), "s"(scalar_pointer(base)), "s"(__builtin_amdgcn_readfirstlane(lds_base))
         : "memory");
 }
 
 // 4 bytes per lane into LDS at lds_base + lane * 4.
-__device__ __forceinline__ void async_copy4(const void* gptr, uint32_t lds_base) {
+__device__ __forceinline__ void async_copy4(uint32_t lane_offset, const void* base, uint32_t lds_base) {
     uint32_t saved;
     asm volatile(
         "s_mov_b32 %0, m0\n\t"
-        "s_mov_b32 m0, %2\n\t"
+        "s_mov_b32 m0, %3\n\t"
         "s_nop 0\n\t"
-        "global_load_lds_dword %1, off\n\t"
+        "global_load_lds_dword %1, %2\n\t"
         "s_mov_b32 m0, %0"
         : "=&s"(saved)
-        : "v"(gptr), "s"(lds_base)
+        : "v"(lane_offset), "s"(scalar_pointer(base)), "s"(__builtin_amdgcn_readfirstlane(lds_base))
         : "memory");
 }
 
@@ -133,7 +143,7 @@ struct Rings {
     static constexpr int kTileElems = kKeyTile * D;   // bf16 elements per K (or V) tile
     uint16_t k[kRing][kTileElems];
     uint16_t v[kRing][kTileElems];
-    uint32_t mask[kRing][kWaves][64];
+    uint32_t mask[kRing][kCells][64];
 };
 
 // Rows of the weight table of the epilogue: key groups of a workgroup, or key ranges of a unit.
@@ -141,7 +151,7 @@ template <int WQ> constexpr int fac_rows() { return WQ == 8 ? 8 : kMaxSplits; }
 
 template <int D, int WQ>
 constexpr size_t epilogue_bytes() {
-    return sizeof(float) * ((size_t)kWaves * (D / 32) * 4 * 256 + kWaves * 128 + (size_t)fac_rows<WQ>() * WQ * 64 + 2 * WQ * 64);
+    return sizeof(float) * ((size_t)kCells * (D / 32) * 4 * 256 + kCells * 128 + (size_t)fac_rows<WQ>() * WQ * 64 + 2 * WQ * 64);
 }
 
 template <int D, int WQ>
@@ -150,9 +160,80 @@ union Smem {
     char epilogue[epilogue_bytes<D, WQ>()];
 };
 
-template <int D, int WQ, int WK>
-__global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaParams p) {
-    static_assert(WQ * WK == kWaves, "wavefront grid");
+// ---- pieces of the tile loop shared by its two forms ---------------------------------------
+
+// lane ^ 32 exchange on the gfx950 lane-swap instruction (no LDS round trip): max / sum of a
+// value over the two halves of the wavefront, in every lane.
+__device__ __forceinline__ float halves_max(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// Replace the scores of invisible keys by -inf.  m: bit x <=> key x of the tile is visible to
+// the query of this lane; accumulator element x holds key (x/4)*8 + half*4 + x%4.
+__device__ __forceinline__ void mask_scores(f32x16_t& s, uint32_t m, int half) {
+    m >>= half * 4;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) s[x] = ((m >> ((x >> 2) * 8 + (x & 3))) & 1u) ? s[x] : -INFINITY;
+}
+
+// One step of the online softmax for one query column per lane: scores of 32 keys in, their
+// probabilities out (packed bf16, in the B-operand layout of the second product).
+//
+// m_run is the reference the exponentials are taken against, not necessarily the running
+// maximum: it only moves when a score exceeds it by more than kSlack (in log2 units), so that
+// probabilities stay below 2^kSlack and the output accumulated so far has to be rescaled
+// rarely -- after the first few tiles, almost never.  Numerator and normaliser share the
+// reference, so the quotient is unchanged.  Returns the rescale factor and whether this lane's
+// reference moved.
+constexpr float kSlack = 8.0f;
+__device__ __forceinline__ float softmax_step(const f32x16_t& s, float scale_log2, float& m_run, float& l_run,
+                                              uint32_t (&pw)[2][4], bool& moved) {
+    float mx = __builtin_fmaxf(__builtin_fmaxf(s[0], s[1]), s[2]);   // three-operand maxima
+#pragma unroll
+    for (int x = 3; x < 15; x += 2) mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[x]), s[x + 1]);
+    mx = fmaxf(mx, s[15]);
+    mx = halves_max(mx) * scale_log2;
+    moved = mx > m_run + kSlack || (m_run == -INFINITY && mx != -INFINITY);
+    const float m_new = moved ? mx : m_run;
+    const float ref = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = moved ? __builtin_amdgcn_exp2f(m_run - ref) : 1.0f;
+    m_run = m_new;
+    const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+    float psum = 0.f;
+#pragma unroll
+    for (int x = 0; x < 16; x += 2) {
+        f32x2_t e;
+        e[0] = __builtin_amdgcn_exp2f(fmaf(s[x], scale_log2, -ref));
+        e[1] = __builtin_amdgcn_exp2f(fmaf(s[x + 1], scale_log2, -ref));
+        const bf16x2_t pk = __builtin_convertvector(e, bf16x2_t);
+        pw[x >> 3][(x & 7) >> 1] = __builtin_bit_cast(uint32_t, pk);
+        psum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum, false);   // the normaliser sums what the product sees
+    }
+    l_run = l_run * alpha + psum;
+    return alpha;
+}
+
+template <int V> struct IntC { static constexpr int value = V; };
+
+// One workgroup = a unit of 32 * WQ query rows x a range of key tiles.  Its 8 (row block, key
+// group) cells -- WQ row blocks of 32 queries times WK key groups, each group taking every
+// WK-th tile of the range -- are spread over 8 / R wavefronts, R row blocks each:
+//   R = 1: eight wavefronts, two per SIMD; while one waits the other computes.
+//   R = 2: four wavefronts, one per SIMD with the whole register file.  A K or V fragment read
+//          from LDS then feeds two matrix instructions instead of one; with R = 1 the LDS port
+//          (128 bytes per clock) is busy exactly as long as the matrix cores, so neither can
+//          ever be saturated.  With nobody else on the SIMD to cover the softmax arithmetic,
+//          the tile loop is software-pipelined: the scores of tile t+1 are in the matrix cores
+//          while the exponentials of tile t are taken.
+template <int D, int WQ, int WK, int R, bool PIPE>
+__global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const MfmaParams p) {
+    static_assert(WQ * WK == kCells, "cell grid");
+    static_assert(R == 1 || (R == 2 && PIPE && WQ % 2 == 0), "two row blocks per wavefront need the pipelined loop");
+    static_assert(!PIPE || WK == 1, "the pipelined loop walks one tile per round");
+    constexpr int kW = kCells / R;         // wavefronts
+    constexpr int kT = kW * 64;            // threads
+    constexpr int WQW = WQ / R;            // wavefronts along the query axis
     constexpr int kKSteps = D / 16;        // contraction steps of Q K^T
     constexpr int kDBlocks = D / 32;       // 32-row blocks of O^T
     constexpr int kChunks = D / 8;         // 16-byte chunks per K/V row
@@ -160,13 +241,16 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
     constexpr int kRowsPerCopy = 64 / kChunks;               // rows one wave-wide copy covers
     constexpr int kCopiesPerTile = kKeyTile / kRowsPerCopy;  // per K (or V) tile
     constexpr int kCopiesPerRound = 2 * kCopiesPerTile * WK; // K and V of the WK tiles of a round
-    constexpr int kCopiesPerWave = kCopiesPerRound / kWaves;
-    constexpr int kLoadsPerRound = kCopiesPerWave + 1;       // + my visibility word
-    constexpr int kAheadRounds = kRing / WK - 1;             // rounds in flight beyond the current one
+    constexpr int kCopiesPerWave = kCopiesPerRound / kW;
+    constexpr int kLoadsPerRound = kCopiesPerWave + R;       // + my visibility words
+    // rounds in flight beyond the one being waited for; the pipelined loop reads K one tile
+    // ahead of V, which takes one more buffer out of the ring
+    constexpr int kAheadRounds = kRing / WK - (PIPE ? 2 : 1);
     constexpr int kUnitRows = 32 * WQ;
     constexpr uint32_t kTileBytes = kKeyTile * D * 2;
-    static_assert(kCopiesPerRound % kWaves == 0, "copies divide evenly among the wavefronts");
+    static_assert(kCopiesPerRound % kW == 0, "copies divide evenly among the wavefronts");
     static_assert(kAheadRounds >= 1, "ring too small");
+    static_assert(kAheadRounds * kLoadsPerRound <= 63, "vmcnt is a 6-bit counter");
     using SM = Smem<D, WQ>;
     __shared__ __attribute__((aligned(1024))) SM sm_union;
     Rings<D>& sm = sm_union.r;
@@ -184,29 +268,41 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
     const int units_per_xcd = (total_units + 7) >> 3;
     // Range-major within an XCD: the workgroups that run at the same time then mostly work on
     // the same key range of their head and find its tiles in L2.
-    const int split = idx / units_per_xcd, local = idx % units_per_xcd;
+    // (Integer division runs on the vector unit and leaves its result in a vector register even
+    // when every lane computes the same thing; everything derived from such a value would then
+    // be vector arithmetic, and every branch on it a divergent one.  So uniform values are moved
+    // back to scalar registers where they are born.)
+    const int split = __builtin_amdgcn_readfirstlane(idx / units_per_xcd);
+    const int local = __builtin_amdgcn_readfirstlane(idx % units_per_xcd);
     const int unit = xcd * units_per_xcd + local;
     if (split >= S || unit >= total_units) return;
-    const int g = unit / p.query_blocks, qb = unit % p.query_blocks;
+    const int g = __builtin_amdgcn_readfirstlane(unit / p.query_blocks);
+    const int qb = __builtin_amdgcn_readfirstlane(unit % p.query_blocks);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wq = wave % WQ, wk = wave / WQ;      // query block and key group of this wavefront
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and the compiler knows it
+    const int wqw = wave % WQW, wk = wave / WQW;   // place of this wavefront in the cell grid
     const int half = lane >> 5, col = lane & 31;
     const int rows = p.G * p.n;
-    const int row0 = qb * kUnitRows + wq * 32;
-    const bool blk_valid = row0 < rows;
-    const int qrow = row0 + col;
-    const bool qvalid = qrow < rows;
-    const int qi = qvalid ? qrow / p.G : 0;
-    const int qh = qvalid ? g * p.G + qrow % p.G : 0;
+    // my R row blocks: rb = wqw * R + r; cell = wk * WQ + rb
+    const bool blk_valid = qb * kUnitRows + wqw * R * 32 < rows;
+    bool qvalid[R];
+    int qi[R], qh[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int qrow = qb * kUnitRows + (wqw * R + r) * 32 + col;
+        qvalid[r] = qrow < rows;
+        qi[r] = qvalid[r] ? qrow / p.G : 0;
+        qh[r] = qvalid[r] ? g * p.G + qrow % p.G : 0;
+    }
 
     // key tiles of this workgroup
     const int last_row = min(rows - 1, qb * kUnitRows + kUnitRows - 1);
-    const int i_max = last_row / p.G;                 // tree rows beyond i_max are masked for all
+    const int i_max = __builtin_amdgcn_readfirstlane(last_row / p.G);   // tree rows beyond i_max are masked for all
     const int tree_tiles = i_max / kKeyTile + 1;
     const int total_tiles = p.prefix_tiles + tree_tiles;
-    const int t_begin = (int)((long long)total_tiles * split / S);
-    const int t_end = (int)((long long)total_tiles * (split + 1) / S);
+    const int t_begin = __builtin_amdgcn_readfirstlane((int)((long long)total_tiles * split / S));
+    const int t_end = __builtin_amdgcn_readfirstlane((int)((long long)total_tiles * (split + 1) / S));
     const int n_rounds = (t_end - t_begin + WK - 1) / WK;
 
     const uint32_t k_lds = lds_address(&sm.k[0][0]);
@@ -218,71 +314,86 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
     // below count them), so tiles past the end of the range and rows past the valid keys fetch
     // valid memory that is never used: the last valid row of the last tile.
     // What a copy of mine moves is fixed for the whole kernel (which tile of the round, K or V,
-    // which 1 KB block of the tile): its lane-dependent part is computed once, here.
-    int cp_tr[kCopiesPerWave], cp_row[kCopiesPerWave];
-    uint32_t cp_chunk[kCopiesPerWave], cp_dst[kCopiesPerWave];
-    const uint16_t* cp_prefix[kCopiesPerWave];   // address of my chunk in row 0 of cache tile 0
+    // which 1 KB block of the tile).  A copy's source is a uniform base, advanced by scalar
+    // arithmetic, plus a per-lane byte offset that for tiles inside the prefix never changes.
+    int cp_row[kCopiesPerWave];
+    uint32_t cp_lane_off[kCopiesPerWave];   // (row * D + swizzled chunk) * 2 bytes: prefix layout
+    uint32_t cp_chunk_bytes[kCopiesPerWave];
 #pragma unroll
     for (int c = 0; c < kCopiesPerWave; ++c) {
-        const int item = wave + c * kWaves;                   // (tile of the round, K|V, copy)
+        const int item = wave + c * kW;                       // (tile of the round, K|V, copy)
         const int is_v = (item / kCopiesPerTile) & 1, copy = item % kCopiesPerTile;
-        cp_tr[c] = item / (2 * kCopiesPerTile);
         cp_row[c] = copy * kRowsPerCopy + lane / kChunks;
         const int swz = is_v ? v_swizzle<D>(cp_row[c]) : k_swizzle<D>(cp_row[c]);
-        cp_chunk[c] = (uint32_t)(((lane % kChunks) ^ swz) * 8) | (is_v ? 0x80000000u : 0u);
-        cp_dst[c] = (is_v ? v_lds : k_lds) + (uint32_t)copy * 1024u;
-        cp_prefix[c] = (is_v ? p.v_cache : p.k_cache) + ((size_t)g * p.cap + cp_row[c]) * D + (cp_chunk[c] & 0xFFFFu);
+        cp_chunk_bytes[c] = (uint32_t)(((lane % kChunks) ^ swz) * 16);
+        cp_lane_off[c] = (uint32_t)cp_row[c] * kRowBytes + cp_chunk_bytes[c];
     }
-    auto issue_round = [&](int rho) {
+    uint32_t mask_lane_off[R];   // my query's row of the ancestor bitset
+#pragma unroll
+    for (int r = 0; r < R; ++r) mask_lane_off[r] = qvalid[r] ? (uint32_t)(qi[r] * p.words_per_row) * 4u : 0u;
+
+    // Issue the copies of round rho; slot = rho % (kRing / WK), a compile-time constant at every
+    // call site, fixes the ring buffers.
+    auto issue_round = [&](int rho, auto slot_c) __attribute__((always_inline)) {
+        constexpr int slot = decltype(slot_c)::value;
         const int j0 = rho * WK;
         const bool inside = (t_begin + j0 + WK) * kKeyTile <= p.P && t_begin + j0 + WK <= t_end;
 #pragma unroll
         for (int c = 0; c < kCopiesPerWave; ++c) {
-            const int j = j0 + cp_tr[c];
-            const uint32_t dst = cp_dst[c] + (uint32_t)(j % kRing) * kTileBytes;
-            const uint16_t* src;
+            const int item = wave + c * kW;
+            const int is_v = (item / kCopiesPerTile) & 1, copy = item % kCopiesPerTile;
+            const int tr = item / (2 * kCopiesPerTile);
+            const uint32_t dst = (is_v ? v_lds : k_lds) + (uint32_t)copy * 1024u + (uint32_t)(slot * WK + tr) * kTileBytes;
+            const int t = max(min(t_begin + j0 + tr, t_end - 1), 0);
             if (inside) {   // every tile of the round lies wholly inside the prefix
-                src = cp_prefix[c] + (size_t)(t_begin + j) * (kKeyTile * D);
+                const uint16_t* base = (is_v ? p.v_cache : p.k_cache) + ((size_t)g * p.cap + (size_t)t * kKeyTile) * D;
+                async_copy16(cp_lane_off[c], base, dst);
             } else {
-                const int t = max(min(t_begin + j, t_end - 1), 0);
                 const bool is_prefix = t < p.prefix_tiles;
-                const bool is_v = (cp_chunk[c] >> 31) != 0;
                 const int key0 = is_prefix ? t * kKeyTile : (t - p.prefix_tiles) * kKeyTile;
                 const int limit = is_prefix ? p.P : p.n;
                 const uint16_t* base = is_prefix ? (is_v ? p.v_cache : p.k_cache) + (size_t)g * p.cap * D
                                                  : (is_v ? p.v_tree : p.k_tree) + (size_t)g * D;
-                const size_t row_stride = is_prefix ? (size_t)D : (size_t)p.Hk * D;
+                const uint32_t row_bytes = is_prefix ? (uint32_t)kRowBytes : (uint32_t)(p.Hk * kRowBytes);
                 const int key = min(key0 + cp_row[c], limit - 1);
-                src = base + (size_t)key * row_stride + (cp_chunk[c] & 0xFFFFu);
+                async_copy16((uint32_t)key * row_bytes + cp_chunk_bytes[c], base, dst);
             }
-            async_copy16(src, __builtin_amdgcn_readfirstlane(dst));
         }
-        {   // visibility word of my query for my tile of this round (tree tiles only; else unused)
-            const int j = j0 + wk;
-            const int t = max(min(t_begin + j, t_end - 1), 0);
-            const int word = t - p.prefix_tiles;
-            const bool real = word >= 0 && qvalid && word < p.words_per_row;
-            const uint32_t* src = p.anc + (real ? (size_t)qi * p.words_per_row + word : 0);
-            async_copy4(src, __builtin_amdgcn_readfirstlane(m_lds + (uint32_t)(((j % kRing) * kWaves + wave) * 256)));
+        // visibility words of my queries for my tile of this round (used for tree tiles only)
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int t = max(min(t_begin + j0 + wk, t_end - 1), 0);
+            const int word = min(max(t - p.prefix_tiles, 0), p.words_per_row - 1);
+            const int cell = wk * WQ + wqw * R + r;
+            async_copy4(mask_lane_off[r], p.anc + word, m_lds + (uint32_t)(((slot * WK + wk) * kCells + cell) * 256));
         }
+    };
+    // rounds rho0 .. rho0 + count - 1, rho0 a multiple of kSlots, through a body that knows its slot
+    constexpr int kSlots = kRing / WK;
+    auto for_slots = [&](int rho0, int rho_end, auto&& body) __attribute__((always_inline)) {
+        [&]<int... Is>(std::integer_sequence<int, Is...>) __attribute__((always_inline)) {
+            (void)(((rho0 + Is < rho_end) ? (body(rho0 + Is, IntC<Is>{}), true) : false) && ...);
+        }(std::make_integer_sequence<int, kSlots>{});
     };
 
     // Q fragments (B operand): lane holds query `col`, features ks*16 + half*8 .. +7.  Requested
     // first, settled after the tile copies have been issued.
-    bf16x8_t qf[kKSteps];
-    {
-        const uint16_t* qp = p.q + ((size_t)qi * p.H + qh) * D + half * 8;
+    bf16x8_t qf[R][kKSteps];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint16_t* qp = p.q + ((size_t)qi[r] * p.H + qh[r]) * D + half * 8;
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (qvalid) v = *reinterpret_cast<const uint4*>(qp + ks * 16);
-            qf[ks] = __builtin_bit_cast(bf16x8_t, v);
+            if (qvalid[r]) v = *reinterpret_cast<const uint4*>(qp + ks * 16);
+            qf[r][ks] = __builtin_bit_cast(bf16x8_t, v);
         }
     }
 
-    // start the tile pipeline (a rolled loop: code that runs once is fetched cold, and slowly)
-#pragma unroll 1
-    for (int a = 0; a < kAheadRounds; ++a) issue_round(a);
+    // start the tile pipeline
+    constexpr int kPrologueRounds = kAheadRounds + (PIPE ? 1 : 0);
+    static_assert(kPrologueRounds <= kSlots, "prologue stays within one turn of the ring");
+    for_slots(0, kPrologueRounds, [&](int rho, auto slot_c) __attribute__((always_inline)) { issue_round(rho, slot_c); });
     ATTN_STAMP(1);
 
     // Make the compiler settle these loads here.  It cannot see the copies issued in assembly,
@@ -291,142 +402,196 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
     // count its wait exactly, is not an option: the compiler may move or reuse the destination
     // registers of a load it does not know to be in flight.)
 #pragma unroll
-    for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[r][ks]));
     ATTN_STAMP(2);
 
-    // Per-lane LDS byte offsets inside a tile, fixed for the whole kernel.  Everything else in
-    // an address is a compile-time constant that goes into the instruction's offset field.
+    // Per-lane LDS addresses of my fragments in ring buffer `wk` (my key group's tile of slot
+    // 0), fixed for the whole kernel; the slot and everything else in an address are
+    // compile-time constants that go into the instruction's offset field.
     //   K (ds_read_b128): key row `col`, chunk (2*ks + half) ^ swizzle
     //   V (transpose read): 16-lane group, lanes 4r..4r+3 address 16 features of key row r
+    typedef __attribute__((address_space(3))) const char* lds_cptr;
     const int grp = lane >> 4, li = lane & 15;
-    uint32_t koff[kKSteps], voff[kDBlocks];
+    lds_cptr kaddr[kKSteps], vaddr[kDBlocks];
 #pragma unroll
     for (int ks = 0; ks < kKSteps; ++ks)
-        koff[ks] = (uint32_t)(col * kRowBytes + (((ks * 2 + half) ^ k_swizzle<D>(col)) * 16));
+        kaddr[ks] = (lds_cptr)(lds_ptr_t)&sm.k[0][0] + wk * kTileBytes +
+                    (uint32_t)(col * kRowBytes + (((ks * 2 + half) ^ k_swizzle<D>(col)) * 16));
 #pragma unroll
     for (int b = 0; b < kDBlocks; ++b) {
         const int vrow = half * 4 + (li >> 2);                    // + (2m+a)*8, multiples of 8
         const int feat = b * 32 + (grp & 1) * 16 + (li & 3) * 4;  // 4 features = 8 bytes
-        voff[b] = (uint32_t)(vrow * kRowBytes + (((feat >> 3) ^ v_swizzle<D>(vrow)) * 16) + (feat & 7) * 2);
+        vaddr[b] = (lds_cptr)(lds_ptr_t)&sm.v[0][0] + wk * kTileBytes +
+                   (uint32_t)(vrow * kRowBytes + (((feat >> 3) ^ v_swizzle<D>(vrow)) * 16) + (feat & 7) * 2);
     }
-    typedef __attribute__((address_space(3))) const char* lds_cptr;
-    const lds_cptr k_base = (lds_cptr)(lds_ptr_t)&sm.k[0][0];
-    const lds_cptr v_base = (lds_cptr)(lds_ptr_t)&sm.v[0][0];
-
-    f32x16_t oacc[kDBlocks];
+    const __attribute__((address_space(3))) uint32_t* maddr[R];
 #pragma unroll
-    for (int b = 0; b < kDBlocks; ++b)
+    for (int r = 0; r < R; ++r)
+        maddr[r] = (const __attribute__((address_space(3))) uint32_t*)(lds_ptr_t)&sm.mask[wk][wk * WQ + wqw * R + r][col];
+
+    f32x16_t oacc[R][kDBlocks];
 #pragma unroll
-        for (int x = 0; x < 16; ++x) oacc[b][x] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int b = 0; b < kDBlocks; ++b)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) oacc[r][b][x] = 0.f;
+    float m_run[R], l_run[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) { m_run[r] = -INFINITY; l_run[r] = 0.f; }
 
-    for (int rho = 0; rho < n_rounds; ++rho) {
-        // my copies of this round have landed once at most the copies of the kAheadRounds - 1
-        // rounds issued after it are in flight (copies complete in order)
-        wait_vmcnt<(kAheadRounds - 1) * kLoadsPerRound>();
-        ATTN_STAMP(10);
-        __syncthreads();   // everybody's copies of this round are in LDS; the previous round's buffers are free
-        ATTN_STAMP(11);
-        issue_round(rho + kAheadRounds);
-        const int j = rho * WK + wk;
-        const int t = t_begin + j;
-        if (!blk_valid || t >= t_end) continue;
-        const int buf = j % kRing;
-        const lds_cptr kt = k_base + buf * kTileBytes;
-        const lds_cptr vt = v_base + buf * kTileBytes;
-
-        // S^T = K Q^T (32 keys x 32 queries): all K fragments are requested before the first
-        // matrix instruction, so that one LDS latency is paid per tile, not one per instruction
+    // S^T = K Q^T for my row blocks (32 keys x 32 queries each), tile in ring slot `slot`.  All
+    // K fragments are requested before the first matrix instruction: one LDS latency per tile.
+    auto scores = [&](auto slot_c, f32x16_t (&sacc)[R]) __attribute__((always_inline)) {
+        constexpr uint32_t kSlotBytes = decltype(slot_c)::value * WK * kTileBytes;
         bf16x8_t kf[kKSteps];
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks)
-            kf[ks] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(kt + koff[ks]);
-        __builtin_amdgcn_sched_barrier(0);
-        f32x16_t sacc;
+            kf[ks] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(kaddr[ks] + kSlotBytes);
+        if (!PIPE) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
-            if (ks == 0) {
-                f32x16_t zero;
 #pragma unroll
-                for (int x = 0; x < 16; ++x) zero[x] = 0.f;
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], zero, 0, 0, 0);
-            } else {
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
+            for (int r = 0; r < R; ++r) {
+                if (ks == 0) {
+                    f32x16_t zero;
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) zero[x] = 0.f;
+                    sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[r][ks], zero, 0, 0, 0);
+                } else {
+                    sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[r][ks], sacc[r], 0, 0, 0);
+                }
             }
         }
-        ATTN_STAMP(12);
-
-        // Tiles that lie wholly inside the prefix need no masking at all.
-        const bool full = t < p.prefix_tiles && (t + 1) * kKeyTile <= p.P;
-        if (!full) {
-            uint32_t m;   // bit x <=> key x of this tile is visible to my query
-            if (t < p.prefix_tiles) {
-                const int left = p.P - t * kKeyTile;
-                m = left >= 32 ? 0xFFFFFFFFu : (left <= 0 ? 0u : ((1u << left) - 1u));
-            } else {
-                const int word = t - p.prefix_tiles;
-                m = (qvalid && word < p.words_per_row) ? sm.mask[buf][wave][col] : 0u;
-            }
-            m >>= half * 4;
-#pragma unroll
-            for (int x = 0; x < 16; ++x)   // accumulator element x holds key (x/4)*8 + half*4 + x%4
-                sacc[x] = ((m >> ((x >> 2) * 8 + (x & 3))) & 1u) ? sacc[x] : -INFINITY;
-        }
-
-        // online softmax per query column (scores are scaled inside the exponential), and the
-        // probabilities packed as the B operand of the second product
-        uint32_t pw[2][4];
-        {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sacc[x]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run, mx * p.scale_log2);
-            const float ref = (m_new == -INFINITY) ? 0.f : m_new;
-            const bool moved = m_new != m_run;
-            const float alpha = __builtin_amdgcn_exp2f(m_run - ref);
-            m_run = m_new;
-            float psum = 0.f;
-#pragma unroll
-            for (int x = 0; x < 16; x += 2) {
-                f32x2_t e;
-                e[0] = __builtin_amdgcn_exp2f(fmaf(sacc[x], p.scale_log2, -ref));
-                e[1] = __builtin_amdgcn_exp2f(fmaf(sacc[x + 1], p.scale_log2, -ref));
-                psum += e[0] + e[1];
-                pw[x >> 3][(x & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(e, bf16x2_t));
-            }
-            l_run = l_run * alpha + psum;
-            if (__any(moved)) {   // the running maximum of some column changed: rescale the output
-#pragma unroll
-                for (int b = 0; b < kDBlocks; ++b)
-#pragma unroll
-                    for (int x = 0; x < 16; ++x) oacc[b][x] *= alpha;
-            }
-        }
-        ATTN_STAMP(13);
-
-        // O^T += V^T P^T.  Matrix step m contracts keys (2m+a)*8 + half*4 + 0..3, a = 0,1 -- the
-        // keys whose probabilities sit in accumulator elements 8m..8m+7.
+    };
+    // Visibility of the keys of tile t (ring slot `slot`) for the queries of this lane.
+    auto tile_is_full = [&](int t) __attribute__((always_inline)) { return t < p.prefix_tiles && (t + 1) * kKeyTile <= p.P; };
+    auto visibility = [&](int t, auto slot_c, int r) __attribute__((always_inline)) -> uint32_t {   // selects only, no branches
+        const int left = p.P - t * kKeyTile;
+        const uint32_t in_prefix = left >= 32 ? 0xFFFFFFFFu : (left <= 0 ? 0u : ((1u << left) - 1u));
+        const int word = t - p.prefix_tiles;
+        const uint32_t in_tree = maddr[r][decltype(slot_c)::value * WK * kCells * 64];
+        return t < p.prefix_tiles ? in_prefix : ((qvalid[r] && word < p.words_per_row) ? in_tree : 0u);
+    };
+    // O^T += V^T P^T.  Matrix step m contracts keys (2m+a)*8 + half*4 + 0..3, a = 0,1 -- the
+    // keys whose probabilities sit in accumulator elements 8m..8m+7.
+    auto weighted_values = [&](auto slot_c, const uint32_t (&pw)[R][2][4]) __attribute__((always_inline)) {
+        constexpr uint32_t kSlotBytes = decltype(slot_c)::value * WK * kTileBytes;
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
-            uint4 pq;
-            pq.x = pw[m][0]; pq.y = pw[m][1]; pq.z = pw[m][2]; pq.w = pw[m][3];
-            const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, pq);
+            bf16x8_t pf[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                uint4 pq;
+                pq.x = pw[r][m][0]; pq.y = pw[r][m][1]; pq.z = pw[r][m][2]; pq.w = pw[r][m][3];
+                pf[r] = __builtin_bit_cast(bf16x8_t, pq);
+            }
 #pragma unroll
             for (int b = 0; b < kDBlocks; ++b) {
                 v4i16 part[2];
 #pragma unroll
                 for (int a = 0; a < 2; ++a)
                     part[a] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (v4i16 __attribute__((address_space(3)))*)(vt + voff[b] + ((2 * m + a) * 8) * kRowBytes));
+                        (v4i16 __attribute__((address_space(3)))*)(vaddr[b] + kSlotBytes + ((2 * m + a) * 8) * kRowBytes));
                 uint4 vw;
                 vw.x = __builtin_bit_cast(uint2, part[0]).x;
                 vw.y = __builtin_bit_cast(uint2, part[0]).y;
                 vw.z = __builtin_bit_cast(uint2, part[1]).x;
                 vw.w = __builtin_bit_cast(uint2, part[1]).y;
-                oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vw), pf, oacc[b], 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    oacc[r][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vw), pf[r], oacc[r][b], 0, 0, 0);
             }
         }
+    };
+    auto rescale = [&](int r, float alpha) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < kDBlocks; ++b)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) oacc[r][b][x] *= alpha;
+    };
+
+    if constexpr (!PIPE) {
+        for (int rho0 = 0; rho0 < n_rounds; rho0 += kSlots) {
+            for_slots(rho0, n_rounds, [&](int rho, auto slot_c) __attribute__((always_inline)) {
+                constexpr int slot = decltype(slot_c)::value;
+                // my copies of this round have landed once at most the copies of the kAheadRounds - 1
+                // rounds issued after it are in flight (copies complete in order)
+                wait_vmcnt<(kAheadRounds - 1) * kLoadsPerRound>();
+                ATTN_STAMP(10);
+                __syncthreads();   // everybody's copies of this round are in LDS; the previous round's buffers are free
+                ATTN_STAMP(11);
+                issue_round(rho + kAheadRounds, IntC<(slot + kAheadRounds) % kSlots>{});
+                const int t = t_begin + rho * WK + wk;
+                if (!blk_valid || t >= t_end) return;
+                f32x16_t sacc[1];
+                scores(slot_c, sacc);
+                ATTN_STAMP(12);
+                if (!tile_is_full(t)) mask_scores(sacc[0], visibility(t, slot_c, 0), half);   // tiles inside the prefix need no mask
+                uint32_t pw[1][2][4];
+                bool moved;
+                const float alpha = softmax_step(sacc[0], p.scale_log2, m_run[0], l_run[0], pw[0], moved);
+                if (__any(moved)) rescale(0, alpha);   // the reference of some column moved
+                ATTN_STAMP(13);
+                weighted_values(slot_c, pw);
+            });
+        }
+    } else {
+        // Software pipeline over the tiles t_begin + rho (WK = 1): iteration rho waits for tile
+        // rho + 1, puts its score products into the matrix cores, and meanwhile turns the scores
+        // of tile rho into probabilities; then the second product of tile rho.  Two bodies, with
+        // and without the mask arithmetic, each free of branches between the score products and
+        // the exponentials, so that the compiler can interleave the two.
+        f32x16_t s_cur[R], s_next[R];
+        wait_vmcnt<kAheadRounds * kLoadsPerRound>();
+        __syncthreads();
+        if (blk_valid) scores(IntC<0>{}, s_cur);
+        auto iteration = [&](int rho, auto slot_c, auto masked) __attribute__((always_inline)) {
+            constexpr int slot = decltype(slot_c)::value;
+            wait_vmcnt<(kAheadRounds - 1) * kLoadsPerRound>();
+            __syncthreads();   // tile rho + 1 is in LDS; the buffer of tile rho - 1 is free
+            issue_round(rho + 1 + kAheadRounds, IntC<(slot + 1 + kAheadRounds) % kSlots>{});
+            if (!blk_valid) return;
+            const int t = t_begin + rho;
+            uint32_t pw[R][2][4];
+            float alpha[R];
+            bool moved[R];
+            // (after the last tile this multiplies a tile nobody needs: cheaper than a branch
+            // that would keep the products and the exponentials in separate blocks)
+            scores(IntC<(slot + 1) % kSlots>{}, s_next);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (decltype(masked)::value) mask_scores(s_cur[r], visibility(t, slot_c, r), half);
+                alpha[r] = softmax_step(s_cur[r], p.scale_log2, m_run[r], l_run[r], pw[r], moved[r]);
+            }
+            // issue order: the fragment reads, then one matrix instruction (32 clocks in the
+            // matrix pipe) followed by as much vector arithmetic as fits under it
+            __builtin_amdgcn_sched_group_barrier(0x100, kKSteps, 0);
+#pragma unroll
+            for (int i = 0; i < kKSteps * R; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (decltype(masked)::value ? 14 : 8) * (R == 1 ? 1 : 1), 0);
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (__any(moved[r])) rescale(r, alpha[r]);
+            weighted_values(slot_c, pw);
+#pragma unroll
+            for (int r = 0; r < R; ++r) s_cur[r] = s_next[r];
+        };
+        // Tiles wholly inside the prefix come first and need no mask arithmetic: a loop of their
+        // own (one loop with a branch per tile would let the compiler merge the common halves
+        // of the two bodies and lose the interleaving).  It ends on a multiple of the ring size;
+        // the few plain tiles left over go through the masked body with an all-ones mask.
+        const int full_tiles = p.P / kKeyTile;
+        const int n_plain = max(0, min(n_rounds, full_tiles - t_begin)) / kSlots * kSlots;
+        int rho0 = 0;
+        for (; rho0 < n_plain; rho0 += kSlots)
+            for_slots(rho0, n_plain, [&](int rho, auto slot_c) __attribute__((always_inline)) { iteration(rho, slot_c, std::false_type{}); });
+        for (; rho0 < n_rounds; rho0 += kSlots)
+            for_slots(rho0, n_rounds, [&](int rho, auto slot_c) __attribute__((always_inline)) { iteration(rho, slot_c, std::true_type{}); });
     }
     wait_vmcnt<0>();   // nothing of mine may still be landing in LDS when the ring is reused below
     ATTN_STAMP(20);
@@ -436,35 +601,37 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
     // loop that sits in the instruction cache, and for short key ranges the epilogue is most of
     // the kernel.  So every wavefront only drops its registers into LDS (a few wide stores) and
     // all merging -- of the key groups of the workgroup, and of the key ranges of the unit --
-    // is done by tight loops over LDS / the workspace with all 512 threads.
+    // is done by tight loops over LDS / the workspace with all threads.
     //
-    // LDS scratch (the tile rings, free by now):
-    //   o[wave][k4][lane][4]   unnormalised output; k4 = b*4 + rq holds features
+    // LDS scratch (the tile rings, free by now), indexed by cell = key group * WQ + row block:
+    //   o[cell][k4][lane][4]   unnormalised output; k4 = b*4 + rq holds features
     //                          b*32 + rq*8 + half*4 .. +3 of query (lane % 32), half = lane / 32
-    //   ml[wave][2][64]        running maximum and (per-lane part of the) normaliser
+    //   ml[cell][2][64]        running maximum and (per-lane part of the) normaliser
     //   fac[*][WQ][64], big_m / big_l [WQ][64]   weights and merged statistics
     constexpr int kK4 = kDBlocks * 4;
     __syncthreads();
     float* const lds_f = reinterpret_cast<float*>(&sm_union);
-    float* const o_s = lds_f;                                        // [kWaves][kK4][64][4]
-    float* const ml_s = o_s + (size_t)kWaves * kK4 * 256;            // [kWaves][2][64]
-    float* const fac_s = ml_s + kWaves * 128;                        // [fac_rows][WQ][64]
+    float* const o_s = lds_f;                                        // [kCells][kK4][64][4]
+    float* const ml_s = o_s + (size_t)kCells * kK4 * 256;            // [kCells][2][64]
+    float* const fac_s = ml_s + kCells * 128;                        // [fac_rows][WQ][64]
     float* const bigm_s = fac_s + (size_t)fac_rows<WQ>() * WQ * 64;  // [WQ][64]
     float* const bigl_s = bigm_s + WQ * 64;                          // [WQ][64]
     static_assert(WK <= fac_rows<WQ>(), "weight table too small");
-    {
-        float4* dst = reinterpret_cast<float4*>(o_s) + (size_t)wave * kK4 * 64 + lane;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int cell = wk * WQ + wqw * R + r;
+        float4* dst = reinterpret_cast<float4*>(o_s) + (size_t)cell * kK4 * 64 + lane;
 #pragma unroll
         for (int b = 0; b < kDBlocks; ++b)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq)
-                dst[(b * 4 + rq) * 64] = make_float4(oacc[b][rq * 4], oacc[b][rq * 4 + 1], oacc[b][rq * 4 + 2], oacc[b][rq * 4 + 3]);
-        ml_s[wave * 128 + lane] = m_run;
-        ml_s[wave * 128 + 64 + lane] = l_run;
+                dst[(b * 4 + rq) * 64] = make_float4(oacc[r][b][rq * 4], oacc[r][b][rq * 4 + 1], oacc[r][b][rq * 4 + 2], oacc[r][b][rq * 4 + 3]);
+        ml_s[cell * 128 + lane] = m_run[r];
+        ml_s[cell * 128 + 64 + lane] = l_run[r];
     }
     __syncthreads();
     // weights of the key groups: per (query block, lane)
-    for (int i = tid; i < WQ * 64; i += kThreads) {
+    for (int i = tid; i < WQ * 64; i += kT) {
         const int q = i >> 6, l = i & 63;
         float big = -INFINITY;
 #pragma unroll 1
@@ -485,7 +652,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
     const size_t block_words = (size_t)kK4 * 256 + 128;            // one (unit, range, query block)
     float* const my_part = p.partials + ((size_t)unit * S + split) * WQ * block_words;
     // 8-byte store of four consecutive output features of one query
-    auto store_out = [&](int q, int l, int k4, float4 acc, float inv) {
+    auto store_out = [&](int q, int l, int k4, float4 acc, float inv) __attribute__((always_inline)) {
         const int qr = qb * kUnitRows + q * 32 + (l & 31);
         if (qr >= rows) return;
         const int node = qr / p.G, head = g * p.G + qr % p.G;
@@ -498,7 +665,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
     };
     // merged output of the workgroup: straight to `out` (single range) or to the workspace
 #pragma unroll 1
-    for (int i = tid; i < WQ * kK4 * 64; i += kThreads) {
+    for (int i = tid; i < WQ * kK4 * 64; i += kT) {
         const int l = i & 63, k4 = (i >> 6) % kK4, q = i / (64 * kK4);
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 1
@@ -512,7 +679,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
         else reinterpret_cast<float4*>(my_part + (size_t)q * block_words)[k4 * 64 + l] = acc;
     }
     if (S == 1) return;
-    for (int i = tid; i < WQ * 64; i += kThreads) {
+    for (int i = tid; i < WQ * 64; i += kT) {
         float* ml = my_part + (size_t)(i >> 6) * block_words + (size_t)kK4 * 256;
         ml[i & 63] = bigm_s[i];
         ml[64 + (i & 63)] = bigl_s[i];
@@ -539,7 +706,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
 
     // merge the ranges of the unit: weights first, then the weighted sums
     const float* const unit_part = p.partials + (size_t)unit * S * WQ * block_words;
-    for (int i = tid; i < WQ * 64; i += kThreads) {
+    for (int i = tid; i < WQ * 64; i += kT) {
         const float* ml = unit_part + (size_t)(i >> 6) * block_words + (size_t)kK4 * 256 + (i & 63);
         float big = -INFINITY;
 #pragma unroll 4
@@ -556,7 +723,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
     }
     __syncthreads();
 #pragma unroll 1
-    for (int i = tid; i < WQ * kK4 * 64; i += kThreads) {
+    for (int i = tid; i < WQ * kK4 * 64; i += kT) {
         const int l = i & 63, k4 = (i >> 6) % kK4, q = i / (64 * kK4);
         const float4* src = reinterpret_cast<const float4*>(unit_part + (size_t)q * block_words) + k4 * 64 + l;
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -576,6 +743,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(const MfmaPara
 
 int g_splits_override = 0;  // tuning hooks, 0 = automatic
 int g_wq_override = 0;
+int g_row_blocks_override = 0;
 
 AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     AttnSchedule s;
@@ -587,7 +755,10 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     s.query_blocks = (rows + unit_rows - 1) / unit_rows;
     const int units = Hk * s.query_blocks;
     const int prefix_tiles = (P + kKeyTile - 1) / kKeyTile;
-    const int wk = kWaves / s.wq;
+    // eight row blocks per workgroup: two per wavefront, four fat wavefronts (see the kernel)
+    s.row_blocks = 1;
+    if (g_row_blocks_override > 0 && s.wq == 8) s.row_blocks = g_row_blocks_override;
+    const int wk = kCells / s.wq;
     // Key ranges per unit.  One workgroup fits on a CU at a time, so the launch runs in batches
     // of 256 workgroups; a range costs its rounds plus a fixed prologue/epilogue (about a dozen
     // rounds' worth, measured) plus the merge.  Take the cheapest count.
@@ -634,17 +805,21 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
     const int units = Hk * sched.query_blocks;
     if (units > kAttnMaxCounters) return SEQ_ERR_SHAPE;
     const int unit_groups = (units + 7) / 8;
-    const dim3 grid((unsigned)(unit_groups * 8 * sched.splits)), block(kThreads);
-#define SEQ_ATTN_LAUNCH(DD, WQ_)                                                                  \
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<DD, WQ_, kWaves / WQ_>), grid, block, 0, stream, p)
+    const dim3 grid((unsigned)(unit_groups * 8 * sched.splits)), block((unsigned)(sched.row_blocks == 2 ? 256 : 512));
+#define SEQ_ATTN_LAUNCH(DD, WQ_, R_, PIPE_)                                                       \
+    hipLaunchKernelGGL((tree_attn_mfma_kernel<DD, WQ_, kCells / WQ_, R_, PIPE_>), grid, block, 0, stream, p)
     if (D == 64) {
-        if (sched.wq == 2) SEQ_ATTN_LAUNCH(64, 2);
-        else if (sched.wq == 4) SEQ_ATTN_LAUNCH(64, 4);
-        else SEQ_ATTN_LAUNCH(64, 8);
+        if (sched.wq == 2) SEQ_ATTN_LAUNCH(64, 2, 1, false);
+        else if (sched.wq == 4) SEQ_ATTN_LAUNCH(64, 4, 1, false);
+        else if (sched.row_blocks == 2) SEQ_ATTN_LAUNCH(64, 8, 2, true);
+        else if (sched.row_blocks == 3) SEQ_ATTN_LAUNCH(64, 8, 1, false);
+        else SEQ_ATTN_LAUNCH(64, 8, 1, true);
     } else {
-        if (sched.wq == 2) SEQ_ATTN_LAUNCH(128, 2);
-        else if (sched.wq == 4) SEQ_ATTN_LAUNCH(128, 4);
-        else SEQ_ATTN_LAUNCH(128, 8);
+        if (sched.wq == 2) SEQ_ATTN_LAUNCH(128, 2, 1, false);
+        else if (sched.wq == 4) SEQ_ATTN_LAUNCH(128, 4, 1, false);
+        else if (sched.row_blocks == 2) SEQ_ATTN_LAUNCH(128, 8, 2, true);
+        else if (sched.row_blocks == 3) SEQ_ATTN_LAUNCH(128, 8, 1, false);
+        else SEQ_ATTN_LAUNCH(128, 8, 1, true);
     }
 #undef SEQ_ATTN_LAUNCH
     return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
@@ -664,3 +839,4 @@ extern "C" int seqtree_internal_read_attn_stamps(long long* out) {
 #endif
 extern "C" void seqtree_internal_set_attn_splits(int splits) { seqtree::g_splits_override = splits; }
 extern "C" void seqtree_internal_set_attn_wq(int wq) { seqtree::g_wq_override = wq; }
+extern "C" void seqtree_internal_set_attn_row_blocks(int r) { seqtree::g_row_blocks_override = r; }
