@@ -16,7 +16,6 @@ int launch_tree_attn_rowwise_f32(const float* q, const float* k_cache, const flo
 // 32-key tiles whose partial results are merged by the last workgroup to finish.
 struct AttnSchedule {
     int wq;             // query blocks per workgroup: 2, 4 or 8
-    int row_blocks;     // query blocks per wavefront: 1 (eight wavefronts) or 2 (four)
     int query_blocks;   // units per KV head
     int splits;
     size_t workspace_bytes;

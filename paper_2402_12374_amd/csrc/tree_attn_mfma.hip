@@ -1,16 +1,19 @@
 // bf16 tree attention on the gfx950 matrix cores.
 //
-// Work split.  A "unit" is a block of 128*R query rows of one KV head -- a query row is a
+// Work split.  A "unit" is a block of 32 * WQ query rows of one KV head -- a query row is a
 // (tree token i, head hh of the group) pair, numbered rho = i * G + hh -- and one workgroup of
-// four wavefronts owns a unit together with a contiguous range of 64-key tiles of the key axis
-// [cache rows 0..P) ++ [tree rows 0..n).  Each wavefront keeps R blocks of 32 query rows
-// (R = 2 when a KV head has many query rows, which halves the LDS traffic per matrix
-// instruction; R = 1 otherwise).
+// eight wavefronts owns a unit together with a contiguous range of 32-key tiles of the key axis
+// [cache rows 0..P) ++ [tree rows 0..n).  The wavefronts form a WQ x WK grid (WQ * WK = 8):
+// wavefront (wq, wk) keeps 32 query rows and takes every WK-th tile of the range.  Few query
+// rows per KV head (small trees, no grouped heads): few row blocks, several key groups.
 //
 // Data path.  K and V tiles go from global memory straight into LDS (global_load_lds_dwordx4,
 // 16 bytes per lane, no register staging) into a ring of kStages tile buffers, several tiles
 // ahead of the one being consumed, so that the HBM/L2 latency of a tile is covered by the work
-// on the tiles before it.  Both tiles are stored row-major; 16-byte chunks are XOR-swizzled
+// on the tiles before it.  A copy's source is a scalar base (advanced by scalar arithmetic) plus
+// a per-lane offset that never changes while the range is inside the prefix; the ring slot of
+// every access is a compile-time constant (the tile loop is unrolled over the ring), so LDS
+// addresses are one register plus an immediate.  Both tiles are stored row-major; 16-byte chunks are XOR-swizzled
 // within their row (the LDS slot is fixed by the lane, so the swizzle is applied to the global
 // address each lane fetches) so that the reads below are free of bank conflicts:
 //   K is read as the A operand of S^T = K Q^T with ds_read_b128 (a lane = a key, 8 features);
@@ -48,7 +51,7 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-constexpr int kCells = 8;             // (row block, key group) cells of a workgroup
+constexpr int kMaxCells = 8;          // (row block, key group) cells = wavefronts of a workgroup
 constexpr int kRing = 8;              // tile buffers in the LDS ring
 constexpr int kMaxSplits = 16;
 
@@ -138,7 +141,7 @@ __device__ int g_attn_stamp_count;
 
 // LDS: a ring of kRing tile buffers (K and V of 32 keys each), and a ring of visibility words.
 // After the last tile the K ring is reused to merge the key groups of the workgroup.
-template <int D>
+template <int D, int kCells>
 struct Rings {
     static constexpr int kTileElems = kKeyTile * D;   // bf16 elements per K (or V) tile
     uint16_t k[kRing][kTileElems];
@@ -147,17 +150,18 @@ struct Rings {
 };
 
 // Rows of the weight table of the epilogue: key groups of a workgroup, or key ranges of a unit.
-template <int WQ> constexpr int fac_rows() { return WQ == 8 ? 8 : kMaxSplits; }
+template <int WQ> constexpr int fac_rows() { return WQ >= 8 ? 8 : kMaxSplits; }
 
-template <int D, int WQ>
+template <int D, int WQ, int kCells>
 constexpr size_t epilogue_bytes() {
-    return sizeof(float) * ((size_t)kCells * (D / 32) * 4 * 256 + kCells * 128 + (size_t)fac_rows<WQ>() * WQ * 64 + 2 * WQ * 64);
+    // (with a single key group, kCells == WQ, the accumulators never pass through LDS)
+    return sizeof(float) * ((kCells == WQ ? 0 : (size_t)kCells * (D / 32) * 4 * 256 + kCells * 128) + (size_t)fac_rows<WQ>() * WQ * 64 + 2 * WQ * 64);
 }
 
-template <int D, int WQ>
+template <int D, int WQ, int kCells>
 union Smem {
-    Rings<D> r;
-    char epilogue[epilogue_bytes<D, WQ>()];
+    Rings<D, kCells> r;
+    char epilogue[epilogue_bytes<D, WQ, kCells>()];
 };
 
 // ---- pieces of the tile loop shared by its two forms ---------------------------------------
@@ -184,11 +188,31 @@ __device__ __forceinline__ void mask_scores(f32x16_t& s, uint32_t m, int half) {
 // maximum: it only moves when a score exceeds it by more than kSlack (in log2 units), so that
 // probabilities stay below 2^kSlack and the output accumulated so far has to be rescaled
 // rarely -- after the first few tiles, almost never.  Numerator and normaliser share the
-// reference, so the quotient is unchanged.  Returns the rescale factor and whether this lane's
-// reference moved.
+// reference, so the quotient is unchanged.
+//
+// The step comes in two halves of about equal cost, so that a wavefront may take them on either
+// side of a workgroup barrier: the first finds the reference and turns keys 0..15 of the tile
+// (accumulator elements 0..7) into probabilities, the second does keys 16..31 and closes the
+// normaliser.  `alpha` is the factor the output accumulated so far has to be scaled by (1 unless
+// `moved`).
 constexpr float kSlack = 8.0f;
-__device__ __forceinline__ float softmax_step(const f32x16_t& s, float scale_log2, float& m_run, float& l_run,
-                                              uint32_t (&pw)[2][4], bool& moved) {
+struct SoftmaxCarry {
+    float ref, alpha, psum;
+};
+__device__ __forceinline__ void softmax_pack8(const f32x16_t& s, int x0, float scale_log2, float ref, uint32_t (&pw)[4], float& psum) {
+    const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int x = 0; x < 8; x += 2) {
+        f32x2_t e;
+        e[0] = __builtin_amdgcn_exp2f(fmaf(s[x0 + x], scale_log2, -ref));
+        e[1] = __builtin_amdgcn_exp2f(fmaf(s[x0 + x + 1], scale_log2, -ref));
+        const bf16x2_t pk = __builtin_convertvector(e, bf16x2_t);
+        pw[x >> 1] = __builtin_bit_cast(uint32_t, pk);
+        psum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum, false);   // the normaliser sums what the product sees
+    }
+}
+__device__ __forceinline__ SoftmaxCarry softmax_first(const f32x16_t& s, float scale_log2, float& m_run,
+                                                      uint32_t (&pw)[2][4], bool& moved) {
     float mx = __builtin_fmaxf(__builtin_fmaxf(s[0], s[1]), s[2]);   // three-operand maxima
 #pragma unroll
     for (int x = 3; x < 15; x += 2) mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[x]), s[x + 1]);
@@ -196,42 +220,42 @@ __device__ __forceinline__ float softmax_step(const f32x16_t& s, float scale_log
     mx = halves_max(mx) * scale_log2;
     moved = mx > m_run + kSlack || (m_run == -INFINITY && mx != -INFINITY);
     const float m_new = moved ? mx : m_run;
-    const float ref = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = moved ? __builtin_amdgcn_exp2f(m_run - ref) : 1.0f;
+    SoftmaxCarry c;
+    c.ref = (m_new == -INFINITY) ? 0.f : m_new;
+    c.alpha = moved ? __builtin_amdgcn_exp2f(m_run - c.ref) : 1.0f;
+    c.psum = 0.f;
     m_run = m_new;
-    const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
-    float psum = 0.f;
-#pragma unroll
-    for (int x = 0; x < 16; x += 2) {
-        f32x2_t e;
-        e[0] = __builtin_amdgcn_exp2f(fmaf(s[x], scale_log2, -ref));
-        e[1] = __builtin_amdgcn_exp2f(fmaf(s[x + 1], scale_log2, -ref));
-        const bf16x2_t pk = __builtin_convertvector(e, bf16x2_t);
-        pw[x >> 3][(x & 7) >> 1] = __builtin_bit_cast(uint32_t, pk);
-        psum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum, false);   // the normaliser sums what the product sees
-    }
-    l_run = l_run * alpha + psum;
-    return alpha;
+    softmax_pack8(s, 0, scale_log2, c.ref, pw[0], c.psum);
+    return c;
+}
+__device__ __forceinline__ void softmax_second(const f32x16_t& s, float scale_log2, SoftmaxCarry c, float& l_run,
+                                               uint32_t (&pw)[2][4]) {
+    softmax_pack8(s, 8, scale_log2, c.ref, pw[1], c.psum);
+    l_run = l_run * c.alpha + c.psum;
 }
 
 template <int V> struct IntC { static constexpr int value = V; };
 
-// One workgroup = a unit of 32 * WQ query rows x a range of key tiles.  Its 8 (row block, key
-// group) cells -- WQ row blocks of 32 queries times WK key groups, each group taking every
-// WK-th tile of the range -- are spread over 8 / R wavefronts, R row blocks each:
-//   R = 1: eight wavefronts, two per SIMD; while one waits the other computes.
-//   R = 2: four wavefronts, one per SIMD with the whole register file.  A K or V fragment read
-//          from LDS then feeds two matrix instructions instead of one; with R = 1 the LDS port
-//          (128 bytes per clock) is busy exactly as long as the matrix cores, so neither can
-//          ever be saturated.  With nobody else on the SIMD to cover the softmax arithmetic,
-//          the tile loop is software-pipelined: the scores of tile t+1 are in the matrix cores
-//          while the exponentials of tile t are taken.
-template <int D, int WQ, int WK, int R, bool PIPE>
-__global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const MfmaParams p) {
-    static_assert(WQ * WK == kCells, "cell grid");
-    static_assert(R == 1 || (R == 2 && PIPE && WQ % 2 == 0), "two row blocks per wavefront need the pipelined loop");
-    static_assert(!PIPE || WK == 1, "the pipelined loop walks one tile per round");
-    constexpr int kW = kCells / R;         // wavefronts
+// One workgroup = a unit of 32 * WQ query rows x a range of key tiles; wavefront w is cell
+// (row block w % WQ, key group w / WQ) of its WQ x WK grid.
+//
+// What bounds the tile loop at large trees (measured with the SQ counters): per tile and
+// wavefront, 16 matrix instructions (512 clocks of the SIMD's matrix pipe) stand against about
+// 100 vector instructions (16 of them exponentials at half rate: about 490 clocks), and the two
+// wavefronts of a SIMD leave every barrier in step, so the two units mostly take turns.  Vector
+// work that is not softmax arithmetic is therefore kept out of the loop: addresses are scalar
+// or immediate, row sums ride on dot2 instructions, the output is rescaled only when a score
+// outgrows the reference by 2^8.  (Tried and slower here: two row blocks per wavefront in four
+// fat wavefronts -- halves the LDS traffic, but the accumulators no longer fit the vector
+// registers and travel through AGPR moves; twelve wavefronts; splitting a tile's work into a
+// matrix phase and a vector phase with a barrier each, or rotating the loop of wavefronts 4..7
+// by half a tile.)
+template <int D, int WQ, int WK>
+__global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const MfmaParams p) {
+    constexpr int kCells = WQ * WK;
+    constexpr int R = 1;   // row blocks per wavefront (the loops below are written for R of them)
+    static_assert(kCells == 8 && R == 1, "cell grid");
+        constexpr int kW = kCells / R;         // wavefronts
     constexpr int kT = kW * 64;            // threads
     constexpr int WQW = WQ / R;            // wavefronts along the query axis
     constexpr int kKSteps = D / 16;        // contraction steps of Q K^T
@@ -243,17 +267,15 @@ __global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const M
     constexpr int kCopiesPerRound = 2 * kCopiesPerTile * WK; // K and V of the WK tiles of a round
     constexpr int kCopiesPerWave = kCopiesPerRound / kW;
     constexpr int kLoadsPerRound = kCopiesPerWave + R;       // + my visibility words
-    // rounds in flight beyond the one being waited for; the pipelined loop reads K one tile
-    // ahead of V, which takes one more buffer out of the ring
-    constexpr int kAheadRounds = kRing / WK - (PIPE ? 2 : 1);
+    static_assert(kCopiesPerRound % kW == 0, "copies divide evenly among the wavefronts");
+    constexpr int kAheadRounds = kRing / WK - 1;             // rounds in flight beyond the one being waited for
     constexpr int kUnitRows = 32 * WQ;
     constexpr uint32_t kTileBytes = kKeyTile * D * 2;
-    static_assert(kCopiesPerRound % kW == 0, "copies divide evenly among the wavefronts");
     static_assert(kAheadRounds >= 1, "ring too small");
     static_assert(kAheadRounds * kLoadsPerRound <= 63, "vmcnt is a 6-bit counter");
-    using SM = Smem<D, WQ>;
+    using SM = Smem<D, WQ, kCells>;
     __shared__ __attribute__((aligned(1024))) SM sm_union;
-    Rings<D>& sm = sm_union.r;
+    Rings<D, kCells>& sm = sm_union.r;
     __shared__ int s_last;
 
     ATTN_STAMP_RESET();
@@ -391,9 +413,7 @@ __global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const M
     }
 
     // start the tile pipeline
-    constexpr int kPrologueRounds = kAheadRounds + (PIPE ? 1 : 0);
-    static_assert(kPrologueRounds <= kSlots, "prologue stays within one turn of the ring");
-    for_slots(0, kPrologueRounds, [&](int rho, auto slot_c) __attribute__((always_inline)) { issue_round(rho, slot_c); });
+    for_slots(0, kAheadRounds, [&](int rho, auto slot_c) __attribute__((always_inline)) { issue_round(rho, slot_c); });
     ATTN_STAMP(1);
 
     // Make the compiler settle these loads here.  It cannot see the copies issued in assembly,
@@ -450,7 +470,7 @@ __global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const M
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks)
             kf[ks] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(kaddr[ks] + kSlotBytes);
-        if (!PIPE) __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
 #pragma unroll
@@ -513,7 +533,7 @@ __global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const M
             for (int x = 0; x < 16; ++x) oacc[r][b][x] *= alpha;
     };
 
-    if constexpr (!PIPE) {
+    {
         for (int rho0 = 0; rho0 < n_rounds; rho0 += kSlots) {
             for_slots(rho0, n_rounds, [&](int rho, auto slot_c) __attribute__((always_inline)) {
                 constexpr int slot = decltype(slot_c)::value;
@@ -532,66 +552,13 @@ __global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const M
                 if (!tile_is_full(t)) mask_scores(sacc[0], visibility(t, slot_c, 0), half);   // tiles inside the prefix need no mask
                 uint32_t pw[1][2][4];
                 bool moved;
-                const float alpha = softmax_step(sacc[0], p.scale_log2, m_run[0], l_run[0], pw[0], moved);
-                if (__any(moved)) rescale(0, alpha);   // the reference of some column moved
+                const SoftmaxCarry c = softmax_first(sacc[0], p.scale_log2, m_run[0], pw[0], moved);
+                if (__any(moved)) rescale(0, c.alpha);   // the reference of some column moved
+                softmax_second(sacc[0], p.scale_log2, c, l_run[0], pw[0]);
                 ATTN_STAMP(13);
                 weighted_values(slot_c, pw);
             });
         }
-    } else {
-        // Software pipeline over the tiles t_begin + rho (WK = 1): iteration rho waits for tile
-        // rho + 1, puts its score products into the matrix cores, and meanwhile turns the scores
-        // of tile rho into probabilities; then the second product of tile rho.  Two bodies, with
-        // and without the mask arithmetic, each free of branches between the score products and
-        // the exponentials, so that the compiler can interleave the two.
-        f32x16_t s_cur[R], s_next[R];
-        wait_vmcnt<kAheadRounds * kLoadsPerRound>();
-        __syncthreads();
-        if (blk_valid) scores(IntC<0>{}, s_cur);
-        auto iteration = [&](int rho, auto slot_c, auto masked) __attribute__((always_inline)) {
-            constexpr int slot = decltype(slot_c)::value;
-            wait_vmcnt<(kAheadRounds - 1) * kLoadsPerRound>();
-            __syncthreads();   // tile rho + 1 is in LDS; the buffer of tile rho - 1 is free
-            issue_round(rho + 1 + kAheadRounds, IntC<(slot + 1 + kAheadRounds) % kSlots>{});
-            if (!blk_valid) return;
-            const int t = t_begin + rho;
-            uint32_t pw[R][2][4];
-            float alpha[R];
-            bool moved[R];
-            // (after the last tile this multiplies a tile nobody needs: cheaper than a branch
-            // that would keep the products and the exponentials in separate blocks)
-            scores(IntC<(slot + 1) % kSlots>{}, s_next);
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (decltype(masked)::value) mask_scores(s_cur[r], visibility(t, slot_c, r), half);
-                alpha[r] = softmax_step(s_cur[r], p.scale_log2, m_run[r], l_run[r], pw[r], moved[r]);
-            }
-            // issue order: the fragment reads, then one matrix instruction (32 clocks in the
-            // matrix pipe) followed by as much vector arithmetic as fits under it
-            __builtin_amdgcn_sched_group_barrier(0x100, kKSteps, 0);
-#pragma unroll
-            for (int i = 0; i < kKSteps * R; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, (decltype(masked)::value ? 14 : 8) * (R == 1 ? 1 : 1), 0);
-            }
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (__any(moved[r])) rescale(r, alpha[r]);
-            weighted_values(slot_c, pw);
-#pragma unroll
-            for (int r = 0; r < R; ++r) s_cur[r] = s_next[r];
-        };
-        // Tiles wholly inside the prefix come first and need no mask arithmetic: a loop of their
-        // own (one loop with a branch per tile would let the compiler merge the common halves
-        // of the two bodies and lose the interleaving).  It ends on a multiple of the ring size;
-        // the few plain tiles left over go through the masked body with an all-ones mask.
-        const int full_tiles = p.P / kKeyTile;
-        const int n_plain = max(0, min(n_rounds, full_tiles - t_begin)) / kSlots * kSlots;
-        int rho0 = 0;
-        for (; rho0 < n_plain; rho0 += kSlots)
-            for_slots(rho0, n_plain, [&](int rho, auto slot_c) __attribute__((always_inline)) { iteration(rho, slot_c, std::false_type{}); });
-        for (; rho0 < n_rounds; rho0 += kSlots)
-            for_slots(rho0, n_rounds, [&](int rho, auto slot_c) __attribute__((always_inline)) { iteration(rho, slot_c, std::true_type{}); });
     }
     wait_vmcnt<0>();   // nothing of mine may still be landing in LDS when the ring is reused below
     ATTN_STAMP(20);
@@ -609,14 +576,50 @@ __global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const M
     //   ml[cell][2][64]        running maximum and (per-lane part of the) normaliser
     //   fac[*][WQ][64], big_m / big_l [WQ][64]   weights and merged statistics
     constexpr int kK4 = kDBlocks * 4;
+    const size_t block_words = (size_t)kK4 * 256 + 128;            // one (unit, range, query block)
+    float* const my_part = p.partials + ((size_t)unit * S + split) * WQ * block_words;
+    // 8-byte store of four consecutive output features of one query
+    auto store_out = [&](int q, int l, int k4, float4 acc, float inv) __attribute__((always_inline)) {
+        const int qr = qb * kUnitRows + q * 32 + (l & 31);
+        if (qr >= rows) return;
+        const int node = qr / p.G, head = g * p.G + qr % p.G;
+        const int d0 = (k4 >> 2) * 32 + (k4 & 3) * 8 + (l >> 5) * 4;
+        f32x2_t lo = {acc.x * inv, acc.y * inv}, hi = {acc.z * inv, acc.w * inv};
+        uint2 w;
+        w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2_t));
+        w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
+        *reinterpret_cast<uint2*>(p.out + ((size_t)node * p.H + head) * D + d0) = w;
+    };
     __syncthreads();
     float* const lds_f = reinterpret_cast<float*>(&sm_union);
     float* const o_s = lds_f;                                        // [kCells][kK4][64][4]
     float* const ml_s = o_s + (size_t)kCells * kK4 * 256;            // [kCells][2][64]
-    float* const fac_s = ml_s + kCells * 128;                        // [fac_rows][WQ][64]
+    float* const fac_s = WK == 1 ? lds_f : ml_s + kCells * 128;      // [fac_rows][WQ][64]
     float* const bigm_s = fac_s + (size_t)fac_rows<WQ>() * WQ * 64;  // [WQ][64]
     float* const bigl_s = bigm_s + WQ * 64;                          // [WQ][64]
     static_assert(WK <= fac_rows<WQ>(), "weight table too small");
+    if constexpr (WK == 1) {
+        // One key group: nothing to merge inside the workgroup.  Every wavefront takes its row
+        // block from registers straight to `out` (single range) or to the workspace.
+        const int q = wqw;
+        if (S == 1) {
+            const auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run[0]), __float_as_uint(l_run[0]), false, false);
+            const float inv = 1.0f / (__uint_as_float(r2[0]) + __uint_as_float(r2[1]));
+#pragma unroll
+            for (int k4 = 0; k4 < kK4; ++k4)
+                store_out(q, lane, k4, make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
+                                                   oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]), inv);
+            return;
+        }
+        float4* dst = reinterpret_cast<float4*>(my_part + (size_t)q * block_words) + lane;
+#pragma unroll
+        for (int k4 = 0; k4 < kK4; ++k4)
+            dst[k4 * 64] = make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
+                                       oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]);
+        float* ml = my_part + (size_t)q * block_words + (size_t)kK4 * 256;
+        ml[lane] = m_run[0];
+        ml[64 + lane] = l_run[0];
+    } else {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int cell = wk * WQ + wqw * R + r;
@@ -649,20 +652,6 @@ __global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const M
     }
     __syncthreads();
 
-    const size_t block_words = (size_t)kK4 * 256 + 128;            // one (unit, range, query block)
-    float* const my_part = p.partials + ((size_t)unit * S + split) * WQ * block_words;
-    // 8-byte store of four consecutive output features of one query
-    auto store_out = [&](int q, int l, int k4, float4 acc, float inv) __attribute__((always_inline)) {
-        const int qr = qb * kUnitRows + q * 32 + (l & 31);
-        if (qr >= rows) return;
-        const int node = qr / p.G, head = g * p.G + qr % p.G;
-        const int d0 = (k4 >> 2) * 32 + (k4 & 3) * 8 + (l >> 5) * 4;
-        f32x2_t lo = {acc.x * inv, acc.y * inv}, hi = {acc.z * inv, acc.w * inv};
-        uint2 w;
-        w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2_t));
-        w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
-        *reinterpret_cast<uint2*>(p.out + ((size_t)node * p.H + head) * D + d0) = w;
-    };
     // merged output of the workgroup: straight to `out` (single range) or to the workspace
 #pragma unroll 1
     for (int i = tid; i < WQ * kK4 * 64; i += kT) {
@@ -683,6 +672,7 @@ __global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const M
         float* ml = my_part + (size_t)(i >> 6) * block_words + (size_t)kK4 * 256;
         ml[i & 63] = bigm_s[i];
         ml[64 + (i & 63)] = bigl_s[i];
+    }
     }
     ATTN_STAMP(21);
 
@@ -743,7 +733,6 @@ __global__ __launch_bounds__(kCells / R * 64) void tree_attn_mfma_kernel(const M
 
 int g_splits_override = 0;  // tuning hooks, 0 = automatic
 int g_wq_override = 0;
-int g_row_blocks_override = 0;
 
 AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     AttnSchedule s;
@@ -755,10 +744,7 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     s.query_blocks = (rows + unit_rows - 1) / unit_rows;
     const int units = Hk * s.query_blocks;
     const int prefix_tiles = (P + kKeyTile - 1) / kKeyTile;
-    // eight row blocks per workgroup: two per wavefront, four fat wavefronts (see the kernel)
-    s.row_blocks = 1;
-    if (g_row_blocks_override > 0 && s.wq == 8) s.row_blocks = g_row_blocks_override;
-    const int wk = kCells / s.wq;
+    const int wk = kMaxCells / s.wq;
     // Key ranges per unit.  One workgroup fits on a CU at a time, so the launch runs in batches
     // of 256 workgroups; a range costs its rounds plus a fixed prologue/epilogue (about a dozen
     // rounds' worth, measured) plus the merge.  Take the cheapest count.
@@ -805,21 +791,17 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
     const int units = Hk * sched.query_blocks;
     if (units > kAttnMaxCounters) return SEQ_ERR_SHAPE;
     const int unit_groups = (units + 7) / 8;
-    const dim3 grid((unsigned)(unit_groups * 8 * sched.splits)), block((unsigned)(sched.row_blocks == 2 ? 256 : 512));
-#define SEQ_ATTN_LAUNCH(DD, WQ_, R_, PIPE_)                                                       \
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<DD, WQ_, kCells / WQ_, R_, PIPE_>), grid, block, 0, stream, p)
+    const dim3 grid((unsigned)(unit_groups * 8 * sched.splits)), block(512);
+#define SEQ_ATTN_LAUNCH(DD, WQ_, WK_)                                                             \
+    hipLaunchKernelGGL((tree_attn_mfma_kernel<DD, WQ_, WK_>), grid, block, 0, stream, p)
     if (D == 64) {
-        if (sched.wq == 2) SEQ_ATTN_LAUNCH(64, 2, 1, false);
-        else if (sched.wq == 4) SEQ_ATTN_LAUNCH(64, 4, 1, false);
-        else if (sched.row_blocks == 2) SEQ_ATTN_LAUNCH(64, 8, 2, true);
-        else if (sched.row_blocks == 3) SEQ_ATTN_LAUNCH(64, 8, 1, false);
-        else SEQ_ATTN_LAUNCH(64, 8, 1, true);
+        if (sched.wq == 2) SEQ_ATTN_LAUNCH(64, 2, 4);
+        else if (sched.wq == 4) SEQ_ATTN_LAUNCH(64, 4, 2);
+        else SEQ_ATTN_LAUNCH(64, 8, 1);
     } else {
-        if (sched.wq == 2) SEQ_ATTN_LAUNCH(128, 2, 1, false);
-        else if (sched.wq == 4) SEQ_ATTN_LAUNCH(128, 4, 1, false);
-        else if (sched.row_blocks == 2) SEQ_ATTN_LAUNCH(128, 8, 2, true);
-        else if (sched.row_blocks == 3) SEQ_ATTN_LAUNCH(128, 8, 1, false);
-        else SEQ_ATTN_LAUNCH(128, 8, 1, true);
+        if (sched.wq == 2) SEQ_ATTN_LAUNCH(128, 2, 4);
+        else if (sched.wq == 4) SEQ_ATTN_LAUNCH(128, 4, 2);
+        else SEQ_ATTN_LAUNCH(128, 8, 1);
     }
 #undef SEQ_ATTN_LAUNCH
     return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
@@ -839,4 +821,3 @@ extern "C" int seqtree_internal_read_attn_stamps(long long* out) {
 #endif
 extern "C" void seqtree_internal_set_attn_splits(int splits) { seqtree::g_splits_override = splits; }
 extern "C" void seqtree_internal_set_attn_wq(int wq) { seqtree::g_wq_override = wq; }
-extern "C" void seqtree_internal_set_attn_row_blocks(int r) { seqtree::g_row_blocks_override = r; }
