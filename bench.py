@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
+# HBM bytes per launch of the attention kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
+# scaled by a copy kernel of known size (profiles/tree_verify_step_C2_hbm_traffic.md gives the commands and
+# the raw counters).  Counters cannot be read from inside this process, so the figure is carried here.
+MEASURED_ATTN_TRAFFIC_BYTES = {"C2": 21.8e6 + 3.8e6}
+
 
 def attn_alg_bytes(cfg, n=None, P=None):
     e = 2 if cfg.dtype == "bf16" else 4
@@ -199,12 +204,12 @@ def main() -> int:
     if hbm_bound:
         roofline = {"kernel": "tree_attn_mfma_kernel" if code == 1 else "tree_attn_rowwise_f32",
                     "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                    "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(args.config),
                     "alg_bytes_per_launch": bytes_alg, "avg_launch_us": round(attn_us, 3)}
     else:
         roofline = {"kernel": "tree_attn_mfma_kernel", "bound": "mfma", "achieved": round(tflops, 1),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(args.config),
                     "alg_flops_per_launch": flops_alg, "avg_launch_us": round(attn_us, 3)}
     e = 2 if tdt == torch.bfloat16 else 4
     verify_bytes = (len(path0) + 1) * 2 * V * e
