@@ -234,7 +234,6 @@ __device__ __forceinline__ void softmax_second(const f32x16_t& s, float scale_lo
     l_run = l_run * c.alpha + c.psum;
 }
 
-template <int V> struct IntC { static constexpr int value = V; };
 
 // One workgroup = a unit of 32 * WQ query rows x a range of key tiles; wavefront w is cell
 // (row block w % WQ, key group w / WQ) of its WQ x WK grid.
@@ -354,10 +353,10 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
 #pragma unroll
     for (int r = 0; r < R; ++r) mask_lane_off[r] = qvalid[r] ? (uint32_t)(qi[r] * p.words_per_row) * 4u : 0u;
 
-    // Issue the copies of round rho; slot = rho % (kRing / WK), a compile-time constant at every
-    // call site, fixes the ring buffers.
-    auto issue_round = [&](int rho, auto slot_c) __attribute__((always_inline)) {
-        constexpr int slot = decltype(slot_c)::value;
+    // Issue the copies of round rho into ring slot `slot` = rho % (kRing / WK).  (Every helper
+    // below takes the slot as a plain int and is inlined: where the tile loop is unrolled over
+    // the ring the slot is a literal and ends up in the instructions' offset fields.)
+    auto issue_round = [&](int rho, int slot) __attribute__((always_inline)) {
         const int j0 = rho * WK;
         const bool inside = (t_begin + j0 + WK) * kKeyTile <= p.P && t_begin + j0 + WK <= t_end;
 #pragma unroll
@@ -390,11 +389,12 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
             async_copy4(mask_lane_off[r], p.anc + word, m_lds + (uint32_t)(((slot * WK + wk) * kCells + cell) * 256));
         }
     };
-    // rounds rho0 .. rho0 + count - 1, rho0 a multiple of kSlots, through a body that knows its slot
+    // One turn of the ring: rounds rho0 .. rho0 + kSlots - 1 (rho0 a multiple of kSlots), each
+    // through a copy of the body that is given its slot as a literal.
     constexpr int kSlots = kRing / WK;
-    auto for_slots = [&](int rho0, int rho_end, auto&& body) __attribute__((always_inline)) {
+    auto one_turn = [&](int rho0, int rho_end, auto&& body) __attribute__((always_inline)) {
         [&]<int... Is>(std::integer_sequence<int, Is...>) __attribute__((always_inline)) {
-            (void)(((rho0 + Is < rho_end) ? (body(rho0 + Is, IntC<Is>{}), true) : false) && ...);
+            (void)(((rho0 + Is < rho_end) ? (body(rho0 + Is, Is), true) : false) && ...);
         }(std::make_integer_sequence<int, kSlots>{});
     };
 
@@ -412,8 +412,9 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         }
     }
 
-    // start the tile pipeline
-    for_slots(0, kAheadRounds, [&](int rho, auto slot_c) __attribute__((always_inline)) { issue_round(rho, slot_c); });
+    // start the tile pipeline (a rolled loop: code that runs once is fetched cold, and slowly)
+#pragma unroll 1
+    for (int a = 0; a < kAheadRounds; ++a) issue_round(a, a);
     ATTN_STAMP(1);
 
     // Make the compiler settle these loads here.  It cannot see the copies issued in assembly,
@@ -464,8 +465,8 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
 
     // S^T = K Q^T for my row blocks (32 keys x 32 queries each), tile in ring slot `slot`.  All
     // K fragments are requested before the first matrix instruction: one LDS latency per tile.
-    auto scores = [&](auto slot_c, f32x16_t (&sacc)[R]) __attribute__((always_inline)) {
-        constexpr uint32_t kSlotBytes = decltype(slot_c)::value * WK * kTileBytes;
+    auto scores = [&](int slot, f32x16_t (&sacc)[R]) __attribute__((always_inline)) {
+        const uint32_t kSlotBytes = (uint32_t)slot * WK * kTileBytes;
         bf16x8_t kf[kKSteps];
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks)
@@ -488,17 +489,17 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     };
     // Visibility of the keys of tile t (ring slot `slot`) for the queries of this lane.
     auto tile_is_full = [&](int t) __attribute__((always_inline)) { return t < p.prefix_tiles && (t + 1) * kKeyTile <= p.P; };
-    auto visibility = [&](int t, auto slot_c, int r) __attribute__((always_inline)) -> uint32_t {   // selects only, no branches
+    auto visibility = [&](int t, int slot, int r) __attribute__((always_inline)) -> uint32_t {   // selects only, no branches
         const int left = p.P - t * kKeyTile;
         const uint32_t in_prefix = left >= 32 ? 0xFFFFFFFFu : (left <= 0 ? 0u : ((1u << left) - 1u));
         const int word = t - p.prefix_tiles;
-        const uint32_t in_tree = maddr[r][decltype(slot_c)::value * WK * kCells * 64];
+        const uint32_t in_tree = maddr[r][slot * WK * kCells * 64];
         return t < p.prefix_tiles ? in_prefix : ((qvalid[r] && word < p.words_per_row) ? in_tree : 0u);
     };
     // O^T += V^T P^T.  Matrix step m contracts keys (2m+a)*8 + half*4 + 0..3, a = 0,1 -- the
     // keys whose probabilities sit in accumulator elements 8m..8m+7.
-    auto weighted_values = [&](auto slot_c, const uint32_t (&pw)[R][2][4]) __attribute__((always_inline)) {
-        constexpr uint32_t kSlotBytes = decltype(slot_c)::value * WK * kTileBytes;
+    auto weighted_values = [&](int slot, const uint32_t (&pw)[R][2][4]) __attribute__((always_inline)) {
+        const uint32_t kSlotBytes = (uint32_t)slot * WK * kTileBytes;
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
             bf16x8_t pf[R];
@@ -533,32 +534,36 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
             for (int x = 0; x < 16; ++x) oacc[r][b][x] *= alpha;
     };
 
-    {
-        for (int rho0 = 0; rho0 < n_rounds; rho0 += kSlots) {
-            for_slots(rho0, n_rounds, [&](int rho, auto slot_c) __attribute__((always_inline)) {
-                constexpr int slot = decltype(slot_c)::value;
-                // my copies of this round have landed once at most the copies of the kAheadRounds - 1
-                // rounds issued after it are in flight (copies complete in order)
-                wait_vmcnt<(kAheadRounds - 1) * kLoadsPerRound>();
-                ATTN_STAMP(10);
-                __syncthreads();   // everybody's copies of this round are in LDS; the previous round's buffers are free
-                ATTN_STAMP(11);
-                issue_round(rho + kAheadRounds, IntC<(slot + kAheadRounds) % kSlots>{});
-                const int t = t_begin + rho * WK + wk;
-                if (!blk_valid || t >= t_end) return;
-                f32x16_t sacc[1];
-                scores(slot_c, sacc);
-                ATTN_STAMP(12);
-                if (!tile_is_full(t)) mask_scores(sacc[0], visibility(t, slot_c, 0), half);   // tiles inside the prefix need no mask
-                uint32_t pw[1][2][4];
-                bool moved;
-                const SoftmaxCarry c = softmax_first(sacc[0], p.scale_log2, m_run[0], pw[0], moved);
-                if (__any(moved)) rescale(0, c.alpha);   // the reference of some column moved
-                softmax_second(sacc[0], p.scale_log2, c, l_run[0], pw[0]);
-                ATTN_STAMP(13);
-                weighted_values(slot_c, pw);
-            });
-        }
+    auto round = [&](int rho, int slot) __attribute__((always_inline)) {
+        // my copies of this round have landed once at most the copies of the kAheadRounds - 1
+        // rounds issued after it are in flight (copies complete in order)
+        wait_vmcnt<(kAheadRounds - 1) * kLoadsPerRound>();
+        ATTN_STAMP(10);
+        __syncthreads();   // everybody's copies of this round are in LDS; the previous round's buffers are free
+        ATTN_STAMP(11);
+        issue_round(rho + kAheadRounds, (slot + kAheadRounds) % kSlots);
+        const int t = t_begin + rho * WK + wk;
+        if (!blk_valid || t >= t_end) return;
+        f32x16_t sacc[1];
+        scores(slot, sacc);
+        ATTN_STAMP(12);
+        if (!tile_is_full(t)) mask_scores(sacc[0], visibility(t, slot, 0), half);   // tiles inside the prefix need no mask
+        uint32_t pw[1][2][4];
+        bool moved;
+        const SoftmaxCarry c = softmax_first(sacc[0], p.scale_log2, m_run[0], pw[0], moved);
+        if (__any(moved)) rescale(0, c.alpha);   // the reference of some column moved
+        softmax_second(sacc[0], p.scale_log2, c, l_run[0], pw[0]);
+        ATTN_STAMP(13);
+        weighted_values(slot, pw);
+    };
+    if constexpr (WK == 1) {
+        // long key ranges, many rounds: unrolled over the ring, slots are literals
+        for (int rho0 = 0; rho0 < n_rounds; rho0 += kSlots) one_turn(rho0, n_rounds, round);
+    } else {
+        // few rounds per workgroup: one copy of the body, fetched once; the slot costs a few
+        // additions per tile
+#pragma unroll 1
+        for (int rho = 0; rho < n_rounds; ++rho) round(rho, rho % kSlots);
     }
     wait_vmcnt<0>();   // nothing of mine may still be landing in LDS when the ring is reused below
     ATTN_STAMP(20);
@@ -679,6 +684,9 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     // See whether we are the last range of this unit to finish.  The partial results must be
     // visible to that workgroup.  When all ranges of a unit run on one XCD they meet in its L2:
     // it is enough that my stores have completed.  Otherwise the L2 has to be written back.
+    // (Sharing the merge among the S workgroups of a unit -- count arrivals, poll a bounded
+    // number of times, claim a slice -- was tried: the polling costs more than the one CU's
+    // memory pipeline it saves, and workgroups that wait hold CUs that a later batch needs.)
     if (p.share_l2) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     else __threadfence();
     __syncthreads();
@@ -694,38 +702,57 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     else __threadfence();
     ATTN_STAMP(23);
 
-    // merge the ranges of the unit: weights first, then the weighted sums
+    // Merge the ranges of the unit: weights first, then the weighted sums.  One workgroup pulls
+    // S partial results through one CU's memory pipeline, so what matters is how many loads are
+    // in flight: every thread requests all S values of an item before it touches the first
+    // (NS = S rounded up to 4, 8 or 16; the surplus requests repeat the last range).
     const float* const unit_part = p.partials + (size_t)unit * S * WQ * block_words;
-    for (int i = tid; i < WQ * 64; i += kT) {
-        const float* ml = unit_part + (size_t)(i >> 6) * block_words + (size_t)kK4 * 256 + (i & 63);
-        float big = -INFINITY;
-#pragma unroll 4
-        for (int r = 0; r < S; ++r) big = fmaxf(big, ml[(size_t)r * WQ * block_words]);
-        const float ref = (big == -INFINITY) ? 0.f : big;
-        float lsum = 0.f;
-#pragma unroll 4
-        for (int r = 0; r < S; ++r) {
-            const float f = __builtin_amdgcn_exp2f(ml[(size_t)r * WQ * block_words] - ref);
-            fac_s[r * WQ * 64 + i] = f;
-            lsum = fmaf(ml[(size_t)r * WQ * block_words + 64], f, lsum);
+    const size_t range_words = (size_t)WQ * block_words;
+    auto merge_ranges = [&](auto ns_c) __attribute__((always_inline)) {
+        constexpr int NS = decltype(ns_c)::value;
+        for (int i = tid; i < WQ * 64; i += kT) {
+            const float* ml = unit_part + (size_t)(i >> 6) * block_words + (size_t)kK4 * 256 + (i & 63);
+            float mv[NS], lv[NS];
+#pragma unroll
+            for (int r = 0; r < NS; ++r) {
+                const float* src = ml + (size_t)min(r, S - 1) * range_words;
+                mv[r] = src[0];
+                lv[r] = src[64];
+            }
+            float big = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < NS; ++r) big = fmaxf(big, mv[r]);
+            const float ref = (big == -INFINITY) ? 0.f : big;
+            float lsum = 0.f;
+#pragma unroll
+            for (int r = 0; r < NS; ++r) {
+                const float f = r < S ? __builtin_amdgcn_exp2f(mv[r] - ref) : 0.f;
+                fac_s[r * WQ * 64 + i] = f;
+                lsum = fmaf(lv[r], f, lsum);
+            }
+            bigl_s[i] = lsum;
         }
-        bigl_s[i] = lsum;
-    }
-    __syncthreads();
+        __syncthreads();
 #pragma unroll 1
-    for (int i = tid; i < WQ * kK4 * 64; i += kT) {
-        const int l = i & 63, k4 = (i >> 6) % kK4, q = i / (64 * kK4);
-        const float4* src = reinterpret_cast<const float4*>(unit_part + (size_t)q * block_words) + k4 * 64 + l;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-        for (int r = 0; r < S; ++r) {
-            const float f = fac_s[r * WQ * 64 + q * 64 + l];
-            const float4 v = src[(size_t)r * WQ * block_words / 4];
-            acc.x = fmaf(v.x, f, acc.x); acc.y = fmaf(v.y, f, acc.y);
-            acc.z = fmaf(v.z, f, acc.z); acc.w = fmaf(v.w, f, acc.w);
+        for (int i = tid; i < WQ * kK4 * 64; i += kT) {
+            const int l = i & 63, k4 = (i >> 6) % kK4, q = i / (64 * kK4);
+            const float4* src = reinterpret_cast<const float4*>(unit_part + (size_t)q * block_words) + k4 * 64 + l;
+            float4 v[NS];
+#pragma unroll
+            for (int r = 0; r < NS; ++r) v[r] = src[(size_t)min(r, S - 1) * (range_words / 4)];
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int r = 0; r < NS; ++r) {
+                const float f = fac_s[r * WQ * 64 + q * 64 + l];   // 0 for the surplus
+                acc.x = fmaf(v[r].x, f, acc.x); acc.y = fmaf(v[r].y, f, acc.y);
+                acc.z = fmaf(v[r].z, f, acc.z); acc.w = fmaf(v[r].w, f, acc.w);
+            }
+            store_out(q, l, k4, acc, 1.0f / (bigl_s[q * 64 + l] + bigl_s[q * 64 + (l ^ 32)]));
         }
-        store_out(q, l, k4, acc, 1.0f / (bigl_s[q * 64 + l] + bigl_s[q * 64 + (l ^ 32)]));
-    }
+    };
+    if (S <= 4) merge_ranges(std::integral_constant<int, 4>{});
+    else if (S <= 8 || fac_rows<WQ>() <= 8) merge_ranges(std::integral_constant<int, 8>{});
+    else merge_ranges(std::integral_constant<int, fac_rows<WQ>()>{});
     ATTN_STAMP(24);
 }
 
