@@ -44,6 +44,92 @@ def attn_alg_flops(cfg, parent):
     return 4 * cfg.head_dim * cfg.heads * (len(parent) * cfg.prefix_len + visible)
 
 
+def graph_time_us(torch, fn, count, reps):
+    """Average duration of one call of fn(i), i = 0..count-1 captured once as a HIP graph."""
+    fn(0)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for i in range(count):
+            fn(i)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(count):
+            fn(i)
+    for _ in range(3):
+        graph.replay()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(reps):
+        graph.replay()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) * 1e3 / (reps * count)
+
+
+def run_sweep(args) -> int:
+    """Latency of the two calls over the tree size, at each configuration's head shape, prefix
+    length and vocabulary: one JSON line per (configuration, n).  Not the benchmark line."""
+    import numpy as np
+    import torch
+
+    import paper_2402_12374_amd as S
+    from paper_2402_12374_amd import workloads as W
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    sizes = [int(x) for x in args.sweep_sizes.split(",")]
+    for key in args.sweep_configs.split(","):
+        cfg = W.CONFIGS[key]
+        H, Hk, d, P, V = cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.prefix_len, cfg.vocab
+        tdt = torch.bfloat16 if cfg.dtype == W.BF16 else torch.float32
+        code = 1 if tdt == torch.bfloat16 else 2
+        T = cfg.temperatures[0]
+        sets = min(cfg.layers, 16)
+        mk = lambda *shape: torch.randn(*shape, device=dev).to(tdt)
+        caches = [(mk(Hk, P, d), mk(Hk, P, d)) for _ in range(sets)]
+        for n in sizes:
+            parent = W.geometric_tree(n, cfg.max_depth)
+            q = [(mk(n, H, d), mk(n, Hk, d), mk(n, Hk, d), torch.empty(n, H, d, device=dev, dtype=tdt)) for _ in range(sets)]
+            ws = torch.empty(S.seq_tree_attn_workspace(P, n, H, Hk, d, code), dtype=torch.uint8, device=dev)
+
+            def attn_call(i):
+                kc, vc = caches[i % sets]
+                qq, kt, vt, out = q[i % sets]
+                S.seq_tree_attn(qq, kc, vc, kt, vt, parent, P, out=out, workspace=ws)
+
+            attn_us = graph_time_us(torch, attn_call, sets, 20)
+            vsets = []
+            for rep in range(2 if n * V > 2 ** 25 else 4):
+                v = W.make_verify_inputs(parent, V, cfg.sigma_target, cfg.sigma_draft, T, cfg.dtype, seed=n + rep)
+                vsets.append(dict(tl=torch.from_numpy(v.target_logits).to(dev).to(tdt), dl=torch.from_numpy(v.draft_logits).to(dev).to(tdt),
+                                  tok=torch.from_numpy(v.tree_tokens).to(dev), un=torch.from_numpy(v.uniforms).to(dev),
+                                  path=torch.empty(n, dtype=torch.int32, device=dev), bonus=torch.empty(1, dtype=torch.int32, device=dev),
+                                  ws=torch.empty(S.seq_verify_workspace(n, V, code), dtype=torch.uint8, device=dev)))
+
+            def verify_call(i):
+                x = vsets[i % len(vsets)]
+                S.seq_verify(x["tl"], x["dl"], x["tok"], parent, T, x["un"], accepted_path=x["path"],
+                             bonus_token=x["bonus"], workspace=x["ws"])
+
+            verify_us = graph_time_us(torch, verify_call, len(vsets), 20)
+            cfg_n = type("C", (), dict(dtype=cfg.dtype, n_tree=n, prefix_len=P, heads=H, kv_heads=Hk, head_dim=d))
+            bytes_alg, flops_alg = attn_alg_bytes(cfg_n), attn_alg_flops(cfg_n, parent)
+            print(json.dumps({"config": cfg.name, "n_tree": n, "prefix_len": P, "vocab": V,
+                              "attn_us_per_layer": round(attn_us, 2), "verify_us": round(verify_us, 2),
+                              "attn_hbm_frac": round(bytes_alg / (attn_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                              "attn_mfma_frac": round(flops_alg / (attn_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}), flush=True)
+            del q, vsets
+        del caches
+        torch.cuda.empty_cache()
+    S.shutdown()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,10 +143,17 @@ def main() -> int:
     ap.add_argument("--yardstick-mib", type=int, default=0,
                     help="after the timed region, also launch a plain copy kernel of this many MiB four times "
                          "(the known-size reference for HBM traffic counters collected with rocprofv3 --pmc)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: latency of both calls over the tree size (one line each)")
+    ap.add_argument("--sweep-configs", default="C2,C3,C4,C5")
+    ap.add_argument("--sweep-sizes", default="16,32,64,128,256,512,768")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         return 2
+
+    if args.sweep:
+        return run_sweep(args)
 
     import numpy as np
     import torch
@@ -213,7 +306,7 @@ def main() -> int:
                     "alg_flops_per_launch": flops_alg, "avg_launch_us": round(attn_us, 3)}
     e = 2 if tdt == torch.bfloat16 else 4
     verify_bytes = (len(path0) + 1) * 2 * V * e
-    per_node = T > 0 and V <= 32768   # the library's own choice of kernel (see include/seqtree.h)
+    per_node = T > 0 and V <= 32768 and n <= 256   # the library's own choice of kernel (see include/seqtree.h)
     leaves = int(sum(1 for ch in W.children_lists(parent) if not ch))
     moved = ((n - leaves) * 2 + leaves) * V * e if per_node else verify_bytes
     verify_info = {"kernel": "verify_chains_kernel" if per_node else "verify_walk_kernel",

@@ -112,8 +112,9 @@ int seq_tree_attn(const void* q, const void* k_cache, const void* v_cache,
  *                  is scratch whose contents are unspecified
  *
  * Two kernels sit behind this call and give the same results.  For sampling (T > 0) over a
- * vocabulary of at most 32768 tokens, every node's accept thresholds are computed at once,
- * one workgroup per node (all 2 * n_tree * vocab logits are read), and a short walk follows;
+ * vocabulary of at most 32768 tokens and a tree of at most 256 nodes, every node's accept
+ * thresholds are computed at once, one workgroup per node (every logit row the tree can visit
+ * is read), and a short walk follows;
  * otherwise only the rows of the nodes the walk visits are read, by workgroups that share the
  * vocabulary.  Calls that overlap in time on one device (different streams) are not supported:
  * both kernels use a per-device synchronisation area.

@@ -150,7 +150,7 @@ struct Rings {
 };
 
 // Rows of the weight table of the epilogue: key groups of a workgroup, or key ranges of a unit.
-template <int WQ> constexpr int fac_rows() { return WQ >= 8 ? 8 : kMaxSplits; }
+template <int WQ> constexpr int fac_rows() { return kMaxSplits; }
 
 template <int D, int WQ, int kCells>
 constexpr size_t epilogue_bytes() {
@@ -765,30 +765,37 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     AttnSchedule s;
     const int G = H / Hk;
     const int rows = G * n;
-    s.wq = rows <= 64 ? 2 : (rows <= 128 ? 4 : 8);
-    if (g_wq_override > 0) s.wq = g_wq_override;
-    const int unit_rows = 32 * s.wq;
-    s.query_blocks = (rows + unit_rows - 1) / unit_rows;
-    const int units = Hk * s.query_blocks;
     const int prefix_tiles = (P + kKeyTile - 1) / kKeyTile;
-    const int wk = kMaxCells / s.wq;
-    // Key ranges per unit.  One workgroup fits on a CU at a time, so the launch runs in batches
-    // of 256 workgroups; a range costs its rounds plus a fixed prologue/epilogue (about a dozen
-    // rounds' worth, measured) plus the merge.  Take the cheapest count.
     const int tiles = prefix_tiles + (n + kKeyTile - 1) / kKeyTile;
-    const int max_splits = std::min(s.wq == 8 ? 8 : kMaxSplits, std::max(1, tiles / wk));
-    int splits = 1;
+    // Two choices: row blocks per workgroup (wq; the 8 / wq wavefronts left over share the key
+    // tiles of a round) and key ranges per unit.  One workgroup fits on a CU at a time, so a
+    // launch runs in batches of 256 workgroups; a workgroup costs its rounds -- dearer the more
+    // tiles a round copies -- plus a fixed prologue/epilogue plus the merge of the ranges
+    // (figures in tenths of a microsecond, from measurements on the configurations of the paper's
+    // models).  A wq beyond what the rows of a KV head fill is never considered; a smaller one
+    // is, because it multiplies the units when there are few KV heads.
+    const int wq_cover = rows <= 64 ? 2 : (rows <= 128 ? 4 : 8);
     long best = -1;
-    for (int cand = 1; cand <= max_splits; ++cand) {
-        const long batches = ((long)units * cand + 255) / 256;
-        const long rounds = (tiles + cand * wk - 1) / (cand * wk);
-        const long cost = batches * (rounds + 12 + (cand > 1 ? cand : 0));
-        if (best < 0 || cost < best) { best = cost; splits = cand; }
+    s.wq = wq_cover;
+    s.splits = 1;
+    for (int wq = 2; wq <= wq_cover; wq *= 2) {
+        if (g_wq_override > 0 && wq != std::min(g_wq_override, wq_cover)) continue;
+        const int wk = kMaxCells / wq;
+        const int units = Hk * ((rows + 32 * wq - 1) / (32 * wq));
+        const long round_cost = wk == 1 ? 9 : (wk == 2 ? 14 : 20);
+        const int max_splits = std::min(kMaxSplits, std::max(1, tiles / wk));
+        for (int cand = 1; cand <= max_splits; ++cand) {
+            if (g_splits_override > 0 && cand != std::min(g_splits_override, max_splits)) continue;
+            const long batches = ((long)units * cand + 255) / 256;
+            const long rounds = (tiles + cand * wk - 1) / (cand * wk);
+            const long cost = batches * (rounds * round_cost + 100 + (cand > 1 ? 4 * cand * wq / 2 : 0));
+            if (best < 0 || cost < best) { best = cost; s.wq = wq; s.splits = cand; }
+        }
     }
-    if (g_splits_override > 0) splits = std::min(g_splits_override, max_splits);
-    s.splits = splits;
+    s.query_blocks = (rows + 32 * s.wq - 1) / (32 * s.wq);
+    const int units = Hk * s.query_blocks;
     const size_t block_words = (size_t)(D / 32) * 4 * 256 + 128;   // one (unit, range, query block)
-    s.workspace_bytes = splits > 1 ? (size_t)units * splits * s.wq * block_words * sizeof(float) : 0;
+    s.workspace_bytes = s.splits > 1 ? (size_t)units * s.splits * s.wq * block_words * sizeof(float) : 0;
     if (s.workspace_bytes < 256) s.workspace_bytes = 256;
     return s;
 }

@@ -46,6 +46,7 @@ struct VerifyParams {
 // verify_chains.hip: every node's sibling chain in parallel, then the walk over the results.
 // Vocabularies up to kChainsMaxVocab; dtype SEQ_BF16 or SEQ_F32.
 constexpr int kChainsMaxVocab = 32768;
+constexpr int kChainsMaxNodes = 256;   // one workgroup per node, one workgroup per CU
 void launch_verify_chains(const VerifyParams& p, int dtype, hipStream_t stream);
 
 template <typename LT> __device__ __forceinline__ float load_logit(const LT* row, int x);

@@ -613,9 +613,11 @@ extern "C" int seq_verify(const void* target_logits, const void* draft_logits,
     const bool greedy = temperature == 0.0f;
     p.inv_T = greedy ? 1.0f : 1.0f / temperature;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    // Sampling with a vocabulary one workgroup can hold: all nodes at once.  Otherwise (and for
-    // greedy decoding, which needs one arg-max per visited node) the lazy walk.
-    if (!greedy && vocab <= kChainsMaxVocab && g_verify_mode != 1) {
+    // Sampling with a vocabulary one workgroup can hold, and a tree whose nodes all find a CU at
+    // once: all nodes at once.  Otherwise (and for greedy decoding, which needs one arg-max per
+    // visited node) the lazy walk.
+    const bool chains_pay = n_tree <= kChainsMaxNodes || g_verify_mode == 2;
+    if (!greedy && vocab <= kChainsMaxVocab && g_verify_mode != 1 && chains_pay) {
         launch_verify_chains(p, dtype, stream);
         return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
     }
