@@ -105,3 +105,26 @@ def test_chain_tree_matches_torch_causal_attention():
     mask = torch.ones(n, P + n, dtype=torch.bool).tril(diagonal=P)
     want = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=mask).permute(1, 0, 2).numpy()
     assert np.abs(got - want).max() <= TOL[W.BF16]
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_every_workgroup_shape_and_range_count(d):
+    """The library chooses row blocks per workgroup and key ranges per unit by a cost model; force
+    every combination the kernels are built for on one shape with ragged tiles, so that no
+    variant goes untested because the model happens not to pick it."""
+    import paper_2402_12374_amd as S
+    rng = np.random.default_rng(11)
+    # 9 x 4 = 36 query rows per KV head would take wq = 2; 70 x 4 = 280 rows lets every wq apply
+    parent = W.random_topological_tree(70, rng)
+    a = W.make_attn_inputs(8, 2, d, 333, parent, W.BF16, seed=d, prefix_cap=340)
+    ref = oracle_attn(a)
+    try:
+        for wq in (2, 4, 8):
+            for splits in (1, 2, 3, 5, 8, 13, 16):
+                S.lib().seqtree_internal_set_attn_wq(wq)
+                S.lib().seqtree_internal_set_attn_splits(splits)
+                err = np.abs(run_attn(a) - ref).max()
+                assert err <= TOL[W.BF16], (wq, splits, err)
+    finally:
+        S.lib().seqtree_internal_set_attn_wq(0)
+        S.lib().seqtree_internal_set_attn_splits(0)
