@@ -248,7 +248,10 @@ __device__ __forceinline__ void softmax_second(const f32x16_t& s, float scale_lo
 // fat wavefronts -- halves the LDS traffic, but the accumulators no longer fit the vector
 // registers and travel through AGPR moves; twelve wavefronts; splitting a tile's work into a
 // matrix phase and a vector phase with a barrier each, or rotating the loop of wavefronts 4..7
-// by half a tile.)
+// by half a tile; dealing equal spans of an XCD's (unit, tile) sequence to 256 workgroups
+// instead of equal key ranges -- the second prologue, epilogue and merge of a span that crosses
+// into the next unit cost what the even load saves, and wrapping the body in a loop over the
+// pieces of a span makes the compiler's tile loop 10-15 % slower.)
 template <int D, int WQ, int WK>
 __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const MfmaParams p) {
     constexpr int kCells = WQ * WK;
@@ -465,13 +468,13 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
 
     // S^T = K Q^T for my row blocks (32 keys x 32 queries each), tile in ring slot `slot`.  All
     // K fragments are requested before the first matrix instruction: one LDS latency per tile.
-    auto scores = [&](int slot, f32x16_t (&sacc)[R]) __attribute__((always_inline)) {
+    auto load_k = [&](int slot, bf16x8_t (&kf)[kKSteps]) __attribute__((always_inline)) {
         const uint32_t kSlotBytes = (uint32_t)slot * WK * kTileBytes;
-        bf16x8_t kf[kKSteps];
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks)
             kf[ks] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t*>(kaddr[ks] + kSlotBytes);
-        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto scores = [&](const bf16x8_t (&kf)[kKSteps], f32x16_t (&sacc)[R]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
 #pragma unroll
@@ -534,18 +537,34 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
             for (int x = 0; x < 16; ++x) oacc[r][b][x] *= alpha;
     };
 
-    auto round = [&](int rho, int slot) __attribute__((always_inline)) {
-        // my copies of this round have landed once at most the copies of the kAheadRounds - 1
-        // rounds issued after it are in flight (copies complete in order)
+    // With one key group every wavefront walks every tile, and the K fragments of tile rho + 1
+    // are requested while tile rho is still being worked on: right after a barrier all eight
+    // wavefronts would otherwise ask LDS for their fragments at once and sit out the queue.
+    // Tile rho + 1 therefore has to be in LDS one barrier earlier.
+    constexpr bool kPrefetchK = WK == 1;
+    bf16x8_t kf[kKSteps];
+    if (kPrefetchK) {
         wait_vmcnt<(kAheadRounds - 1) * kLoadsPerRound>();
+        __syncthreads();   // tile 0 is in LDS
+        load_k(0, kf);
+    }
+    auto round = [&](int rho, int slot) __attribute__((always_inline)) {
+        // my copies of the round needed next have landed once at most the copies of the rounds
+        // issued after it are in flight (copies complete in order)
+        wait_vmcnt<(kAheadRounds - 1 - (kPrefetchK ? 1 : 0)) * kLoadsPerRound>();
         ATTN_STAMP(10);
-        __syncthreads();   // everybody's copies of this round are in LDS; the previous round's buffers are free
+        __syncthreads();   // everybody's copies are in LDS; the previous round's buffers are free
         ATTN_STAMP(11);
         issue_round(rho + kAheadRounds, (slot + kAheadRounds) % kSlots);
         const int t = t_begin + rho * WK + wk;
         if (!blk_valid || t >= t_end) return;
         f32x16_t sacc[1];
-        scores(slot, sacc);
+        if (!kPrefetchK) {
+            load_k(slot, kf);   // all K fragments before the first matrix instruction: one LDS latency per tile
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        scores(kf, sacc);
+        if (kPrefetchK) load_k((slot + 1) % kSlots, kf);   // (past the last tile: a tile nobody needs)
         ATTN_STAMP(12);
         if (!tile_is_full(t)) mask_scores(sacc[0], visibility(t, slot, 0), half);   // tiles inside the prefix need no mask
         uint32_t pw[1][2][4];
