@@ -20,6 +20,7 @@ SEQ_OK = 0
 SEQ_ERR_NULL, SEQ_ERR_SHAPE, SEQ_ERR_TREE, SEQ_ERR_DTYPE = -1, -2, -3, -4
 SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE, SEQ_ERR_HIP = -5, -6, -7
 SEQ_MAX_TREE = 1024
+SEQ_MAX_VOCAB = 524288
 TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
 EXPORTS = ("seq_tree_attn", "seq_verify", "seq_tree_attn_workspace", "seq_verify_workspace",
