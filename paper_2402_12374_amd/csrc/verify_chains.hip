@@ -32,6 +32,7 @@ struct ChainShared {
     float block_mass[64];              // residual mass of (chunk, wavefront) blocks, in token order
     float ctl_a, ctl_b;                // coefficients of the residual for the next pass
     int ctl_zero;                      // token whose probabilities the next pass clears (-1: none)
+    int ctl_sum_q;                     // the next pass also sums the draft mass that is left
     BlockPick pick;
     int bonus_token;
     float bonus_info[3];               // total mass, CDF just below and just above the bonus token
@@ -111,11 +112,11 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
     float pr[EPT], qr[EPT];
 #pragma unroll
     for (int c = 0; c < CH; ++c)
-        load_row_slice<LT, kChunk>(trow, (c * kThreads + tid) * kChunk, V, p.inv_T, vec_ok, pr + c * kChunk);
+        load_row_slice<LT, kChunk>(trow, (c * kThreads + tid) * kChunk, V, 1.0f, vec_ok, pr + c * kChunk);
     if (K > 0) {
 #pragma unroll
         for (int c = 0; c < CH; ++c)
-            load_row_slice<LT, kChunk>(drow, (c * kThreads + tid) * kChunk, V, p.inv_T, vec_ok, qr + c * kChunk);
+            load_row_slice<LT, kChunk>(drow, (c * kThreads + tid) * kChunk, V, 1.0f, vec_ok, qr + c * kChunk);
     } else {
 #pragma unroll
         for (int e = 0; e < EPT; ++e) qr[e] = -INFINITY;   // a leaf has no draft row to read
@@ -135,8 +136,10 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
     float mt_wave = -INFINITY, md_wave = -INFINITY;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) { mt_wave = fmaxf(mt_wave, pr[e]); md_wave = fmaxf(md_wave, qr[e]); }
-    mt_wave = wave_reduce<kOpMax>(mt_wave);
-    md_wave = wave_reduce<kOpMax>(md_wave);
+    // (raw logits so far: the temperature goes into the constants of the exponent, and the
+    // maxima are tempered here -- multiplying by a positive number commutes with taking them)
+    mt_wave = wave_reduce<kOpMax>(mt_wave) * p.inv_T;
+    md_wave = wave_reduce<kOpMax>(md_wave) * p.inv_T;
     {
         // The bulk of the vocabulary goes through the bare hardware exponential: e^(x - m) as
         // 2^(x * log2(e) - m * log2(e)), a fused multiply-add and one v_exp_f32 per token.  The
@@ -144,13 +147,14 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
         // touches terms that are negligible in every sum taken below; the probabilities that
         // decide an accept test (the children's tokens) take the compensated exponential.
         constexpr float kLog2e = 1.44269504088896341f;
+        const float slope = p.inv_T * kLog2e;
         const float bt = mt_wave == -INFINITY ? 0.f : -mt_wave * kLog2e;
         const float bd = md_wave == -INFINITY ? 0.f : -md_wave * kLog2e;
         float zt = 0.f, zd = 0.f;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            pr[e] = __builtin_amdgcn_exp2f(fmaf(pr[e], kLog2e, bt));
-            qr[e] = __builtin_amdgcn_exp2f(fmaf(qr[e], kLog2e, bd));
+            pr[e] = __builtin_amdgcn_exp2f(fmaf(pr[e], slope, bt));
+            qr[e] = __builtin_amdgcn_exp2f(fmaf(qr[e], slope, bd));
             zt += pr[e];
             zd += qr[e];
         }
@@ -191,7 +195,14 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
     // Thread 0 owns the scalar state.  Iteration j: it applies the pass that followed child j-1,
     // writes that child's record, tests child j and publishes the coefficients of the next pass;
     // iteration K only closes child K-1 and publishes the coefficients of the bonus draw.
+    //
+    // The draft mass left after a rejection is the mass before it minus the rejected token's: as
+    // long as a twentieth of the mass is left, thread 0 takes that difference (in fp64; its error
+    // is that of the initial normalisation, 1e-7 absolute) and the pass skips the sum over q.  Once
+    // less is left the pass sums q again, which is also what finds the mass exactly zero.
     NodeState ns;
+    double q_predicted = 1.0;
+    bool q_summed = true;
     if (tid == 0) { node_begin(ns); ns.fallbacks = 0; ns.degenerate = 0; }
     int par = 1;
     for (int j = 0; j <= K; ++j) {
@@ -202,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
             if (tid == 0) {
                 if (j > 0) {
                     const int fb = ns.fallbacks, dg = ns.degenerate;
-                    node_apply_pass(ns, (double)w_new, (double)q_new);
+                    node_apply_pass(ns, (double)w_new, q_summed ? (double)q_new : q_predicted);
                     const uint32_t events = (uint32_t)(ns.fallbacks - fb) | ((uint32_t)(ns.degenerate - dg) << 1);
                     sh.w_rec[j - 1][4] = __uint_as_float(events);
                 }
@@ -214,6 +225,9 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
                     sh.w_rec[j][2] = t.rhs_r; sh.w_rec[j][3] = t.rhs_m;
                     node_reject_child(ns, in_s, V);
                     sh.ctl_zero = in_s ? -1 : sh.child_tok[j];
+                    q_predicted = ns.massQ - (in_s ? 0.0 : (double)sh.child_ld[j]);
+                    q_summed = ns.fallback || !(q_predicted >= 0.05);
+                    sh.ctl_sum_q = q_summed ? 1 : 0;
                 }
                 sh.ctl_a = ns.af;
                 sh.ctl_b = ns.bf;
@@ -234,7 +248,10 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
             }
         }
         float r_loc = 0.f, q_loc = 0.f;
-        if (bf == 0.f) {   // B only moves once the draft has run out of mass
+        if (bf == 0.f && !sh.ctl_sum_q) {   // the common pass: three instructions per token
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) r_loc += fmaxf(fmaf(-af, qr[e], pr[e]), 0.f);
+        } else if (bf == 0.f) {   // B only moves once the draft has run out of mass
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
                 r_loc += fmaxf(fmaf(-af, qr[e], pr[e]), 0.f);
