@@ -309,8 +309,19 @@ def main() -> int:
     per_node = T > 0 and V <= 32768 and n <= 256   # the library's own choice of kernel (see include/seqtree.h)
     leaves = int(sum(1 for ch in W.children_lists(parent) if not ch))
     moved = ((n - leaves) * 2 + leaves) * V * e if per_node else verify_bytes
+    # The per-node kernel is bound by the vector unit of the ONE compute unit that holds the node with
+    # the longest sibling chain: per vocabulary entry 2 x 8 instruction slots for the two softmaxes
+    # (conversion, maximum, fma, exponential at half rate, sum, scaling) and 3 per rejection (fma, max,
+    # add), on 64 lanes per clock (4 SIMDs x 16 lanes) at 2.4 GHz.
+    k_max = max(len(ch) for ch in W.children_lists(parent))
+    chain_slots = V * (16 + 3 * k_max)
+    chain_us = chain_slots / 64.0 / 2.4e9 * 1e6
     verify_info = {"kernel": "verify_chains_kernel" if per_node else "verify_walk_kernel",
                    "avg_launch_us": round(verify_us, 3),
+                   "bound": "alu (one compute unit, longest sibling chain)" if per_node else "latency",
+                   "critical_chain_children": k_max if per_node else None,
+                   "critical_cu_alu_us": round(chain_us, 3) if per_node else None,
+                   "critical_cu_alu_frac": round(chain_us / verify_us, 4) if per_node else None,
                    "accepted_path_len_set0": len(path0), "alg_bytes_lazy_set0": verify_bytes,
                    "hbm_frac_lazy_set0": round(verify_bytes / (verify_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 5),
                    "logit_bytes_read": moved,
