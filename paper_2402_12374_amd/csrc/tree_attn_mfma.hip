@@ -325,8 +325,9 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     const int i_max = __builtin_amdgcn_readfirstlane(last_row / p.G);   // tree rows beyond i_max are masked for all
     const int tree_tiles = i_max / kKeyTile + 1;
     const int total_tiles = p.prefix_tiles + tree_tiles;
-    const int t_begin = __builtin_amdgcn_readfirstlane((int)((long long)total_tiles * split / S));
-    const int t_end = __builtin_amdgcn_readfirstlane((int)((long long)total_tiles * (split + 1) / S));
+    // (32-bit: at most 2^26 tiles times 16 ranges; a 64-bit division is a long routine here)
+    const int t_begin = __builtin_amdgcn_readfirstlane((int)((uint32_t)total_tiles * (uint32_t)split / (uint32_t)S));
+    const int t_end = __builtin_amdgcn_readfirstlane((int)((uint32_t)total_tiles * (uint32_t)(split + 1) / (uint32_t)S));
     const int n_rounds = (t_end - t_begin + WK - 1) / WK;
 
     const uint32_t k_lds = lds_address(&sm.k[0][0]);
