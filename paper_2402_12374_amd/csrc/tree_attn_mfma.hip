@@ -149,13 +149,10 @@ struct Rings {
     uint32_t mask[kRing][kCells][64];
 };
 
-// Rows of the weight table of the epilogue: key groups of a workgroup, or key ranges of a unit.
-template <int WQ> constexpr int fac_rows() { return kMaxSplits; }
-
 template <int D, int WQ, int kCells>
 constexpr size_t epilogue_bytes() {
     // (with a single key group, kCells == WQ, the accumulators never pass through LDS)
-    return sizeof(float) * ((kCells == WQ ? 0 : (size_t)kCells * (D / 32) * 4 * 256 + kCells * 128) + (size_t)fac_rows<WQ>() * WQ * 64 + 2 * WQ * 64);
+    return sizeof(float) * (kCells == WQ ? 64 : (size_t)kCells * (D / 32) * 4 * 256 + kCells * 128);
 }
 
 template <int D, int WQ, int kCells>
@@ -591,114 +588,91 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     // ---- epilogue ---------------------------------------------------------------------------
     // Code that runs once per workgroup is fetched cold, at a small fraction of the speed of a
     // loop that sits in the instruction cache, and for short key ranges the epilogue is most of
-    // the kernel.  So every wavefront only drops its registers into LDS (a few wide stores) and
-    // all merging -- of the key groups of the workgroup, and of the key ranges of the unit --
-    // is done by tight loops over LDS / the workspace with all threads.
+    // the kernel: it is kept short, and every pass over LDS or the workspace that can be left
+    // out is left out.
     //
-    // LDS scratch (the tile rings, free by now), indexed by cell = key group * WQ + row block:
+    // Wavefronts of the same row block hold their cells in the same register layout, so the key
+    // groups of a workgroup are merged lane by lane: the wavefronts of key groups 1.. drop their
+    // registers into LDS (the tile rings, free by now), the wavefront of key group 0 folds them
+    // into its own registers and takes the row block to `out` (single range) or the workspace.
     //   o[cell][k4][lane][4]   unnormalised output; k4 = b*4 + rq holds features
     //                          b*32 + rq*8 + half*4 .. +3 of query (lane % 32), half = lane / 32
     //   ml[cell][2][64]        running maximum and (per-lane part of the) normaliser
-    //   fac[*][WQ][64], big_m / big_l [WQ][64]   weights and merged statistics
     constexpr int kK4 = kDBlocks * 4;
     const size_t block_words = (size_t)kK4 * 256 + 128;            // one (unit, range, query block)
     float* const my_part = p.partials + ((size_t)unit * S + split) * WQ * block_words;
-    // 8-byte store of four consecutive output features of one query
-    auto store_out = [&](int q, int l, int k4, float4 acc, float inv) __attribute__((always_inline)) {
-        const int qr = qb * kUnitRows + q * 32 + (l & 31);
-        if (qr >= rows) return;
-        const int node = qr / p.G, head = g * p.G + qr % p.G;
-        const int d0 = (k4 >> 2) * 32 + (k4 & 3) * 8 + (l >> 5) * 4;
+    // 8-byte store of four consecutive output features of my query (the row block of my wavefront)
+    uint16_t* const out_row = p.out + ((size_t)qi[0] * p.H + qh[0]) * D + half * 4;
+    auto store_out = [&](int k4, float4 acc, float inv) __attribute__((always_inline)) {
+        if (!qvalid[0]) return;
         f32x2_t lo = {acc.x * inv, acc.y * inv}, hi = {acc.z * inv, acc.w * inv};
         uint2 w;
         w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2_t));
         w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
-        *reinterpret_cast<uint2*>(p.out + ((size_t)node * p.H + head) * D + d0) = w;
+        *reinterpret_cast<uint2*>(out_row + (k4 >> 2) * 32 + (k4 & 3) * 8) = w;
     };
     __syncthreads();
     float* const lds_f = reinterpret_cast<float*>(&sm_union);
     float* const o_s = lds_f;                                        // [kCells][kK4][64][4]
     float* const ml_s = o_s + (size_t)kCells * kK4 * 256;            // [kCells][2][64]
-    float* const fac_s = WK == 1 ? lds_f : ml_s + kCells * 128;      // [fac_rows][WQ][64]
-    float* const bigm_s = fac_s + (size_t)fac_rows<WQ>() * WQ * 64;  // [WQ][64]
-    float* const bigl_s = bigm_s + WQ * 64;                          // [WQ][64]
-    static_assert(WK <= fac_rows<WQ>(), "weight table too small");
-    if constexpr (WK == 1) {
-        // One key group: nothing to merge inside the workgroup.  Every wavefront takes its row
-        // block from registers straight to `out` (single range) or to the workspace.
+    if constexpr (WK > 1) {
+        if (wk != 0) {
+            const int cell = wk * WQ + wqw;
+            float4* dst = reinterpret_cast<float4*>(o_s) + (size_t)cell * kK4 * 64 + lane;
+#pragma unroll
+            for (int k4 = 0; k4 < kK4; ++k4)
+                dst[k4 * 64] = make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
+                                           oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]);
+            ml_s[cell * 128 + lane] = m_run[0];
+            ml_s[cell * 128 + 64 + lane] = l_run[0];
+        }
+        __syncthreads();
+        if (wk == 0) {
+#pragma unroll 1
+            for (int o = 1; o < WK; ++o) {
+                const int cell = o * WQ + wqw;
+                const float m_o = ml_s[cell * 128 + lane], l_o = ml_s[cell * 128 + 64 + lane];
+                const float big = fmaxf(m_run[0], m_o);
+                const float ref = (big == -INFINITY) ? 0.f : big;
+                const float f_mine = __builtin_amdgcn_exp2f(m_run[0] - ref), f_o = __builtin_amdgcn_exp2f(m_o - ref);
+                m_run[0] = big;
+                l_run[0] = fmaf(l_o, f_o, l_run[0] * f_mine);
+                const float4* src = reinterpret_cast<const float4*>(o_s) + (size_t)cell * kK4 * 64 + lane;
+#pragma unroll
+                for (int k4 = 0; k4 < kK4; ++k4) {
+                    const float4 v = src[k4 * 64];
+                    f32x16_t& acc = oacc[0][k4 >> 2];
+                    const int e = (k4 & 3) * 4;
+                    acc[e] = fmaf(v.x, f_o, acc[e] * f_mine);
+                    acc[e + 1] = fmaf(v.y, f_o, acc[e + 1] * f_mine);
+                    acc[e + 2] = fmaf(v.z, f_o, acc[e + 2] * f_mine);
+                    acc[e + 3] = fmaf(v.w, f_o, acc[e + 3] * f_mine);
+                }
+            }
+        }
+    }
+    if (wk == 0) {
+        // my row block, merged over the key groups of the workgroup, is in my registers
         const int q = wqw;
         if (S == 1) {
             const auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run[0]), __float_as_uint(l_run[0]), false, false);
-            const float inv = 1.0f / (__uint_as_float(r2[0]) + __uint_as_float(r2[1]));
+            const float inv = __builtin_amdgcn_rcpf(__uint_as_float(r2[0]) + __uint_as_float(r2[1]));
 #pragma unroll
             for (int k4 = 0; k4 < kK4; ++k4)
-                store_out(q, lane, k4, make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
+                store_out(k4, make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
                                                    oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]), inv);
-            return;
+        } else {
+            float4* dst = reinterpret_cast<float4*>(my_part + (size_t)q * block_words) + lane;
+#pragma unroll
+            for (int k4 = 0; k4 < kK4; ++k4)
+                dst[k4 * 64] = make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
+                                           oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]);
+            float* ml = my_part + (size_t)q * block_words + (size_t)kK4 * 256;
+            ml[lane] = m_run[0];
+            ml[64 + lane] = l_run[0];
         }
-        float4* dst = reinterpret_cast<float4*>(my_part + (size_t)q * block_words) + lane;
-#pragma unroll
-        for (int k4 = 0; k4 < kK4; ++k4)
-            dst[k4 * 64] = make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
-                                       oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]);
-        float* ml = my_part + (size_t)q * block_words + (size_t)kK4 * 256;
-        ml[lane] = m_run[0];
-        ml[64 + lane] = l_run[0];
-    } else {
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int cell = wk * WQ + wqw * R + r;
-        float4* dst = reinterpret_cast<float4*>(o_s) + (size_t)cell * kK4 * 64 + lane;
-#pragma unroll
-        for (int b = 0; b < kDBlocks; ++b)
-#pragma unroll
-            for (int rq = 0; rq < 4; ++rq)
-                dst[(b * 4 + rq) * 64] = make_float4(oacc[r][b][rq * 4], oacc[r][b][rq * 4 + 1], oacc[r][b][rq * 4 + 2], oacc[r][b][rq * 4 + 3]);
-        ml_s[cell * 128 + lane] = m_run[r];
-        ml_s[cell * 128 + 64 + lane] = l_run[r];
-    }
-    __syncthreads();
-    // weights of the key groups: per (query block, lane)
-    for (int i = tid; i < WQ * 64; i += kT) {
-        const int q = i >> 6, l = i & 63;
-        float big = -INFINITY;
-#pragma unroll 1
-        for (int o = 0; o < WK; ++o) big = fmaxf(big, ml_s[(o * WQ + q) * 128 + l]);
-        const float ref = (big == -INFINITY) ? 0.f : big;
-        float lsum = 0.f;
-#pragma unroll 1
-        for (int o = 0; o < WK; ++o) {
-            const float f = __builtin_amdgcn_exp2f(ml_s[(o * WQ + q) * 128 + l] - ref);
-            fac_s[(o * WQ + q) * 64 + l] = f;
-            lsum = fmaf(ml_s[(o * WQ + q) * 128 + 64 + l], f, lsum);
-        }
-        bigm_s[i] = big;
-        bigl_s[i] = lsum;
-    }
-    __syncthreads();
-
-    // merged output of the workgroup: straight to `out` (single range) or to the workspace
-#pragma unroll 1
-    for (int i = tid; i < WQ * kK4 * 64; i += kT) {
-        const int l = i & 63, k4 = (i >> 6) % kK4, q = i / (64 * kK4);
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 1
-        for (int o = 0; o < WK; ++o) {
-            const float f = fac_s[(o * WQ + q) * 64 + l];
-            const float4 v = reinterpret_cast<const float4*>(o_s)[((size_t)(o * WQ + q) * kK4 + k4) * 64 + l];
-            acc.x = fmaf(v.x, f, acc.x); acc.y = fmaf(v.y, f, acc.y);
-            acc.z = fmaf(v.z, f, acc.z); acc.w = fmaf(v.w, f, acc.w);
-        }
-        if (S == 1) store_out(q, l, k4, acc, 1.0f / (bigl_s[q * 64 + l] + bigl_s[q * 64 + (l ^ 32)]));
-        else reinterpret_cast<float4*>(my_part + (size_t)q * block_words)[k4 * 64 + l] = acc;
     }
     if (S == 1) return;
-    for (int i = tid; i < WQ * 64; i += kT) {
-        float* ml = my_part + (size_t)(i >> 6) * block_words + (size_t)kK4 * 256;
-        ml[i & 63] = bigm_s[i];
-        ml[64 + (i & 63)] = bigl_s[i];
-    }
-    }
     ATTN_STAMP(21);
 
     // See whether we are the last range of this unit to finish.  The partial results must be
@@ -722,57 +696,84 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     else __threadfence();
     ATTN_STAMP(23);
 
-    // Merge the ranges of the unit: weights first, then the weighted sums.  One workgroup pulls
-    // S partial results through one CU's memory pipeline, so what matters is how many loads are
-    // in flight: every thread requests all S values of an item before it touches the first
-    // (NS = S rounded up to 4, 8 or 16; the surplus requests repeat the last range).
-    const float* const unit_part = p.partials + (size_t)unit * S * WQ * block_words;
+    // Merge the ranges of the unit.  One workgroup pulls S partial results through one CU's memory
+    // pipeline, so what matters is how many loads are in flight, how few round trips there are,
+    // and that the arithmetic around them stays small.  Wavefront (row block q, key group j) merges
+    // features j * kK4 / WK .. of row block q: a lane keeps one query for the whole merge (its row
+    // of `out` and its weights are worked out once, in registers), requests all S values of a
+    // batch of items before it touches the first (NS = S rounded up to 4, 8 or 16; the surplus
+    // requests repeat the last range), and requests the first batch before the statistics, which
+    // are a round trip of their own.
+    const float* const row_part = p.partials + (size_t)unit * S * WQ * block_words + (size_t)wqw * block_words;
     const size_t range_words = (size_t)WQ * block_words;
     auto merge_ranges = [&](auto ns_c) __attribute__((always_inline)) {
         constexpr int NS = decltype(ns_c)::value;
-        for (int i = tid; i < WQ * 64; i += kT) {
-            const float* ml = unit_part + (size_t)(i >> 6) * block_words + (size_t)kK4 * 256 + (i & 63);
+        constexpr int kItems = kK4 / WK;                                 // per lane
+        constexpr int kBatch = 16 / NS < kItems ? 16 / NS : kItems;      // items requested together
+        static_assert(kItems % kBatch == 0, "batches");
+        // (addresses: a uniform base per range and item, plus the lane)
+        const float4* const src = reinterpret_cast<const float4*>(row_part) + (wk * kItems) * 64;
+        float4 v[2][kBatch][NS];   // two batches: one being summed, one in flight
+        auto request = [&](int k0, float4 (&dst)[kBatch][NS]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int r = 0; r < NS; ++r) {
+                const float4* const src_r = src + (size_t)min(r, S - 1) * (range_words / 4) + k0 * 64;
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) dst[j][r] = src_r[j * 64 + lane];
+            }
+        };
+        request(0, v[0]);
+        float f[NS];
+        float lsum = 0.f;
+        {
+            const float* ml = row_part + (size_t)kK4 * 256;
             float mv[NS], lv[NS];
 #pragma unroll
             for (int r = 0; r < NS; ++r) {
-                const float* src = ml + (size_t)min(r, S - 1) * range_words;
-                mv[r] = src[0];
-                lv[r] = src[64];
+                const float* m = ml + (size_t)min(r, S - 1) * range_words;
+                mv[r] = m[lane];
+                lv[r] = m[64 + lane];
             }
             float big = -INFINITY;
 #pragma unroll
             for (int r = 0; r < NS; ++r) big = fmaxf(big, mv[r]);
             const float ref = (big == -INFINITY) ? 0.f : big;
-            float lsum = 0.f;
 #pragma unroll
             for (int r = 0; r < NS; ++r) {
-                const float f = r < S ? __builtin_amdgcn_exp2f(mv[r] - ref) : 0.f;
-                fac_s[r * WQ * 64 + i] = f;
-                lsum = fmaf(lv[r], f, lsum);
+                f[r] = r < S ? __builtin_amdgcn_exp2f(mv[r] - ref) : 0.f;
+                lsum = fmaf(lv[r], f[r], lsum);
             }
-            bigl_s[i] = lsum;
         }
-        __syncthreads();
-#pragma unroll 1
-        for (int i = tid; i < WQ * kK4 * 64; i += kT) {
-            const int l = i & 63, k4 = (i >> 6) % kK4, q = i / (64 * kK4);
-            const float4* src = reinterpret_cast<const float4*>(unit_part + (size_t)q * block_words) + k4 * 64 + l;
-            float4 v[NS];
+        const auto l2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
+        const float inv = __builtin_amdgcn_rcpf(__uint_as_float(l2[0]) + __uint_as_float(l2[1]));
+        auto sum_up = [&](int k0, const float4 (&src_v)[kBatch][NS]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 0; r < NS; ++r) v[r] = src[(size_t)min(r, S - 1) * (range_words / 4)];
-            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int j = 0; j < kBatch; ++j) {
+                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int r = 0; r < NS; ++r) {
-                const float f = fac_s[r * WQ * 64 + q * 64 + l];   // 0 for the surplus
-                acc.x = fmaf(v[r].x, f, acc.x); acc.y = fmaf(v[r].y, f, acc.y);
-                acc.z = fmaf(v[r].z, f, acc.z); acc.w = fmaf(v[r].w, f, acc.w);
+                for (int r = 0; r < NS; ++r) {
+                    acc.x = fmaf(src_v[j][r].x, f[r], acc.x); acc.y = fmaf(src_v[j][r].y, f[r], acc.y);
+                    acc.z = fmaf(src_v[j][r].z, f[r], acc.z); acc.w = fmaf(src_v[j][r].w, f[r], acc.w);
+                }
+                store_out(wk * kItems + k0 + j, acc, inv);
             }
-            store_out(q, l, k4, acc, 1.0f / (bigl_s[q * 64 + l] + bigl_s[q * 64 + (l ^ 32)]));
+        };
+        if constexpr (kItems == kBatch) {
+            sum_up(0, v[0]);
+        } else {
+            static_assert(kItems % (2 * kBatch) == 0, "pairs of batches");
+#pragma unroll 1
+            for (int k0 = 0; k0 < kItems; k0 += 2 * kBatch) {
+                request(k0 + kBatch, v[1]);
+                sum_up(k0, v[0]);
+                if (k0 + 2 * kBatch < kItems) request(k0 + 2 * kBatch, v[0]);
+                sum_up(k0 + kBatch, v[1]);
+            }
         }
     };
     if (S <= 4) merge_ranges(std::integral_constant<int, 4>{});
-    else if (S <= 8 || fac_rows<WQ>() <= 8) merge_ranges(std::integral_constant<int, 8>{});
-    else merge_ranges(std::integral_constant<int, fac_rows<WQ>()>{});
+    else if (S <= 8) merge_ranges(std::integral_constant<int, 8>{});
+    else merge_ranges(std::integral_constant<int, kMaxSplits>{});
     ATTN_STAMP(24);
 }
 
