@@ -127,16 +127,26 @@ template <int D> __device__ __forceinline__ int v_swizzle(int row) {
     return D == 128 ? (row & 3) << 2 : ((row >> 1) & 1) << 2;
 }
 
-// Phase timestamps of workgroup 0 (100 MHz wall clock), compiled in with -DSEQTREE_STAMPS only.
+// Phase timestamps of one thread of workgroup 0 (100 MHz wall clock), compiled in with
+// -DSEQTREE_STAMPS only.  They are kept in LDS while the kernel runs -- a stamp that touched global
+// memory would wait for, or add to, the copies in flight that the tile loop counts -- and written
+// out where the thread leaves the kernel.
 #ifdef SEQTREE_STAMPS
+#ifndef SEQTREE_STAMP_THREAD
+#define SEQTREE_STAMP_THREAD 0
+#endif
 __device__ long long g_attn_stamps[128];
 __device__ int g_attn_stamp_count;
-#define ATTN_STAMP_RESET() do { if (blockIdx.x == 0 && threadIdx.x == 0) g_attn_stamp_count = 0; } while (0)
-#define ATTN_STAMP(id) do { if (blockIdx.x == 0 && threadIdx.x == 0 && g_attn_stamp_count < 63) { \
-    g_attn_stamps[2 * g_attn_stamp_count] = (id); g_attn_stamps[2 * g_attn_stamp_count + 1] = wall_clock64(); ++g_attn_stamp_count; } } while (0)
+#define ATTN_STAMP_RESET() __shared__ long long s_stamps[128]; int stamp_count = 0; \
+    const bool stamp_on = blockIdx.x == 0 && threadIdx.x == SEQTREE_STAMP_THREAD
+#define ATTN_STAMP(id) do { if (stamp_on && stamp_count < 63) { \
+    s_stamps[2 * stamp_count] = (id); s_stamps[2 * stamp_count + 1] = wall_clock64(); ++stamp_count; } } while (0)
+#define ATTN_STAMP_FLUSH() do { if (stamp_on) { \
+    for (int i = 0; i < 2 * stamp_count; ++i) g_attn_stamps[i] = s_stamps[i]; g_attn_stamp_count = stamp_count; } } while (0)
 #else
 #define ATTN_STAMP_RESET() do {} while (0)
 #define ATTN_STAMP(id) do {} while (0)
+#define ATTN_STAMP_FLUSH() do {} while (0)
 #endif
 
 // LDS: a ring of kRing tile buffers (K and V of 32 keys each), and a ring of visibility words.
@@ -235,20 +245,39 @@ __device__ __forceinline__ void softmax_second(const f32x16_t& s, float scale_lo
 // One workgroup = a unit of 32 * WQ query rows x a range of key tiles; wavefront w is cell
 // (row block w % WQ, key group w / WQ) of its WQ x WK grid.
 //
-// What bounds the tile loop at large trees (measured with the SQ counters): per tile and
-// wavefront, 16 matrix instructions (512 clocks of the SIMD's matrix pipe) stand against about
-// 100 vector instructions (16 of them exponentials at half rate: about 490 clocks), and the two
-// wavefronts of a SIMD leave every barrier in step, so the two units mostly take turns.  Vector
-// work that is not softmax arithmetic is therefore kept out of the loop: addresses are scalar
-// or immediate, row sums ride on dot2 instructions, the output is rescaled only when a score
-// outgrows the reference by 2^8.  (Tried and slower here: two row blocks per wavefront in four
-// fat wavefronts -- halves the LDS traffic, but the accumulators no longer fit the vector
-// registers and travel through AGPR moves; twelve wavefronts; splitting a tile's work into a
-// matrix phase and a vector phase with a barrier each, or rotating the loop of wavefronts 4..7
-// by half a tile; dealing equal spans of an XCD's (unit, tile) sequence to 256 workgroups
-// instead of equal key ranges -- the second prologue, epilogue and merge of a span that crosses
-// into the next unit cost what the even load saves, and wrapping the body in a loop over the
-// pieces of a span makes the compiler's tile loop 10-15 % slower.)
+// What bounds the tile loop at large trees (timing of variants with one part of the work taken
+// out, and of single instructions): per tile and wavefront, 16 matrix instructions (512 clocks of
+// the SIMD's matrix pipe) stand against about 70 vector instructions.  One wavefront issues a
+// vector instruction every 6 clocks at best, every 9 to 11 when it needs the result of the one
+// before, so a tile's softmax takes a wavefront 600 to 1000 clocks however idle the SIMD is; the
+// vector pipe has room for the second wavefront of the SIMD beside it, the matrix pipe does not.
+// A round of the two wavefronts of a SIMD costs about the two products of both (1024 clocks)
+// plus one softmax: taking the softmax out of the loop nearly halves the kernel, taking out half
+// of the matrix instructions saves a tenth, taking out the exponentials alone 2 %.  Vector work
+// that is not softmax arithmetic is kept out of the loop: addresses are scalar or immediate, row
+// sums ride on dot2 instructions, the output is rescaled only when a score outgrows the
+// reference by 2^8.  Tried and not faster here:
+//  - two row blocks per wavefront in four fat wavefronts (halves the LDS traffic, but the
+//    accumulators no longer fit the vector registers and travel through AGPR moves); twelve
+//    wavefronts; two workgroups of four wavefronts per CU with half the ring each;
+//  - raising the priority of a wavefront around its matrix instructions, or around its softmax;
+//    fetching the V fragments from LDS before the softmax instead of after it;
+//  - scores one tile ahead of the softmax (so that a wavefront has matrix work in flight while
+//    it takes exponentials), with the compiler's instruction order or with one matrix
+//    instruction pinned after every six vector instructions;
+//  - on top of that, the two wavefronts of a SIMD taking turns, one in a matrix phase (scores of
+//    tile t + 1, weighted values of tile t) while the other is in its vector phase, a barrier at
+//    every change: the matrix work then hides completely, but a lone wavefront's vector phase
+//    takes as long as both phases took before;
+//  - the scale folded into Q and minus the reference as the start value of the score product, so
+//    that the accumulator comes back as the exponent (one vector instruction per score less, 16
+//    registers more: 20 % slower);
+//  - splitting a tile's work into a matrix phase and a vector phase for all wavefronts at once,
+//    or rotating the loop of wavefronts 4..7 by half a tile;
+//  - dealing equal spans of an XCD's (unit, tile) sequence to 256 workgroups instead of equal key
+//    ranges: the second prologue, epilogue and merge of a span that crosses into the next unit
+//    cost what the even load saves, and wrapping the body in a loop over the pieces of a span
+//    makes the compiler's tile loop 10-15 % slower.
 template <int D, int WQ, int WK>
 __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const MfmaParams p) {
     constexpr int kCells = WQ * WK;
@@ -672,7 +701,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
             ml[64 + lane] = l_run[0];
         }
     }
-    if (S == 1) return;
+    if (S == 1) { ATTN_STAMP_FLUSH(); return; }
     ATTN_STAMP(21);
 
     // See whether we are the last range of this unit to finish.  The partial results must be
@@ -691,7 +720,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     }
     __syncthreads();
     ATTN_STAMP(22);
-    if (!s_last) return;
+    if (!s_last) { ATTN_STAMP_FLUSH(); return; }
     if (p.share_l2) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     else __threadfence();
     ATTN_STAMP(23);
@@ -775,6 +804,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     else if (S <= 8) merge_ranges(std::integral_constant<int, 8>{});
     else merge_ranges(std::integral_constant<int, kMaxSplits>{});
     ATTN_STAMP(24);
+    ATTN_STAMP_FLUSH();
 }
 
 }  // namespace
