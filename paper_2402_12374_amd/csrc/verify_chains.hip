@@ -200,7 +200,8 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
     // long as a twentieth of the mass is left, thread 0 takes that difference (in fp64; its error
     // is that of the initial normalisation, 1e-7 absolute) and the pass skips the sum over q.  Once
     // less is left the pass sums q again, which is also what finds the mass exactly zero.
-    NodeState ns;
+    NodeState ns, before;
+    uint32_t events = 0;
     double q_predicted = 1.0;
     bool q_summed = true;
     if (tid == 0) { node_begin(ns); ns.fallbacks = 0; ns.degenerate = 0; }
@@ -211,18 +212,17 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
             const float w_new = lane_value(row_reduce<kOpSum>(sh.part[par ^ 1][lane & 15][0]), 0);
             const float q_new = lane_value(row_reduce<kOpSum>(sh.part[par ^ 1][lane & 15][1]), 0);
             if (tid == 0) {
+                // Everybody waits for the coefficients of the next pass, so they go out first; the
+                // test of child j, which needs the state before its rejection, is worked out from
+                // a copy after the barrier, while the pass runs.
                 if (j > 0) {
                     const int fb = ns.fallbacks, dg = ns.degenerate;
                     node_apply_pass(ns, (double)w_new, q_summed ? (double)q_new : q_predicted);
-                    const uint32_t events = (uint32_t)(ns.fallbacks - fb) | ((uint32_t)(ns.degenerate - dg) << 1);
-                    sh.w_rec[j - 1][4] = __uint_as_float(events);
+                    events = (uint32_t)(ns.fallbacks - fb) | ((uint32_t)(ns.degenerate - dg) << 1);
                 }
                 if (j < K) {
-                    // records wait in shared memory; they leave together once the chain is done
+                    before = ns;
                     const bool in_s = sh.child_dup[j] != 0;
-                    const ChildTest t = node_test_child(ns, sh.child_lt[j], sh.child_ld[j], in_s, V);
-                    sh.w_rec[j][0] = t.lhs_w; sh.w_rec[j][1] = t.lhs_q;
-                    sh.w_rec[j][2] = t.rhs_r; sh.w_rec[j][3] = t.rhs_m;
                     node_reject_child(ns, in_s, V);
                     sh.ctl_zero = in_s ? -1 : sh.child_tok[j];
                     q_predicted = ns.massQ - (in_s ? 0.0 : (double)sh.child_ld[j]);
@@ -235,6 +235,15 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
         }
         __syncthreads();
         CHAIN_STAMP(10);
+        if (tid == 0) {
+            // records wait in shared memory; they leave together once the chain is done
+            if (j > 0) sh.w_rec[j - 1][4] = __uint_as_float(events);
+            if (j < K) {
+                const ChildTest t = node_test_child(before, sh.child_lt[j], sh.child_ld[j], sh.child_dup[j] != 0, V);
+                sh.w_rec[j][0] = t.lhs_w; sh.w_rec[j][1] = t.lhs_q;
+                sh.w_rec[j][2] = t.rhs_r; sh.w_rec[j][3] = t.rhs_m;
+            }
+        }
         if (j == K) break;
         const float af = sh.ctl_a, bf = sh.ctl_b;
         const int zero_token = sh.ctl_zero;
@@ -248,13 +257,15 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
             }
         }
         float r_loc = 0.f, q_loc = 0.f;
-        if (bf == 0.f && !sh.ctl_sum_q) {   // the common pass: three instructions per token
+        // (p - A q never exceeds p <= 1, so the maximum with 0 is a clamp to [0, 1], which rides on
+        // the multiply-add as an output modifier)
+        if (bf == 0.f && !sh.ctl_sum_q) {   // the common pass: two instructions per token
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) r_loc += fmaxf(fmaf(-af, qr[e], pr[e]), 0.f);
+            for (int e = 0; e < EPT; ++e) r_loc += __builtin_amdgcn_fmed3f(fmaf(-af, qr[e], pr[e]), 0.f, 1.f);
         } else if (bf == 0.f) {   // B only moves once the draft has run out of mass
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
-                r_loc += fmaxf(fmaf(-af, qr[e], pr[e]), 0.f);
+                r_loc += __builtin_amdgcn_fmed3f(fmaf(-af, qr[e], pr[e]), 0.f, 1.f);
                 q_loc += qr[e];
             }
         } else {
