@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the attention kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
 # scaled by a copy kernel of known size (profiles/tree_verify_step_C2_hbm_traffic.md gives the commands and
 # the raw counters).  Counters cannot be read from inside this process, so the figure is carried here.
-MEASURED_ATTN_TRAFFIC_BYTES = {"C2": 21.8e6 + 3.8e6}
+MEASURED_ATTN_TRAFFIC_BYTES = {"C2": 23.9e6 + 5.9e6}
 
 
 def attn_alg_bytes(cfg, n=None, P=None):
