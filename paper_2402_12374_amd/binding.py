@@ -60,6 +60,8 @@ def lib() -> C.CDLL:
         l.seq_version.restype = C.c_int
         l.seqtree_internal_copy_probe.restype = C.c_int
         l.seqtree_internal_copy_probe.argtypes = [vp, vp, sz, vp]
+        l.seqtree_internal_fast_div.restype = C.c_uint32
+        l.seqtree_internal_fast_div.argtypes = [C.c_uint32, C.c_uint32]
         _lib = l
     return _lib
 

@@ -39,6 +39,7 @@
 
 #include "seq_internal.h"
 #include "tree_attn_kernels.h"
+#include "fast_div.h"
 
 namespace seqtree {
 namespace {
@@ -72,6 +73,7 @@ struct MfmaParams {
     uint32_t* counters;
     float scale_log2;     // log2(e) / sqrt(D)
     int share_l2;         // all workgroups of a unit run on one XCD (checked once per device)
+    FastDiv by_units_per_xcd, by_query_blocks, by_G, by_splits;   // the divisions of the prologue
 };
 
 // A pointer that is the same in every lane, moved to scalar registers whatever the compiler
@@ -137,12 +139,15 @@ template <int D> __device__ __forceinline__ int v_swizzle(int row) {
 #endif
 __device__ long long g_attn_stamps[128];
 __device__ int g_attn_stamp_count;
+__device__ long long g_attn_wg_times[2 * 4096];   // start and end of every workgroup
 #define ATTN_STAMP_RESET() __shared__ long long s_stamps[128]; int stamp_count = 0; \
-    const bool stamp_on = blockIdx.x == 0 && threadIdx.x == SEQTREE_STAMP_THREAD
+    const bool stamp_on = blockIdx.x == 0 && threadIdx.x == SEQTREE_STAMP_THREAD; \
+    if (threadIdx.x == 0 && blockIdx.x < 4096) { g_attn_wg_times[2 * blockIdx.x] = wall_clock64(); g_attn_wg_times[2 * blockIdx.x + 1] = 0; }
 #define ATTN_STAMP(id) do { if (stamp_on && stamp_count < 63) { \
     s_stamps[2 * stamp_count] = (id); s_stamps[2 * stamp_count + 1] = wall_clock64(); ++stamp_count; } } while (0)
 #define ATTN_STAMP_FLUSH() do { if (stamp_on) { \
-    for (int i = 0; i < 2 * stamp_count; ++i) g_attn_stamps[i] = s_stamps[i]; g_attn_stamp_count = stamp_count; } } while (0)
+    for (int i = 0; i < 2 * stamp_count; ++i) g_attn_stamps[i] = s_stamps[i]; g_attn_stamp_count = stamp_count; } \
+    if (threadIdx.x == 0 && blockIdx.x < 4096) g_attn_wg_times[2 * blockIdx.x + 1] = wall_clock64(); } while (0)
 #else
 #define ATTN_STAMP_RESET() do {} while (0)
 #define ATTN_STAMP(id) do {} while (0)
@@ -318,16 +323,17 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     const int units_per_xcd = (total_units + 7) >> 3;
     // Range-major within an XCD: the workgroups that run at the same time then mostly work on
     // the same key range of their head and find its tiles in L2.
-    // (Integer division runs on the vector unit and leaves its result in a vector register even
-    // when every lane computes the same thing; everything derived from such a value would then
-    // be vector arithmetic, and every branch on it a divergent one.  So uniform values are moved
-    // back to scalar registers where they are born.)
-    const int split = __builtin_amdgcn_readfirstlane(idx / units_per_xcd);
-    const int local = __builtin_amdgcn_readfirstlane(idx % units_per_xcd);
+    // (An integer division is a 25-instruction sequence on the vector unit, fetched cold, and it
+    // leaves its result in a vector register even when every lane computes the same thing, so
+    // that everything derived from it would be vector arithmetic and every branch on it a
+    // divergent one.  All divisors here are fixed per launch: the host supplies multipliers, and
+    // a uniform quotient is three scalar instructions.)
+    const int split = (int)fast_div((uint32_t)idx, p.by_units_per_xcd);
+    const int local = idx - split * units_per_xcd;
     const int unit = xcd * units_per_xcd + local;
     if (split >= S || unit >= total_units) return;
-    const int g = __builtin_amdgcn_readfirstlane(unit / p.query_blocks);
-    const int qb = __builtin_amdgcn_readfirstlane(unit % p.query_blocks);
+    const int g = (int)fast_div((uint32_t)unit, p.by_query_blocks);
+    const int qb = unit - g * p.query_blocks;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and the compiler knows it
@@ -342,18 +348,19 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     for (int r = 0; r < R; ++r) {
         const int qrow = qb * kUnitRows + (wqw * R + r) * 32 + col;
         qvalid[r] = qrow < rows;
-        qi[r] = qvalid[r] ? qrow / p.G : 0;
-        qh[r] = qvalid[r] ? g * p.G + qrow % p.G : 0;
+        const int node = (int)fast_div((uint32_t)qrow, p.by_G);
+        qi[r] = qvalid[r] ? node : 0;
+        qh[r] = qvalid[r] ? g * p.G + (qrow - node * p.G) : 0;
     }
 
     // key tiles of this workgroup
     const int last_row = min(rows - 1, qb * kUnitRows + kUnitRows - 1);
-    const int i_max = __builtin_amdgcn_readfirstlane(last_row / p.G);   // tree rows beyond i_max are masked for all
+    const int i_max = (int)fast_div((uint32_t)last_row, p.by_G);   // tree rows beyond i_max are masked for all
     const int tree_tiles = i_max / kKeyTile + 1;
     const int total_tiles = p.prefix_tiles + tree_tiles;
-    // (32-bit: at most 2^26 tiles times 16 ranges; a 64-bit division is a long routine here)
-    const int t_begin = __builtin_amdgcn_readfirstlane((int)((uint32_t)total_tiles * (uint32_t)split / (uint32_t)S));
-    const int t_end = __builtin_amdgcn_readfirstlane((int)((uint32_t)total_tiles * (uint32_t)(split + 1) / (uint32_t)S));
+    // (at most 2^26 tiles times 16 ranges: below 2^31)
+    const int t_begin = (int)fast_div((uint32_t)total_tiles * (uint32_t)split, p.by_splits);
+    const int t_end = (int)fast_div((uint32_t)total_tiles * (uint32_t)(split + 1), p.by_splits);
     const int n_rounds = (t_end - t_begin + WK - 1) / WK;
 
     const uint32_t k_lds = lds_address(&sm.k[0][0]);
@@ -874,6 +881,10 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
     p.scale_log2 = 1.4426950408889634f / sqrtf((float)D);
     p.share_l2 = units_share_l2 ? 1 : 0;
     const int units = Hk * sched.query_blocks;
+    p.by_units_per_xcd = make_fast_div((uint32_t)((units + 7) >> 3));
+    p.by_query_blocks = make_fast_div((uint32_t)sched.query_blocks);
+    p.by_G = make_fast_div((uint32_t)(H / Hk));
+    p.by_splits = make_fast_div((uint32_t)sched.splits);
     if (units > kAttnMaxCounters) return SEQ_ERR_SHAPE;
     const int unit_groups = (units + 7) / 8;
     const dim3 grid((unsigned)(unit_groups * 8 * sched.splits)), block(512);
@@ -897,6 +908,9 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
 // Tuning hooks (not part of the public header): force the number of key-axis ranges and the
 // number of query blocks per workgroup (2, 4 or 8).
 #ifdef SEQTREE_STAMPS
+extern "C" void seqtree_internal_read_attn_wg_times(long long* out, int count) {
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(seqtree::g_attn_wg_times), sizeof(long long) * 2 * count);
+}
 extern "C" int seqtree_internal_read_attn_stamps(long long* out) {
     int count = 0;
     (void)hipMemcpyFromSymbol(&count, HIP_SYMBOL(seqtree::g_attn_stamp_count), sizeof(int));
@@ -906,3 +920,5 @@ extern "C" int seqtree_internal_read_attn_stamps(long long* out) {
 #endif
 extern "C" void seqtree_internal_set_attn_splits(int splits) { seqtree::g_splits_override = splits; }
 extern "C" void seqtree_internal_set_attn_wq(int wq) { seqtree::g_wq_override = wq; }
+// the prologue's division by multiplication, evaluated on the host (for the tests)
+extern "C" uint32_t seqtree_internal_fast_div(uint32_t n, uint32_t d) { return seqtree::fast_div(n, seqtree::make_fast_div(d)); }

@@ -143,3 +143,24 @@ def test_workload_generators_are_seeded_and_shaped():
     # bf16 storage: values survive a bf16 round trip exactly
     assert np.array_equal(W.quantize(v.target_logits, W.BF16), v.target_logits)
     assert (v.uniforms >= 0).all() and (v.uniforms < 1).all()
+
+
+def test_division_by_multiplication_is_exact():
+    """The attention kernel divides by per-launch constants with a host-prepared multiplier; the
+    host evaluation of that formula must equal integer division for every dividend below 2^31."""
+    fd = S.lib().seqtree_internal_fast_div
+    rng = np.random.default_rng(5)
+    divisors = list(range(1, 70)) + [127, 128, 129, 255, 256, 257, 1000, 1023, 1024, 1025, 4095, 4096, 4097,
+                                     65535, 65536, 65537, (1 << 26) - 1, 1 << 26, (1 << 30) + 1, (1 << 31) - 1]
+    divisors += [int(x) for x in rng.integers(2, 1 << 20, size=200)]
+    top = (1 << 31) - 1
+    for d in divisors:
+        edge = [0, 1, d - 1, d, d + 1, 2 * d - 1, 2 * d, top, top - 1, top - d, (top // d) * d, (top // d) * d - 1]
+        dividends = [n for n in edge if 0 <= n <= top] + [int(x) for x in rng.integers(0, top, size=64)]
+        for n in dividends:
+            assert fd(n, d) == n // d, (n, d)
+    # small divisors, every dividend up to 2^16 (the row and workgroup indices of the kernel)
+    for d in range(1, 33):
+        n = np.arange(1 << 16, dtype=np.int64)
+        got = np.array([fd(int(x), d) for x in n[:: 7]], dtype=np.int64)
+        assert np.array_equal(got, n[:: 7] // d)
