@@ -128,3 +128,33 @@ def test_every_workgroup_shape_and_range_count(d):
     finally:
         S.lib().seqtree_internal_set_attn_wq(0)
         S.lib().seqtree_internal_set_attn_splits(0)
+
+
+@pytest.mark.parametrize("H,Hk,P,n", [(4, 4, 700, 40), (16, 2, 1500, 300)])
+@pytest.mark.parametrize("order", ["rising", "falling", "spiky"])
+def test_scores_of_large_and_moving_magnitude(H, Hk, P, n, order):
+    """The running reference of the softmax has to follow scores that keep growing along the key
+    axis (every tile raises the maximum by more than the slack the kernel allows itself), must
+    not lose keys far below it when they come first, and must survive isolated huge scores."""
+    d = 128
+    rng = np.random.default_rng(P + n)
+    parent = W.geometric_tree(n, 9)
+    a = W.make_attn_inputs(H, Hk, d, P, parent, W.BF16, seed=3 * P + n)
+    # keys get a component along one direction every query shares: score = base + ramp(key)
+    u = np.zeros(d, dtype=np.float32)
+    u[:8] = 1.0
+    a.q[:] = W.quantize(a.q * 0.25 + 4.0 * u, W.BF16)          # q.u = 32, so q.k = 32 ramp + noise
+    keys = P + n
+    if order == "rising":
+        ramp = np.linspace(-8.0, 8.0, keys)                      # q.k/sqrt(d) from about -23 to +23
+    elif order == "falling":
+        ramp = np.linspace(8.0, -8.0, keys)
+    else:
+        ramp = np.where(rng.random(keys) < 0.02, 8.0, -2.0) * rng.random(keys)
+    ramp = ramp.astype(np.float32)
+    a.k_cache[:, :P, :] = W.quantize(a.k_cache[:, :P, :] * 0.25 + ramp[None, :P, None] * u[None, None, :], W.BF16)
+    a.k_tree[:] = W.quantize(a.k_tree * 0.25 + ramp[P:, None, None] * u[None, None, :], W.BF16)
+    got, want = run_attn(a), oracle_attn(a)
+    assert np.isfinite(got).all()
+    err = np.abs(got - want).max()
+    assert err <= TOL[a.dtype], err
