@@ -337,6 +337,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and the compiler knows it
+    __builtin_assume(wave >= 0 && wave < kW);   // (lets the copy plan below fold: most of its items coincide)
     const int wqw = wave % WQW, wk = wave / WQW;   // place of this wavefront in the cell grid
     const int half = lane >> 5, col = lane & 31;
     const int rows = p.G * p.n;
