@@ -738,7 +738,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     // and that the arithmetic around them stays small.  Wavefront (row block q, key group j) merges
     // features j * kK4 / WK .. of row block q: a lane keeps one query for the whole merge (its row
     // of `out` and its weights are worked out once, in registers), requests all S values of a
-    // batch of items before it touches the first (NS = S rounded up to 4, 8 or 16; the surplus
+    // batch of items before it touches the first (NS = S, rounded up beyond 8; the surplus
     // requests repeat the last range), and requests the first batch before the statistics, which
     // are a round trip of their own.
     const float* const row_part = p.partials + (size_t)unit * S * WQ * block_words + (size_t)wqw * block_words;
@@ -746,7 +746,9 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     auto merge_ranges = [&](auto ns_c) __attribute__((always_inline)) {
         constexpr int NS = decltype(ns_c)::value;
         constexpr int kItems = kK4 / WK;                                 // per lane
-        constexpr int kBatch = 16 / NS < kItems ? 16 / NS : kItems;      // items requested together
+        // items requested together: the largest power of two with at most 16 requests per lane
+        constexpr int kFit = NS <= 2 ? 8 : (NS <= 4 ? 4 : (NS <= 8 ? 2 : 1));
+        constexpr int kBatch = kFit < kItems ? kFit : kItems;
         static_assert(kItems % kBatch == 0, "batches");
         // (addresses: a uniform base per range and item, plus the lane)
         const float4* const src = reinterpret_cast<const float4*>(row_part) + (wk * kItems) * 64;
@@ -808,9 +810,20 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
             }
         }
     };
-    if (S <= 4) merge_ranges(std::integral_constant<int, 4>{});
-    else if (S <= 8) merge_ranges(std::integral_constant<int, 8>{});
-    else merge_ranges(std::integral_constant<int, kMaxSplits>{});
+    // (one copy of the merge per number of ranges up to 8: a surplus request costs as much of the
+    // CU's memory pipeline as a real one)
+    switch (S) {
+        case 2: merge_ranges(std::integral_constant<int, 2>{}); break;
+        case 3: merge_ranges(std::integral_constant<int, 3>{}); break;
+        case 4: merge_ranges(std::integral_constant<int, 4>{}); break;
+        case 5: merge_ranges(std::integral_constant<int, 5>{}); break;
+        case 6: merge_ranges(std::integral_constant<int, 6>{}); break;
+        case 7: merge_ranges(std::integral_constant<int, 7>{}); break;
+        case 8: merge_ranges(std::integral_constant<int, 8>{}); break;
+        case 9: case 10: merge_ranges(std::integral_constant<int, 10>{}); break;
+        case 11: case 12: merge_ranges(std::integral_constant<int, 12>{}); break;
+        default: merge_ranges(std::integral_constant<int, kMaxSplits>{}); break;
+    }
     ATTN_STAMP(24);
     ATTN_STAMP_FLUSH();
 }
