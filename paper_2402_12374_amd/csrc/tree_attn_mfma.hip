@@ -629,9 +629,8 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     // out is left out.
     //
     // Wavefronts of the same row block hold their cells in the same register layout, so the key
-    // groups of a workgroup are merged lane by lane: the wavefronts of key groups 1.. drop their
-    // registers into LDS (the tile rings, free by now), the wavefront of key group 0 folds them
-    // into its own registers and takes the row block to `out` (single range) or the workspace.
+    // groups of a workgroup are merged lane by lane, through LDS (the tile rings, free by now),
+    // and the merged row block goes to `out` (single range) or the workspace.
     //   o[cell][k4][lane][4]   unnormalised output; k4 = b*4 + rq holds features
     //                          b*32 + rq*8 + half*4 .. +3 of query (lane % 32), half = lane / 32
     //   ml[cell][2][64]        running maximum and (per-lane part of the) normaliser
@@ -652,61 +651,93 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     float* const lds_f = reinterpret_cast<float*>(&sm_union);
     float* const o_s = lds_f;                                        // [kCells][kK4][64][4]
     float* const ml_s = o_s + (size_t)kCells * kK4 * 256;            // [kCells][2][64]
-    if constexpr (WK > 1) {
-        if (wk != 0) {
-            const int cell = wk * WQ + wqw;
-            float4* dst = reinterpret_cast<float4*>(o_s) + (size_t)cell * kK4 * 64 + lane;
-#pragma unroll
-            for (int k4 = 0; k4 < kK4; ++k4)
-                dst[k4 * 64] = make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
-                                           oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]);
-            ml_s[cell * 128 + lane] = m_run[0];
-            ml_s[cell * 128 + 64 + lane] = l_run[0];
-        }
-        __syncthreads();
-        if (wk == 0) {
-#pragma unroll 1
-            for (int o = 1; o < WK; ++o) {
-                const int cell = o * WQ + wqw;
-                const float m_o = ml_s[cell * 128 + lane], l_o = ml_s[cell * 128 + 64 + lane];
-                const float big = fmaxf(m_run[0], m_o);
-                const float ref = (big == -INFINITY) ? 0.f : big;
-                const float f_mine = __builtin_amdgcn_exp2f(m_run[0] - ref), f_o = __builtin_amdgcn_exp2f(m_o - ref);
-                m_run[0] = big;
-                l_run[0] = fmaf(l_o, f_o, l_run[0] * f_mine);
-                const float4* src = reinterpret_cast<const float4*>(o_s) + (size_t)cell * kK4 * 64 + lane;
-#pragma unroll
-                for (int k4 = 0; k4 < kK4; ++k4) {
-                    const float4 v = src[k4 * 64];
-                    f32x16_t& acc = oacc[0][k4 >> 2];
-                    const int e = (k4 & 3) * 4;
-                    acc[e] = fmaf(v.x, f_o, acc[e] * f_mine);
-                    acc[e + 1] = fmaf(v.y, f_o, acc[e + 1] * f_mine);
-                    acc[e + 2] = fmaf(v.z, f_o, acc[e + 2] * f_mine);
-                    acc[e + 3] = fmaf(v.w, f_o, acc[e + 3] * f_mine);
-                }
-            }
-        }
-    }
-    if (wk == 0) {
-        // my row block, merged over the key groups of the workgroup, is in my registers
-        const int q = wqw;
+    auto item_of = [&](int k4) __attribute__((always_inline)) {
+        return make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
+                           oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]);
+    };
+    float* const part_ml = my_part + (size_t)wqw * block_words + (size_t)kK4 * 256;
+    float4* const part_o = reinterpret_cast<float4*>(my_part + (size_t)wqw * block_words) + lane;
+    if constexpr (WK == 1) {
+        // my row block is in my registers
         if (S == 1) {
             const auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run[0]), __float_as_uint(l_run[0]), false, false);
             const float inv = __builtin_amdgcn_rcpf(__uint_as_float(r2[0]) + __uint_as_float(r2[1]));
 #pragma unroll
-            for (int k4 = 0; k4 < kK4; ++k4)
-                store_out(k4, make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
-                                                   oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]), inv);
+            for (int k4 = 0; k4 < kK4; ++k4) store_out(k4, item_of(k4), inv);
         } else {
-            float4* dst = reinterpret_cast<float4*>(my_part + (size_t)q * block_words) + lane;
 #pragma unroll
-            for (int k4 = 0; k4 < kK4; ++k4)
-                dst[k4 * 64] = make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
-                                           oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]);
-            float* ml = my_part + (size_t)q * block_words + (size_t)kK4 * 256;
-            ml[lane] = m_run[0];
-            ml[64 + lane] = l_run[0];
+            for (int k4 = 0; k4 < kK4; ++k4) part_o[k4 * 64] = item_of(k4);
+            part_ml[lane] = m_run[0];
+            part_ml[64 + lane] = l_run[0];
+        }
+    } else {
+        // Every wavefront drops its cell; wavefront (row block q, key group j) then merges items
+        // j * kK4 / WK .. of row block q over the WK cells (a lone wavefront issues a vector
+        // instruction every 6 to 10 clocks: the merge is shared by all, not left to one per row
+        // block).  Its own items it takes from registers, which is why the fold is written once
+        // per key group: register arrays want literal indices.
+        {
+            const int cell = wk * WQ + wqw;
+            float4* dst = reinterpret_cast<float4*>(o_s) + (size_t)cell * kK4 * 64 + lane;
+#pragma unroll
+            for (int k4 = 0; k4 < kK4; ++k4) dst[k4 * 64] = item_of(k4);
+            ml_s[cell * 128 + lane] = m_run[0];
+            ml_s[cell * 128 + 64 + lane] = l_run[0];
+        }
+        __syncthreads();
+        float f[WK];
+        float big = -INFINITY, lsum = 0.f;
+#pragma unroll
+        for (int o = 0; o < WK; ++o) {
+            f[o] = ml_s[(o * WQ + wqw) * 128 + lane];
+            big = fmaxf(big, f[o]);
+        }
+        const float ref = (big == -INFINITY) ? 0.f : big;
+#pragma unroll
+        for (int o = 0; o < WK; ++o) {
+            f[o] = __builtin_amdgcn_exp2f(f[o] - ref);
+            lsum = fmaf(ml_s[(o * WQ + wqw) * 128 + 64 + lane], f[o], lsum);
+        }
+        constexpr int kMine = kK4 / WK;
+        float4 acc[kMine];
+        auto fold = [&](auto j_c) __attribute__((always_inline)) {
+            constexpr int J = decltype(j_c)::value;
+#pragma unroll
+            for (int i = 0; i < kMine; ++i) {
+                const float4 mine = item_of(J * kMine + i);
+                acc[i] = make_float4(mine.x * f[J], mine.y * f[J], mine.z * f[J], mine.w * f[J]);
+            }
+#pragma unroll
+            for (int o = 0; o < WK; ++o) {
+                if (o == J) continue;
+                const float4* src = reinterpret_cast<const float4*>(o_s) + ((size_t)(o * WQ + wqw) * kK4 + J * kMine) * 64 + lane;
+#pragma unroll
+                for (int i = 0; i < kMine; ++i) {
+                    const float4 v = src[i * 64];
+                    acc[i].x = fmaf(v.x, f[o], acc[i].x); acc[i].y = fmaf(v.y, f[o], acc[i].y);
+                    acc[i].z = fmaf(v.z, f[o], acc[i].z); acc[i].w = fmaf(v.w, f[o], acc[i].w);
+                }
+            }
+        };
+        if (wk == 0) fold(std::integral_constant<int, 0>{});
+        else if (wk == 1) fold(std::integral_constant<int, 1>{});
+        else if constexpr (WK > 2) {
+            if (wk == 2) fold(std::integral_constant<int, 2>{});
+            else fold(std::integral_constant<int, 3>{});
+        }
+        static_assert(WK == 2 || WK == 4, "one fold per key group");
+        if (S == 1) {
+            const auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
+            const float inv = __builtin_amdgcn_rcpf(__uint_as_float(r2[0]) + __uint_as_float(r2[1]));
+#pragma unroll
+            for (int i = 0; i < kMine; ++i) store_out(wk * kMine + i, acc[i], inv);
+        } else {
+#pragma unroll
+            for (int i = 0; i < kMine; ++i) part_o[(wk * kMine + i) * 64] = acc[i];
+            if (wk == 0) {
+                part_ml[lane] = big;
+                part_ml[64 + lane] = lsum;
+            }
         }
     }
     if (S == 1) { ATTN_STAMP_FLUSH(); return; }
