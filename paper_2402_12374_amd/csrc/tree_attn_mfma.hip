@@ -874,8 +874,9 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     // tiles of a round) and key ranges per unit.  One workgroup fits on a CU at a time, so a
     // launch runs in batches of 256 workgroups; a workgroup costs its rounds -- dearer the more
     // tiles a round copies -- plus a fixed prologue/epilogue plus the merge of the ranges
-    // (figures in tenths of a microsecond, from measurements on the configurations of the paper's
-    // models).  A wq beyond what the rows of a KV head fill is never considered; a smaller one
+    // (figures in tenths of a microsecond, fitted to the measured times of every (wq, ranges) pair
+    // at the head shapes of the paper's models and trees of 16 to 768 nodes: the choice is within
+    // 10 % of the best pair everywhere, the best pair itself in 24 of 28 cases).  A wq beyond what the rows of a KV head fill is never considered; a smaller one
     // is, because it multiplies the units when there are few KV heads.
     const int wq_cover = rows <= 64 ? 2 : (rows <= 128 ? 4 : 8);
     long best = -1;
@@ -885,13 +886,13 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
         if (g_wq_override > 0 && wq != std::min(g_wq_override, wq_cover)) continue;
         const int wk = kMaxCells / wq;
         const int units = Hk * ((rows + 32 * wq - 1) / (32 * wq));
-        const long round_cost = wk == 1 ? 9 : (wk == 2 ? 14 : 20);
+        const long round_cost = wk == 1 ? 9 : (wk == 2 ? 10 : 13);
         const int max_splits = std::min(kMaxSplits, std::max(1, tiles / wk));
         for (int cand = 1; cand <= max_splits; ++cand) {
             if (g_splits_override > 0 && cand != std::min(g_splits_override, max_splits)) continue;
             const long batches = ((long)units * cand + 255) / 256;
             const long rounds = (tiles + cand * wk - 1) / (cand * wk);
-            const long cost = batches * (rounds * round_cost + 100 + (cand > 1 ? 4 * cand * wq / 2 : 0));
+            const long cost = batches * (rounds * round_cost + 100 + (cand > 1 ? 5 * cand * wq / 2 : 0));
             if (best < 0 || cost < best) { best = cost; s.wq = wq; s.splits = cand; }
         }
     }
