@@ -313,6 +313,10 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
 
     ATTN_STAMP_RESET();
     ATTN_STAMP(0);
+    // The arguments span four cache lines that nobody has touched yet; left to itself the compiler
+    // fetches them in three groups where they are first needed, a trip to memory each.  Asking
+    // for one field of every line here puts all of them in flight at once.
+    asm volatile("" :: "s"(p.q), "s"(p.words_per_row), "s"(p.scale_log2), "s"(p.by_splits.one));
     const int S = p.splits;
     const int bid = blockIdx.x;
     // Consecutive workgroup ids go to consecutive XCDs, each with its own L2.  Give every XCD a
