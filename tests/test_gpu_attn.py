@@ -116,11 +116,13 @@ def test_every_workgroup_shape_and_range_count(d):
     rng = np.random.default_rng(11)
     # 9 x 4 = 36 query rows per KV head would take wq = 2; 70 x 4 = 280 rows lets every wq apply
     parent = W.random_topological_tree(70, rng)
-    a = W.make_attn_inputs(8, 2, d, 333, parent, W.BF16, seed=d, prefix_cap=340)
+    # 1101 prefix keys + 70 tree keys = 38 tiles: up to 9 ranges with wq = 2 and all 16 with wq = 4, 8
+    # (the merge of the ranges is compiled once per number of ranges up to 8, then for 10, 12, 16)
+    a = W.make_attn_inputs(8, 2, d, 1101, parent, W.BF16, seed=d, prefix_cap=1110)
     ref = oracle_attn(a)
     try:
         for wq in (2, 4, 8):
-            for splits in (1, 2, 3, 5, 8, 13, 16):
+            for splits in range(1, 17):
                 S.lib().seqtree_internal_set_attn_wq(wq)
                 S.lib().seqtree_internal_set_attn_splits(splits)
                 err = np.abs(run_attn(a) - ref).max()
