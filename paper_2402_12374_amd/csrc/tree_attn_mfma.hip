@@ -273,7 +273,12 @@ __device__ __forceinline__ void softmax_second(const f32x16_t& s, float scale_lo
 //  - on top of that, the two wavefronts of a SIMD taking turns, one in a matrix phase (scores of
 //    tile t + 1, weighted values of tile t) while the other is in its vector phase, a barrier at
 //    every change: the matrix work then hides completely, but a lone wavefront's vector phase
-//    takes as long as both phases took before;
+//    takes as long as both phases took before; and the same with two tiles per phase (two
+//    independent softmax steps fill each other's latencies: the vector phase of a pair of tiles
+//    then takes 0.55 us), K copied a pair of tiles further ahead than V, fragments requested
+//    from LDS a group ahead of their matrix instructions: now the 32 matrix instructions of a
+//    phase take 1.04 us beside the other wavefront's vector phase, twice what they take alone,
+//    and the kernel is as fast as before;
 //  - the scale folded into Q and minus the reference as the start value of the score product, so
 //    that the accumulator comes back as the exponent (one vector instruction per score less, 16
 //    registers more: 20 % slower);
