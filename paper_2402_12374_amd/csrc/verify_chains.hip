@@ -80,12 +80,15 @@ __device__ __forceinline__ bool get(const unsigned long long* src, uint32_t tag,
 #ifdef SEQTREE_STAMPS
 __device__ long long g_chain_stamps[64];
 __device__ int g_chain_stamp_count;
+__device__ long long g_chain_wg_times[4 * 1024];   // per workgroup: start, rows in registers, chain done, end
 #define CHAIN_STAMP_RESET() do { if (blockIdx.x == 0 && threadIdx.x == 0) g_chain_stamp_count = 0; } while (0)
+#define CHAIN_WG_TIME(k) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_chain_wg_times[4 * blockIdx.x + (k)] = wall_clock64(); } while (0)
 #define CHAIN_STAMP(id) do { if (blockIdx.x == 0 && threadIdx.x == 0 && g_chain_stamp_count < 31) { \
     g_chain_stamps[2 * g_chain_stamp_count] = (id); g_chain_stamps[2 * g_chain_stamp_count + 1] = wall_clock64(); ++g_chain_stamp_count; } } while (0)
 #else
 #define CHAIN_STAMP_RESET() do {} while (0)
 #define CHAIN_STAMP(id) do {} while (0)
+#define CHAIN_WG_TIME(k) do {} while (0)
 #endif
 
 template <typename LT, int CH>
@@ -106,6 +109,7 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
     const uint32_t tag = __hip_atomic_load(p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
     CHAIN_STAMP_RESET();
     CHAIN_STAMP(0);
+    CHAIN_WG_TIME(0);
 
     const bool vec_ok = (V % (16 / (int)sizeof(LT)) == 0) &&
                         ((reinterpret_cast<uintptr_t>(p.target) | reinterpret_cast<uintptr_t>(p.draft)) & 15) == 0;
@@ -190,6 +194,7 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
         }
     }
     CHAIN_STAMP(2);
+    CHAIN_WG_TIME(1);
 
     // ---- the chain: children in order, each taken as rejected ---------------------------------
     // Thread 0 owns the scalar state.  Iteration j: it applies the pass that followed child j-1,
@@ -346,6 +351,7 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
         __syncthreads();
     }
     CHAIN_STAMP(30);
+    CHAIN_WG_TIME(2);
 
     // ---- hand over, and see whether everybody else is done ------------------------------------
     for (int k = tid; k < K; k += kThreads) {
@@ -369,6 +375,7 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
     }
     __syncthreads();
     CHAIN_STAMP(41);
+    CHAIN_WG_TIME(3);
     if (!sh.last) return;
 
     // ---- the walk (Sec. 2.2: Algorithm 2 applied recursively from the root) -------------------
@@ -481,6 +488,9 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
 }  // namespace
 
 #ifdef SEQTREE_STAMPS
+extern "C" void seqtree_internal_read_chain_wg_times(long long* out, int count) {
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_chain_wg_times), sizeof(long long) * 4 * count);
+}
 extern "C" int seqtree_internal_read_chain_stamps(long long* out) {
     int count = 0;
     (void)hipMemcpyFromSymbol(&count, HIP_SYMBOL(g_chain_stamp_count), sizeof(int));
