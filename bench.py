@@ -282,6 +282,11 @@ def main() -> int:
     verify_ev_s, _ = timed(run_verify, blocks)
     attn_us = attn_ev_s / steps * 1e6
     verify_us = verify_ev_s / steps * 1e6
+    # spread of the step latency: a few blocks timed one by one (outside the timed region above)
+    per_block_us = sorted(timed(run_step, 1)[0] / per_block * 1e6 for _ in range(min(20, blocks)))
+    pct = lambda q: round(per_block_us[min(len(per_block_us) - 1, int(q * len(per_block_us)))], 3)
+    spread = {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90), "blocks": len(per_block_us),
+              "steps_per_block": per_block}
 
     # ---- results still right?  (set 0 is the seeded host-generated one) -------------------
     v0 = verify_sets[0]
@@ -311,10 +316,10 @@ def main() -> int:
     moved = ((n - leaves) * 2 + leaves) * V * e if per_node else verify_bytes
     # The per-node kernel is bound by the vector unit of the ONE compute unit that holds the node with
     # the longest sibling chain: per vocabulary entry 2 x 8 instruction slots for the two softmaxes
-    # (conversion, maximum, fma, exponential at half rate, sum, scaling) and 3 per rejection (fma, max,
+    # (conversion, maximum, fma, exponential at half rate, sum, scaling) and 2 per rejection (clamped fma,
     # add), on 64 lanes per clock (4 SIMDs x 16 lanes) at 2.4 GHz.
     k_max = max(len(ch) for ch in W.children_lists(parent))
-    chain_slots = V * (16 + 3 * k_max)
+    chain_slots = V * (16 + 2 * k_max)
     chain_us = chain_slots / 64.0 / 2.4e9 * 1e6
     verify_info = {"kernel": "verify_chains_kernel" if per_node else "verify_walk_kernel",
                    "avg_launch_us": round(verify_us, 3),
@@ -372,6 +377,7 @@ def main() -> int:
         "tree_tokens_per_s": round(n / (step_us * 1e-6), 1),
         "attn_us_per_layer": round(attn_us, 3), "verify_us": round(verify_us, 3),
         "gpu_event_us_per_step": round(ev_s / steps * 1e6, 3),
+        "step_us_spread": spread,
         "roofline": roofline, "verify": verify_info, "cpu_baseline": cpu,
     }
     if args.yardstick_mib > 0:
