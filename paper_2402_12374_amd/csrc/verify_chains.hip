@@ -33,6 +33,7 @@ struct ChainShared {
     float ctl_a, ctl_b;                // coefficients of the residual for the next pass
     int ctl_zero;                      // token whose probabilities the next pass clears (-1: none)
     int ctl_sum_q;                     // the next pass also sums the draft mass that is left
+    int ctl_stop;                      // the child before was accepted: the walk leaves this node through it, nothing after it is needed
     BlockPick pick;
     int bonus_token;
     float bonus_info[3];               // total mass, CDF just below and just above the bonus token
@@ -42,6 +43,7 @@ struct ChainShared {
     float child_ld[SEQ_MAX_TREE];
     int child_tok[SEQ_MAX_TREE];
     unsigned char child_dup[SEQ_MAX_TREE];
+    float child_u[SEQ_MAX_TREE];       // the children's uniforms
     // the final walk (last workgroup only)
     int w_child_start[SEQ_MAX_TREE + 1];
     int w_child_list[SEQ_MAX_TREE];
@@ -129,6 +131,7 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
     for (int k = tid; k < K; k += kThreads) {
         const int s = min(max(p.tokens[p.child_list[c_begin + k]], 0), V - 1);  // stay inside the row
         sh.child_tok[k] = s;
+        sh.child_u[k] = p.uniforms[p.child_list[c_begin + k]];
         sh.child_lt[k] = load_logit<LT>(trow, s) * p.inv_T;
         sh.child_ld[k] = load_logit<LT>(drow, s) * p.inv_T;
         bool dup = false;
@@ -206,6 +209,7 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
     // is that of the initial normalisation, 1e-7 absolute) and the pass skips the sum over q.  Once
     // less is left the pass sums q again, which is also what finds the mass exactly zero.
     NodeState ns, before;
+    bool accepted = false, stopped = false;   // (accepted: thread 0 only)
     uint32_t events = 0;
     double q_predicted = 1.0;
     bool q_summed = true;
@@ -219,13 +223,19 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
             if (tid == 0) {
                 // Everybody waits for the coefficients of the next pass, so they go out first; the
                 // test of child j, which needs the state before its rejection, is worked out from
-                // a copy after the barrier, while the pass runs.
-                if (j > 0) {
+                // a copy after the barrier, while the pass runs.  The uniforms are inputs: if that
+                // test accepts, the walk will leave this node through child j and never look at
+                // the later children or at this node's bonus token, so the chain ends at the next
+                // step (the pass under way is the price of not waiting for the test here).
+                sh.ctl_stop = accepted ? 1 : 0;
+                if (accepted) {
+                    sh.w_rec[j - 1][4] = 0.f;   // no rejection followed child j - 1
+                } else if (j > 0) {
                     const int fb = ns.fallbacks, dg = ns.degenerate;
                     node_apply_pass(ns, (double)w_new, q_summed ? (double)q_new : q_predicted);
                     events = (uint32_t)(ns.fallbacks - fb) | ((uint32_t)(ns.degenerate - dg) << 1);
                 }
-                if (j < K) {
+                if (j < K && !accepted) {
                     before = ns;
                     const bool in_s = sh.child_dup[j] != 0;
                     node_reject_child(ns, in_s, V);
@@ -240,6 +250,14 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
         }
         __syncthreads();
         CHAIN_STAMP(10);
+        if (sh.ctl_stop) {
+            for (int k = j + tid; k < K; k += kThreads) {
+#pragma unroll
+                for (int w = 0; w < kChildRecordWords; ++w) sh.w_rec[k][w] = 0.f;   // 0 < 0: never accepted
+            }
+            stopped = true;
+            break;
+        }
         if (tid == 0) {
             // records wait in shared memory; they leave together once the chain is done
             if (j > 0) sh.w_rec[j - 1][4] = __uint_as_float(events);
@@ -247,6 +265,7 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
                 const ChildTest t = node_test_child(before, sh.child_lt[j], sh.child_ld[j], sh.child_dup[j] != 0, V);
                 sh.w_rec[j][0] = t.lhs_w; sh.w_rec[j][1] = t.lhs_q;
                 sh.w_rec[j][2] = t.rhs_r; sh.w_rec[j][3] = t.rhs_m;
+                accepted = t.accepts(sh.child_u[j]);
             }
         }
         if (j == K) break;
@@ -289,7 +308,10 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
     }
 
     // ---- the bonus token this node would emit: x ~ R by inverse CDF with uniforms[0] ----------
-    {
+    if (stopped) {   // the walk goes on through the accepted child: no token is drawn here
+        if (tid == 0) { sh.bonus_token = -1; sh.bonus_info[0] = sh.bonus_info[1] = sh.bonus_info[2] = 0.f; }
+        __syncthreads();
+    } else {
         const float af = sh.ctl_a, bf = sh.ctl_b;
         const float u0 = p.uniforms[0];
         float mass[CH];
