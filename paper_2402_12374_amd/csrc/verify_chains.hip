@@ -132,31 +132,37 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
         const int s = min(max(p.tokens[p.child_list[c_begin + k]], 0), V - 1);  // stay inside the row
         sh.child_tok[k] = s;
         sh.child_u[k] = p.uniforms[p.child_list[c_begin + k]];
-        sh.child_lt[k] = load_logit<LT>(trow, s) * p.inv_T;
-        sh.child_ld[k] = load_logit<LT>(drow, s) * p.inv_T;
+        sh.child_lt[k] = load_logit<LT>(trow, s);   // raw: the temperature is in the exponent's slope
+        sh.child_ld[k] = load_logit<LT>(drow, s);
         bool dup = false;
         for (int j = 0; j < k; ++j) dup |= min(max(p.tokens[p.child_list[c_begin + j]], 0), V - 1) == s;
         sh.child_dup[k] = dup ? 1 : 0;
     }
 
     // ---- softmax of both rows: per wavefront first, then folded by everybody ------------------
+    // The bulk of the vocabulary goes through the bare hardware exponential, one fused
+    // multiply-add and one v_exp_f32 per token: p ~ 2^(x * slope + b), slope = log2(e) / T.  The
+    // product is exact inside the multiply-add, so what matters is b: it stands for minus the
+    // wavefront's maximum times slope, and if it were that product rounded to a float, every
+    // wavefront would scale its tokens by its own factor 1 +- 1e-6 that the later rescaling knows
+    // nothing of -- an error that the accept ratios, which subtract nearly equal numbers when the
+    // drafter is good, magnify several times.  So b is rounded to a multiple of 1/256 instead:
+    // sums and differences of such offsets are exact, the reference is merely not quite the
+    // maximum (values reach 2^(1/256) at most).  The probabilities that decide an accept test
+    // (the children's tokens) take the same offsets with a compensated product and exponential.
+    constexpr float kLog2e = 1.44269504088896341f;
+    const float slope = p.inv_T * kLog2e;
+    auto offset_of = [&](float raw_max) __attribute__((always_inline)) {
+        return raw_max == -INFINITY ? INFINITY : __builtin_rintf(-raw_max * slope * 256.0f) * (1.0f / 256.0f);
+    };
     float mt_wave = -INFINITY, md_wave = -INFINITY;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) { mt_wave = fmaxf(mt_wave, pr[e]); md_wave = fmaxf(md_wave, qr[e]); }
-    // (raw logits so far: the temperature goes into the constants of the exponent, and the
-    // maxima are tempered here -- multiplying by a positive number commutes with taking them)
-    mt_wave = wave_reduce<kOpMax>(mt_wave) * p.inv_T;
-    md_wave = wave_reduce<kOpMax>(md_wave) * p.inv_T;
+    const float bt_wave = offset_of(wave_reduce<kOpMax>(mt_wave));   // +inf: nothing but -inf in my part of the row
+    const float bd_wave = offset_of(wave_reduce<kOpMax>(md_wave));
     {
-        // The bulk of the vocabulary goes through the bare hardware exponential: e^(x - m) as
-        // 2^(x * log2(e) - m * log2(e)), a fused multiply-add and one v_exp_f32 per token.  The
-        // rounding of the product costs up to |x - m| * 2^-24 of relative accuracy, which only
-        // touches terms that are negligible in every sum taken below; the probabilities that
-        // decide an accept test (the children's tokens) take the compensated exponential.
-        constexpr float kLog2e = 1.44269504088896341f;
-        const float slope = p.inv_T * kLog2e;
-        const float bt = mt_wave == -INFINITY ? 0.f : -mt_wave * kLog2e;
-        const float bd = md_wave == -INFINITY ? 0.f : -md_wave * kLog2e;
+        const float bt = bt_wave == INFINITY ? 0.f : bt_wave;
+        const float bd = bd_wave == INFINITY ? 0.f : bd_wave;
         float zt = 0.f, zd = 0.f;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
@@ -167,33 +173,47 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
         }
         zt = wave_reduce<kOpSum>(zt);
         zd = wave_reduce<kOpSum>(zd);
-        if (lane == 0) { sh.part[0][wave][0] = mt_wave; sh.part[0][wave][1] = zt; sh.part[0][wave][2] = md_wave; sh.part[0][wave][3] = zd; }
+        if (lane == 0) { sh.part[0][wave][0] = bt_wave; sh.part[0][wave][1] = zt; sh.part[0][wave][2] = bd_wave; sh.part[0][wave][3] = zd; }
     }
     __syncthreads();
     CHAIN_STAMP(1);
-    float mt, md, inv_zt, inv_zd;
+    float bt_row, bd_row, inv_zt, inv_zd;   // offsets of the rows (those of the wavefronts with the largest maxima)
     {
         // every wavefront folds the same 16 partials in the same order: identical results
         const int w = lane & 15;
-        const float mt_w = sh.part[0][w][0], zt_w = sh.part[0][w][1];
-        const float md_w = sh.part[0][w][2], zd_w = sh.part[0][w][3];
-        mt = lane_value(row_reduce<kOpMax>(mt_w), 0);
-        md = lane_value(row_reduce<kOpMax>(md_w), 0);
-        const float zt = lane_value(row_reduce<kOpSum>(zt_w > 0.f ? zt_w * exp_fast(mt_w - mt) : 0.f), 0);
-        const float zd = lane_value(row_reduce<kOpSum>(zd_w > 0.f ? zd_w * exp_fast(md_w - md) : 0.f), 0);
+        const float bt_w = sh.part[0][w][0], zt_w = sh.part[0][w][1];
+        const float bd_w = sh.part[0][w][2], zd_w = sh.part[0][w][3];
+        bt_row = -lane_value(row_reduce<kOpMax>(-bt_w), 0);
+        bd_row = -lane_value(row_reduce<kOpMax>(-bd_w), 0);
+        // (bt_row - bt_w is an exact multiple of 1/256, at most 0: the hardware exponential of it
+        // is the same number wherever it is taken)
+        const float zt = lane_value(row_reduce<kOpSum>(bt_w != INFINITY ? zt_w * __builtin_amdgcn_exp2f(bt_row - bt_w) : 0.f), 0);
+        const float zd = lane_value(row_reduce<kOpSum>(bd_w != INFINITY ? zd_w * __builtin_amdgcn_exp2f(bd_row - bd_w) : 0.f), 0);
         inv_zt = 1.0f / zt;
         inv_zd = 1.0f / zd;
-        const float ft = mt_wave == -INFINITY ? 0.f : exp_fast(mt_wave - mt) * inv_zt;
-        const float fd = md_wave == -INFINITY ? 0.f : exp_fast(md_wave - md) * inv_zd;
+        const float ft = bt_wave == INFINITY ? 0.f : __builtin_amdgcn_exp2f(bt_row - bt_wave) * inv_zt;
+        const float fd = bd_wave == INFINITY ? 0.f : __builtin_amdgcn_exp2f(bd_row - bd_wave) * inv_zd;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) { pr[e] *= ft; qr[e] *= fd; }
     }
     // the children's logits become probabilities in the first wavefront, whose first lane is
     // their only reader: no barrier needed
     if (wave == 0) {
+        auto exact_prob = [&](float raw, float b_row, float inv_z) __attribute__((always_inline)) {
+            // 2^(raw * slope + b_row) / z with the rounding errors of the product and of the sum
+            // carried into the result
+            if (raw == -INFINITY || b_row == INFINITY) return 0.f;
+            const float hi = raw * slope;
+            const float lo = fmaf(raw, slope, -hi);
+            const float sum = hi + b_row;
+            const float bb = sum - hi;
+            const float err = (hi - (sum - bb)) + (b_row - bb);
+            const float e2 = __builtin_amdgcn_exp2f(sum);
+            return fmaf(e2, (lo + err) * 0.693147180559945309f, e2) * inv_z;
+        };
         for (int k = lane; k < K; k += 64) {
-            sh.child_lt[k] = prob_of(sh.child_lt[k], mt, inv_zt);
-            sh.child_ld[k] = prob_of(sh.child_ld[k], md, inv_zd);
+            sh.child_lt[k] = exact_prob(sh.child_lt[k], bt_row, inv_zt);
+            sh.child_ld[k] = exact_prob(sh.child_ld[k], bd_row, inv_zd);
         }
     }
     CHAIN_STAMP(2);

@@ -49,6 +49,30 @@ def test_shapes_and_temperatures(V, n, dtype, T):
     assert flagged <= 1
 
 
+@pytest.mark.parametrize("sigma_d", [0.8, 0.4, 0.15])
+def test_good_drafters_accept_at_every_sibling_position(sigma_d):
+    """With a draft close to the target the walk accepts often, and not only first children: the
+    per-node kernel ends a node's chain at the child its uniform accepts, wherever in the sibling
+    order that is, and must leave the same path, bonus token and trace as the checker."""
+    flagged, positions, lengths = 0, set(), []
+    for rep in range(10):
+        parent = W.geometric_tree(64, 6) if rep % 2 == 0 else W.random_topological_tree(48, np.random.default_rng(100 + rep))
+        v = W.make_verify_inputs(parent, 32000 if rep < 4 else 5000, 3.0, sigma_d, 0.6, W.BF16, seed=7000 + rep)
+        got = run_verify(v)
+        flagged += check_verify(v, got) == "flagged"
+        ch = W.children_lists(parent)
+        path = [int(x) for x in got[0] if x >= 0]
+        lengths.append(len(path))
+        prev = 0
+        for node in path:
+            positions.add(ch[prev].index(node))
+            prev = node
+    assert flagged <= 1
+    assert max(lengths) >= 2          # the inputs do exercise acceptance ...
+    if sigma_d >= 0.4:
+        assert len(positions) >= 2    # ... and not only of first children
+
+
 def test_long_accepted_paths_when_draft_equals_target():
     # ratio exactly 1 at the first child of every node: the walk runs to a leaf
     for rep in range(3):
