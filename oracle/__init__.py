@@ -28,6 +28,9 @@ def lib() -> C.CDLL:
         _LIB = C.CDLL(path)
         _LIB.oracle_tree_attn_row.restype = C.c_int
         _LIB.oracle_tree_attn.restype = C.c_int
+        _LIB.oracle_draft_sample.restype = C.c_int
+        _LIB.oracle_draft_uniform.restype = C.c_double
+        _LIB.oracle_philox4x32_10.restype = None
         _LIB.oracle_verify.restype = C.c_int
         _LIB.oracle_verify_trials.restype = C.c_int
     return _LIB
@@ -163,3 +166,51 @@ def verify_trials(target_logits, draft_logits, tree_tokens, parent, temperature:
     if rc:
         raise ValueError(f"oracle_verify_trials rc={rc}")
     return plen, first, bonus
+
+
+# --------------------------------------------------------------------------
+# the drafter's ordered draw of child tokens (sampling without replacement, Sec. 3.2.1 / 4.1)
+# --------------------------------------------------------------------------
+@dataclass
+class DraftSample:
+    tokens: np.ndarray       # [rows, k_stride] int32: the drawn tokens in order, then -1
+    order_keys: np.ndarray   # [rows, k_stride + 1] float64: keys of the first k+1 tokens of the order
+    order_class: np.ndarray  # [rows, k_stride + 1] int32: 1 where that token had zero probability
+
+    def closest_call(self, r: int, k: int) -> float:
+        """Smallest gap between neighbours among the first k+1 keys of row r's order (inf if
+        the neighbours are of different classes): how far the order is from flipping."""
+        keys, cls = self.order_keys[r, : k + 1], self.order_class[r, : k + 1]
+        gaps = [keys[j] - keys[j + 1] for j in range(len(keys) - 1)
+                if cls[j] == cls[j + 1] and np.isfinite(keys[j]) and np.isfinite(keys[j + 1])]
+        return min(gaps) if gaps else float("inf")
+
+
+def philox4x32_10(counter, key) -> np.ndarray:
+    c = np.ascontiguousarray(counter, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(c.ctypes.data_as(C.c_void_p), k.ctypes.data_as(C.c_void_p),
+                               out.ctypes.data_as(C.c_void_p))
+    return out
+
+
+def draft_uniform(seed: int, step: int, row: int, x: int) -> float:
+    return float(lib().oracle_draft_uniform(C.c_uint64(seed), C.c_uint64(step), C.c_int32(row), C.c_int32(x)))
+
+
+def draft_sample(draft_logits, n_children, temperature: float, seed: int, step: int,
+                 k_stride: Optional[int] = None) -> DraftSample:
+    dl = _f32(draft_logits)
+    nc = _i32(n_children)
+    rows, V = dl.shape
+    ks = int(max(1, nc.max())) if k_stride is None else int(k_stride)
+    tokens = np.full((rows, ks), -1, dtype=np.int32)
+    keys = np.zeros((rows, ks + 1), dtype=np.float64)
+    cls = np.zeros((rows, ks + 1), dtype=np.int32)
+    rc = lib().oracle_draft_sample(_ptr(dl), C.c_int32(rows), C.c_int32(V), _ptr(nc),
+                                   C.c_double(temperature), C.c_uint64(seed), C.c_uint64(step),
+                                   C.c_int32(ks), _ptr(tokens), _ptr(keys), _ptr(cls))
+    if rc:
+        raise ValueError(f"oracle_draft_sample rc={rc}")
+    return DraftSample(tokens, keys, cls)
