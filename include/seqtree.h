@@ -2,7 +2,8 @@
  * seqtree -- the target model's verification step over a speculated token tree
  * (Sequoia, arxiv 2402.12374), as a C-ABI library for AMD MI355X (gfx950).
  *
- * Two operations make up the step:
+ * Two operations make up the step (a third, seq_draft_sample, is the drafter's step just
+ * before it):
  *   seq_tree_attn   one attention layer of the single target forward pass that scores every
  *                   token of the tree at once (Sec. 1: the tree is "verified in parallel
  *                   through a single forward pass"; Sec. 2.1: the root stands for the current
@@ -52,6 +53,7 @@ extern "C" {
 
 #define SEQ_MAX_TREE 1024
 #define SEQ_MAX_VOCAB 524288
+#define SEQ_MAX_CHILDREN 64      /* most tokens seq_draft_sample draws for one node */
 
 /*
  * Tree-masked attention with grouped-query heads (one layer).
@@ -139,10 +141,46 @@ int seq_verify(const void* target_logits, const void* draft_logits,
 #define SEQ_TRACE_HEADER_INTS 8
 #define SEQ_TRACE_RECORD_WORDS 4
 
-/* Scratch sizes in bytes for the two calls above (0 is never returned; at least 256). */
+/*
+ * The drafter's ordered draw of child tokens without replacement -- the sampling half of
+ * Algorithm 2 (Sec. 3.2.1: children are drawn without replacement from the draft distribution,
+ * and uniformly from the tokens not drawn yet once its support is used up), by the
+ * exponential-sort method the implementation details name (Sec. 4.1).
+ *
+ * For every row r and token x:
+ *     word  = output word x % 4 of Philox4x32-10 with key (seed low, seed high) and
+ *             counter (x / 4, r, step low, step high)
+ *     w     = ((word >> 9) + 0.5) * 2^-23                    uniform in (0,1)
+ *     key   = draft_logits[r,x] / temperature - ln(-ln w)    (exponential sort, in logarithms)
+ * and tokens[r, 0 .. n_children[r]) are the tokens of the n_children[r] largest keys in
+ * descending order of key (lower id first among equal keys), the rest of the row -1.  Tokens of
+ * zero probability (logit -inf or NaN, or logit / temperature below -2^103) come after all
+ * others, in descending order of -ln(-ln w) alone, i.e. uniformly at random.
+ * temperature = 0 is the limit T -> 0+: the n_children[r] largest logits in descending order,
+ * lower id first among equals (top-k drafting, Sec. 2.2); seed and step are not read.
+ * Keys are computed in fp32; two keys closer than a few 1e-6 may come out in either order.
+ *
+ *   draft_logits  [n_rows, vocab]   one row per node whose children are drawn now
+ *   n_children    DEVICE [n_rows] int32, each in [0, k_max] (values outside are clamped)
+ *   rng           DEVICE [2] uint64: seed, step.  It lives on the device so that a captured
+ *                 graph draws fresh numbers on every replay once the caller has advanced step.
+ *   tokens        [n_rows, k_max] int32 out
+ *   n_rows        1 .. SEQ_MAX_TREE;  vocab 2 .. SEQ_MAX_VOCAB;  k_max 1 .. min(SEQ_MAX_CHILDREN, vocab)
+ *   workspace     DEVICE, 16-byte aligned, at least seq_draft_sample_workspace(...) bytes; scratch
+ *
+ * Errors: SEQ_ERR_NULL, SEQ_ERR_DTYPE, SEQ_ERR_SHAPE, SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE,
+ * SEQ_ERR_HIP.  Uses no per-device state: calls on different streams may overlap.
+ */
+int seq_draft_sample(const void* draft_logits, const int32_t* n_children, float temperature,
+                     const uint64_t* rng, int32_t* tokens, int32_t n_rows, int32_t vocab,
+                     int32_t k_max, int32_t dtype, void* workspace, size_t workspace_bytes,
+                     void* hip_stream);
+
+/* Scratch sizes in bytes for the calls above (0 is never returned; at least 256). */
 size_t seq_tree_attn_workspace(int32_t prefix_len, int32_t n_tree, int32_t heads,
                                int32_t kv_heads, int32_t head_dim, int32_t dtype);
 size_t seq_verify_workspace(int32_t n_tree, int32_t vocab, int32_t dtype);
+size_t seq_draft_sample_workspace(int32_t n_rows, int32_t vocab, int32_t k_max, int32_t dtype);
 
 /*
  * Host-only helper: the tree plan both calls derive from parent[] (no GPU involved).

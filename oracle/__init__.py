@@ -200,15 +200,17 @@ def draft_uniform(seed: int, step: int, row: int, x: int) -> float:
 
 
 def draft_sample(draft_logits, n_children, temperature: float, seed: int, step: int,
-                 k_stride: Optional[int] = None) -> DraftSample:
+                 k_stride: Optional[int] = None, row_ids=None) -> DraftSample:
+    """row_ids: the row numbers the given rows have in the call being checked (default 0, 1, ...)."""
     dl = _f32(draft_logits)
     nc = _i32(n_children)
+    ids = None if row_ids is None else _i32(row_ids)
     rows, V = dl.shape
     ks = int(max(1, nc.max())) if k_stride is None else int(k_stride)
     tokens = np.full((rows, ks), -1, dtype=np.int32)
     keys = np.zeros((rows, ks + 1), dtype=np.float64)
     cls = np.zeros((rows, ks + 1), dtype=np.int32)
-    rc = lib().oracle_draft_sample(_ptr(dl), C.c_int32(rows), C.c_int32(V), _ptr(nc),
+    rc = lib().oracle_draft_sample(_ptr(dl), _ptr(ids), C.c_int32(rows), C.c_int32(V), _ptr(nc),
                                    C.c_double(temperature), C.c_uint64(seed), C.c_uint64(step),
                                    C.c_int32(ks), _ptr(tokens), _ptr(keys), _ptr(cls))
     if rc:

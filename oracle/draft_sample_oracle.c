@@ -82,6 +82,8 @@ static int before(const void* pa, const void* pb)
 
 /*
  * logits      [n_rows][V]
+ * row_ids     optional [n_rows]: the row number each row draws its random numbers with (so that
+ *             a test can check single rows of a large call); NULL = 0, 1, 2, ...
  * n_children  [n_rows], each in [0, k_stride]; row r receives its first n_children[r] tokens of
  *             the order, then -1 up to k_stride
  * order_keys  optional [n_rows][k_stride + 1]: the keys of the first k+1 tokens of the order
@@ -90,8 +92,8 @@ static int before(const void* pa, const void* pb)
  * order_class optional [n_rows][k_stride + 1]: 1 where that token had zero probability
  * Returns 0, or -1 on bad arguments.
  */
-int oracle_draft_sample(const float* logits, int32_t n_rows, int32_t V, const int32_t* n_children,
-                        double T, uint64_t seed, uint64_t step, int32_t k_stride, int32_t* tokens,
+int oracle_draft_sample(const float* logits, const int32_t* row_ids, int32_t n_rows, int32_t V,
+                        const int32_t* n_children, double T, uint64_t seed, uint64_t step, int32_t k_stride, int32_t* tokens,
                         double* order_keys, int32_t* order_class)
 {
     if (!logits || !n_children || !tokens || n_rows < 1 || V < 1 || k_stride < 1 || !(T >= 0.0)) return -1;
@@ -109,7 +111,7 @@ int oracle_draft_sample(const float* logits, int32_t n_rows, int32_t V, const in
             if (T == 0.0) {
                 e[x].key = zero ? 0.0 : l;
             } else {
-                const double w = oracle_draft_uniform(seed, step, r, x);
+                const double w = oracle_draft_uniform(seed, step, row_ids ? row_ids[r] : r, x);
                 const double g = -log(-log(w));
                 e[x].key = zero ? g : l / T + g;
             }

@@ -1,5 +1,8 @@
 """Sequoia tree-verify hot path for AMD MI355X: tree-masked GQA attention and the
 sampling-without-replacement verification walk, as HIP kernels behind a C ABI."""
-from .binding import (SeqTreeError, lib, read_verify_trace, seq_tree_attn,  # noqa: F401
-                      seq_tree_attn_workspace, seq_tree_plan_host, seq_verify,
-                      seq_verify_workspace, shutdown, strerror, version)
+from .binding import (SEQ_ERR_DTYPE, SEQ_ERR_HIP, SEQ_ERR_NULL, SEQ_ERR_SHAPE,  # noqa: F401
+                      SEQ_ERR_TEMPERATURE, SEQ_ERR_TREE, SEQ_ERR_WORKSPACE, SEQ_MAX_CHILDREN,
+                      SeqTreeError, lib, read_verify_trace, seq_draft_sample,
+                      seq_draft_sample_workspace, seq_tree_attn, seq_tree_attn_workspace,
+                      seq_tree_plan_host, seq_verify, seq_verify_workspace, shutdown, strerror,
+                      version)

@@ -21,10 +21,12 @@ SEQ_ERR_NULL, SEQ_ERR_SHAPE, SEQ_ERR_TREE, SEQ_ERR_DTYPE = -1, -2, -3, -4
 SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE, SEQ_ERR_HIP = -5, -6, -7
 SEQ_MAX_TREE = 1024
 SEQ_MAX_VOCAB = 524288
+SEQ_MAX_CHILDREN = 64
 TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
-EXPORTS = ("seq_tree_attn", "seq_verify", "seq_tree_attn_workspace", "seq_verify_workspace",
-           "seq_tree_plan_host", "seq_shutdown", "seq_strerror", "seq_version")
+EXPORTS = ("seq_tree_attn", "seq_verify", "seq_draft_sample", "seq_tree_attn_workspace",
+           "seq_verify_workspace", "seq_draft_sample_workspace", "seq_tree_plan_host",
+           "seq_shutdown", "seq_strerror", "seq_version")
 
 _lib: Optional[C.CDLL] = None
 
@@ -52,6 +54,12 @@ def lib() -> C.CDLL:
         l.seq_tree_attn_workspace.argtypes = [i32] * 6
         l.seq_verify_workspace.restype = sz
         l.seq_verify_workspace.argtypes = [i32] * 3
+        l.seq_draft_sample.restype = C.c_int
+        l.seq_draft_sample.argtypes = [vp, vp, C.c_float, vp, vp, i32, i32, i32, i32, vp, sz, vp]
+        l.seq_draft_sample_workspace.restype = sz
+        l.seq_draft_sample_workspace.argtypes = [i32] * 4
+        l.seqtree_internal_set_draft_chunks.restype = None
+        l.seqtree_internal_set_draft_chunks.argtypes = [C.c_int]
         l.seq_tree_plan_host.restype = C.c_int
         l.seq_tree_plan_host.argtypes = [vp, i32, vp, vp, vp, vp]
         l.seq_shutdown.restype = C.c_int
@@ -174,6 +182,36 @@ def seq_verify(target_logits, draft_logits, tree_tokens, parent, temperature: fl
     if rc != SEQ_OK:
         raise SeqTreeError(rc, "seq_verify")
     return accepted_path, bonus_token, workspace
+
+
+def seq_draft_sample_workspace(n_rows, vocab, k_max, dtype_code) -> int:
+    return int(lib().seq_draft_sample_workspace(n_rows, vocab, k_max, dtype_code))
+
+
+def seq_draft_sample(draft_logits, n_children, temperature: float, rng, k_max: int, tokens=None,
+                     workspace=None, stream=None):
+    """draft_logits [rows,V] (bf16 or fp32), n_children int32 [rows], rng int64 [2] = (seed, step),
+    all on the GPU.  Returns (tokens int32 [rows,k_max], workspace)."""
+    import torch
+    rows, V = draft_logits.shape
+    code = _dtype_code(draft_logits)
+    for t in (draft_logits, n_children, rng):
+        if not t.is_contiguous() or not t.is_cuda:
+            raise SeqTreeError(SEQ_ERR_SHAPE, "seq_draft_sample (tensors must be contiguous GPU tensors)")
+    if n_children.dtype != torch.int32 or n_children.numel() != rows or rng.element_size() != 8 or rng.numel() != 2:
+        raise SeqTreeError(SEQ_ERR_SHAPE, "seq_draft_sample (n_children int32 [rows], rng 64-bit [2])")
+    if tokens is None:
+        tokens = torch.empty((rows, max(int(k_max), 1)), dtype=torch.int32, device=draft_logits.device)
+    need = seq_draft_sample_workspace(rows, V, k_max, code)
+    if workspace is None or workspace.numel() * workspace.element_size() < need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=draft_logits.device)
+    rc = lib().seq_draft_sample(draft_logits.data_ptr(), n_children.data_ptr(), float(temperature),
+                                rng.data_ptr(), tokens.data_ptr(), rows, V, int(k_max), code,
+                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                _stream_ptr(stream))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_draft_sample")
+    return tokens, workspace
 
 
 def read_verify_trace(workspace) -> dict:

@@ -87,7 +87,33 @@ def test_verify_argument_errors_need_no_gpu():
     assert _verify(good, ws_bytes=S.seq_verify_workspace(3, 64, B.SEQ_F32) - 1) == B.SEQ_ERR_WORKSPACE
 
 
+def _draft(logits=0x1000, nc=0x1000, temperature=1.0, rng=0x1000, tokens=0x1000, rows=4, vocab=100,
+           k_max=8, dtype=B.SEQ_F32, ws=0x1000, ws_bytes=1 << 24):
+    return S.lib().seq_draft_sample(logits, nc, temperature, rng, tokens, rows, vocab, k_max, dtype,
+                                    ws, ws_bytes, None)
+
+
+def test_draft_sample_argument_errors_need_no_gpu():
+    for missing in ("logits", "nc", "rng", "tokens"):
+        assert _draft(**{missing: None}) == B.SEQ_ERR_NULL
+    assert _draft(dtype=7) == B.SEQ_ERR_DTYPE
+    assert _draft(rows=0) == B.SEQ_ERR_SHAPE
+    assert _draft(rows=B.SEQ_MAX_TREE + 1) == B.SEQ_ERR_SHAPE
+    assert _draft(vocab=1) == B.SEQ_ERR_SHAPE
+    assert _draft(vocab=B.SEQ_MAX_VOCAB + 1) == B.SEQ_ERR_SHAPE
+    assert _draft(k_max=0) == B.SEQ_ERR_SHAPE
+    assert _draft(k_max=B.SEQ_MAX_CHILDREN + 1, vocab=1000) == B.SEQ_ERR_SHAPE
+    assert _draft(k_max=9, vocab=8) == B.SEQ_ERR_SHAPE          # more children than tokens
+    for t in (-0.5, float("nan"), float("inf")):
+        assert _draft(temperature=t) == B.SEQ_ERR_TEMPERATURE
+    assert _draft(ws=None) == B.SEQ_ERR_WORKSPACE
+    assert _draft(ws=0x1008) == B.SEQ_ERR_WORKSPACE             # not 16-byte aligned
+    assert _draft(ws_bytes=S.seq_draft_sample_workspace(4, 100, 8, B.SEQ_F32) - 1) == B.SEQ_ERR_WORKSPACE
+
+
 def test_workspace_sizes():
+    assert S.seq_draft_sample_workspace(1, 2, 1, B.SEQ_F32) >= 256
+    assert S.seq_draft_sample_workspace(768, 128256, 10, B.SEQ_BF16) >= 768 * 10 * 8
     assert S.seq_tree_attn_workspace(256, 16, 2, 2, 64, B.SEQ_F32) >= 256
     assert S.seq_verify_workspace(768, 128256, B.SEQ_BF16) >= 4 * (8 + 4 * 1024 + 4)
     # bigger trees never need less attention scratch at the same head shape

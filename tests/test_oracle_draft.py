@@ -192,6 +192,8 @@ def test_rows_and_steps_draw_independently_and_reproducibly():
     other[:4] = np.random.default_rng(45).standard_normal((4, 1000))
     b = oracle.draft_sample(other, np.full(8, 3), 1.0, 50, 0).tokens
     assert np.array_equal(a[4:], b[4:])                             # a row depends on itself only
+    c = oracle.draft_sample(logits[[5, 2]], [3, 3], 1.0, 50, 0, row_ids=[5, 2]).tokens
+    assert np.array_equal(c, a[[5, 2]])                             # single rows of a larger call
 
 
 def test_keys_reported_in_descending_order_with_their_gap():
