@@ -130,6 +130,79 @@ def run_sweep(args) -> int:
     return 0
 
 
+# Vector instructions the sampling kernel spends per token on its fast path, as compiled (Philox4x32-10:
+# 4.5 64-bit multiplies and 9 logic operations; 3 to turn the word into a uniform; 2 logarithms and a
+# multiply-add for the Gumbel variate; 4 for the key and the class of zero-probability tokens; unpacking the
+# logit and the compare against the bar), and the chip's rate for them: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.
+DRAFT_LANE_INSTR_PER_TOKEN = 30.0
+VALU_PEAK_T_LANE_INSTR = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
+def run_draft_sample(args) -> int:
+    """Latency of seq_draft_sample (the drafter's ordered draw of child tokens): for each
+    configuration, one call over every node of its tree that has children (rows = internal
+    nodes, n_children = their fan-outs), and one call for a single level of the tree.  One JSON
+    line per case.  Not the benchmark line."""
+    import numpy as np
+    import torch
+
+    import paper_2402_12374_amd as S
+    from paper_2402_12374_amd import workloads as W
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    first = True
+    for key in args.sweep_configs.split(","):
+        cfg = W.CONFIGS[key]
+        idx = list(W.CONFIGS).index(key) + 1
+        parent = W.make_tree(cfg, W.seed_for(idx))
+        fan = np.bincount(parent[1:], minlength=len(parent))
+        depth = W.depths(parent)
+        level = int(np.argmax(np.bincount(depth[fan > 0])))     # the level with most internal nodes
+        tdt = torch.bfloat16 if cfg.dtype == W.BF16 else torch.float32
+        T = cfg.temperatures[0]
+        for name, rows_of in (("tree", np.nonzero(fan > 0)[0]), (f"level{level}", np.nonzero((fan > 0) & (depth == level))[0])):
+            ks = fan[rows_of].astype(np.int32)
+            rows, V, k_max = len(ks), cfg.vocab, int(ks.max())
+            n_sets = 2 if rows * V > 2 ** 24 else 8
+            gen = np.random.Generator(np.random.PCG64(W.seed_for(idx) + 900))
+            sets = []
+            for _ in range(n_sets):
+                x = gen.standard_normal((rows, V), dtype=np.float32) * np.float32(np.hypot(cfg.sigma_target, cfg.sigma_draft))
+                sets.append(torch.from_numpy(x).to(dev).to(tdt))
+            nc = torch.from_numpy(ks).to(dev)
+            rng = torch.tensor([2024, 0], dtype=torch.int64, device=dev)
+            tokens = torch.empty((rows, k_max), dtype=torch.int32, device=dev)
+            ws = torch.empty(S.seq_draft_sample_workspace(rows, V, k_max, 1), dtype=torch.uint8, device=dev)
+
+            def call(i):
+                S.seq_draft_sample(sets[i % n_sets], nc, T, rng, k_max, tokens=tokens, workspace=ws)
+
+            us = graph_time_us(torch, call, n_sets, 40)
+            tok_per_s = rows * V / (us * 1e-6)
+            achieved = tok_per_s * DRAFT_LANE_INSTR_PER_TOKEN / 1e12
+            line = {"op": "seq_draft_sample", "config": cfg.name, "case": name, "rows": rows, "vocab": V,
+                    "children": int(ks.sum()), "k_max": k_max, "temperature": T, "dtype": cfg.dtype,
+                    "us": round(us, 2), "g_tokens_per_s": round(tok_per_s / 1e9, 1),
+                    "roofline": {"bound": "alu", "achieved": round(achieved, 2), "peak": round(VALU_PEAK_T_LANE_INSTR, 1),
+                                 "unit": "T lane-instr/s", "frac": round(achieved / VALU_PEAK_T_LANE_INSTR, 4),
+                                 "hbm_frac": round(rows * V * (2 if tdt == torch.bfloat16 else 4) / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}}
+            if first and not args.no_cpu_baseline:
+                import oracle
+                host = sets[0][: min(rows, 16)].float().cpu().numpy()
+                t0 = time.perf_counter()
+                oracle.draft_sample(host, ks[: len(host)], T, 2024, 0, k_stride=k_max)
+                dt = time.perf_counter() - t0
+                line["cpu_baseline"] = {"value": round(len(host) * V / dt / 1e9, 4), "unit": "G tokens/s", "cores": 1,
+                                        "kind": "oracle", "sample": f"{len(host)} rows of {V} logits"}
+                first = False
+            print(json.dumps(line), flush=True)
+            del sets
+        torch.cuda.empty_cache()
+    S.shutdown()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -145,6 +218,8 @@ def main() -> int:
                          "(the known-size reference for HBM traffic counters collected with rocprofv3 --pmc)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: latency of both calls over the tree size (one line each)")
+    ap.add_argument("--draft-sample", action="store_true",
+                    help="instead of the benchmark line: latency of seq_draft_sample per configuration (one line each)")
     ap.add_argument("--sweep-configs", default="C2,C3,C4,C5")
     ap.add_argument("--sweep-sizes", default="16,32,64,128,256,512,768")
     args = ap.parse_args()
@@ -154,6 +229,8 @@ def main() -> int:
 
     if args.sweep:
         return run_sweep(args)
+    if args.draft_sample:
+        return run_draft_sample(args)
 
     import numpy as np
     import torch

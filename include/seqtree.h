@@ -167,9 +167,12 @@ int seq_verify(const void* target_logits, const void* draft_logits,
  *   tokens        [n_rows, k_max] int32 out
  *   n_rows        1 .. SEQ_MAX_TREE;  vocab 2 .. SEQ_MAX_VOCAB;  k_max 1 .. min(SEQ_MAX_CHILDREN, vocab)
  *   workspace     DEVICE, 16-byte aligned, at least seq_draft_sample_workspace(...) bytes; scratch
+ *                 (reserved: the current kernel keeps everything in registers and in the
+ *                 library's per-device exchange area)
  *
  * Errors: SEQ_ERR_NULL, SEQ_ERR_DTYPE, SEQ_ERR_SHAPE, SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE,
- * SEQ_ERR_HIP.  Uses no per-device state: calls on different streams may overlap.
+ * SEQ_ERR_HIP.  One launch.  Rows that several workgroups share meet in the per-device
+ * synchronisation area, so calls that overlap in time on one device race (see above).
  */
 int seq_draft_sample(const void* draft_logits, const int32_t* n_children, float temperature,
                      const uint64_t* rng, int32_t* tokens, int32_t n_rows, int32_t vocab,

@@ -60,6 +60,8 @@ def lib() -> C.CDLL:
         l.seq_draft_sample_workspace.argtypes = [i32] * 4
         l.seqtree_internal_set_draft_chunks.restype = None
         l.seqtree_internal_set_draft_chunks.argtypes = [C.c_int]
+        l.seqtree_internal_set_draft_max_groups.restype = None
+        l.seqtree_internal_set_draft_max_groups.argtypes = [C.c_int]
         l.seq_tree_plan_host.restype = C.c_int
         l.seq_tree_plan_host.argtypes = [vp, i32, vp, vp, vp, vp]
         l.seq_shutdown.restype = C.c_int

@@ -29,6 +29,8 @@ struct SyncArea {
     uint32_t* verify_epoch = nullptr;            // [2] tag base of the next verify launch, poison flag
     uint32_t* verify_arrivals = nullptr;         // [1] workgroups of a per-node verify launch that are done
     uint32_t* attn_counters = nullptr;           // [kAttnMaxCounters]
+    unsigned long long* draft_exchange = nullptr;  // [kDraftMaxGroups][64] lists of a split row, zero between calls
+    uint32_t* draft_arrivals = nullptr;          // [SEQ_MAX_TREE] workgroups of a row that are done
     // Measured once per device: do workgroups whose ids are congruent mod 8 share an XCD (one
     // L2)?  The attention kernel then keeps all key ranges of a unit on one XCD and can hand
     // partial results over through that L2 without writing it back to memory.
@@ -39,6 +41,7 @@ constexpr int kVerifyMaxGroups = 64;
 constexpr int kVerifySlotWords = 4;
 constexpr int kVerifyTagsPerCall = 4096;
 constexpr int kAttnMaxCounters = 16384;
+constexpr int kDraftMaxGroups = 16384;
 
 // Looks up (or builds and uploads) the plan for this parent array on the current device.
 // Returns SEQ_OK or an error code; *plan receives a copy whose device pointers stay owned by

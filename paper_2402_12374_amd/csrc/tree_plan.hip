@@ -164,19 +164,26 @@ int get_sync_area(SyncArea** out) {
     const size_t slot_words = (size_t)2 * kVerifyMaxGroups * kVerifySlotWords;
     const size_t slot_bytes = sizeof(unsigned long long) * (slot_words + 2);
     const size_t ctr_bytes = sizeof(uint32_t) * kAttnMaxCounters;
+    // the lists of split rows (8 MiB), then one arrival counter per row
+    const size_t draft_words = (size_t)kDraftMaxGroups * 64;
+    const size_t draft_bytes = sizeof(unsigned long long) * draft_words + sizeof(uint32_t) * SEQ_MAX_TREE;
     bool ok = hipMalloc(&s.area.verify_slots, slot_bytes) == hipSuccess &&
               hipMalloc(&s.area.attn_counters, ctr_bytes) == hipSuccess &&
+              hipMalloc(&s.area.draft_exchange, draft_bytes) == hipSuccess &&
               hipMemset(s.area.verify_slots, 0, slot_bytes) == hipSuccess &&
               hipMemset(s.area.attn_counters, 0, ctr_bytes) == hipSuccess &&
+              hipMemset(s.area.draft_exchange, 0, draft_bytes) == hipSuccess &&
               hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         if (s.area.verify_slots) (void)hipFree(s.area.verify_slots);
         if (s.area.attn_counters) (void)hipFree(s.area.attn_counters);
+        if (s.area.draft_exchange) (void)hipFree(s.area.draft_exchange);
         (void)hipGetLastError();
         return SEQ_ERR_HIP;
     }
     s.area.verify_epoch = reinterpret_cast<uint32_t*>(s.area.verify_slots + slot_words);
     s.area.verify_arrivals = s.area.verify_epoch + 2;
+    s.area.draft_arrivals = reinterpret_cast<uint32_t*>(s.area.draft_exchange + draft_words);
     s.area.round_robin_xcds = probe_round_robin_xcds();
     g_sync.push_back(s);
     *out = &g_sync.back().area;
@@ -196,6 +203,7 @@ int release_all() {
         if (have_dev) (void)hipSetDevice(s.device);
         if (s.area.verify_slots) (void)hipFree(s.area.verify_slots);
         if (s.area.attn_counters) (void)hipFree(s.area.attn_counters);
+        if (s.area.draft_exchange) (void)hipFree(s.area.draft_exchange);
     }
     g_sync.clear();
     if (have_dev) (void)hipSetDevice(current);

@@ -114,6 +114,21 @@ def test_any_number_of_workgroups_per_row(chunks):
         assert check_draft(logits, ks, 0.8, 5, chunks, W.BF16, 20, chunks=chunks) <= 1
 
 
+@pytest.mark.parametrize("groups", [1, 7, 64])
+def test_workgroups_that_take_many_runs(groups):
+    """A grid much smaller than the number of runs: every workgroup works through several rows
+    and parts of rows, and finishes rows whose other parts it or others computed earlier."""
+    rng = np.random.default_rng(groups)
+    logits = 2.0 * rng.standard_normal((40, 9000), dtype=np.float32)
+    ks = rng.integers(0, 9, size=40)
+    S.lib().seqtree_internal_set_draft_max_groups(groups)
+    try:
+        for chunks in (1, 3, 5):
+            assert check_draft(logits, ks, 0.7, 3, groups, W.BF16, 8, chunks=chunks) <= 1
+    finally:
+        S.lib().seqtree_internal_set_draft_max_groups(0)
+
+
 def test_most_children_per_node():
     rng = np.random.default_rng(64)
     logits = 2.0 * rng.standard_normal((5, 9000), dtype=np.float32)
