@@ -152,7 +152,7 @@ __device__ __forceinline__ u64 no_token(int lane) { return (u64)lane + 2; }   //
 __device__ __forceinline__ u64 sort_descending(u64 v, u64* row, int lane) {
     row[lane] = v;
     int place = 0;
-#pragma unroll 4
+#pragma unroll 8
     for (int l = 0; l < 64; l += 2) {
         const ulonglong2 o = *reinterpret_cast<const ulonglong2*>(row + l);   // same address in every lane
         place += (o.x > v) + (o.y > v);
@@ -203,6 +203,10 @@ __device__ __forceinline__ void absorb(u64& list, u64& bar, u64 word, bool wante
         }
     }
 }
+
+// idx / d for 0 <= idx < 2^14 and 1 <= d <= 64, through one multiply: (idx + 1/2) / d is at
+// least 1/(2d) away from every integer, far more than the rounding of the product.
+__device__ __forceinline__ int small_div(int idx, float inv_d) { return (int)(((float)idx + 0.5f) * inv_d); }
 
 // Number of the first k entries of a descending list that are larger than v.
 __device__ __forceinline__ int count_larger(const u64* list, int k, u64 v) {
@@ -339,12 +343,17 @@ __global__ void __launch_bounds__(kThreads) draft_sample_kernel(const DraftParam
             list = sort_descending(seeded, lists[wave], lane);
             bar = read_lane(list, k - 1);
         }
-#pragma unroll 1
-        for (int i = 0; i < kPerLane; ++i) {
-            const u64 w = word[0];
+        bool more = false;     // usually the lanes' own best words were all there was to take
 #pragma unroll
-            for (int j = 0; j + 1 < kPerLane; ++j) word[j] = word[j + 1];
-            absorb(list, bar, w, w > bar && w != seeded, k, lists[wave], lane);
+        for (int i = 0; i < kPerLane; ++i) more |= word[i] > bar && word[i] != seeded;
+        if (__ballot(more) != 0) {
+#pragma unroll 1
+            for (int i = 0; i < kPerLane; ++i) {
+                const u64 w = word[0];
+#pragma unroll
+                for (int j = 0; j + 1 < kPerLane; ++j) word[j] = word[j + 1];
+                absorb(list, bar, w, w > bar && w != seeded, k, lists[wave], lane);
+            }
         }
         const float bar_key = key_of(bar);
         pass_key = bar_key > -0x1p103f ? bar_key : -INFINITY;
@@ -358,21 +367,23 @@ __global__ void __launch_bounds__(kThreads) draft_sample_kernel(const DraftParam
     lists[wave][lane] = list;
     places[wave][lane] = 0;
     u64* exchange = p.exchange + (size_t)row * p.chunks * 64;
+    const float inv_k = 1.0f / (float)k;
     int n_lists = kWaves;
 #pragma unroll 1
     for (int stage = 0;; ++stage) {
         __syncthreads();
         const int entries = n_lists * k;
+        const float inv_lists = 1.0f / (float)n_lists;
         for (int idx = tid; idx < entries * n_lists; idx += kThreads) {
-            const int e = idx / n_lists, c = idx - e * n_lists;
-            const int l = e / k, j = e - l * k;
+            const int e = small_div(idx, inv_lists), c = idx - e * n_lists;
+            const int l = small_div(e, inv_k), j = e - l * k;
             const u64 v = lists[l][j];
             if (v >= kSmallestWord) atomicAdd(&places[l][j], c == l ? j : count_larger(lists[c], k, v));
         }
         __syncthreads();
         const bool final_stage = stage == 1 || p.chunks == 1;
         for (int e = tid; e < entries; e += kThreads) {
-            const int l = e / k, j = e - l * k;
+            const int l = small_div(e, inv_k), j = e - l * k;
             const u64 v = lists[l][j];
             const int place = places[l][j];
             if (v >= kSmallestWord && place < k) {
@@ -398,7 +409,7 @@ __global__ void __launch_bounds__(kThreads) draft_sample_kernel(const DraftParam
         if (!s_last) break;
         n_lists = p.chunks;
         for (int e = tid; e < n_lists * k; e += kThreads) {
-            const int c = e / k, j = e - c * k;
+            const int c = small_div(e, inv_k), j = e - c * k;
             u64* slot = exchange + c * 64 + j;
             // the writer's store may still be on its way: bounded wait, then leave the slot empty again
             u64 v = 0;
@@ -428,11 +439,15 @@ int g_forced_chunks = 0;
 int g_max_groups = SEQ_MAX_TREE * kMaxChunks;   // workgroups per launch, at most: as many as there can be runs
 
 // Workgroups per row: enough to fill the chip, not more than the row has steps, and few enough
-// that the last one's placement of chunks * k entries against chunks lists stays short.
+// that the last one's placement of chunks * k entries against chunks lists stays short
+// (chunks^2 * k pairs, 256 at a time).  With many rows the per-workgroup fixed work (seeding,
+// two placements, the hand-over) is what fills the chip, so the budget of pairs is halved:
+// measured at 64 and 128 rows, 8 workgroups per row beat 16 by 4 us; at 1 row 16 beat 8 by 1 us.
 void plan_chunks(int rows, int V, int k_max, int* chunks, int* chunk_tokens) {
     const int steps = (V + kStepTokens - 1) / kStepTokens;
     int want = (kTargetGroups + rows - 1) / rows;
-    while (want > 1 && want * want * k_max > 1024) --want;
+    const int pair_budget = rows <= 8 ? 2048 : 1024;
+    while (want > 1 && want * want * k_max > pair_budget) --want;
     if (g_forced_chunks > 0) want = g_forced_chunks;
     want = std::max(1, std::min(want, std::min(kMaxChunks, steps)));
     const int steps_per_chunk = (steps + want - 1) / want;
