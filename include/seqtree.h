@@ -197,6 +197,50 @@ size_t seq_draft_sample_workspace(int32_t n_rows, int32_t vocab, int32_t k_max, 
 int seq_tree_plan_host(const int32_t* parent, int32_t n_tree, int32_t* depth,
                        int32_t* child_start, int32_t* child_list, uint32_t* anc_words);
 
+/*
+ * Sequoia tree construction (Sec. 3.1.2, Algorithm 1 with the depth bound of its appendix).  HOST
+ * only, no GPU involved; meant to run once, ahead of time.
+ *
+ * acceptance[k-1] is the probability that the token at child position k of an accepted node is
+ * accepted (the acceptance vector).  The expected number of tokens one verification of a tree
+ * generates is F = sum over its nodes of the product of the rates along the node's path (root: 1).
+ * seq_build_tree returns a tree of exactly n_tree nodes, at most max_branch children per node
+ * and depth at most max_depth (edges below the root) that maximises F, as a parent array in the
+ * order the other calls expect: parent[0] = -1, parent[i] < i, breadth-first, the children of a
+ * node in ascending id = child positions 1, 2, ... (the order they are drafted in).
+ *
+ *   acceptance       HOST [max_branch], each in [0, 1];  max_branch 1 .. SEQ_MAX_CHILDREN
+ *   n_tree           1 .. SEQ_MAX_TREE;  max_depth >= 0
+ *   parent           HOST out [n_tree]
+ *   expected_tokens  HOST out, may be NULL: F of the returned tree
+ * Returns SEQ_ERR_SHAPE if no tree of that size exists within the bounds (or a rate is outside
+ * [0, 1]).  Cost: n_tree^2 * max_depth * max_branch / 2 multiply-adds, 8 * n_tree * max_depth *
+ * max_branch bytes (1024 nodes, 32 levels, 64 branches: about a second, 17 MB).
+ */
+int seq_build_tree(const double* acceptance, int32_t max_branch, int32_t n_tree, int32_t max_depth,
+                   int32_t* parent, double* expected_tokens);
+
+/* F of a given tree (HOST only): the closed form of Sec. 3.1.2.  Children beyond position
+ * max_branch count with rate 0. */
+int seq_tree_expected_tokens(const int32_t* parent, int32_t n_tree, const double* acceptance,
+                             int32_t max_branch, double* expected_tokens);
+
+/*
+ * The hardware-aware choice of tree size and depth (Sec. 4.1), HOST only: over the given sizes n
+ * and every depth d <= max_depth, maximise
+ *     Speedup(n, d) = G(n, d) / (t(n) + d * c),
+ * G(n, d) = F of the best tree of n nodes and depth <= d, t(n) = verify_time[i] / decode_time (the
+ * target's time to verify n tokens relative to decoding one), c = draft_time / decode_time (one
+ * draft step relative to the same).  Times are in any one unit, > 0 (draft_time may be 0).
+ *   sizes, verify_time   HOST [n_sizes]: tree sizes (1 .. SEQ_MAX_TREE) and the measured time of
+ *                        the target's forward pass over a tree of that size
+ *   best_size, best_depth, best_speedup   HOST out (best_speedup may be NULL)
+ */
+int seq_pick_tree_shape(const double* acceptance, int32_t max_branch, const int32_t* sizes,
+                        const double* verify_time, int32_t n_sizes, int32_t max_depth,
+                        double decode_time, double draft_time, int32_t* best_size,
+                        int32_t* best_depth, double* best_speedup);
+
 /* Releases the plan cache and the synchronisation area of every device.  Safe to call twice. */
 int seq_shutdown(void);
 

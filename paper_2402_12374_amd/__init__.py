@@ -2,7 +2,8 @@
 sampling-without-replacement verification walk, as HIP kernels behind a C ABI."""
 from .binding import (SEQ_ERR_DTYPE, SEQ_ERR_HIP, SEQ_ERR_NULL, SEQ_ERR_SHAPE,  # noqa: F401
                       SEQ_ERR_TEMPERATURE, SEQ_ERR_TREE, SEQ_ERR_WORKSPACE, SEQ_MAX_CHILDREN,
-                      SeqTreeError, lib, read_verify_trace, seq_draft_sample,
-                      seq_draft_sample_workspace, seq_tree_attn, seq_tree_attn_workspace,
+                      SeqTreeError, lib, read_verify_trace, seq_build_tree, seq_draft_sample,
+                      seq_draft_sample_workspace, seq_pick_tree_shape, seq_tree_attn,
+                      seq_tree_attn_workspace, seq_tree_expected_tokens,
                       seq_tree_plan_host, seq_verify, seq_verify_workspace, shutdown, strerror,
                       version)

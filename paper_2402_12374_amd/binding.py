@@ -26,6 +26,7 @@ TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
 EXPORTS = ("seq_tree_attn", "seq_verify", "seq_draft_sample", "seq_tree_attn_workspace",
            "seq_verify_workspace", "seq_draft_sample_workspace", "seq_tree_plan_host",
+           "seq_build_tree", "seq_tree_expected_tokens", "seq_pick_tree_shape",
            "seq_shutdown", "seq_strerror", "seq_version")
 
 _lib: Optional[C.CDLL] = None
@@ -64,6 +65,12 @@ def lib() -> C.CDLL:
         l.seqtree_internal_set_draft_max_groups.argtypes = [C.c_int]
         l.seq_tree_plan_host.restype = C.c_int
         l.seq_tree_plan_host.argtypes = [vp, i32, vp, vp, vp, vp]
+        l.seq_build_tree.restype = C.c_int
+        l.seq_build_tree.argtypes = [vp, i32, i32, i32, vp, vp]
+        l.seq_tree_expected_tokens.restype = C.c_int
+        l.seq_tree_expected_tokens.argtypes = [vp, i32, vp, i32, vp]
+        l.seq_pick_tree_shape.restype = C.c_int
+        l.seq_pick_tree_shape.argtypes = [vp, i32, vp, vp, i32, i32, C.c_double, C.c_double, vp, vp, vp]
         l.seq_shutdown.restype = C.c_int
         l.seq_strerror.restype = C.c_char_p
         l.seq_strerror.argtypes = [C.c_int]
@@ -121,6 +128,44 @@ def seq_tree_plan_host(parent):
     if rc != SEQ_OK:
         raise SeqTreeError(rc, "seq_tree_plan_host")
     return depth, cstart, clist[: n - 1], anc
+
+
+def _rates(acceptance) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(acceptance, dtype=np.float64))
+
+
+def seq_build_tree(acceptance, n_tree: int, max_depth: int):
+    """The Sequoia tree of n_tree nodes and depth <= max_depth for this acceptance vector (host
+    only).  Returns (parent int32 [n_tree], expected tokens per verification)."""
+    p = _rates(acceptance)
+    parent = np.zeros(max(int(n_tree), 1), np.int32)
+    f = C.c_double(0.0)
+    rc = lib().seq_build_tree(p.ctypes.data, len(p), int(n_tree), int(max_depth), parent.ctypes.data, C.byref(f))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_build_tree")
+    return parent, f.value
+
+
+def seq_tree_expected_tokens(parent, acceptance) -> float:
+    par, p = _parent_array(parent), _rates(acceptance)
+    f = C.c_double(0.0)
+    rc = lib().seq_tree_expected_tokens(par.ctypes.data, len(par), p.ctypes.data, len(p), C.byref(f))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_tree_expected_tokens")
+    return f.value
+
+
+def seq_pick_tree_shape(acceptance, sizes, verify_time, max_depth: int, decode_time: float, draft_time: float):
+    """(size, depth, speedup) maximising G(n, d) / (t(n) + d c) over the given sizes (host only)."""
+    p = _rates(acceptance)
+    sz = np.ascontiguousarray(np.asarray(sizes), dtype=np.int32)
+    vt = np.ascontiguousarray(np.asarray(verify_time), dtype=np.float64)
+    n, d, s = C.c_int32(0), C.c_int32(0), C.c_double(0.0)
+    rc = lib().seq_pick_tree_shape(p.ctypes.data, len(p), sz.ctypes.data, vt.ctypes.data, len(sz), int(max_depth),
+                                   float(decode_time), float(draft_time), C.byref(n), C.byref(d), C.byref(s))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_pick_tree_shape")
+    return n.value, d.value, s.value
 
 
 def seq_tree_attn_workspace(prefix_len, n_tree, heads, kv_heads, head_dim, dtype_code) -> int:
