@@ -83,6 +83,7 @@ def run_sweep(args) -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     sizes = [int(x) for x in args.sweep_sizes.split(",")]
+    results = []
     for key in args.sweep_configs.split(","):
         cfg = W.CONFIGS[key]
         H, Hk, d, P, V = cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.prefix_len, cfg.vocab
@@ -93,7 +94,10 @@ def run_sweep(args) -> int:
         mk = lambda *shape: torch.randn(*shape, device=dev).to(tdt)
         caches = [(mk(Hk, P, d), mk(Hk, P, d)) for _ in range(sets)]
         for n in sizes:
-            parent = W.geometric_tree(n, cfg.max_depth)
+            if args.sweep_tree == "sequoia":
+                parent, _ = S.seq_build_tree(W.PAPER_ACCEPTANCE_VECTOR, n, cfg.max_depth)
+            else:
+                parent = W.geometric_tree(n, cfg.max_depth)
             q = [(mk(n, H, d), mk(n, Hk, d), mk(n, Hk, d), torch.empty(n, H, d, device=dev, dtype=tdt)) for _ in range(sets)]
             ws = torch.empty(S.seq_tree_attn_workspace(P, n, H, Hk, d, code), dtype=torch.uint8, device=dev)
 
@@ -119,13 +123,26 @@ def run_sweep(args) -> int:
             verify_us = graph_time_us(torch, verify_call, len(vsets), 20)
             cfg_n = type("C", (), dict(dtype=cfg.dtype, n_tree=n, prefix_len=P, heads=H, kv_heads=Hk, head_dim=d))
             bytes_alg, flops_alg = attn_alg_bytes(cfg_n), attn_alg_flops(cfg_n, parent)
-            print(json.dumps({"config": cfg.name, "n_tree": n, "prefix_len": P, "vocab": V,
+            results.append((key, n, attn_us, verify_us))
+            print(json.dumps({"config": cfg.name, "tree": args.sweep_tree, "n_tree": n, "prefix_len": P, "vocab": V,
                               "attn_us_per_layer": round(attn_us, 2), "verify_us": round(verify_us, 2),
                               "attn_hbm_frac": round(bytes_alg / (attn_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                               "attn_mfma_frac": round(flops_alg / (attn_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}), flush=True)
             del q, vsets
         del caches
         torch.cuda.empty_cache()
+        if args.pick_tree:
+            # The hardware-aware choice of Sec. 4.1 fed with what was just measured.  t(n) here is the
+            # part of the target's pass this library covers -- every layer's tree attention plus the
+            # verification walk, not the linear layers -- relative to the same at the smallest size.
+            mine = [(n, cfg.layers * a + v) for k, n, a, v in results if k == key]
+            decode = mine[0][1]
+            n_best, d_best, s_best = S.seq_pick_tree_shape(W.PAPER_ACCEPTANCE_VECTOR, [n for n, _ in mine], [t for _, t in mine],
+                                                           cfg.max_depth, decode_time=decode, draft_time=args.draft_cost * decode)
+            _, g_best = S.seq_build_tree(W.PAPER_ACCEPTANCE_VECTOR, n_best, d_best)
+            print(json.dumps({"config": cfg.name, "pick_tree": {"size": n_best, "depth": d_best, "speedup": round(s_best, 3),
+                              "expected_tokens": round(g_best, 3), "draft_cost": args.draft_cost,
+                              "t_of_n": {str(n): round(t / decode, 3) for n, t in mine}}}), flush=True)
     S.shutdown()
     return 0
 
@@ -218,6 +235,13 @@ def main() -> int:
                          "(the known-size reference for HBM traffic counters collected with rocprofv3 --pmc)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: latency of both calls over the tree size (one line each)")
+    ap.add_argument("--sweep-tree", choices=("geometric", "sequoia"), default="geometric",
+                    help="tree of the sweep: the configurations' geometric tree, or the Sequoia tree of that size built "
+                         "by seq_build_tree from the paper's printed acceptance vector")
+    ap.add_argument("--pick-tree", action="store_true",
+                    help="with --sweep: after each configuration, the tree size and depth that maximise Speedup(n, d) for "
+                         "the measured t(n) (first sweep size = the decoding step)")
+    ap.add_argument("--draft-cost", type=float, default=0.05, help="c of Speedup(n, d): one draft step relative to one decoding step")
     ap.add_argument("--draft-sample", action="store_true",
                     help="instead of the benchmark line: latency of seq_draft_sample per configuration (one line each)")
     ap.add_argument("--sweep-configs", default="C2,C3,C4,C5")

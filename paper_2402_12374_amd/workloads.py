@@ -214,6 +214,15 @@ def make_attn_inputs(heads: int, kv_heads: int, head_dim: int, prefix_len: int, 
                       int(prefix_len), int(cap), dtype)
 
 
+# The acceptance rate vector the paper prints in its appendix "Examples of Sequoia trees" (Llama3-70B
+# target, Llama3-8B draft, CNN daily news): entry k-1 = probability that the token at child position k
+# of an accepted node is accepted.  Input data for the tree construction, nothing is computed here.
+PAPER_ACCEPTANCE_VECTOR = (
+    0.7732, 0.1039, 0.0402, 0.0206, 0.0128, 0.0081, 0.0064, 0.0043, 0.0035, 0.0026, 0.0025, 0.0021,
+    0.0016, 0.0014, 0.0010, 0.0010, 0.0010, 0.0007, 0.0007, 0.0006, 0.0007, 0.0006, 0.0004, 0.0004,
+    0.0005, 0.0006, 0.0004, 0.0003, 0.0002, 0.0004, 0.0001)
+
+
 # --------------------------------------------------------------------------
 # verification inputs
 # --------------------------------------------------------------------------

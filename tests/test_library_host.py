@@ -171,6 +171,12 @@ def test_workload_generators_are_seeded_and_shaped():
     assert (v.uniforms >= 0).all() and (v.uniforms < 1).all()
 
 
+def test_acceptance_vector_of_the_generators_is_the_printed_one():
+    import json
+    golden = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_acceptance_vector.json")))
+    assert list(W.PAPER_ACCEPTANCE_VECTOR) == golden["acceptance"]
+
+
 def test_division_by_multiplication_is_exact():
     """The attention kernel divides by per-launch constants with a host-prepared multiplier; the
     host evaluation of that formula must equal integer division for every dividend below 2^31."""
