@@ -29,6 +29,7 @@ def lib() -> C.CDLL:
         _LIB.oracle_tree_attn_row.restype = C.c_int
         _LIB.oracle_tree_attn.restype = C.c_int
         _LIB.oracle_draft_sample.restype = C.c_int
+        _LIB.oracle_verify_baseline.restype = C.c_int
         _LIB.oracle_draft_uniform.restype = C.c_double
         _LIB.oracle_philox4x32_10.restype = None
         _LIB.oracle_verify.restype = C.c_int
@@ -216,3 +217,45 @@ def draft_sample(draft_logits, n_children, temperature: float, seed: int, step: 
     if rc:
         raise ValueError(f"oracle_draft_sample rc={rc}")
     return DraftSample(tokens, keys, cls)
+
+
+# --------------------------------------------------------------------------
+# the baseline verification algorithms of Sec. 2.2 (SpecInfer; naive / top-k sampling)
+# --------------------------------------------------------------------------
+SPECINFER, TOPK = 1, 2
+
+
+@dataclass
+class BaselineResult:
+    accepted_path: np.ndarray   # [n] int32, -1 terminated
+    bonus_token: int
+    records: np.ndarray         # [m, 8] float64, see verify_baselines_oracle.c
+    stop_node: int
+    bonus_u: float
+    bonus_total: float
+    bonus_cdf_lo: float
+    bonus_cdf_hi: float
+    bonus_margin: float
+
+    @property
+    def path(self) -> List[int]:
+        return [int(x) for x in self.accepted_path if x >= 0]
+
+
+def verify_baseline(algorithm: int, target_logits, draft_logits, tree_tokens, parent, temperature: float,
+                    uniforms) -> BaselineResult:
+    tl, dl, un = _f32(target_logits), _f32(draft_logits), _f32(uniforms)
+    tok, par = _i32(tree_tokens), _i32(parent)
+    n, V = tl.shape
+    path = np.full(n, -1, dtype=np.int32)
+    bonus = np.zeros(1, dtype=np.int32)
+    rec = np.zeros((n, 8), dtype=np.float64)
+    nrec = np.zeros(1, dtype=np.int32)
+    binfo = np.zeros(8, dtype=np.float64)
+    rc = lib().oracle_verify_baseline(C.c_int32(algorithm), _ptr(tl), _ptr(dl), _ptr(tok), _ptr(par),
+                                      C.c_double(temperature), _ptr(un), C.c_int32(n), C.c_int32(V),
+                                      _ptr(path), _ptr(bonus), _ptr(rec), _ptr(nrec), _ptr(binfo))
+    if rc:
+        raise ValueError(f"oracle_verify_baseline rc={rc}")
+    return BaselineResult(path, int(bonus[0]), rec[: int(nrec[0])].copy(), int(binfo[0]), float(binfo[1]),
+                          float(binfo[2]), float(binfo[3]), float(binfo[4]), float(binfo[5]))

@@ -5,7 +5,7 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ["tree_attn_oracle.c", "verify_oracle.c", "draft_sample_oracle.c"]
+SOURCES = ["tree_attn_oracle.c", "verify_oracle.c", "draft_sample_oracle.c", "verify_baselines_oracle.c"]
 LIB = os.path.join(HERE, "liboracle.so")
 
 
