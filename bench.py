@@ -220,6 +220,63 @@ def run_draft_sample(args) -> int:
     return 0
 
 
+def run_rejection_curve(args) -> int:
+    """Rejection rate at one node against the number of speculated children k, for Sequoia's
+    algorithm and the two baselines of Sec. 2.2, each with children drawn the way it assumes
+    (without replacement / independently / the draft's top k): the shape of the paper's figure
+    "rejection rate vs. number of speculated tokens" on synthetic distributions (Gaussian target
+    logits, draft = target + noise).  One JSON line per temperature.  Not the benchmark line."""
+    import numpy as np
+    import torch
+
+    import paper_2402_12374_amd as S
+    from paper_2402_12374_amd import workloads as W
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    V, pairs, trials, ks = 32000, 32, args.curve_trials, [1, 2, 3, 4, 6, 8, 12, 16]
+    k_max = max(ks)
+    g = torch.Generator(device=dev)
+    g.manual_seed(2402)
+    target_rows = (3.0 * torch.randn((pairs, V), device=dev, generator=g))
+    draft_rows = target_rows + args.curve_draft_noise * torch.randn((pairs, V), device=dev, generator=g)
+    # a star needs k+1 rows; only the root's matter for what happens at the root
+    tl = target_rows.to(torch.bfloat16)[:, None, :].expand(pairs, k_max + 1, V).contiguous()
+    dl = draft_rows.to(torch.bfloat16)[:, None, :].expand(pairs, k_max + 1, V).contiguous()
+    ws = torch.empty(S.seq_verify_workspace(k_max + 1, V, 1), dtype=torch.uint8, device=dev)
+    rng = torch.tensor([2402, 0], dtype=torch.int64, device=dev)
+    for T in (0.2, 0.6, 1.0):
+        out = {"rejection_curve": {"temperature": T, "vocab": V, "trials": trials, "draft_noise": args.curve_draft_noise, "k": ks}}
+        for name, alg in (("sequoia", S.SEQ_VERIFY_SEQUOIA), ("specinfer", S.SEQ_VERIFY_SPECINFER), ("topk", S.SEQ_VERIFY_TOPK)):
+            rates = []
+            for k in ks:
+                n = k + 1
+                parent = W.star_tree(n)
+                paths = torch.empty((trials, n), dtype=torch.int32, device=dev)
+                bonus = torch.empty((trials, 1), dtype=torch.int32, device=dev)
+                tokens = torch.zeros((trials, n), dtype=torch.int32, device=dev)
+                uniforms = torch.rand((trials, n), device=dev, generator=g).clamp_(max=1.0 - 2.0 ** -24)
+                nc = torch.full((1,), k, dtype=torch.int32, device=dev)
+                for t in range(trials):
+                    r = t % pairs
+                    if alg == S.SEQ_VERIFY_SEQUOIA:
+                        rng[1] += 1
+                        S.seq_draft_sample(dl[r, :1], nc, T, rng, k, tokens=tokens[t, 1:].view(1, k))
+                    elif alg == S.SEQ_VERIFY_SPECINFER:
+                        q = torch.softmax(dl[r, 0].float() / T, dim=0)
+                        tokens[t, 1:] = torch.multinomial(q, k, replacement=True, generator=g).to(torch.int32)
+                    else:
+                        tokens[t, 1:] = torch.topk(dl[r, 0].float(), k).indices.to(torch.int32)
+                    S.seq_verify_with(alg, tl[r, :n], dl[r, :n], tokens[t], parent, T, uniforms[t],
+                                      accepted_path=paths[t], bonus_token=bonus[t], workspace=ws)
+                torch.cuda.synchronize()
+                rates.append(round(float((paths[:, 0] < 0).float().mean().item()), 4))
+            out["rejection_curve"][name] = rates
+        print(json.dumps(out), flush=True)
+    S.shutdown()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -242,6 +299,11 @@ def main() -> int:
                     help="with --sweep: after each configuration, the tree size and depth that maximise Speedup(n, d) for "
                          "the measured t(n) (first sweep size = the decoding step)")
     ap.add_argument("--draft-cost", type=float, default=0.05, help="c of Speedup(n, d): one draft step relative to one decoding step")
+    ap.add_argument("--rejection-curve", action="store_true",
+                    help="instead of the benchmark line: rejection rate against the number of children for the three "
+                         "verification algorithms (one line per temperature)")
+    ap.add_argument("--curve-trials", type=int, default=512)
+    ap.add_argument("--curve-draft-noise", type=float, default=1.0)
     ap.add_argument("--draft-sample", action="store_true",
                     help="instead of the benchmark line: latency of seq_draft_sample per configuration (one line each)")
     ap.add_argument("--sweep-configs", default="C2,C3,C4,C5")
@@ -255,6 +317,8 @@ def main() -> int:
         return run_sweep(args)
     if args.draft_sample:
         return run_draft_sample(args)
+    if args.rejection_curve:
+        return run_rejection_curve(args)
 
     import numpy as np
     import torch

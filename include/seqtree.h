@@ -50,6 +50,7 @@ extern "C" {
 #define SEQ_ERR_TEMPERATURE (-5) /* temperature negative, NaN or infinite */
 #define SEQ_ERR_WORKSPACE (-6)   /* workspace NULL, smaller than the matching *_workspace(), or not 16-byte aligned */
 #define SEQ_ERR_HIP (-7)         /* a HIP runtime call failed (no device, launch failure, ...) */
+#define SEQ_ERR_ALGORITHM (-8)   /* algorithm is none of SEQ_VERIFY_* */
 
 #define SEQ_MAX_TREE 1024
 #define SEQ_MAX_VOCAB 524288
@@ -126,6 +127,36 @@ int seq_verify(const void* target_logits, const void* draft_logits,
                const float* uniforms, int32_t* accepted_path, int32_t* bonus_token,
                int32_t n_tree, int32_t vocab, int32_t dtype,
                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The same walk with one of the baseline verification algorithms of Sec. 2.2 at every node
+ * (seq_verify is seq_verify_with(SEQ_VERIFY_SEQUOIA, ...)).  Arguments, outputs, workspace and
+ * errors as for seq_verify; SEQ_ERR_ALGORITHM for an unknown algorithm.
+ *
+ *   SEQ_VERIFY_SPECINFER  Algorithm 2 without its blue lines: the children are taken to be
+ *       independent draws from the draft distribution, which therefore stays what it was after a
+ *       rejection (no token is struck out, nothing is renormalised, repeated tokens are legal):
+ *       accept c iff uniforms[c] < R[s] / Q[s];  rejected: R = norm(max(R - Q, 0)).
+ *   SEQ_VERIFY_TOPK       naive / top-k sampling: at the node v the walk stands on, draw
+ *       x ~ softmax(target_logits[v] / T) by inverse CDF with uniforms[v] (the root: uniforms[0]);
+ *       if x is the token of a child of v, the first such child in sibling order is accepted and
+ *       the walk goes on there; otherwise bonus_token = x and the walk ends.  draft_logits is not
+ *       read and may be NULL.  Every node's draw is computed (one workgroup per node), then the
+ *       walk follows them.
+ * At temperature 0 all three accept a child exactly when its token is the arg-max of the
+ * target's row and emit that arg-max.
+ * Trace: as below for SPECINFER.  For TOPK one record per visited node: int32 node, int32 accepted
+ * child or -1, int32 drawn token, float uniform; header [3], [4] are zero; the four floats about
+ * the bonus draw describe the last draw.
+ */
+#define SEQ_VERIFY_SEQUOIA 0
+#define SEQ_VERIFY_SPECINFER 1
+#define SEQ_VERIFY_TOPK 2
+int seq_verify_with(int32_t algorithm, const void* target_logits, const void* draft_logits,
+                    const int32_t* tree_tokens, const int32_t* parent, float temperature,
+                    const float* uniforms, int32_t* accepted_path, int32_t* bonus_token,
+                    int32_t n_tree, int32_t vocab, int32_t dtype,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Trace left at the start of the seq_verify workspace.  Header of 8 int32:

@@ -18,13 +18,14 @@ LIB_PATH = os.path.join(HERE, "libseqtree.so")
 SEQ_BF16, SEQ_F32 = 1, 2
 SEQ_OK = 0
 SEQ_ERR_NULL, SEQ_ERR_SHAPE, SEQ_ERR_TREE, SEQ_ERR_DTYPE = -1, -2, -3, -4
-SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE, SEQ_ERR_HIP = -5, -6, -7
+SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE, SEQ_ERR_HIP, SEQ_ERR_ALGORITHM = -5, -6, -7, -8
+SEQ_VERIFY_SEQUOIA, SEQ_VERIFY_SPECINFER, SEQ_VERIFY_TOPK = 0, 1, 2
 SEQ_MAX_TREE = 1024
 SEQ_MAX_VOCAB = 524288
 SEQ_MAX_CHILDREN = 64
 TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
-EXPORTS = ("seq_tree_attn", "seq_verify", "seq_draft_sample", "seq_tree_attn_workspace",
+EXPORTS = ("seq_tree_attn", "seq_verify", "seq_verify_with", "seq_draft_sample", "seq_tree_attn_workspace",
            "seq_verify_workspace", "seq_draft_sample_workspace", "seq_tree_plan_host",
            "seq_build_tree", "seq_tree_expected_tokens", "seq_pick_tree_shape",
            "seq_shutdown", "seq_strerror", "seq_version")
@@ -51,6 +52,8 @@ def lib() -> C.CDLL:
         l.seq_tree_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, i32, vp, sz, vp]
         l.seq_verify.restype = C.c_int
         l.seq_verify.argtypes = [vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
+        l.seq_verify_with.restype = C.c_int
+        l.seq_verify_with.argtypes = [i32, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
         l.seq_tree_attn_workspace.restype = sz
         l.seq_tree_attn_workspace.argtypes = [i32] * 6
         l.seq_verify_workspace.restype = sz
@@ -203,7 +206,7 @@ def seq_tree_attn(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len: int, 
 
 
 def seq_verify(target_logits, draft_logits, tree_tokens, parent, temperature: float, uniforms,
-               accepted_path=None, bonus_token=None, workspace=None, stream=None):
+               accepted_path=None, bonus_token=None, workspace=None, stream=None, algorithm: int = SEQ_VERIFY_SEQUOIA):
     """Logits [n,V] (bf16 or fp32), tree_tokens int32 [n], uniforms float32 [n] on the GPU; parent
     on the host.  Returns (accepted_path int32 [n], bonus_token int32 [1], workspace) -- device
     tensors, valid after the stream has been synchronised."""
@@ -219,13 +222,13 @@ def seq_verify(target_logits, draft_logits, tree_tokens, parent, temperature: fl
     if workspace is None or workspace.numel() * workspace.element_size() < need:
         workspace = torch.empty(need, dtype=torch.uint8, device=target_logits.device)
     for t in (target_logits, draft_logits, tree_tokens, uniforms):
-        if not t.is_contiguous() or not t.is_cuda:
+        if t is not None and (not t.is_contiguous() or not t.is_cuda):
             raise SeqTreeError(SEQ_ERR_SHAPE, "seq_verify (tensors must be contiguous GPU tensors)")
-    rc = lib().seq_verify(target_logits.data_ptr(), draft_logits.data_ptr(), tree_tokens.data_ptr(),
-                          par.ctypes.data, float(temperature), uniforms.data_ptr(),
-                          accepted_path.data_ptr(), bonus_token.data_ptr(), n, V, code,
-                          workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                          _stream_ptr(stream))
+    args = (target_logits.data_ptr(), None if draft_logits is None else draft_logits.data_ptr(),
+            tree_tokens.data_ptr(), par.ctypes.data, float(temperature), uniforms.data_ptr(),
+            accepted_path.data_ptr(), bonus_token.data_ptr(), n, V, code,
+            workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    rc = lib().seq_verify(*args) if algorithm == SEQ_VERIFY_SEQUOIA else lib().seq_verify_with(int(algorithm), *args)
     if rc != SEQ_OK:
         raise SeqTreeError(rc, "seq_verify")
     return accepted_path, bonus_token, workspace
@@ -261,15 +264,24 @@ def seq_draft_sample(draft_logits, n_children, temperature: float, rng, k_max: i
     return tokens, workspace
 
 
+def seq_verify_with(algorithm: int, target_logits, draft_logits, tree_tokens, parent, temperature: float, uniforms,
+                    **kw):
+    """seq_verify with one of SEQ_VERIFY_SEQUOIA / SEQ_VERIFY_SPECINFER / SEQ_VERIFY_TOPK at every node."""
+    return seq_verify(target_logits, draft_logits, tree_tokens, parent, temperature, uniforms,
+                      algorithm=algorithm, **kw)
+
+
 def read_verify_trace(workspace) -> dict:
-    """Decode the trace seq_verify leaves at the start of its workspace (synchronises)."""
+    """Decode the trace seq_verify leaves at the start of its workspace (synchronises).  For
+    SEQ_VERIFY_TOPK at T > 0 the records read: nodes = visited node, accepted = a child matched,
+    and raw[:, 1] / raw[:, 2] (kept as 'children' / 'drawn') the accepted child or -1 and the drawn token."""
     raw = workspace.cpu().numpy().view(np.int32)
     n_dec, status, stop, fallbacks, degenerate = (int(x) for x in raw[:5])
     rec = raw[TRACE_HEADER_INTS: TRACE_HEADER_INTS + n_dec * TRACE_RECORD_WORDS].reshape(-1, 4)
     binfo = raw[TRACE_HEADER_INTS + SEQ_MAX_TREE * TRACE_RECORD_WORDS:][:4].view(np.float32)
     return {
         "status": status, "stop_node": stop, "fallbacks": fallbacks, "degenerate": degenerate,
-        "nodes": rec[:, 0].copy(), "accepted": rec[:, 1].astype(bool),
+        "nodes": rec[:, 0].copy(), "accepted": rec[:, 1].astype(bool), "children": rec[:, 1].copy(), "drawn": rec[:, 2].copy(),
         "ratios": rec[:, 2].copy().view(np.float32), "uniforms": rec[:, 3].copy().view(np.float32),
         "bonus_u": float(binfo[0]), "bonus_total": float(binfo[1]),
         "bonus_cdf_lo": float(binfo[2]), "bonus_cdf_hi": float(binfo[3]),

@@ -240,6 +240,7 @@ extern "C" const char* seq_strerror(int code) {
         case SEQ_ERR_TEMPERATURE: return "temperature must be finite and >= 0";
         case SEQ_ERR_WORKSPACE: return "workspace missing or too small";
         case SEQ_ERR_HIP: return "HIP runtime error";
+        case SEQ_ERR_ALGORITHM: return "algorithm must be one of SEQ_VERIFY_*";
         default: return "unknown seqtree error code";
     }
 }

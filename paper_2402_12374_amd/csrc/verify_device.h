@@ -41,6 +41,7 @@ struct VerifyParams {
     uint32_t spin_limit;
     int n, V, W;
     float inv_T;
+    int with_replacement;   // SpecInfer: the draft distribution is never updated (Algorithm 2 without its blue lines)
 };
 
 // verify_chains.hip: every node's sibling chain in parallel, then the walk over the results.
@@ -48,6 +49,8 @@ struct VerifyParams {
 constexpr int kChainsMaxVocab = 32768;
 constexpr int kChainsMaxNodes = 256;   // one workgroup per node, one workgroup per CU
 void launch_verify_chains(const VerifyParams& p, int dtype, hipStream_t stream);
+// verify_topk.hip: naive / top-k sampling (Sec. 2.2): one draw from the target per node, then the walk.
+void launch_verify_topk(const VerifyParams& p, int dtype, hipStream_t stream);
 
 template <typename LT> __device__ __forceinline__ float load_logit(const LT* row, int x);
 template <> __device__ __forceinline__ float load_logit<float>(const float* row, int x) { return row[x]; }
@@ -192,7 +195,7 @@ __device__ __forceinline__ ChildTest node_test_child(const NodeState& st, float 
 
 // Rejection: R <- norm(max(R - D, 0)), then D[s] <- 0 (uniform over what is left once the draft
 // has no mass).  Only the coefficients move here; the pass over the vocabulary follows.
-__device__ __forceinline__ void node_reject_child(NodeState& st, bool in_s, int V) {
+__device__ __forceinline__ void node_reject_child(NodeState& st, bool in_s, int V, bool keep_draft = false) {
     const int left = V - st.n_rej;
     st.dA = 0.0;
     st.dB = 0.0;
@@ -202,7 +205,7 @@ __device__ __forceinline__ void node_reject_child(NodeState& st, bool in_s, int 
     st.B += st.dB;
     st.af = (float)st.A;
     st.bf = (float)st.B;
-    if (!in_s) ++st.n_rej;
+    if (!in_s && !keep_draft) ++st.n_rej;
 }
 
 // Inverse CDF over 64 consecutive blocks of the vocabulary, one per lane of a wavefront: which

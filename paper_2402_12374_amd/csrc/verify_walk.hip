@@ -183,14 +183,15 @@ __device__ void leader_step(const VerifyParams& p, Shared& sh, int c_begin, int 
     const int k = st.ci - c_begin;
     const int c = sh.child_list[st.ci];
     const float u = sh.uniform[c];
-    const bool in_s = sh.child_dup[k] != 0;
+    // SpecInfer keeps the draft distribution as it is: no token is ever struck out
+    const bool in_s = !p.with_replacement && sh.child_dup[k] != 0;
     const ChildTest t = node_test_child(st.ns, sh.child_lt[k], sh.child_ld[k], in_s, V);  // probabilities by now
     const bool accept = t.accepts(u);
     record(p, st.n_dec, c, accept, t.ratio(), u);
     ++st.n_dec;
     if (accept) { st.action = kActAccepted; st.next = c; return; }
-    node_reject_child(st.ns, in_s, V);
-    st.zero_token = in_s ? -1 : sh.token[c];
+    node_reject_child(st.ns, in_s, V, p.with_replacement != 0);
+    st.zero_token = (in_s || p.with_replacement) ? -1 : sh.token[c];
     ++st.ci;
     st.action = kActPass;
 }
@@ -571,8 +572,20 @@ extern "C" int seq_verify(const void* target_logits, const void* draft_logits,
                           const float* uniforms, int32_t* accepted_path, int32_t* bonus_token,
                           int32_t n_tree, int32_t vocab, int32_t dtype, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
-    if (!target_logits || !draft_logits || !tree_tokens || !parent || !uniforms || !accepted_path ||
-        !bonus_token)
+    return seq_verify_with(SEQ_VERIFY_SEQUOIA, target_logits, draft_logits, tree_tokens, parent, temperature,
+                           uniforms, accepted_path, bonus_token, n_tree, vocab, dtype, workspace,
+                           workspace_bytes, hip_stream);
+}
+
+extern "C" int seq_verify_with(int32_t algorithm, const void* target_logits, const void* draft_logits,
+                               const int32_t* tree_tokens, const int32_t* parent, float temperature,
+                               const float* uniforms, int32_t* accepted_path, int32_t* bonus_token,
+                               int32_t n_tree, int32_t vocab, int32_t dtype, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+    if (algorithm != SEQ_VERIFY_SEQUOIA && algorithm != SEQ_VERIFY_SPECINFER && algorithm != SEQ_VERIFY_TOPK)
+        return SEQ_ERR_ALGORITHM;
+    if (!target_logits || (!draft_logits && algorithm != SEQ_VERIFY_TOPK) || !tree_tokens || !parent ||
+        !uniforms || !accepted_path || !bonus_token)
         return SEQ_ERR_NULL;
     if (dtype != SEQ_BF16 && dtype != SEQ_F32) return SEQ_ERR_DTYPE;
     if (n_tree < 1 || n_tree > SEQ_MAX_TREE || vocab < 2 || vocab > SEQ_MAX_VOCAB) return SEQ_ERR_SHAPE;
@@ -612,12 +625,19 @@ extern "C" int seq_verify(const void* target_logits, const void* draft_logits,
     p.W = (vocab + kThreads * ept - 1) / (kThreads * ept);
     const bool greedy = temperature == 0.0f;
     p.inv_T = greedy ? 1.0f : 1.0f / temperature;
+    p.with_replacement = algorithm == SEQ_VERIFY_SPECINFER;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (algorithm == SEQ_VERIFY_TOPK && !greedy) {
+        launch_verify_topk(p, dtype, stream);
+        return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
+    }
     // Sampling with a vocabulary one workgroup can hold, and a tree whose nodes all find a CU at
     // once: all nodes at once.  Otherwise (and for greedy decoding, which needs one arg-max per
     // visited node) the lazy walk.
     const bool chains_pay = n_tree <= kChainsMaxNodes || g_verify_mode == 2;
-    if (!greedy && vocab <= kChainsMaxVocab && g_verify_mode != 1 && chains_pay) {
+    // (T = 0: all three algorithms accept a child exactly when its token is the target's arg-max
+    // and emit that arg-max, so the greedy kernel serves them all.)
+    if (!greedy && algorithm == SEQ_VERIFY_SEQUOIA && vocab <= kChainsMaxVocab && g_verify_mode != 1 && chains_pay) {
         launch_verify_chains(p, dtype, stream);
         return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
     }

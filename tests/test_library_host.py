@@ -111,6 +111,25 @@ def test_draft_sample_argument_errors_need_no_gpu():
     assert _draft(ws_bytes=S.seq_draft_sample_workspace(4, 100, 8, B.SEQ_F32) - 1) == B.SEQ_ERR_WORKSPACE
 
 
+def test_verify_with_argument_errors_need_no_gpu():
+    par = np.array([-1, 0, 0], dtype=np.int32)
+    ptr, ws = 0x1000, 0x1000
+    need = S.seq_verify_workspace(3, 64, B.SEQ_F32)
+
+    def call(algorithm, tl=ptr, dl=ptr, temperature=1.0):
+        return S.lib().seq_verify_with(algorithm, tl, dl, ptr, par.ctypes.data, temperature, ptr, ptr, ptr, 3, 64,
+                                       B.SEQ_F32, ws, need, None)
+
+    for bad in (-1, 3, 99):
+        assert call(bad) == B.SEQ_ERR_ALGORITHM
+    for alg in (B.SEQ_VERIFY_SEQUOIA, B.SEQ_VERIFY_SPECINFER, B.SEQ_VERIFY_TOPK):
+        assert call(alg, tl=None) == B.SEQ_ERR_NULL
+        assert call(alg, temperature=-1.0) == B.SEQ_ERR_TEMPERATURE
+    assert call(B.SEQ_VERIFY_SEQUOIA, dl=None) == B.SEQ_ERR_NULL
+    assert call(B.SEQ_VERIFY_SPECINFER, dl=None) == B.SEQ_ERR_NULL
+    assert S.strerror(B.SEQ_ERR_ALGORITHM) != S.strerror(-99)
+
+
 def test_workspace_sizes():
     assert S.seq_draft_sample_workspace(1, 2, 1, B.SEQ_F32) >= 256
     assert S.seq_draft_sample_workspace(768, 128256, 10, B.SEQ_BF16) >= 256
