@@ -62,6 +62,8 @@ def lib() -> C.CDLL:
         l.seq_draft_sample.argtypes = [vp, vp, C.c_float, vp, vp, i32, i32, i32, i32, vp, sz, vp]
         l.seq_draft_sample_workspace.restype = sz
         l.seq_draft_sample_workspace.argtypes = [i32] * 4
+        l.seqtree_internal_set_topk_mode.restype = None
+        l.seqtree_internal_set_topk_mode.argtypes = [C.c_int]
         l.seqtree_internal_set_draft_chunks.restype = None
         l.seqtree_internal_set_draft_chunks.argtypes = [C.c_int]
         l.seqtree_internal_set_draft_max_groups.restype = None

@@ -20,13 +20,25 @@ constexpr int kStep = kThreads * kEpt;
 
 struct Draw { int32_t token; float u, total, lo, hi; int32_t pad[3]; };   // 32 bytes per node
 
+struct DrawShared {
+    float part[kWaves];
+    double scan[kWaves];
+    int found_at, last_with_mass;
+    double found_lo, found_hi;
+    Draw result;
+};
+
+// The draw of node v by the whole workgroup; the result is left in sh.result (valid after the
+// barrier this ends with).
 template <typename LT>
-__global__ void __launch_bounds__(kThreads) topk_draw_kernel(const VerifyParams p, Draw* draws) {
-    __shared__ float part[kWaves];
-    __shared__ double scan[kWaves];
-    __shared__ int found_at, last_with_mass;
-    __shared__ double found_lo, found_hi;
-    const int v = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+__device__ __forceinline__ void draw_node(const VerifyParams& p, int v, DrawShared& sh) {
+    float (&part)[kWaves] = sh.part;
+    double (&scan)[kWaves] = sh.scan;
+    int& found_at = sh.found_at;
+    int& last_with_mass = sh.last_with_mass;
+    double& found_lo = sh.found_lo;
+    double& found_hi = sh.found_hi;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int V = p.V;
     const LT* row = static_cast<const LT*>(p.target) + (size_t)v * V;
     const bool vec_ok = (V % (16 / (int)sizeof(LT)) == 0) && (reinterpret_cast<uintptr_t>(p.target) & 15) == 0;
@@ -112,17 +124,30 @@ __global__ void __launch_bounds__(kThreads) topk_draw_kernel(const VerifyParams 
             d.lo = d.hi = 1.f;
         }
         d.pad[0] = d.pad[1] = d.pad[2] = 0;
-        draws[v] = d;
+        sh.result = d;
     }
+    __syncthreads();
 }
 
-// One wavefront follows the draws from the root: a lane per child looks for the drawn token.
-__global__ void __launch_bounds__(64) topk_walk_kernel(const VerifyParams p, const Draw* draws) {
-    const int lane = threadIdx.x;
+template <typename LT>
+__global__ void __launch_bounds__(kThreads) topk_draw_kernel(const VerifyParams p, Draw* draws) {
+    __shared__ DrawShared sh;
+    draw_node<LT>(p, blockIdx.x, sh);
+    if (threadIdx.x == 0) draws[blockIdx.x] = sh.result;
+}
+
+// Follows the draws from the root: a lane per child looks for the drawn token.  With draws given
+// (DRAWS != nullptr) one wavefront reads them; without, one workgroup makes each draw when the
+// walk gets there (a big tree over a big vocabulary: the walk visits a handful of the nodes).
+template <typename LT>
+__global__ void __launch_bounds__(kThreads) topk_walk_kernel(const VerifyParams p, const Draw* draws) {
+    __shared__ DrawShared sh;
+    const int lane = threadIdx.x & 63;
     int v = 0, path_len = 0, n_rec = 0;
     Draw d;
     for (;;) {
-        d = draws[v];
+        if (draws) d = draws[v];
+        else { draw_node<LT>(p, v, sh); d = sh.result; __syncthreads(); }
         const int c_begin = p.child_start[v], c_end = p.child_start[v + 1];
         int next = -1;
         for (int k0 = c_begin; k0 < c_end && next < 0; k0 += 64) {
@@ -132,18 +157,18 @@ __global__ void __launch_bounds__(64) topk_walk_kernel(const VerifyParams p, con
             const unsigned long long hits = __ballot(match);
             if (hits) next = __builtin_amdgcn_readlane(c, __builtin_ctzll(hits));   // the first such child
         }
-        if (lane == 0) {
+        if (threadIdx.x == 0) {
             int32_t* rec = p.trace + SEQ_TRACE_HEADER_INTS + n_rec * SEQ_TRACE_RECORD_WORDS;
             rec[0] = v; rec[1] = next; rec[2] = d.token; rec[3] = __float_as_int(d.u);
         }
         ++n_rec;
         if (next < 0) break;
-        if (lane == 0) p.path[path_len] = next;
+        if (threadIdx.x == 0) p.path[path_len] = next;
         ++path_len;
         v = next;
     }
-    for (int i = path_len + lane; i < p.n; i += 64) p.path[i] = -1;
-    if (lane == 0) {
+    for (int i = path_len + (int)threadIdx.x; i < p.n; i += (int)blockDim.x) p.path[i] = -1;
+    if (threadIdx.x == 0) {
         p.bonus[0] = d.token;
         p.trace[0] = n_rec; p.trace[1] = 0; p.trace[2] = v;
         p.trace[3] = p.trace[4] = p.trace[5] = p.trace[6] = p.trace[7] = 0;
@@ -152,16 +177,28 @@ __global__ void __launch_bounds__(64) topk_walk_kernel(const VerifyParams p, con
     }
 }
 
+int g_topk_mode = 0;   // test hook: 1 = always all draws at once, 2 = always where the walk goes
+
 }  // namespace
+
+void set_topk_mode(int mode) { g_topk_mode = mode; }
 
 void launch_verify_topk(const VerifyParams& p, int dtype, hipStream_t stream) {
     // the draws live where the per-node kernel keeps its records: after the trace
     Draw* draws = reinterpret_cast<Draw*>(p.records);
     static_assert(sizeof(Draw) * SEQ_MAX_TREE <=
                   sizeof(unsigned long long) * (size_t)SEQ_MAX_TREE * (kChildRecordWords + kNodeRecordWords), "workspace");
+    // all draws at once while that is cheap (three sweeps over every row); beyond 2^24 logits one
+    // workgroup draws only where the walk goes (measured at 768 x 128256: 73 us against 205 us)
+    const bool lazy = (long long)p.n * p.V > (1ll << 24) || g_topk_mode == 2;
+    if (lazy && g_topk_mode != 1) {
+        if (dtype == SEQ_BF16) topk_walk_kernel<uint16_t><<<1, kThreads, 0, stream>>>(p, nullptr);
+        else topk_walk_kernel<float><<<1, kThreads, 0, stream>>>(p, nullptr);
+        return;
+    }
     if (dtype == SEQ_BF16) topk_draw_kernel<uint16_t><<<p.n, kThreads, 0, stream>>>(p, draws);
     else topk_draw_kernel<float><<<p.n, kThreads, 0, stream>>>(p, draws);
-    topk_walk_kernel<<<1, 64, 0, stream>>>(p, draws);
+    topk_walk_kernel<uint16_t><<<1, 64, 0, stream>>>(p, draws);
 }
 
 }  // namespace verify

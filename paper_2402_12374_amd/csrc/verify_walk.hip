@@ -560,6 +560,9 @@ extern "C" void seqtree_internal_set_spin_limit(uint32_t polls) { g_spin_limit =
 // wherever the vocabulary allows it.
 static int g_verify_mode = 0;
 extern "C" void seqtree_internal_set_verify_mode(int mode) { g_verify_mode = mode; }
+// Test hook for SEQ_VERIFY_TOPK: 0 = the library chooses, 1 = every node draws at once, 2 = one
+// workgroup draws where the walk goes.
+extern "C" void seqtree_internal_set_topk_mode(int mode) { set_topk_mode(mode); }
 
 extern "C" size_t seq_verify_workspace(int32_t n_tree, int32_t vocab, int32_t dtype) {
     (void)n_tree; (void)vocab; (void)dtype;

@@ -15,6 +15,15 @@ from gpu_util import DEV, FLAG_MARGIN, to_dev
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["draws at once", "draws along the walk"])
+def topk_kernel_choice(request):
+    """Top-k sampling has two kernels (every node draws at once; one workgroup draws where the walk
+    goes): every case runs with each forced."""
+    S.lib().seqtree_internal_set_topk_mode(1 if request.param == "draws at once" else 2)
+    yield request.param
+    S.lib().seqtree_internal_set_topk_mode(0)
+
+
 def inputs_for(algorithm, parent, V, T, dtype, seed, sigma_d=1.5):
     """Logits as for the Sequoia tests; children drawn the way the algorithm assumes: independent
     draws from the draft distribution (repeats allowed) for SpecInfer, its top-k tokens for top-k."""
