@@ -210,6 +210,27 @@ int seq_draft_sample(const void* draft_logits, const int32_t* n_children, float 
                      int32_t k_max, int32_t dtype, void* workspace, size_t workspace_bytes,
                      void* hip_stream);
 
+/*
+ * Appends the K/V rows of the root and of the accepted tree nodes to the cache, in path order:
+ * row prefix_len of every head receives node 0's, row prefix_len + j the j-th accepted node's
+ * (loop glue between two steps; not described in the paper, whose KV cache lives inside the
+ * Transformers library).  The next step runs with the new prefix length and a new tree.
+ *
+ *   k_tree, v_tree   [n_tree, kv_heads, head_dim]   this step's tree tensors
+ *   accepted_path    DEVICE [n_tree] int32, as seq_verify leaves it (node ids, then -1)
+ *   parent           HOST [n_tree]: bounds the path length (the tree's depth)
+ *   k_cache, v_cache [kv_heads, prefix_cap, head_dim], written in place at rows >= prefix_len
+ *   new_prefix_len   DEVICE [1] out, may be NULL: prefix_len + 1 + number of accepted nodes
+ * Rows that would fall at or beyond prefix_cap are not written and new_prefix_len stops at
+ * prefix_cap: the caller sizes the cache for prefix_len + depth + 1.  A path entry that is not a
+ * node id ends the path.  Pointers 16-byte aligned.  Asynchronous on hip_stream, no host sync.
+ * Errors: SEQ_ERR_NULL, SEQ_ERR_DTYPE, SEQ_ERR_SHAPE, SEQ_ERR_TREE, SEQ_ERR_HIP.
+ */
+int seq_kv_append(const void* k_tree, const void* v_tree, const int32_t* accepted_path,
+                  const int32_t* parent, void* k_cache, void* v_cache, int32_t prefix_len,
+                  int32_t n_tree, int32_t kv_heads, int32_t head_dim, int32_t prefix_cap,
+                  int32_t dtype, int32_t* new_prefix_len, void* hip_stream);
+
 /* Scratch sizes in bytes for the calls above (0 is never returned; at least 256). */
 size_t seq_tree_attn_workspace(int32_t prefix_len, int32_t n_tree, int32_t heads,
                                int32_t kv_heads, int32_t head_dim, int32_t dtype);

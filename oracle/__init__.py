@@ -259,3 +259,24 @@ def verify_baseline(algorithm: int, target_logits, draft_logits, tree_tokens, pa
         raise ValueError(f"oracle_verify_baseline rc={rc}")
     return BaselineResult(path, int(bonus[0]), rec[: int(nrec[0])].copy(), int(binfo[0]), float(binfo[1]),
                           float(binfo[2]), float(binfo[3]), float(binfo[4]), float(binfo[5]))
+
+
+# --------------------------------------------------------------------------
+# loop glue: the accepted path's K/V rows join the prefix
+# --------------------------------------------------------------------------
+def kv_append(k_tree, v_tree, accepted_path, k_cache, v_cache, prefix_len: int):
+    """The caches after a step: the root's rows, then the accepted nodes' rows in path order, behind
+    the prefix_len valid rows of every head.  Returns (k_cache, v_cache, new_prefix_len); rows that
+    do not fit the cache are dropped."""
+    kc, vc = np.array(k_cache, copy=True), np.array(v_cache, copy=True)
+    nodes = [0]
+    for x in np.asarray(accepted_path):
+        if x < 0 or x >= len(k_tree):
+            break
+        nodes.append(int(x))
+    cap = kc.shape[1]
+    for j, node in enumerate(nodes):
+        if prefix_len + j < cap:
+            kc[:, prefix_len + j, :] = k_tree[node]
+            vc[:, prefix_len + j, :] = v_tree[node]
+    return kc, vc, min(prefix_len + len(nodes), cap)

@@ -25,7 +25,7 @@ SEQ_MAX_VOCAB = 524288
 SEQ_MAX_CHILDREN = 64
 TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
-EXPORTS = ("seq_tree_attn", "seq_verify", "seq_verify_with", "seq_draft_sample", "seq_tree_attn_workspace",
+EXPORTS = ("seq_tree_attn", "seq_verify", "seq_verify_with", "seq_draft_sample", "seq_kv_append", "seq_tree_attn_workspace",
            "seq_verify_workspace", "seq_draft_sample_workspace", "seq_tree_plan_host",
            "seq_build_tree", "seq_tree_expected_tokens", "seq_pick_tree_shape",
            "seq_shutdown", "seq_strerror", "seq_version")
@@ -54,6 +54,8 @@ def lib() -> C.CDLL:
         l.seq_verify.argtypes = [vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
         l.seq_verify_with.restype = C.c_int
         l.seq_verify_with.argtypes = [i32, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
+        l.seq_kv_append.restype = C.c_int
+        l.seq_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp]
         l.seq_tree_attn_workspace.restype = sz
         l.seq_tree_attn_workspace.argtypes = [i32] * 6
         l.seq_verify_workspace.restype = sz
@@ -264,6 +266,27 @@ def seq_draft_sample(draft_logits, n_children, temperature: float, rng, k_max: i
     if rc != SEQ_OK:
         raise SeqTreeError(rc, "seq_draft_sample")
     return tokens, workspace
+
+
+def seq_kv_append(k_tree, v_tree, accepted_path, parent, k_cache, v_cache, prefix_len: int, new_prefix_len=None,
+                  stream=None):
+    """Appends the root's and the accepted nodes' K/V rows to the caches in place (GPU tensors;
+    accepted_path int32 [n] on the GPU, parent on the host).  Returns new_prefix_len (int32 [1], GPU)."""
+    import torch
+    par = _parent_array(parent)
+    n, Hk, d = k_tree.shape
+    code = _dtype_code(k_tree)
+    for t in (k_tree, v_tree, k_cache, v_cache, accepted_path):
+        if not t.is_contiguous() or not t.is_cuda:
+            raise SeqTreeError(SEQ_ERR_SHAPE, "seq_kv_append (tensors must be contiguous GPU tensors)")
+    if new_prefix_len is None:
+        new_prefix_len = torch.empty(1, dtype=torch.int32, device=k_tree.device)
+    rc = lib().seq_kv_append(k_tree.data_ptr(), v_tree.data_ptr(), accepted_path.data_ptr(), par.ctypes.data,
+                             k_cache.data_ptr(), v_cache.data_ptr(), int(prefix_len), n, Hk, d, k_cache.shape[1], code,
+                             new_prefix_len.data_ptr(), _stream_ptr(stream))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_kv_append")
+    return new_prefix_len
 
 
 def seq_verify_with(algorithm: int, target_logits, draft_logits, tree_tokens, parent, temperature: float, uniforms,
