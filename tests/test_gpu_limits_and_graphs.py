@@ -113,3 +113,77 @@ def test_graph_replays_match_eager_results():
         assert np.array_equal(got_out, eager_out.astype(np.float32))
         assert check_verify(v, (got_path, got_bonus, trace)) in ("exact", "flagged")
         assert np.abs(got_out - oracle_attn(a)).max() <= TOL[W.BF16]
+
+
+def test_whole_iteration_in_one_graph():
+    """Draw the root's children, verify the tree with each of the three algorithms, append the
+    accepted path to the cache -- captured once, replayed with the step counter advanced on the
+    device and new logits copied in; every replay must equal what the checker computes for that
+    step number (no host value is baked into the graph except sizes and pointers)."""
+    n, V, T, Hk, d, P, cap = 6, 4096, 0.8, 4, 64, 20, 32
+    parent = W.star_tree(n)
+    k = n - 1
+    seed = 31337
+    rng = torch.tensor([seed, 0], dtype=torch.int64, device=DEV)
+    nc = torch.tensor([k], dtype=torch.int32, device=DEV)
+    tokens = torch.zeros(n, dtype=torch.int32, device=DEV)
+    tl = torch.zeros((n, V), dtype=torch.bfloat16, device=DEV)
+    dl = torch.zeros((n, V), dtype=torch.bfloat16, device=DEV)
+    un = torch.zeros(n, dtype=torch.float32, device=DEV)
+    outs = {alg: (torch.empty(n, dtype=torch.int32, device=DEV), torch.empty(1, dtype=torch.int32, device=DEV),
+                  torch.empty(S.seq_verify_workspace(n, V, 1), dtype=torch.uint8, device=DEV))
+            for alg in (S.SEQ_VERIFY_SEQUOIA, S.SEQ_VERIFY_SPECINFER, S.SEQ_VERIFY_TOPK)}
+    a0 = W.make_attn_inputs(Hk, Hk, d, P, parent, W.BF16, seed=1, prefix_cap=cap)
+    kt, vt = to_dev(a0.k_tree, W.BF16), to_dev(a0.v_tree, W.BF16)
+    kc, vc = to_dev(a0.k_cache, W.BF16), to_dev(a0.v_cache, W.BF16)
+    new_len = torch.zeros(1, dtype=torch.int32, device=DEV)
+    dws = torch.empty(S.seq_draft_sample_workspace(1, V, k, 1), dtype=torch.uint8, device=DEV)
+
+    def iteration():
+        S.seq_draft_sample(dl[:1], nc, T, rng, k, tokens=tokens[1:].view(1, k), workspace=dws)
+        for alg, (path, bonus, ws) in outs.items():
+            S.seq_verify_with(alg, tl, dl, tokens, parent, T, un, accepted_path=path, bonus_token=bonus, workspace=ws)
+        S.seq_kv_append(kt, vt, outs[S.SEQ_VERIFY_SEQUOIA][0], parent, kc, vc, P, new_prefix_len=new_len)
+        rng[1] += 1          # the next replay draws with the next step number
+
+    iteration()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        iteration()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        iteration()
+    step = int(rng[1].item())
+    for rep in range(4):
+        v = W.make_verify_inputs(parent, V, 3.0, 0.6, T, W.BF16, seed=40 + rep)
+        tl.copy_(to_dev(v.target_logits, W.BF16)); dl.copy_(to_dev(v.draft_logits, W.BF16))
+        un.copy_(torch.from_numpy(v.uniforms).to(DEV))
+        kc.copy_(to_dev(a0.k_cache, W.BF16)); vc.copy_(to_dev(a0.v_cache, W.BF16))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        drawn = oracle.draft_sample(v.draft_logits[:1], [k], T, seed, step, k_stride=k)
+        if drawn.closest_call(0, k) < 1e-4:
+            step += 1
+            continue
+        assert np.array_equal(tokens[1:].cpu().numpy(), drawn.tokens[0]), rep
+        v.tree_tokens[1:] = drawn.tokens[0]
+        ref = oracle.verify(v.target_logits, v.draft_logits, v.tree_tokens, parent, T, v.uniforms)
+        if all(dec.margin > 1e-5 for dec in ref.decisions) and ref.bonus_margin > 1e-5:
+            path, bonus, _ = outs[S.SEQ_VERIFY_SEQUOIA]
+            assert [int(x) for x in path.cpu().numpy() if x >= 0] == ref.path and int(bonus.item()) == ref.bonus_token
+            want_k, want_v, want_len = oracle.kv_append(a0.k_tree, a0.v_tree, path.cpu().numpy(), a0.k_cache, a0.v_cache, P)
+            assert int(new_len.item()) == want_len
+            assert np.array_equal(kc.float().cpu().numpy(), want_k) and np.array_equal(vc.float().cpu().numpy(), want_v)
+        for alg in (S.SEQ_VERIFY_SPECINFER, S.SEQ_VERIFY_TOPK):
+            refb = oracle.verify_baseline(alg, v.target_logits, v.draft_logits, v.tree_tokens, parent, T, v.uniforms)
+            margins = [abs(r[2] - r[5]) for r in refb.records] if alg == S.SEQ_VERIFY_SPECINFER else [r[5] for r in refb.records]
+            if min(margins + [refb.bonus_margin]) > 1e-5:
+                path, bonus, _ = outs[alg]
+                assert [int(x) for x in path.cpu().numpy() if x >= 0] == refb.path and int(bonus.item()) == refb.bonus_token, (rep, alg)
+        step += 1
+    assert int(rng[1].item()) == step
