@@ -231,6 +231,26 @@ int seq_kv_append(const void* k_tree, const void* v_tree, const int32_t* accepte
                   int32_t n_tree, int32_t kv_heads, int32_t head_dim, int32_t prefix_cap,
                   int32_t dtype, int32_t* new_prefix_len, void* hip_stream);
 
+/*
+ * Nucleus (top-p) filtering of logit rows, the sampling hyper-parameter of the paper's table on
+ * robustness to top-p (appendix "Robustness additional results"): of softmax(logits / temperature)
+ * the most probable tokens are kept, as few as reach a total probability of top_p (equal
+ * probabilities at the cut: lower token id first); every other logit becomes -inf, which
+ * seq_verify and seq_draft_sample read as probability zero.  Kept logits are copied unchanged.
+ * temperature 0: only the arg-max (lowest id) is kept.  NaN reads as -inf.
+ *
+ *   logits    [n_rows, vocab];  filtered  [n_rows, vocab] out, may be the same buffer
+ *   top_p     in (0, 1];  n_rows 1 .. SEQ_MAX_TREE;  vocab 2 .. SEQ_MAX_VOCAB
+ *   kept      DEVICE [n_rows] int32 out, may be NULL: tokens kept per row
+ * Probabilities are fp32 (sums in fp64): a cut that falls within about 1e-6 of top_p, or between
+ * tokens whose probabilities agree to fp32 precision, may keep one token more or fewer than exact
+ * arithmetic.  One workgroup per row; rows above 32768 tokens are re-read from cache at each of the
+ * 30 bisection steps (slow).  Errors: SEQ_ERR_NULL, SEQ_ERR_DTYPE, SEQ_ERR_SHAPE (top_p outside
+ * (0, 1] included), SEQ_ERR_TEMPERATURE, SEQ_ERR_HIP.
+ */
+int seq_top_p_filter(const void* logits, void* filtered, float top_p, float temperature,
+                     int32_t n_rows, int32_t vocab, int32_t dtype, int32_t* kept, void* hip_stream);
+
 /* Scratch sizes in bytes for the calls above (0 is never returned; at least 256). */
 size_t seq_tree_attn_workspace(int32_t prefix_len, int32_t n_tree, int32_t heads,
                                int32_t kv_heads, int32_t head_dim, int32_t dtype);

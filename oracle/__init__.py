@@ -280,3 +280,32 @@ def kv_append(k_tree, v_tree, accepted_path, k_cache, v_cache, prefix_len: int):
             kc[:, prefix_len + j, :] = k_tree[node]
             vc[:, prefix_len + j, :] = v_tree[node]
     return kc, vc, min(prefix_len + len(nodes), cap)
+
+
+def top_p_filter(logits, top_p: float, temperature: float):
+    """Nucleus filtering by its definition: sort the tokens of a row by probability (descending,
+    lower id first among equals), keep the shortest prefix whose probabilities sum to at least
+    top_p, set every other logit to -inf.  fp64.  Returns (filtered [rows,V] float32, probabilities
+    [rows,V] float64, kept mask [rows,V] bool)."""
+    x = np.asarray(logits, dtype=np.float64)
+    x = np.where(np.isnan(x), -np.inf, x)
+    rows, V = x.shape
+    prob = np.zeros_like(x)
+    keep = np.zeros(x.shape, dtype=bool)
+    for r in range(rows):
+        if not np.isfinite(x[r]).any() and not (x[r] == np.inf).any():
+            keep[r] = temperature > 0          # a row without mass is left as it is
+            continue
+        if temperature == 0:
+            prob[r, int(np.argmax(x[r]))] = 1.0
+        else:
+            z = np.exp((x[r] - x[r].max()) / temperature)
+            prob[r] = z / z.sum()
+        order = np.lexsort((np.arange(V), -prob[r]))
+        cum = np.cumsum(prob[r][order])
+        reach = np.nonzero(cum >= top_p)[0]
+        n_keep = int(reach[0]) + 1 if len(reach) else int((prob[r] > 0).sum())
+        n_keep = min(n_keep, int((prob[r] > 0).sum()))
+        keep[r, order[:n_keep]] = True
+    out = np.where(keep, np.asarray(logits, dtype=np.float32), np.float32(-np.inf)).astype(np.float32)
+    return out, prob, keep

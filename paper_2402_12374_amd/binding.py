@@ -25,7 +25,7 @@ SEQ_MAX_VOCAB = 524288
 SEQ_MAX_CHILDREN = 64
 TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
-EXPORTS = ("seq_tree_attn", "seq_verify", "seq_verify_with", "seq_draft_sample", "seq_kv_append", "seq_tree_attn_workspace",
+EXPORTS = ("seq_tree_attn", "seq_verify", "seq_verify_with", "seq_draft_sample", "seq_kv_append", "seq_top_p_filter", "seq_tree_attn_workspace",
            "seq_verify_workspace", "seq_draft_sample_workspace", "seq_tree_plan_host",
            "seq_build_tree", "seq_tree_expected_tokens", "seq_pick_tree_shape",
            "seq_shutdown", "seq_strerror", "seq_version")
@@ -54,6 +54,8 @@ def lib() -> C.CDLL:
         l.seq_verify.argtypes = [vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
         l.seq_verify_with.restype = C.c_int
         l.seq_verify_with.argtypes = [i32, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
+        l.seq_top_p_filter.restype = C.c_int
+        l.seq_top_p_filter.argtypes = [vp, vp, C.c_float, C.c_float, i32, i32, i32, vp, vp]
         l.seq_kv_append.restype = C.c_int
         l.seq_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp]
         l.seq_tree_attn_workspace.restype = sz
@@ -266,6 +268,24 @@ def seq_draft_sample(draft_logits, n_children, temperature: float, rng, k_max: i
     if rc != SEQ_OK:
         raise SeqTreeError(rc, "seq_draft_sample")
     return tokens, workspace
+
+
+def seq_top_p_filter(logits, top_p: float, temperature: float, filtered=None, kept=None, stream=None):
+    """logits [rows,V] (bf16 or fp32, GPU).  Returns (filtered logits, kept int32 [rows])."""
+    import torch
+    rows, V = logits.shape
+    code = _dtype_code(logits)
+    if not logits.is_contiguous() or not logits.is_cuda:
+        raise SeqTreeError(SEQ_ERR_SHAPE, "seq_top_p_filter (logits must be a contiguous GPU tensor)")
+    if filtered is None:
+        filtered = torch.empty_like(logits)
+    if kept is None:
+        kept = torch.empty(rows, dtype=torch.int32, device=logits.device)
+    rc = lib().seq_top_p_filter(logits.data_ptr(), filtered.data_ptr(), float(top_p), float(temperature), rows, V, code,
+                                kept.data_ptr(), _stream_ptr(stream))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_top_p_filter")
+    return filtered, kept
 
 
 def seq_kv_append(k_tree, v_tree, accepted_path, parent, k_cache, v_cache, prefix_len: int, new_prefix_len=None,
