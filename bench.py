@@ -8,6 +8,12 @@ the model has layers), so no step finds its K/V or logits in a cache left by the
 All inputs are in HBM before the timed region starts.
 
 Prints ONE JSON line (see the design doc for how each figure is formed).
+
+Other modes print lines of their own instead of the benchmark line: --sweep (latency of both calls
+over the tree size; --sweep-tree sequoia for trees built by seq_build_tree; --pick-tree for the
+hardware-aware choice fed with the measured times), --draft-sample (seq_draft_sample per
+configuration), --rejection-curve (rejection rate against the number of children for the three
+verification algorithms).
 """
 from __future__ import annotations
 

@@ -2,8 +2,7 @@
  * seqtree -- the target model's verification step over a speculated token tree
  * (Sequoia, arxiv 2402.12374), as a C-ABI library for AMD MI355X (gfx950).
  *
- * Two operations make up the step (a third, seq_draft_sample, is the drafter's step just
- * before it):
+ * Two operations make up the step:
  *   seq_tree_attn   one attention layer of the single target forward pass that scores every
  *                   token of the tree at once (Sec. 1: the tree is "verified in parallel
  *                   through a single forward pass"; Sec. 2.1: the root stands for the current
@@ -11,12 +10,21 @@
  *                   the tree and to itself.
  *   seq_verify      Algorithm 2 (Sec. 3.2.1, "Sequoia Sampling and Verification") applied
  *                   recursively from the root (Sec. 2.2), on caller-supplied uniforms.
+ * Around them:
+ *   seq_draft_sample      the drafter's ordered draw of child tokens without replacement (Sec. 3.2.1, 4.1)
+ *   seq_verify_with       the same walk with SpecInfer's or naive / top-k sampling's rule (Sec. 2.2)
+ *   seq_build_tree, seq_tree_expected_tokens, seq_pick_tree_shape
+ *                         Sequoia's tree construction and hardware-aware choice of size and depth
+ *                         (Sec. 3.1.2, 4.1; host only)
+ *   seq_top_p_filter, seq_kv_append
+ *                         glue between two steps: nucleus filtering of logit rows; the accepted
+ *                         path's K/V rows join the prefix
  *
  * Conventions for every entry point
  *   - Tensors are row-major and contiguous.  Pointers are DEVICE pointers unless marked HOST.
  *   - The caller owns every buffer.  Inputs are never written.  The library keeps, per
  *     process, a small cache of tree plans (device copies of the ancestor bitset and the
- *     child lists, keyed by the contents of parent[]) and one small synchronisation area;
+ *     child lists, keyed by the contents of parent[]) and one synchronisation area (8 MiB);
  *     both are created on first use and released by seq_shutdown().  A call whose tree is
  *     already cached allocates nothing, copies nothing and never synchronises with the host.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
