@@ -92,11 +92,12 @@ def run_sweep(args) -> int:
     results = []
     for key in args.sweep_configs.split(","):
         cfg = W.CONFIGS[key]
-        H, Hk, d, P, V = cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.prefix_len, cfg.vocab
+        # a batch of sequences (same tree, same prefix length) is a call with more heads
+        H, Hk, d, P, V = cfg.heads * args.sweep_batch, cfg.kv_heads * args.sweep_batch, cfg.head_dim, cfg.prefix_len, cfg.vocab
         tdt = torch.bfloat16 if cfg.dtype == W.BF16 else torch.float32
         code = 1 if tdt == torch.bfloat16 else 2
         T = cfg.temperatures[0]
-        sets = min(cfg.layers, 16)
+        sets = max(2, min(cfg.layers, 16) // args.sweep_batch)
         mk = lambda *shape: torch.randn(*shape, device=dev).to(tdt)
         caches = [(mk(Hk, P, d), mk(Hk, P, d)) for _ in range(sets)]
         for n in sizes:
@@ -130,7 +131,7 @@ def run_sweep(args) -> int:
             cfg_n = type("C", (), dict(dtype=cfg.dtype, n_tree=n, prefix_len=P, heads=H, kv_heads=Hk, head_dim=d))
             bytes_alg, flops_alg = attn_alg_bytes(cfg_n), attn_alg_flops(cfg_n, parent)
             results.append((key, n, attn_us, verify_us))
-            print(json.dumps({"config": cfg.name, "tree": args.sweep_tree, "n_tree": n, "prefix_len": P, "vocab": V,
+            print(json.dumps({"config": cfg.name, "tree": args.sweep_tree, "batch": args.sweep_batch, "n_tree": n, "prefix_len": P, "vocab": V,
                               "attn_us_per_layer": round(attn_us, 2), "verify_us": round(verify_us, 2),
                               "attn_hbm_frac": round(bytes_alg / (attn_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                               "attn_mfma_frac": round(flops_alg / (attn_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}), flush=True)
@@ -301,6 +302,9 @@ def main() -> int:
     ap.add_argument("--sweep-tree", choices=("geometric", "sequoia"), default="geometric",
                     help="tree of the sweep: the configurations' geometric tree, or the Sequoia tree of that size built "
                          "by seq_build_tree from the paper's printed acceptance vector")
+    ap.add_argument("--sweep-batch", type=int, default=1,
+                    help="with --sweep: attention over this many sequences per call (heads and KV heads times the batch; "
+                         "the verification walk stays one sequence)")
     ap.add_argument("--pick-tree", action="store_true",
                     help="with --sweep: after each configuration, the tree size and depth that maximise Speedup(n, d) for "
                          "the measured t(n) (first sweep size = the decoding step)")

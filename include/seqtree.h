@@ -84,6 +84,11 @@ extern "C" {
  *   workspace, workspace_bytes   scratch of at least seq_tree_attn_workspace(...) bytes
  *
  * prefix_len = 0 (tree only) and n_tree = 1 (plain decode attention) are legal.
+ *
+ * A batch of B sequences that share the tree and the prefix length is one call with
+ * heads = B * H and kv_heads = B * Hk on tensors laid out q, out [n_tree, B, H, head_dim],
+ * k_tree, v_tree [n_tree, B, Hk, head_dim], k_cache, v_cache [B, Hk, prefix_cap, head_dim]:
+ * query head b * H + h uses KV head b * Hk + h / (H / Hk), so a sequence sees only its own rows.
  */
 int seq_tree_attn(const void* q, const void* k_cache, const void* v_cache,
                   const void* k_tree, const void* v_tree, const int32_t* parent,

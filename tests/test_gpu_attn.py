@@ -160,3 +160,22 @@ def test_scores_of_large_and_moving_magnitude(H, Hk, P, n, order):
     assert np.isfinite(got).all()
     err = np.abs(got - want).max()
     assert err <= TOL[a.dtype], err
+
+
+def test_a_batch_of_sequences_is_a_call_with_more_heads():
+    """B sequences that share the tree and the prefix length: heads = B*H, kv_heads = B*Hk on
+    tensors laid out [n, B, H, d] and [B, Hk, cap, d].  Query head b*H + h maps to KV head
+    b*Hk + h/G, i.e. sequence b only ever sees its own cache and tree rows."""
+    B, H, Hk, d, P, n = 3, 8, 2, 128, 333, 40
+    parent = W.geometric_tree(n, 6)
+    seqs = [W.make_attn_inputs(H, Hk, d, P, parent, W.BF16, seed=90 + b) for b in range(B)]
+    folded = W.AttnInputs(q=np.stack([s.q for s in seqs], axis=1).reshape(n, B * H, d),
+                          k_cache=np.concatenate([s.k_cache for s in seqs], axis=0),
+                          v_cache=np.concatenate([s.v_cache for s in seqs], axis=0),
+                          k_tree=np.stack([s.k_tree for s in seqs], axis=1).reshape(n, B * Hk, d),
+                          v_tree=np.stack([s.v_tree for s in seqs], axis=1).reshape(n, B * Hk, d),
+                          parent=parent, prefix_len=P, prefix_cap=seqs[0].prefix_cap, dtype=W.BF16)
+    got = run_attn(folded).reshape(n, B, H, d)
+    for b, s in enumerate(seqs):
+        assert np.abs(got[:, b] - oracle_attn(s)).max() <= TOL[W.BF16], b
+        assert np.abs(got[:, b] - run_attn(s)).max() <= 2 ** -6, b      # the same numbers up to the schedule's rounding
