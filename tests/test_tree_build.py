@@ -111,3 +111,43 @@ def test_argument_errors():
     assert lib.seq_build_tree(rates.ctypes.data, 2, 8, 3, out.ctypes.data, None) == B.SEQ_OK
     with pytest.raises(S.SeqTreeError):
         S.seq_pick_tree_shape(rates, [4], [0.0], 3, 1.0, 1.0)
+
+
+def k_sequences(k, length):
+    """k independent chains of `length` nodes below the root (the tree SpecInfer uses)."""
+    parent = [-1]
+    for _ in range(k):
+        parent.append(0)
+    tails = list(range(1, k + 1))
+    for _ in range(length - 1):
+        for j in range(k):
+            parent.append(tails[j])
+            tails[j] = len(parent) - 1
+    return parent
+
+
+def binary_tree(n):
+    return [-1] + [(i - 1) // 2 for i in range(1, n)]
+
+
+def test_sequoia_tree_beats_the_baseline_shapes_and_their_bounds_hold():
+    """Sec. 3.1.3: one sequence generates at most 1/(1 - p1) tokens, k sequences at most one more,
+    a binary tree at most 1/(1 - p1 - p2) however deep; the tree of the dynamic program is at
+    least as good as each of them at equal size."""
+    p = PAPER_P
+    for n in (16, 41, 64, 128):
+        _, best = S.seq_build_tree(p, n, n - 1)
+        chain = S.seq_tree_expected_tokens(list(range(-1, n - 1)), p)
+        assert chain < 1 / (1 - p[0]) and best >= chain
+        binary = S.seq_tree_expected_tokens(binary_tree(n), p)
+        assert binary < 1 / (1 - p[0] - p[1]) and best >= binary
+    for k, length in ((5, 8), (3, 21), (8, 5)):
+        seqs = k_sequences(k, length)
+        f = S.seq_tree_expected_tokens(seqs, p)
+        assert f < 1 / (1 - p[0]) + 1
+        _, best = S.seq_build_tree(p, len(seqs), len(seqs) - 1)
+        assert best >= f
+    # and it keeps growing where they have levelled off
+    _, g64 = S.seq_build_tree(p, 64, 63)
+    _, g512 = S.seq_build_tree(p, 512, 511)
+    assert g512 > g64 + 1.5 and g64 > 1 / (1 - p[0]) + 1
