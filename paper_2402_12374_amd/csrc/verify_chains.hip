@@ -257,10 +257,12 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
                 }
                 if (j < K && !accepted) {
                     before = ns;
-                    const bool in_s = sh.child_dup[j] != 0;
-                    node_reject_child(ns, in_s, V);
-                    sh.ctl_zero = in_s ? -1 : sh.child_tok[j];
-                    q_predicted = ns.massQ - (in_s ? 0.0 : (double)sh.child_ld[j]);
+                    // (SpecInfer: the draft distribution stays what it was -- nothing is struck out)
+                    const bool in_s = !p.with_replacement && sh.child_dup[j] != 0;
+                    const bool strike = !in_s && !p.with_replacement;
+                    node_reject_child(ns, in_s, V, p.with_replacement != 0);
+                    sh.ctl_zero = strike ? sh.child_tok[j] : -1;
+                    q_predicted = ns.massQ - (strike ? (double)sh.child_ld[j] : 0.0);
                     q_summed = ns.fallback || !(q_predicted >= 0.05);
                     sh.ctl_sum_q = q_summed ? 1 : 0;
                 }
@@ -282,7 +284,8 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
             // records wait in shared memory; they leave together once the chain is done
             if (j > 0) sh.w_rec[j - 1][4] = __uint_as_float(events);
             if (j < K) {
-                const ChildTest t = node_test_child(before, sh.child_lt[j], sh.child_ld[j], sh.child_dup[j] != 0, V);
+                const ChildTest t = node_test_child(before, sh.child_lt[j], sh.child_ld[j],
+                                                    !p.with_replacement && sh.child_dup[j] != 0, V);
                 sh.w_rec[j][0] = t.lhs_w; sh.w_rec[j][1] = t.lhs_q;
                 sh.w_rec[j][2] = t.rhs_r; sh.w_rec[j][3] = t.rhs_m;
                 accepted = t.accepts(sh.child_u[j]);

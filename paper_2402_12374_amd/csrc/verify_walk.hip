@@ -640,7 +640,7 @@ extern "C" int seq_verify_with(int32_t algorithm, const void* target_logits, con
     const bool chains_pay = n_tree <= kChainsMaxNodes || g_verify_mode == 2;
     // (T = 0: all three algorithms accept a child exactly when its token is the target's arg-max
     // and emit that arg-max, so the greedy kernel serves them all.)
-    if (!greedy && algorithm == SEQ_VERIFY_SEQUOIA && vocab <= kChainsMaxVocab && g_verify_mode != 1 && chains_pay) {
+    if (!greedy && vocab <= kChainsMaxVocab && g_verify_mode != 1 && chains_pay) {
         launch_verify_chains(p, dtype, stream);
         return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
     }

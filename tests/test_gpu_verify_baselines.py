@@ -24,6 +24,15 @@ def topk_kernel_choice(request):
     S.lib().seqtree_internal_set_topk_mode(0)
 
 
+@pytest.fixture(autouse=True, params=["auto", "lazy"])
+def walk_kernel_choice(request):
+    """SpecInfer runs on both kernels of the walk (the per-node one where temperature, vocabulary
+    and tree size allow it): every case runs with the library's choice and with the lazy walk forced."""
+    S.lib().seqtree_internal_set_verify_mode(0 if request.param == "auto" else 1)
+    yield request.param
+    S.lib().seqtree_internal_set_verify_mode(0)
+
+
 def inputs_for(algorithm, parent, V, T, dtype, seed, sigma_d=1.5):
     """Logits as for the Sequoia tests; children drawn the way the algorithm assumes: independent
     draws from the draft distribution (repeats allowed) for SpecInfer, its top-k tokens for top-k."""
