@@ -13,6 +13,7 @@
  * Around them:
  *   seq_draft_sample      the drafter's ordered draw of child tokens without replacement (Sec. 3.2.1, 4.1)
  *   seq_verify_with       the same walk with SpecInfer's or naive / top-k sampling's rule (Sec. 2.2)
+ *   seq_verify_batched    the walk for several sequences that share the tree
  *   seq_build_tree, seq_tree_expected_tokens, seq_pick_tree_shape
  *                         Sequoia's tree construction and hardware-aware choice of size and depth
  *                         (Sec. 3.1.2, 4.1; host only)
@@ -170,6 +171,20 @@ int seq_verify_with(int32_t algorithm, const void* target_logits, const void* dr
                     const float* uniforms, int32_t* accepted_path, int32_t* bonus_token,
                     int32_t n_tree, int32_t vocab, int32_t dtype,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The walk for a batch of sequences that share the tree: every array of seq_verify_with gains a
+ * leading dimension `batch` (logits [batch, n_tree, vocab], tree_tokens, uniforms, accepted_path
+ * [batch, n_tree], bonus_token [batch]); parent stays one tree.  The workspace is batch times
+ * seq_verify_workspace(...) bytes, sequence b's trace starting at byte b * seq_verify_workspace(...).
+ * batch 1 .. 256.  Where the per-node kernel applies, floor(256 / n_tree) sequences run per launch;
+ * otherwise the sequences are verified one after the other on the stream.
+ */
+int seq_verify_batched(int32_t algorithm, int32_t batch, const void* target_logits, const void* draft_logits,
+                       const int32_t* tree_tokens, const int32_t* parent, float temperature,
+                       const float* uniforms, int32_t* accepted_path, int32_t* bonus_token,
+                       int32_t n_tree, int32_t vocab, int32_t dtype,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Trace left at the start of the seq_verify workspace.  Header of 8 int32:

@@ -6,5 +6,6 @@ from .binding import (SEQ_ERR_ALGORITHM, SEQ_ERR_DTYPE, SEQ_ERR_HIP, SEQ_ERR_NUL
                       SeqTreeError, lib, read_verify_trace, seq_build_tree, seq_draft_sample,
                       seq_draft_sample_workspace, seq_kv_append, seq_pick_tree_shape, seq_top_p_filter, seq_tree_attn,
                       seq_tree_attn_workspace, seq_tree_expected_tokens,
-                      seq_tree_plan_host, seq_verify, seq_verify_with, seq_verify_workspace, shutdown, strerror,
+                      seq_tree_plan_host, seq_verify, seq_verify_batched, seq_verify_with,
+                      seq_verify_workspace, shutdown, strerror,
                       version)

@@ -25,7 +25,7 @@ SEQ_MAX_VOCAB = 524288
 SEQ_MAX_CHILDREN = 64
 TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
-EXPORTS = ("seq_tree_attn", "seq_verify", "seq_verify_with", "seq_draft_sample", "seq_kv_append", "seq_top_p_filter", "seq_tree_attn_workspace",
+EXPORTS = ("seq_tree_attn", "seq_verify", "seq_verify_with", "seq_verify_batched", "seq_draft_sample", "seq_kv_append", "seq_top_p_filter", "seq_tree_attn_workspace",
            "seq_verify_workspace", "seq_draft_sample_workspace", "seq_tree_plan_host",
            "seq_build_tree", "seq_tree_expected_tokens", "seq_pick_tree_shape",
            "seq_shutdown", "seq_strerror", "seq_version")
@@ -52,6 +52,8 @@ def lib() -> C.CDLL:
         l.seq_tree_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, i32, vp, sz, vp]
         l.seq_verify.restype = C.c_int
         l.seq_verify.argtypes = [vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
+        l.seq_verify_batched.restype = C.c_int
+        l.seq_verify_batched.argtypes = [i32, i32, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
         l.seq_verify_with.restype = C.c_int
         l.seq_verify_with.argtypes = [i32, vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
         l.seq_top_p_filter.restype = C.c_int
@@ -307,6 +309,35 @@ def seq_kv_append(k_tree, v_tree, accepted_path, parent, k_cache, v_cache, prefi
     if rc != SEQ_OK:
         raise SeqTreeError(rc, "seq_kv_append")
     return new_prefix_len
+
+
+def seq_verify_batched(algorithm: int, target_logits, draft_logits, tree_tokens, parent, temperature: float, uniforms,
+                       accepted_path=None, bonus_token=None, workspace=None, stream=None):
+    """Logits [B,n,V]; tree_tokens int32 [B,n]; uniforms float32 [B,n] (GPU); parent on the host.
+    Returns (accepted_path int32 [B,n], bonus_token int32 [B], workspace uint8 [B, bytes per sequence])."""
+    import torch
+    par = _parent_array(parent)
+    B, n, V = target_logits.shape
+    code = _dtype_code(target_logits)
+    dev = target_logits.device
+    if accepted_path is None:
+        accepted_path = torch.empty((B, n), dtype=torch.int32, device=dev)
+    if bonus_token is None:
+        bonus_token = torch.empty(B, dtype=torch.int32, device=dev)
+    per = seq_verify_workspace(n, V, code)
+    if workspace is None or workspace.numel() * workspace.element_size() < per * B:
+        workspace = torch.empty((B, per), dtype=torch.uint8, device=dev)
+    for t in (target_logits, draft_logits, tree_tokens, uniforms):
+        if t is not None and (not t.is_contiguous() or not t.is_cuda):
+            raise SeqTreeError(SEQ_ERR_SHAPE, "seq_verify_batched (tensors must be contiguous GPU tensors)")
+    rc = lib().seq_verify_batched(int(algorithm), B, target_logits.data_ptr(),
+                                  None if draft_logits is None else draft_logits.data_ptr(), tree_tokens.data_ptr(),
+                                  par.ctypes.data, float(temperature), uniforms.data_ptr(), accepted_path.data_ptr(),
+                                  bonus_token.data_ptr(), n, V, code, workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_verify_batched")
+    return accepted_path, bonus_token, workspace
 
 
 def seq_verify_with(algorithm: int, target_logits, draft_logits, tree_tokens, parent, temperature: float, uniforms,

@@ -31,6 +31,7 @@ struct SyncArea {
     uint32_t* attn_counters = nullptr;           // [kAttnMaxCounters]
     unsigned long long* draft_exchange = nullptr;  // [kDraftMaxGroups][64] lists of a split row, zero between calls
     uint32_t* draft_arrivals = nullptr;          // [SEQ_MAX_TREE] workgroups of a row that are done
+    uint32_t* verify_batch_ctl = nullptr;        // [kVerifyMaxBatch][4] per sequence of a batched launch: epoch, unused, arrivals, unused
     // Measured once per device: do workgroups whose ids are congruent mod 8 share an XCD (one
     // L2)?  The attention kernel then keeps all key ranges of a unit on one XCD and can hand
     // partial results over through that L2 without writing it back to memory.
@@ -42,6 +43,7 @@ constexpr int kVerifySlotWords = 4;
 constexpr int kVerifyTagsPerCall = 4096;
 constexpr int kAttnMaxCounters = 16384;
 constexpr int kDraftMaxGroups = 16384;
+constexpr int kVerifyMaxBatch = 256;
 
 // Looks up (or builds and uploads) the plan for this parent array on the current device.
 // Returns SEQ_OK or an error code; *plan receives a copy whose device pointers stay owned by

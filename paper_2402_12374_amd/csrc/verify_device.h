@@ -42,13 +42,16 @@ struct VerifyParams {
     int n, V, W;
     float inv_T;
     int with_replacement;   // SpecInfer: the draft distribution is never updated (Algorithm 2 without its blue lines)
+    // a batched launch of the per-node kernel (grid.y = sequences): byte strides between sequences
+    size_t batch_logit_bytes, batch_workspace_bytes;
+    uint32_t* batch_ctl;    // [sequences][4]: epoch, -, arrivals, -
 };
 
 // verify_chains.hip: every node's sibling chain in parallel, then the walk over the results.
 // Vocabularies up to kChainsMaxVocab; dtype SEQ_BF16 or SEQ_F32.
 constexpr int kChainsMaxVocab = 32768;
 constexpr int kChainsMaxNodes = 256;   // one workgroup per node, one workgroup per CU
-void launch_verify_chains(const VerifyParams& p, int dtype, hipStream_t stream);
+void launch_verify_chains(const VerifyParams& p, int dtype, hipStream_t stream, int batch = 1);
 // verify_topk.hip: naive / top-k sampling (Sec. 2.2): one draw from the target per node, then the walk.
 void launch_verify_topk(const VerifyParams& p, int dtype, hipStream_t stream);
 void set_topk_mode(int mode);

@@ -585,17 +585,28 @@ extern "C" int seq_verify_with(int32_t algorithm, const void* target_logits, con
                                const float* uniforms, int32_t* accepted_path, int32_t* bonus_token,
                                int32_t n_tree, int32_t vocab, int32_t dtype, void* workspace,
                                size_t workspace_bytes, void* hip_stream) {
+    return seq_verify_batched(algorithm, 1, target_logits, draft_logits, tree_tokens, parent, temperature, uniforms,
+                              accepted_path, bonus_token, n_tree, vocab, dtype, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* target_logits, const void* draft_logits,
+                                  const int32_t* tree_tokens, const int32_t* parent, float temperature,
+                                  const float* uniforms, int32_t* accepted_path, int32_t* bonus_token,
+                                  int32_t n_tree, int32_t vocab, int32_t dtype, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
     if (algorithm != SEQ_VERIFY_SEQUOIA && algorithm != SEQ_VERIFY_SPECINFER && algorithm != SEQ_VERIFY_TOPK)
         return SEQ_ERR_ALGORITHM;
     if (!target_logits || (!draft_logits && algorithm != SEQ_VERIFY_TOPK) || !tree_tokens || !parent ||
         !uniforms || !accepted_path || !bonus_token)
         return SEQ_ERR_NULL;
     if (dtype != SEQ_BF16 && dtype != SEQ_F32) return SEQ_ERR_DTYPE;
-    if (n_tree < 1 || n_tree > SEQ_MAX_TREE || vocab < 2 || vocab > SEQ_MAX_VOCAB) return SEQ_ERR_SHAPE;
+    if (n_tree < 1 || n_tree > SEQ_MAX_TREE || vocab < 2 || vocab > SEQ_MAX_VOCAB || batch < 1 || batch > kVerifyMaxBatch)
+        return SEQ_ERR_SHAPE;
     if (!(temperature >= 0.0f) || std::isinf(temperature)) return SEQ_ERR_TEMPERATURE;
     int rc = validate_parent(parent, n_tree);
     if (rc != SEQ_OK) return rc;
-    if (!workspace || workspace_bytes < seq_verify_workspace(n_tree, vocab, dtype) ||
+    const size_t per_sequence = seq_verify_workspace(n_tree, vocab, dtype);
+    if (!workspace || workspace_bytes < per_sequence * (size_t)batch ||
         (reinterpret_cast<uintptr_t>(workspace) & 15) != 0)
         return SEQ_ERR_WORKSPACE;
 
@@ -630,21 +641,35 @@ extern "C" int seq_verify_with(int32_t algorithm, const void* target_logits, con
     p.inv_T = greedy ? 1.0f : 1.0f / temperature;
     p.with_replacement = algorithm == SEQ_VERIFY_SPECINFER;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (algorithm == SEQ_VERIFY_TOPK && !greedy) {
-        launch_verify_topk(p, dtype, stream);
-        return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
-    }
+    const size_t elt = dtype == SEQ_BF16 ? 2 : 4;
+    p.batch_logit_bytes = (size_t)n_tree * vocab * elt;
+    p.batch_workspace_bytes = per_sequence;
+    p.batch_ctl = sync->verify_batch_ctl;
     // Sampling with a vocabulary one workgroup can hold, and a tree whose nodes all find a CU at
-    // once: all nodes at once.  Otherwise (and for greedy decoding, which needs one arg-max per
-    // visited node) the lazy walk.
-    const bool chains_pay = n_tree <= kChainsMaxNodes || g_verify_mode == 2;
+    // once: all nodes at once -- of as many sequences of the batch as still fit.  Otherwise (and
+    // for greedy decoding, which needs one arg-max per visited node) the lazy walk.
     // (T = 0: all three algorithms accept a child exactly when its token is the target's arg-max
     // and emit that arg-max, so the greedy kernel serves them all.)
-    if (!greedy && vocab <= kChainsMaxVocab && g_verify_mode != 1 && chains_pay) {
-        launch_verify_chains(p, dtype, stream);
-        return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
+    const bool per_node_kernel = !greedy && algorithm != SEQ_VERIFY_TOPK && vocab <= kChainsMaxVocab && g_verify_mode != 1;
+    // sequences per launch: as many as the per-node kernel has CUs for, else one
+    int group = 1;
+    if (per_node_kernel && (n_tree <= kChainsMaxNodes || g_verify_mode == 2)) group = std::max(1, kChainsMaxNodes / n_tree);
+    for (int b = 0; b < batch; b += group) {      // one group of sequences after the other on the stream
+        const int count = std::min(group, batch - b);
+        VerifyParams q = p;
+        q.target = static_cast<const char*>(target_logits) + (size_t)b * p.batch_logit_bytes;
+        q.draft = draft_logits ? static_cast<const char*>(draft_logits) + (size_t)b * p.batch_logit_bytes : nullptr;
+        q.tokens = tree_tokens + (size_t)b * n_tree;
+        q.uniforms = uniforms + (size_t)b * n_tree;
+        q.path = accepted_path + (size_t)b * n_tree;
+        q.bonus = bonus_token + b;
+        q.trace = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + (size_t)b * per_sequence);
+        q.records = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + (size_t)b * per_sequence + kTraceBytesPadded);
+        if (count > 1) { launch_verify_chains(q, dtype, stream, count); continue; }
+        if (algorithm == SEQ_VERIFY_TOPK && !greedy) launch_verify_topk(q, dtype, stream);
+        else if (per_node_kernel && (n_tree <= kChainsMaxNodes || g_verify_mode == 2)) launch_verify_chains(q, dtype, stream);
+        else if (dtype == SEQ_BF16) launch_verify<uint16_t>(q, greedy, ept, stream);
+        else launch_verify<float>(q, greedy, ept, stream);
     }
-    if (dtype == SEQ_BF16) launch_verify<uint16_t>(p, greedy, ept, stream);
-    else launch_verify<float>(p, greedy, ept, stream);
     return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
 }

@@ -221,3 +221,30 @@ def test_bounded_wait_always_terminates(kernel_choice):
         assert trace["status"] == 1 and bonus == -1
         S.shutdown()
     assert check_verify(v) in ("exact", "flagged")
+
+
+@pytest.mark.parametrize("n,V,B,T", [(16, 2049, 5, 0.6), (64, 32000, 4, 0.6), (64, 5000, 9, 1.0), (40, 3000, 3, 0.0), (12, 50257, 3, 0.8)])
+def test_a_batch_of_sequences_over_one_tree(n, V, B, T):
+    """seq_verify_batched: every sequence of the batch must get what seq_verify gives it alone
+    (the checker's answer), whether the batch runs as one launch of the per-node kernel or as one
+    launch per sequence; each sequence's trace sits at its own offset of the workspace."""
+    parent = W.geometric_tree(n, 6)
+    vs = [W.make_verify_inputs(parent, V, 3.0, 0.8, T, W.BF16, seed=500 + 17 * b + n) for b in range(B)]
+    stack = lambda key: torch.from_numpy(np.stack([getattr(v, key) for v in vs])).to(DEV)
+    for alg in (S.SEQ_VERIFY_SEQUOIA, S.SEQ_VERIFY_SPECINFER):
+        path, bonus, ws = S.seq_verify_batched(alg, stack("target_logits").to(torch.bfloat16), stack("draft_logits").to(torch.bfloat16),
+                                               stack("tree_tokens"), parent, T, stack("uniforms"))
+        torch.cuda.synchronize()
+        flagged = 0
+        for b, v in enumerate(vs):
+            got = (path[b].cpu().numpy(), int(bonus[b].item()), S.read_verify_trace(ws[b]))
+            if alg == S.SEQ_VERIFY_SEQUOIA:
+                flagged += check_verify(v, got) == "flagged"
+            else:
+                ref = oracle.verify_baseline(oracle.SPECINFER, v.target_logits, v.draft_logits, v.tree_tokens, parent, T, v.uniforms)
+                close = T > 0 and (min([abs(r[2] - r[5]) for r in ref.records] + [1.0]) < 1e-5 or ref.bonus_margin < 1e-5)
+                if close:
+                    flagged += 1
+                else:
+                    assert [int(x) for x in got[0] if x >= 0] == ref.path and got[1] == ref.bonus_token, (alg, b)
+        assert flagged <= 1

@@ -130,6 +130,19 @@ def test_verify_with_argument_errors_need_no_gpu():
     assert S.strerror(B.SEQ_ERR_ALGORITHM) != S.strerror(-99)
 
 
+def test_verify_batched_argument_errors_need_no_gpu():
+    par = np.array([-1, 0, 0], dtype=np.int32)
+    ptr = 0x1000
+    need = S.seq_verify_workspace(3, 64, B.SEQ_F32)
+
+    def call(batch, ws_bytes):
+        return S.lib().seq_verify_batched(B.SEQ_VERIFY_SEQUOIA, batch, ptr, ptr, ptr, par.ctypes.data, 1.0, ptr, ptr, ptr, 3, 64,
+                                          B.SEQ_F32, ptr, ws_bytes, None)
+
+    assert call(0, need) == B.SEQ_ERR_SHAPE and call(257, 257 * need) == B.SEQ_ERR_SHAPE
+    assert call(4, 4 * need - 1) == B.SEQ_ERR_WORKSPACE and call(2, need) == B.SEQ_ERR_WORKSPACE
+
+
 def test_workspace_sizes():
     assert S.seq_draft_sample_workspace(1, 2, 1, B.SEQ_F32) >= 256
     assert S.seq_draft_sample_workspace(768, 128256, 10, B.SEQ_BF16) >= 256
