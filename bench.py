@@ -278,6 +278,14 @@ def run_rejection_curve(args) -> int:
                                       accepted_path=paths[t], bonus_token=bonus[t], workspace=ws)
                 torch.cuda.synchronize()
                 rates.append(round(float((paths[:, 0] < 0).float().mean().item()), 4))
+                if k == k_max:
+                    # the acceptance vector of Sec. 3.1.1 as measured here: how often the child at
+                    # position j is the one accepted; and what Sequoia's dynamic program makes of it
+                    first = paths[:, 0].cpu().numpy()
+                    vector = [round(float((first == j).mean()), 4) for j in range(1, k + 1)]
+                    _, g64 = S.seq_build_tree(vector, 64, 8)
+                    out["rejection_curve"].setdefault("acceptance_vector", {})[name] = vector
+                    out["rejection_curve"].setdefault("expected_tokens_64_nodes_depth_8", {})[name] = round(g64, 3)
             out["rejection_curve"][name] = rates
         print(json.dumps(out), flush=True)
     S.shutdown()
