@@ -187,3 +187,35 @@ def test_whole_iteration_in_one_graph():
                 assert [int(x) for x in path.cpu().numpy() if x >= 0] == refb.path and int(bonus.item()) == refb.bonus_token, (rep, alg)
         step += 1
     assert int(rng[1].item()) == step
+
+
+def test_new_calls_at_their_largest_sizes():
+    """The largest vocabulary (524288) and row count (1024) for the drafter's draw and the top-p
+    filter, the largest tree for the KV append and the top-k walk."""
+    from test_gpu_draft import check_draft
+    rng = np.random.default_rng(99)
+    big = 3.0 * rng.standard_normal((2, S.binding.SEQ_MAX_VOCAB), dtype=np.float32)
+    assert check_draft(big, [64, 5], 0.7, 1, 2, W.BF16, 64) <= 1
+    many = rng.standard_normal((1024, 512), dtype=np.float32)
+    assert check_draft(many, rng.integers(0, 5, size=1024), 1.0, 3, 4, W.F32, 4) <= 3
+    # top-p on the largest row: the kept set has the defining properties
+    from test_top_p import has_defining_properties
+    logits = W.quantize(big[:1], W.BF16)
+    got, kept = S.seq_top_p_filter(to_dev(logits, W.BF16), 0.9, 0.8)
+    torch.cuda.synchronize()
+    want, prob, keep = oracle.top_p_filter(logits, 0.9, 0.8)
+    got_keep = ~np.isneginf(got.float().cpu().numpy())
+    assert int(kept.item()) == got_keep.sum()
+    assert np.array_equal(got_keep, keep) or has_defining_properties(prob[0], got_keep[0], 0.9, 2e-6)
+    # a chain of 1024 nodes: the deepest possible path, all of it accepted
+    n, Hk, d = 1024, 2, 64
+    parent = W.chain_tree(n)
+    a = W.make_attn_inputs(Hk, Hk, d, 8, parent, W.F32, seed=5, prefix_cap=8 + n)
+    path = np.full(n, -1, dtype=np.int32)
+    path[: n - 1] = np.arange(1, n)
+    kc, vc = to_dev(a.k_cache, W.F32), to_dev(a.v_cache, W.F32)
+    new_len = S.seq_kv_append(to_dev(a.k_tree, W.F32), to_dev(a.v_tree, W.F32), torch.from_numpy(path).to(DEV), parent, kc, vc, 8)
+    torch.cuda.synchronize()
+    want_k, want_v, want_len = oracle.kv_append(a.k_tree, a.v_tree, path, a.k_cache, a.v_cache, 8)
+    assert int(new_len.item()) == want_len == 8 + n
+    assert np.array_equal(kc.cpu().numpy(), want_k) and np.array_equal(vc.cpu().numpy(), want_v)
