@@ -265,7 +265,8 @@ int seq_kv_append(const void* k_tree, const void* v_tree, const int32_t* accepte
  * the most probable tokens are kept, as few as reach a total probability of top_p (equal
  * probabilities at the cut: lower token id first); every other logit becomes -inf, which
  * seq_verify and seq_draft_sample read as probability zero.  Kept logits are copied unchanged.
- * temperature 0: only the arg-max (lowest id) is kept.  NaN reads as -inf.
+ * temperature 0: only the arg-max (lowest id) is kept.  top_p = 1: every token whose fp32
+ * probability is not zero is kept.  NaN reads as -inf.
  *
  *   logits    [n_rows, vocab];  filtered  [n_rows, vocab] out, may be the same buffer
  *   top_p     in (0, 1];  n_rows 1 .. SEQ_MAX_TREE;  vocab 2 .. SEQ_MAX_VOCAB

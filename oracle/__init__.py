@@ -304,7 +304,9 @@ def top_p_filter(logits, top_p: float, temperature: float):
         order = np.lexsort((np.arange(V), -prob[r]))
         cum = np.cumsum(prob[r][order])
         reach = np.nonzero(cum >= top_p)[0]
-        n_keep = int(reach[0]) + 1 if len(reach) else int((prob[r] > 0).sum())
+        # top_p = 1 is the whole support in exact arithmetic: the rounding of the running sum
+        # (which reaches 1.0 a little early in fp64) must not cut it short
+        n_keep = int(reach[0]) + 1 if len(reach) and top_p < 1.0 else int((prob[r] > 0).sum())
         n_keep = min(n_keep, int((prob[r] > 0).sum()))
         keep[r, order[:n_keep]] = True
     out = np.where(keep, np.asarray(logits, dtype=np.float32), np.float32(-np.inf)).astype(np.float32)

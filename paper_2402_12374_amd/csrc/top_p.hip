@@ -147,6 +147,8 @@ __global__ void __launch_bounds__(kThreads) top_p_kernel(const TopPParams p) {
     unsigned long long cut_word = 0;
     if (p.greedy || !(m_all > -INFINITY)) {
         cut = 0xFFFFFFFFu;     // nothing is "above"; the arg-max alone is kept below
+    } else if (p.top_p >= 1.0f) {
+        cut = 0;               // everything of non-zero probability stays: no search, no rounding
     } else {
         float z_f = 0.f;
         visit([&](float v, int) { z_f += v; });

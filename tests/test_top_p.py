@@ -38,6 +38,8 @@ def test_limits():
     logits[2, 6] = np.nan
     out, prob, keep = oracle.top_p_filter(logits, 1.0, 0.8)
     assert keep[0].all() and keep[1].sum() == 39 and not keep[1, 5] and not keep[2, 6]
+    wide = np.array([[0.0, -50.0, -100.0, -700.0, -np.inf]], dtype=np.float32)     # the tail is below fp64's epsilon
+    assert oracle.top_p_filter(wide, 1.0, 1.0)[2][0].tolist() == [True, True, True, True, False]
     out, prob, keep = oracle.top_p_filter(logits, 0.5, 0.0)
     assert keep.sum(axis=1).tolist() == [1, 1, 1] and keep[0, int(np.argmax(logits[0]))]
     out, prob, keep = oracle.top_p_filter(logits, 1e-6, 1.0)
@@ -102,6 +104,8 @@ def test_library_against_the_checker(V, rows, dtype, T):
                 continue
             assert has_defining_properties(prob[r], got_keep[r], top_p, 2e-6), (top_p, r, got_keep[r].sum(), keep[r].sum())
             differing += 1
+            if top_p == 1.0:        # no search at all: exactly the tokens whose fp32 probability is not zero
+                assert np.array_equal(got_keep[r], prob[r] > 1e-37) or not ((prob[r] > 1e-37) & ~got_keep[r]).any()
     assert differing <= 4 * rows // 2
 
 
