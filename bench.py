@@ -13,7 +13,7 @@ Other modes print lines of their own instead of the benchmark line: --sweep (lat
 over the tree size; --sweep-tree sequoia for trees built by seq_build_tree; --pick-tree for the
 hardware-aware choice fed with the measured times), --draft-sample (seq_draft_sample per
 configuration), --rejection-curve (rejection rate against the number of children for the three
-verification algorithms).
+verification algorithms), --verify-batch (seq_verify_batched over the batch size).
 """
 from __future__ import annotations
 
@@ -227,6 +227,52 @@ def run_draft_sample(args) -> int:
     return 0
 
 
+def run_verify_batch(args) -> int:
+    """Latency of seq_verify_batched over the number of sequences, per configuration (its tree,
+    its vocabulary; --verify-batch-vocab overrides the vocabulary, --verify-batch-temperature
+    the temperature).  Graph replay over two rotating input sets.  One JSON line per case.  Not
+    the benchmark line."""
+    import numpy as np
+    import torch
+
+    import paper_2402_12374_amd as S
+    from paper_2402_12374_amd import workloads as W
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    for key in args.sweep_configs.split(","):
+        cfg = W.CONFIGS[key]
+        parent = W.make_tree(cfg, W.seed_for(list(W.CONFIGS).index(key) + 1))
+        n = len(parent)
+        V = args.verify_batch_vocab or cfg.vocab
+        T = cfg.temperatures[0] if args.verify_batch_temperature < 0 else args.verify_batch_temperature
+        for B in (int(x) for x in args.verify_batch.split(",")):
+            if 2 * 2 * B * n * V * 2 > 24e9:      # two sets of two bf16 logit tensors
+                continue
+            sets = []
+            for s in range(2):
+                vs = [W.make_verify_inputs(parent, V, cfg.sigma_target, cfg.sigma_draft, T, W.BF16, seed=1000 * s + b)
+                      for b in range(B)]
+                stack = lambda k: torch.from_numpy(np.stack([getattr(v, k) for v in vs])).to(dev)
+                sets.append((stack("target_logits").to(torch.bfloat16), stack("draft_logits").to(torch.bfloat16),
+                             stack("tree_tokens"), stack("uniforms")))
+                del vs
+            path = torch.empty((B, n), dtype=torch.int32, device=dev)
+            bonus = torch.empty(B, dtype=torch.int32, device=dev)
+            ws = torch.empty((B, S.seq_verify_workspace(n, V, 1)), dtype=torch.uint8, device=dev)
+
+            def call(i):
+                tl, dl, tok, un = sets[i % 2]
+                S.seq_verify_batched(S.SEQ_VERIFY_SEQUOIA, tl, dl, tok, parent, T, un, accepted_path=path,
+                                     bonus_token=bonus, workspace=ws)
+
+            us = graph_time_us(torch, call, 4, 30)
+            print(json.dumps({"config": cfg.name, "n_tree": n, "vocab": V, "temperature": T, "batch": B,
+                              "verify_us": round(us, 2), "us_per_sequence": round(us / B, 2)}), flush=True)
+            del sets
+    return 0
+
+
 def run_rejection_curve(args) -> int:
     """Rejection rate at one node against the number of speculated children k, for Sequoia's
     algorithm and the two baselines of Sec. 2.2, each with children drawn the way it assumes
@@ -324,6 +370,10 @@ def main() -> int:
     ap.add_argument("--curve-draft-noise", type=float, default=1.0)
     ap.add_argument("--draft-sample", action="store_true",
                     help="instead of the benchmark line: latency of seq_draft_sample per configuration (one line each)")
+    ap.add_argument("--verify-batch", default="",
+                    help="instead of the benchmark line: latency of seq_verify_batched for these batch sizes, e.g. 1,2,4,8,16,64")
+    ap.add_argument("--verify-batch-vocab", type=int, default=0, help="vocabulary for --verify-batch (0 = the configuration's)")
+    ap.add_argument("--verify-batch-temperature", type=float, default=-1.0, help="temperature for --verify-batch (< 0 = the configuration's)")
     ap.add_argument("--sweep-configs", default="C2,C3,C4,C5")
     ap.add_argument("--sweep-sizes", default="16,32,64,128,256,512,768")
     args = ap.parse_args()
@@ -337,6 +387,8 @@ def main() -> int:
         return run_draft_sample(args)
     if args.rejection_curve:
         return run_rejection_curve(args)
+    if args.verify_batch:
+        return run_verify_batch(args)
 
     import numpy as np
     import torch

@@ -25,7 +25,7 @@
  *   - Tensors are row-major and contiguous.  Pointers are DEVICE pointers unless marked HOST.
  *   - The caller owns every buffer.  Inputs are never written.  The library keeps, per
  *     process, a small cache of tree plans (device copies of the ancestor bitset and the
- *     child lists, keyed by the contents of parent[]) and one synchronisation area (8 MiB);
+ *     child lists, keyed by the contents of parent[]) and one synchronisation area (8.3 MiB);
  *     both are created on first use and released by seq_shutdown().  A call whose tree is
  *     already cached allocates nothing, copies nothing and never synchronises with the host.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
@@ -177,8 +177,11 @@ int seq_verify_with(int32_t algorithm, const void* target_logits, const void* dr
  * leading dimension `batch` (logits [batch, n_tree, vocab], tree_tokens, uniforms, accepted_path
  * [batch, n_tree], bonus_token [batch]); parent stays one tree.  The workspace is batch times
  * seq_verify_workspace(...) bytes, sequence b's trace starting at byte b * seq_verify_workspace(...).
- * batch 1 .. 256.  Where the per-node kernel applies, floor(256 / n_tree) sequences run per launch;
- * otherwise the sequences are verified one after the other on the stream.
+ * batch 1 .. 256.  Sequences share launches: floor(256 / n_tree) of them where the per-node
+ * kernel applies and the batch fits in as few launches that way, otherwise the lazy walk with the
+ * teams of min(64, floor(256 / W)) sequences side by side, W = ceil(vocab / 8192) workgroups per
+ * team.  Only SEQ_VERIFY_TOPK at temperature > 0 takes the sequences one after the other.  A team
+ * that times out waiting for its members reports status 1 in its own sequence's trace.
  */
 int seq_verify_batched(int32_t algorithm, int32_t batch, const void* target_logits, const void* draft_logits,
                        const int32_t* tree_tokens, const int32_t* parent, float temperature,

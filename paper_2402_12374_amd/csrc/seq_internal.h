@@ -31,7 +31,9 @@ struct SyncArea {
     uint32_t* attn_counters = nullptr;           // [kAttnMaxCounters]
     unsigned long long* draft_exchange = nullptr;  // [kDraftMaxGroups][64] lists of a split row, zero between calls
     uint32_t* draft_arrivals = nullptr;          // [SEQ_MAX_TREE] workgroups of a row that are done
-    uint32_t* verify_batch_ctl = nullptr;        // [kVerifyMaxBatch][4] per sequence of a batched launch: epoch, unused, arrivals, unused
+    uint32_t* verify_batch_ctl = nullptr;        // [kVerifyMaxBatch][4] per sequence of a batched launch: tag epoch of the
+                                                 // per-node kernel, tag epoch of the walk's teams, arrivals, the teams' poison flag
+    unsigned long long* verify_batch_slots = nullptr;  // [kWalkMaxBatch][2][kVerifyMaxGroups][kVerifySlotWords]
     // Measured once per device: do workgroups whose ids are congruent mod 8 share an XCD (one
     // L2)?  The attention kernel then keeps all key ranges of a unit on one XCD and can hand
     // partial results over through that L2 without writing it back to memory.
@@ -44,6 +46,7 @@ constexpr int kVerifyTagsPerCall = 4096;
 constexpr int kAttnMaxCounters = 16384;
 constexpr int kDraftMaxGroups = 16384;
 constexpr int kVerifyMaxBatch = 256;
+constexpr int kWalkMaxBatch = 64;     // teams of the lazy walk that one launch runs side by side
 
 // Looks up (or builds and uploads) the plan for this parent array on the current device.
 // Returns SEQ_OK or an error code; *plan receives a copy whose device pointers stay owned by

@@ -166,8 +166,11 @@ int get_sync_area(SyncArea** out) {
     const size_t ctr_bytes = sizeof(uint32_t) * kAttnMaxCounters;
     // the lists of split rows (8 MiB), then one arrival counter per row
     const size_t draft_words = (size_t)kDraftMaxGroups * 64;
+    // ... then the per-sequence cells and exchange slots of batched verification launches
+    const size_t batch_slot_words = (size_t)kWalkMaxBatch * 2 * kVerifyMaxGroups * kVerifySlotWords;
+    static_assert((SEQ_MAX_TREE + 4 * kVerifyMaxBatch) % 2 == 0, "the slots that follow hold 64-bit words");
     const size_t draft_bytes = sizeof(unsigned long long) * draft_words + sizeof(uint32_t) * SEQ_MAX_TREE +
-                               sizeof(uint32_t) * 4 * kVerifyMaxBatch;
+                               sizeof(uint32_t) * 4 * kVerifyMaxBatch + sizeof(unsigned long long) * batch_slot_words;
     bool ok = hipMalloc(&s.area.verify_slots, slot_bytes) == hipSuccess &&
               hipMalloc(&s.area.attn_counters, ctr_bytes) == hipSuccess &&
               hipMalloc(&s.area.draft_exchange, draft_bytes) == hipSuccess &&
@@ -186,6 +189,7 @@ int get_sync_area(SyncArea** out) {
     s.area.verify_arrivals = s.area.verify_epoch + 2;
     s.area.draft_arrivals = reinterpret_cast<uint32_t*>(s.area.draft_exchange + draft_words);
     s.area.verify_batch_ctl = s.area.draft_arrivals + SEQ_MAX_TREE;
+    s.area.verify_batch_slots = reinterpret_cast<unsigned long long*>(s.area.verify_batch_ctl + 4 * kVerifyMaxBatch);
     s.area.round_robin_xcds = probe_round_robin_xcds();
     g_sync.push_back(s);
     *out = &g_sync.back().area;

@@ -93,26 +93,9 @@ __device__ long long g_chain_wg_times[4 * 1024];   // per workgroup: start, rows
 #define CHAIN_WG_TIME(k) do {} while (0)
 #endif
 
-// A batched launch runs the same code once per sequence (grid.y): every sequence has its own
-// logits, tokens, uniforms, outputs, workspace, tag epoch and arrival counter; the tree is shared.
-__device__ __forceinline__ VerifyParams params_of_sequence(const VerifyParams& in, int b) {
-    VerifyParams p = in;
-    p.target = static_cast<const char*>(in.target) + (size_t)b * in.batch_logit_bytes;
-    p.draft = static_cast<const char*>(in.draft) + (size_t)b * in.batch_logit_bytes;
-    p.tokens = in.tokens + (size_t)b * in.n;
-    p.uniforms = in.uniforms + (size_t)b * in.n;
-    p.path = in.path + (size_t)b * in.n;
-    p.bonus = in.bonus + b;
-    p.trace = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(in.trace) + (size_t)b * in.batch_workspace_bytes);
-    p.records = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(in.records) + (size_t)b * in.batch_workspace_bytes);
-    p.epoch = in.batch_ctl + 4 * b;
-    p.arrivals = in.batch_ctl + 4 * b + 2;
-    return p;
-}
-
 template <typename LT, int CH, bool BATCHED>
 __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyParams p_in) {
-    const VerifyParams p = BATCHED ? params_of_sequence(p_in, blockIdx.y) : p_in;
+    const VerifyParams p = BATCHED ? params_of_sequence(p_in, blockIdx.y, false) : p_in;
     __shared__ ChainShared sh;
     constexpr int EPT = CH * kChunk;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

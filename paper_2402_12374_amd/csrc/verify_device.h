@@ -37,15 +37,37 @@ struct VerifyParams {
     unsigned long long* records;   // per-node kernel: child records, then node records
     unsigned long long* slots;
     uint32_t* epoch;
+    uint32_t* poison;       // lazy walk: set after a timed-out wait, later launches refuse to run
     uint32_t* arrivals;
     uint32_t spin_limit;
     int n, V, W;
     float inv_T;
     int with_replacement;   // SpecInfer: the draft distribution is never updated (Algorithm 2 without its blue lines)
-    // a batched launch of the per-node kernel (grid.y = sequences): byte strides between sequences
+    // a batched launch (grid.y = sequences): byte strides between sequences
     size_t batch_logit_bytes, batch_workspace_bytes;
-    uint32_t* batch_ctl;    // [sequences][4]: epoch, -, arrivals, -
+    uint32_t* batch_ctl;    // [sequences][4]: per-node kernel's epoch, walk's epoch, arrivals, walk's poison flag
+    unsigned long long* batch_slots;   // [sequences][2][kVerifyMaxGroups][kVerifySlotWords]
 };
+
+// A batched launch runs the same code once per sequence (grid.y): every sequence has its own
+// logits, tokens, uniforms, outputs, workspace, tag epochs, arrival counter and exchange slots;
+// the tree is shared.
+__device__ __forceinline__ VerifyParams params_of_sequence(const VerifyParams& in, int b, bool walk_team) {
+    VerifyParams p = in;
+    p.target = static_cast<const char*>(in.target) + (size_t)b * in.batch_logit_bytes;
+    p.draft = in.draft ? static_cast<const char*>(in.draft) + (size_t)b * in.batch_logit_bytes : nullptr;
+    p.tokens = in.tokens + (size_t)b * in.n;
+    p.uniforms = in.uniforms + (size_t)b * in.n;
+    p.path = in.path + (size_t)b * in.n;
+    p.bonus = in.bonus + b;
+    p.trace = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(in.trace) + (size_t)b * in.batch_workspace_bytes);
+    p.records = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(in.records) + (size_t)b * in.batch_workspace_bytes);
+    p.epoch = in.batch_ctl + 4 * b + (walk_team ? 1 : 0);
+    p.poison = in.batch_ctl + 4 * b + 3;
+    p.arrivals = in.batch_ctl + 4 * b + 2;
+    if (walk_team) p.slots = in.batch_slots + (size_t)b * 2 * kVerifyMaxGroups * kVerifySlotWords;
+    return p;
+}
 
 // verify_chains.hip: every node's sibling chain in parallel, then the walk over the results.
 // Vocabularies up to kChainsMaxVocab; dtype SEQ_BF16 or SEQ_F32.

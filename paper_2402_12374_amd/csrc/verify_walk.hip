@@ -124,10 +124,11 @@ __device__ __forceinline__ bool exchange(const VerifyParams& p, uint32_t tag_bas
 // arguments) and agree between the workgroups of one launch.  epoch[0] is the tag base: every
 // workgroup reads it on entry and workgroup 0 moves it on when it leaves -- which it cannot do
 // before every workgroup has published, hence read the epoch, at least once.  That argument
-// fails only after a timed-out wait, so a timeout also sets epoch[1], and every later launch
-// refuses to run (status 1) until seq_shutdown() has discarded the area.
+// fails only after a timed-out wait, so a timeout also sets the poison flag, and every later launch
+// refuses to run (status 1) until seq_shutdown() has discarded the area.  (A batched launch has
+// an epoch, a flag and a set of slots per sequence: its teams share nothing.)
 __device__ __forceinline__ uint32_t launch_tag_base(const VerifyParams& p, bool* poisoned) {
-    *poisoned = __hip_atomic_load(p.epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+    *poisoned = __hip_atomic_load(p.poison, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
     return __hip_atomic_load(p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -154,7 +155,7 @@ __device__ __forceinline__ void finish(const VerifyParams& p, int path_len, int 
         p.trace[5] = p.trace[6] = p.trace[7] = 0;
         if (status != 0) {
             p.bonus[0] = -1;
-            __hip_atomic_store(p.epoch + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.poison, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         atomicAdd(p.epoch, (uint32_t)kVerifyTagsPerCall);
     }
@@ -212,8 +213,9 @@ __device__ __forceinline__ float fold_waves(const Shared& sh, int par, int k, fl
     return lane_value(row_reduce<OP>(v), 0);
 }
 
-template <typename LT, int EPT>
-__global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParams p) {
+template <typename LT, int EPT, bool BATCHED>
+__global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParams p_in) {
+    const VerifyParams p = BATCHED ? params_of_sequence(p_in, blockIdx.y, true) : p_in;
     __shared__ Shared sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int base = (wg_rank() * kThreads + tid) * EPT;  // my EPT consecutive tokens
@@ -447,8 +449,9 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
 // with D[s] = 0 is accepted iff R[s] > 0, the residual stays one-hot through every rejection,
 // and the draft falls back to uniform once its single token has been rejected.  The bonus token
 // is the arg-max at the node where the walk stops.  Only the target rows are read.
-template <typename LT, int EPT>
-__global__ __launch_bounds__(kThreads) void verify_greedy_kernel(const VerifyParams p) {
+template <typename LT, int EPT, bool BATCHED>
+__global__ __launch_bounds__(kThreads) void verify_greedy_kernel(const VerifyParams p_in) {
+    const VerifyParams p = BATCHED ? params_of_sequence(p_in, blockIdx.y, true) : p_in;
     __shared__ Shared sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int base = (wg_rank() * kThreads + tid) * EPT;
@@ -528,17 +531,19 @@ __global__ __launch_bounds__(kThreads) void verify_greedy_kernel(const VerifyPar
 
 uint32_t g_spin_limit = 1u << 22;
 
+// One team of p.W workgroups per sequence; `batch` > 1 puts the teams of that many sequences
+// side by side in one launch (grid.y).  The caller keeps p.W * batch within what the chip holds
+// at once: a team waits for its own members only, but they must all be running.
 template <typename LT>
-void launch_verify(const VerifyParams& p, bool greedy, int ept, hipStream_t stream) {
-    const dim3 grid((unsigned)p.W), block(kThreads);
-#define SEQ_LAUNCH(E)                                                                          \
-    do {                                                                                       \
-        if (greedy) hipLaunchKernelGGL((verify_greedy_kernel<LT, E>), grid, block, 0, stream, p); \
-        else hipLaunchKernelGGL((verify_walk_kernel<LT, E>), grid, block, 0, stream, p);       \
-    } while (0)
-    (void)ept;
-    SEQ_LAUNCH(8);
-#undef SEQ_LAUNCH
+void launch_verify(const VerifyParams& p, bool greedy, hipStream_t stream, int batch) {
+    const dim3 grid((unsigned)p.W, (unsigned)batch), block(kThreads);
+    if (batch > 1) {
+        if (greedy) hipLaunchKernelGGL((verify_greedy_kernel<LT, 8, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((verify_walk_kernel<LT, 8, true>), grid, block, 0, stream, p);
+    } else {
+        if (greedy) hipLaunchKernelGGL((verify_greedy_kernel<LT, 8, false>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((verify_walk_kernel<LT, 8, false>), grid, block, 0, stream, p);
+    }
 }
 
 }  // namespace
@@ -617,7 +622,7 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
     rc = get_sync_area(&sync);
     if (rc != SEQ_OK) return rc;
 
-    const int ept = 8;  // kVerifyMaxGroups * kThreads * 8 = SEQ_MAX_VOCAB
+    constexpr int ept = 8;  // kVerifyMaxGroups * kThreads * 8 = SEQ_MAX_VOCAB
     static_assert((long long)kVerifyMaxGroups * kThreads * 8 >= SEQ_MAX_VOCAB, "vocabulary limit");
     VerifyParams p;
     p.target = target_logits;
@@ -633,6 +638,7 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
     p.arrivals = sync->verify_arrivals;
     p.slots = sync->verify_slots;
     p.epoch = sync->verify_epoch;
+    p.poison = sync->verify_epoch + 1;
     p.spin_limit = g_spin_limit;
     p.n = n_tree;
     p.V = vocab;
@@ -645,15 +651,28 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
     p.batch_logit_bytes = (size_t)n_tree * vocab * elt;
     p.batch_workspace_bytes = per_sequence;
     p.batch_ctl = sync->verify_batch_ctl;
+    p.batch_slots = sync->verify_batch_slots;
     // Sampling with a vocabulary one workgroup can hold, and a tree whose nodes all find a CU at
     // once: all nodes at once -- of as many sequences of the batch as still fit.  Otherwise (and
     // for greedy decoding, which needs one arg-max per visited node) the lazy walk.
     // (T = 0: all three algorithms accept a child exactly when its token is the target's arg-max
     // and emit that arg-max, so the greedy kernel serves them all.)
-    const bool per_node_kernel = !greedy && algorithm != SEQ_VERIFY_TOPK && vocab <= kChainsMaxVocab && g_verify_mode != 1;
-    // sequences per launch: as many as the per-node kernel has CUs for, else one
-    int group = 1;
-    if (per_node_kernel && (n_tree <= kChainsMaxNodes || g_verify_mode == 2)) group = std::max(1, kChainsMaxNodes / n_tree);
+    bool per_node_kernel = !greedy && algorithm != SEQ_VERIFY_TOPK && vocab <= kChainsMaxVocab &&
+                           g_verify_mode != 1 && (n_tree <= kChainsMaxNodes || g_verify_mode == 2);
+    const bool topk_draws = algorithm == SEQ_VERIFY_TOPK && !greedy;
+    // sequences per launch: as many as find a CU for every workgroup they need -- a workgroup per
+    // node in the per-node kernel, a team of W in the lazy walk (whose members wait for each
+    // other, so all of them must be running); the top-k draws take one sequence at a time
+    constexpr int kWorkgroupsAtOnce = kChainsMaxNodes;
+    const int per_launch_nodes = std::max(1, kWorkgroupsAtOnce / n_tree);
+    const int per_launch_teams = std::min(kWalkMaxBatch, std::max(1, kWorkgroupsAtOnce / p.W));
+    // A batch that the per-node kernel needs more launches for than the teams do goes to the
+    // teams: a launch of either costs about the same whatever it holds (64 nodes, 32000 tokens:
+    // 4 sequences per per-node launch of 22 us; 16 sequences as teams 42 us, 64 sequences 55 us).
+    if (per_node_kernel && g_verify_mode != 2 &&
+        (batch + per_launch_nodes - 1) / per_launch_nodes > (batch + per_launch_teams - 1) / per_launch_teams)
+        per_node_kernel = false;
+    const int group = topk_draws ? 1 : per_node_kernel ? per_launch_nodes : per_launch_teams;
     for (int b = 0; b < batch; b += group) {      // one group of sequences after the other on the stream
         const int count = std::min(group, batch - b);
         VerifyParams q = p;
@@ -665,11 +684,10 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
         q.bonus = bonus_token + b;
         q.trace = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + (size_t)b * per_sequence);
         q.records = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + (size_t)b * per_sequence + kTraceBytesPadded);
-        if (count > 1) { launch_verify_chains(q, dtype, stream, count); continue; }
-        if (algorithm == SEQ_VERIFY_TOPK && !greedy) launch_verify_topk(q, dtype, stream);
-        else if (per_node_kernel && (n_tree <= kChainsMaxNodes || g_verify_mode == 2)) launch_verify_chains(q, dtype, stream);
-        else if (dtype == SEQ_BF16) launch_verify<uint16_t>(q, greedy, ept, stream);
-        else launch_verify<float>(q, greedy, ept, stream);
+        if (topk_draws) launch_verify_topk(q, dtype, stream);
+        else if (per_node_kernel) launch_verify_chains(q, dtype, stream, count);
+        else if (dtype == SEQ_BF16) launch_verify<uint16_t>(q, greedy, stream, count);
+        else launch_verify<float>(q, greedy, stream, count);
     }
     return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
 }

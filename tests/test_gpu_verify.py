@@ -223,11 +223,45 @@ def test_bounded_wait_always_terminates(kernel_choice):
     assert check_verify(v) in ("exact", "flagged")
 
 
-@pytest.mark.parametrize("n,V,B,T", [(16, 2049, 5, 0.6), (64, 32000, 4, 0.6), (64, 5000, 9, 1.0), (40, 3000, 3, 0.0), (12, 50257, 3, 0.8)])
+def test_a_timed_out_team_of_a_batch_is_reported(kernel_choice):
+    """As above for a batched launch: with no patience at all every team either finishes or
+    reports status 1 with bonus -1, and every kernel exits."""
+    if kernel_choice != "lazy":
+        pytest.skip("only the lazy walk waits for other workgroups")
+    parent = W.geometric_tree(16, 4)
+    vs = [W.make_verify_inputs(parent, 40000, 3.0, 0.8, 0.6, W.BF16, seed=900 + b) for b in range(6)]
+    stack = lambda key: torch.from_numpy(np.stack([getattr(v, key) for v in vs])).to(DEV)
+    args = (S.SEQ_VERIFY_SEQUOIA, stack("target_logits").to(torch.bfloat16), stack("draft_logits").to(torch.bfloat16),
+            stack("tree_tokens"), parent, 0.6, stack("uniforms"))
+    S.lib().seqtree_internal_set_spin_limit(0)
+    try:
+        path, bonus, ws = S.seq_verify_batched(*args)
+        torch.cuda.synchronize()
+    finally:
+        S.lib().seqtree_internal_set_spin_limit(1 << 22)
+    timed_out = False
+    for b in range(6):
+        trace = S.read_verify_trace(ws[b])
+        assert trace["status"] in (0, 1)
+        if trace["status"] == 1:
+            timed_out = True
+            assert int(bonus[b].item()) == -1
+    if timed_out:
+        S.shutdown()
+    path, bonus, ws = S.seq_verify_batched(*args)
+    torch.cuda.synchronize()
+    for b, v in enumerate(vs):
+        assert check_verify(v, (path[b].cpu().numpy(), int(bonus[b].item()), S.read_verify_trace(ws[b]))) in ("exact", "flagged")
+
+
+@pytest.mark.parametrize("n,V,B,T", [(16, 2049, 5, 0.6), (64, 32000, 4, 0.6), (64, 5000, 9, 1.0), (40, 3000, 3, 0.0),
+                                     (12, 50257, 3, 0.8), (8, 128256, 18, 0.6), (6, 40000, 70, 0.0), (5, 9000, 67, 0.9)])
 def test_a_batch_of_sequences_over_one_tree(n, V, B, T):
     """seq_verify_batched: every sequence of the batch must get what seq_verify gives it alone
-    (the checker's answer), whether the batch runs as one launch of the per-node kernel or as one
-    launch per sequence; each sequence's trace sits at its own offset of the workspace."""
+    (the checker's answer), whether the batch runs as launches of the per-node kernel, or as
+    launches of the lazy walk with the teams of several sequences side by side (the last cases
+    need more than one such launch); each sequence's trace sits at its own offset of the
+    workspace."""
     parent = W.geometric_tree(n, 6)
     vs = [W.make_verify_inputs(parent, V, 3.0, 0.8, T, W.BF16, seed=500 + 17 * b + n) for b in range(B)]
     stack = lambda key: torch.from_numpy(np.stack([getattr(v, key) for v in vs])).to(DEV)
@@ -247,4 +281,6 @@ def test_a_batch_of_sequences_over_one_tree(n, V, B, T):
                     flagged += 1
                 else:
                     assert [int(x) for x in got[0] if x >= 0] == ref.path and got[1] == ref.bonus_token, (alg, b)
-        assert flagged <= 1
+        # where the residual is flat the edges of the bonus draw's CDF are about 1/V apart, not far
+        # from the flag margin of 1e-5: a bonus token drawn there is often flagged by definition
+        assert flagged <= max(1, B // 3)
