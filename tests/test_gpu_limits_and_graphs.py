@@ -115,6 +115,54 @@ def test_graph_replays_match_eager_results():
         assert np.abs(got_out - oracle_attn(a)).max() <= TOL[W.BF16]
 
 
+def test_batched_walk_in_a_graph():
+    """seq_verify_batched with the teams of several sequences in one launch, captured once and
+    replayed with new logits and uniforms in the same buffers: every replay gives every sequence
+    what the checker gives it, and no team reports a timeout."""
+    n, V, B, T = 24, 20000, 7, 0.7          # three workgroups per team
+    parent = W.geometric_tree(n, 5)
+    make = lambda rep: [W.make_verify_inputs(parent, V, 3.0, 1.0, T, W.BF16, seed=40 * rep + b) for b in range(B)]
+    stack = lambda vs, key: torch.from_numpy(np.stack([getattr(v, key) for v in vs])).to(DEV)
+    vs = make(0)
+    buf = dict(tl=stack(vs, "target_logits").to(torch.bfloat16), dl=stack(vs, "draft_logits").to(torch.bfloat16),
+               tok=stack(vs, "tree_tokens"), un=stack(vs, "uniforms"))
+    path = torch.empty((B, n), dtype=torch.int32, device=DEV)
+    bonus = torch.empty(B, dtype=torch.int32, device=DEV)
+    ws = torch.empty((B, S.seq_verify_workspace(n, V, 1)), dtype=torch.uint8, device=DEV)
+
+    def step():
+        S.seq_verify_batched(S.SEQ_VERIFY_SEQUOIA, buf["tl"], buf["dl"], buf["tok"], parent, T, buf["un"],
+                             accepted_path=path, bonus_token=bonus, workspace=ws)
+
+    S.lib().seqtree_internal_set_verify_mode(1)
+    try:
+        step()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for rep in range(1, 4):
+            vs = make(rep)
+            buf["tl"].copy_(stack(vs, "target_logits").to(torch.bfloat16))
+            buf["dl"].copy_(stack(vs, "draft_logits").to(torch.bfloat16))
+            buf["tok"].copy_(stack(vs, "tree_tokens"))
+            buf["un"].copy_(stack(vs, "uniforms"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for b, v in enumerate(vs):
+                got = (path[b].cpu().numpy(), int(bonus[b].item()), S.read_verify_trace(ws[b]))
+                assert check_verify(v, got) in ("exact", "flagged"), (rep, b)
+    finally:
+        S.lib().seqtree_internal_set_verify_mode(0)
+
+
 def test_whole_iteration_in_one_graph():
     """Draw the root's children, verify the tree with each of the three algorithms, append the
     accepted path to the cache -- captured once, replayed with the step counter advanced on the
