@@ -180,7 +180,7 @@ int seq_verify_with(int32_t algorithm, const void* target_logits, const void* dr
  * batch 1 .. 256.  Sequences share launches: floor(256 / n_tree) of them where the per-node
  * kernel applies and the batch fits in as few launches that way, otherwise the lazy walk with the
  * teams of min(64, floor(256 / W)) sequences side by side, W = ceil(vocab / 8192) workgroups per
- * team.  Only SEQ_VERIFY_TOPK at temperature > 0 takes the sequences one after the other.  A team
+ * team; SEQ_VERIFY_TOPK at temperature > 0 runs the whole batch in one launch per kernel.  A team
  * that times out waiting for its members reports status 1 in its own sequence's trace.
  */
 int seq_verify_batched(int32_t algorithm, int32_t batch, const void* target_logits, const void* draft_logits,

@@ -75,7 +75,7 @@ constexpr int kChainsMaxVocab = 32768;
 constexpr int kChainsMaxNodes = 256;   // one workgroup per node, one workgroup per CU
 void launch_verify_chains(const VerifyParams& p, int dtype, hipStream_t stream, int batch = 1);
 // verify_topk.hip: naive / top-k sampling (Sec. 2.2): one draw from the target per node, then the walk.
-void launch_verify_topk(const VerifyParams& p, int dtype, hipStream_t stream);
+void launch_verify_topk(const VerifyParams& p, int dtype, hipStream_t stream, int batch = 1);
 void set_topk_mode(int mode);
 
 template <typename LT> __device__ __forceinline__ float load_logit(const LT* row, int x);

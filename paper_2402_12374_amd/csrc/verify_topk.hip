@@ -129,18 +129,26 @@ __device__ __forceinline__ void draw_node(const VerifyParams& p, int v, DrawShar
     __syncthreads();
 }
 
+// The draws of a sequence live where the per-node kernel keeps its records: after the trace.
+__device__ __forceinline__ Draw* draws_of(const VerifyParams& p) { return reinterpret_cast<Draw*>(p.records); }
+
+// grid.x = node, grid.y = sequence of the batch (nothing is shared between sequences but the tree)
 template <typename LT>
-__global__ void __launch_bounds__(kThreads) topk_draw_kernel(const VerifyParams p, Draw* draws) {
+__global__ void __launch_bounds__(kThreads) topk_draw_kernel(const VerifyParams p_in) {
+    const VerifyParams p = params_of_sequence(p_in, blockIdx.y, false);
     __shared__ DrawShared sh;
     draw_node<LT>(p, blockIdx.x, sh);
-    if (threadIdx.x == 0) draws[blockIdx.x] = sh.result;
+    if (threadIdx.x == 0) draws_of(p)[blockIdx.x] = sh.result;
 }
 
-// Follows the draws from the root: a lane per child looks for the drawn token.  With draws given
-// (DRAWS != nullptr) one wavefront reads them; without, one workgroup makes each draw when the
-// walk gets there (a big tree over a big vocabulary: the walk visits a handful of the nodes).
+// Follows the draws from the root: a lane per child looks for the drawn token.  With draws made
+// beforehand one wavefront reads them; without, one workgroup makes each draw when the walk gets
+// there (a big tree over a big vocabulary: the walk visits a handful of the nodes).  grid.y =
+// sequence of the batch.
 template <typename LT>
-__global__ void __launch_bounds__(kThreads) topk_walk_kernel(const VerifyParams p, const Draw* draws) {
+__global__ void __launch_bounds__(kThreads) topk_walk_kernel(const VerifyParams p_in, int have_draws) {
+    const VerifyParams p = params_of_sequence(p_in, blockIdx.y, false);
+    const Draw* draws = have_draws ? draws_of(p) : nullptr;
     __shared__ DrawShared sh;
     const int lane = threadIdx.x & 63;
     int v = 0, path_len = 0, n_rec = 0;
@@ -183,22 +191,22 @@ int g_topk_mode = 0;   // test hook: 1 = always all draws at once, 2 = always wh
 
 void set_topk_mode(int mode) { g_topk_mode = mode; }
 
-void launch_verify_topk(const VerifyParams& p, int dtype, hipStream_t stream) {
-    // the draws live where the per-node kernel keeps its records: after the trace
-    Draw* draws = reinterpret_cast<Draw*>(p.records);
+void launch_verify_topk(const VerifyParams& p, int dtype, hipStream_t stream, int batch) {
     static_assert(sizeof(Draw) * SEQ_MAX_TREE <=
                   sizeof(unsigned long long) * (size_t)SEQ_MAX_TREE * (kChildRecordWords + kNodeRecordWords), "workspace");
     // all draws at once while that is cheap (three sweeps over every row); beyond 2^24 logits one
     // workgroup draws only where the walk goes (measured at 768 x 128256: 73 us against 205 us)
     const bool lazy = (long long)p.n * p.V > (1ll << 24) || g_topk_mode == 2;
+    const dim3 per_sequence(1, (unsigned)batch);
     if (lazy && g_topk_mode != 1) {
-        if (dtype == SEQ_BF16) topk_walk_kernel<uint16_t><<<1, kThreads, 0, stream>>>(p, nullptr);
-        else topk_walk_kernel<float><<<1, kThreads, 0, stream>>>(p, nullptr);
+        if (dtype == SEQ_BF16) topk_walk_kernel<uint16_t><<<per_sequence, kThreads, 0, stream>>>(p, 0);
+        else topk_walk_kernel<float><<<per_sequence, kThreads, 0, stream>>>(p, 0);
         return;
     }
-    if (dtype == SEQ_BF16) topk_draw_kernel<uint16_t><<<p.n, kThreads, 0, stream>>>(p, draws);
-    else topk_draw_kernel<float><<<p.n, kThreads, 0, stream>>>(p, draws);
-    topk_walk_kernel<uint16_t><<<1, 64, 0, stream>>>(p, draws);
+    const dim3 per_node((unsigned)p.n, (unsigned)batch);
+    if (dtype == SEQ_BF16) topk_draw_kernel<uint16_t><<<per_node, kThreads, 0, stream>>>(p);
+    else topk_draw_kernel<float><<<per_node, kThreads, 0, stream>>>(p);
+    topk_walk_kernel<uint16_t><<<per_sequence, 64, 0, stream>>>(p, 1);
 }
 
 }  // namespace verify

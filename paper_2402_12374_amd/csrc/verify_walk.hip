@@ -662,7 +662,7 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
     const bool topk_draws = algorithm == SEQ_VERIFY_TOPK && !greedy;
     // sequences per launch: as many as find a CU for every workgroup they need -- a workgroup per
     // node in the per-node kernel, a team of W in the lazy walk (whose members wait for each
-    // other, so all of them must be running); the top-k draws take one sequence at a time
+    // other, so all of them must be running); the top-k draws, which wait for nobody, all of them
     constexpr int kWorkgroupsAtOnce = kChainsMaxNodes;
     const int per_launch_nodes = std::max(1, kWorkgroupsAtOnce / n_tree);
     const int per_launch_teams = std::min(kWalkMaxBatch, std::max(1, kWorkgroupsAtOnce / p.W));
@@ -672,7 +672,7 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
     if (per_node_kernel && g_verify_mode != 2 &&
         (batch + per_launch_nodes - 1) / per_launch_nodes > (batch + per_launch_teams - 1) / per_launch_teams)
         per_node_kernel = false;
-    const int group = topk_draws ? 1 : per_node_kernel ? per_launch_nodes : per_launch_teams;
+    const int group = topk_draws ? batch : per_node_kernel ? per_launch_nodes : per_launch_teams;
     for (int b = 0; b < batch; b += group) {      // one group of sequences after the other on the stream
         const int count = std::min(group, batch - b);
         VerifyParams q = p;
@@ -684,7 +684,7 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
         q.bonus = bonus_token + b;
         q.trace = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + (size_t)b * per_sequence);
         q.records = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + (size_t)b * per_sequence + kTraceBytesPadded);
-        if (topk_draws) launch_verify_topk(q, dtype, stream);
+        if (topk_draws) launch_verify_topk(q, dtype, stream, count);
         else if (per_node_kernel) launch_verify_chains(q, dtype, stream, count);
         else if (dtype == SEQ_BF16) launch_verify<uint16_t>(q, greedy, stream, count);
         else launch_verify<float>(q, greedy, stream, count);

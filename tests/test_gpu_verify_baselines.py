@@ -58,8 +58,8 @@ def run(algorithm, v, draft=True):
     return path.cpu().numpy(), int(bonus.item()), S.read_verify_trace(ws)
 
 
-def check(algorithm, v, draft=True):
-    p, bonus, trace = run(algorithm, v, draft)
+def check(algorithm, v, draft=True, got=None):
+    p, bonus, trace = run(algorithm, v, draft) if got is None else got
     assert trace["status"] == 0
     ref = oracle.verify_baseline(algorithm, v.target_logits, v.draft_logits, v.tree_tokens, v.parent,
                                  v.temperature, v.uniforms)
@@ -148,3 +148,21 @@ def test_unknown_algorithm_is_refused():
     with pytest.raises(S.SeqTreeError) as e:
         run(7, v)
     assert e.value.code == S.SEQ_ERR_ALGORITHM
+
+
+@pytest.mark.parametrize("algorithm", ALGORITHMS)
+@pytest.mark.parametrize("V,n,B,T", [(3000, 20, 9, 0.8), (32000, 64, 3, 0.6), (40000, 7, 70, 1.0), (2049, 12, 5, 0.0)])
+def test_a_batch_of_sequences(algorithm, V, n, B, T):
+    """seq_verify_batched with the baselines' rules: every sequence gets what it gets alone."""
+    parent = W.geometric_tree(n, 5)
+    vs = [inputs_for(algorithm, parent, V, T, W.BF16, seed=3000 + 13 * b + n) for b in range(B)]
+    stack = lambda key: torch.from_numpy(np.stack([getattr(v, key) for v in vs])).to(DEV)
+    path, bonus, ws = S.seq_verify_batched(algorithm, stack("target_logits").to(torch.bfloat16),
+                                           stack("draft_logits").to(torch.bfloat16), stack("tree_tokens"), parent, T,
+                                           stack("uniforms"))
+    torch.cuda.synchronize()
+    flagged = 0
+    for b, v in enumerate(vs):
+        got = (path[b].cpu().numpy(), int(bonus[b].item()), S.read_verify_trace(ws[b]))
+        flagged += check(algorithm, v, got=got) == "flagged"
+    assert flagged <= max(1, B // 3)
