@@ -166,3 +166,28 @@ def test_a_batch_of_sequences(algorithm, V, n, B, T):
         got = (path[b].cpu().numpy(), int(bonus[b].item()), S.read_verify_trace(ws[b]))
         flagged += check(algorithm, v, got=got) == "flagged"
     assert flagged <= max(1, B // 3)
+
+
+def test_random_batches_equal_one_call_per_sequence():
+    """Random trees, vocabularies, batch sizes, temperatures and algorithms: what seq_verify_batched
+    gives a sequence is what seq_verify_with gives it alone (the checker is not involved here; the
+    single calls are held against it everywhere else)."""
+    rng = np.random.default_rng(11)
+    for case in range(12):
+        n = int(rng.integers(1, 80))
+        V = int(rng.choice([64, 777, 2049, 9000, 32000, 40000]))
+        B = max(1, min(int(rng.integers(1, 30)), int(4e7 // (n * V))))
+        T = float(rng.choice([0.0, 0.6, 1.0]))
+        alg = int(rng.choice([S.SEQ_VERIFY_SEQUOIA, S.SEQ_VERIFY_SPECINFER, S.SEQ_VERIFY_TOPK]))
+        parent = W.random_topological_tree(n, np.random.default_rng(case)) if n > 1 else np.array([-1], np.int32)
+        vs = [W.make_verify_inputs(parent, V, 3.0, 1.5, T, W.BF16, seed=7000 + 50 * case + b) for b in range(B)]
+        stack = lambda key: torch.from_numpy(np.stack([getattr(v, key) for v in vs])).to(DEV)
+        tl, dl = stack("target_logits").to(torch.bfloat16), stack("draft_logits").to(torch.bfloat16)
+        tok, un = stack("tree_tokens"), stack("uniforms")
+        path, bonus, ws = S.seq_verify_batched(alg, tl, dl, tok, parent, T, un)
+        torch.cuda.synchronize()
+        for b in range(B):
+            p1, b1, w1 = S.seq_verify_with(alg, tl[b], dl[b], tok[b], parent, T, un[b])
+            torch.cuda.synchronize()
+            assert S.read_verify_trace(ws[b])["status"] == 0 and S.read_verify_trace(w1)["status"] == 0
+            assert torch.equal(path[b], p1) and int(bonus[b].item()) == int(b1.item()), (case, n, V, B, T, alg, b)
