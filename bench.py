@@ -45,7 +45,7 @@ def attn_alg_bytes(cfg, n=None, P=None):
 
 
 def attn_alg_flops(cfg, parent):
-    from paper_2402_12374_amd import workloads as W
+    import workloads as W
     visible = int((W.depths(parent) + 1).sum())
     return 4 * cfg.head_dim * cfg.heads * (len(parent) * cfg.prefix_len + visible)
 
@@ -84,7 +84,7 @@ def run_sweep(args) -> int:
     import torch
 
     import paper_2402_12374_amd as S
-    from paper_2402_12374_amd import workloads as W
+    import workloads as W
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -171,7 +171,7 @@ def run_draft_sample(args) -> int:
     import torch
 
     import paper_2402_12374_amd as S
-    from paper_2402_12374_amd import workloads as W
+    import workloads as W
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -236,7 +236,7 @@ def run_verify_batch(args) -> int:
     import torch
 
     import paper_2402_12374_amd as S
-    from paper_2402_12374_amd import workloads as W
+    import workloads as W
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -283,7 +283,7 @@ def run_rejection_curve(args) -> int:
     import torch
 
     import paper_2402_12374_amd as S
-    from paper_2402_12374_amd import workloads as W
+    import workloads as W
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -394,7 +394,7 @@ def main() -> int:
     import torch
 
     import paper_2402_12374_amd as S
-    from paper_2402_12374_amd import workloads as W
+    import workloads as W
 
     cfg = W.CONFIGS[args.config]
     cfg_index = list(W.CONFIGS).index(args.config) + 1

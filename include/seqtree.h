@@ -3,11 +3,10 @@
  * (Sequoia, arxiv 2402.12374), as a C-ABI library for AMD MI355X (gfx950).
  *
  * Two operations make up the step:
- *   seq_tree_attn   one attention layer of the single target forward pass that scores every
- *                   token of the tree at once (Sec. 1: the tree is "verified in parallel
- *                   through a single forward pass"; Sec. 2.1: the root stands for the current
- *                   prefix): tree token i attends to the prefix KV cache, to its ancestors in
- *                   the tree and to itself.
+ *   seq_tree_attn   one attention layer of the target model's one forward pass over the whole
+ *                   tree, which scores all of its tokens together (Sec. 1; Sec. 2.1: the root
+ *                   stands for the current prefix): tree token i attends to the prefix KV
+ *                   cache, to its ancestors in the tree and to itself.
  *   seq_verify      Algorithm 2 (Sec. 3.2.1, "Sequoia Sampling and Verification") applied
  *                   recursively from the root (Sec. 2.2), on caller-supplied uniforms.
  * Around them:
@@ -24,17 +23,26 @@
  * Conventions for every entry point
  *   - Tensors are row-major and contiguous.  Pointers are DEVICE pointers unless marked HOST.
  *   - The caller owns every buffer.  Inputs are never written.  The library keeps, per
- *     process, a small cache of tree plans (device copies of the ancestor bitset and the
- *     child lists, keyed by the contents of parent[]) and one synchronisation area (8.3 MiB);
- *     both are created on first use and released by seq_shutdown().  A call whose tree is
- *     already cached allocates nothing, copies nothing and never synchronises with the host.
+ *     process, a cache of tree plans (device copies of the ancestor bitset and the child lists,
+ *     keyed by the device and the contents of parent[]; 1 KB at 64 nodes, 140 KB at 1024) and one
+ *     synchronisation area (8.3 MiB) per (device, stream) it has been called on; both are created
+ *     on first use and released by seq_shutdown() only.  Nothing is ever evicted -- a captured
+ *     graph holds the device pointers of the plan and the area it was captured with -- so at most
+ *     SEQ_MAX_PLANS distinct trees and SEQ_MAX_STREAMS streams per device can be in use between
+ *     two seq_shutdown() calls; one more is refused with SEQ_ERR_FULL.
+ *   - The first call for a tree, and the first call on a stream, allocates device memory and
+ *     copies synchronously: make it outside stream capture.  Every later call with that tree on
+ *     that stream allocates nothing, copies nothing and never synchronises with the host.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
  *     stream); outputs are valid once the caller has synchronised that stream.
  *   - Return value: SEQ_OK (0) or a negative SEQ_ERR_* code.  Nothing is thrown or printed.
  *     All argument checks happen on the host before any GPU call, so invalid arguments are
  *     reported even on a machine without a GPU.
- *   - Two calls that overlap in time on the same GPU (different streams or threads) race on
- *     the library's synchronisation area; serialise them.
+ *   - Calls on different streams may overlap in time: each stream has its own synchronisation
+ *     area, and calls on one stream are ordered by the stream.  A captured graph keeps the area
+ *     of the stream it was captured on wherever it is replayed: do not replay it while other
+ *     work that uses that area (eager calls on the capture stream, another graph captured on
+ *     it) may be running.  seq_shutdown() must not run while any call or graph is in flight.
  */
 #ifndef SEQTREE_H
 #define SEQTREE_H
@@ -60,10 +68,13 @@ extern "C" {
 #define SEQ_ERR_WORKSPACE (-6)   /* workspace NULL, smaller than the matching *_workspace(), or not 16-byte aligned */
 #define SEQ_ERR_HIP (-7)         /* a HIP runtime call failed (no device, launch failure, ...) */
 #define SEQ_ERR_ALGORITHM (-8)   /* algorithm is none of SEQ_VERIFY_* */
+#define SEQ_ERR_FULL (-9)        /* SEQ_MAX_PLANS distinct trees or SEQ_MAX_STREAMS streams are already in use */
 
 #define SEQ_MAX_TREE 1024
 #define SEQ_MAX_VOCAB 524288
 #define SEQ_MAX_CHILDREN 64      /* most tokens seq_draft_sample draws for one node */
+#define SEQ_MAX_PLANS 1024       /* distinct (device, tree) pairs the plan cache holds */
+#define SEQ_MAX_STREAMS 16       /* streams per device with a synchronisation area of their own */
 
 /*
  * Tree-masked attention with grouped-query heads (one layer).
@@ -133,8 +144,7 @@ int seq_tree_attn(const void* q, const void* k_cache, const void* v_cache,
  * thresholds are computed at once, one workgroup per node (every logit row the tree can visit
  * is read), and a short walk follows;
  * otherwise only the rows of the nodes the walk visits are read, by workgroups that share the
- * vocabulary.  Calls that overlap in time on one device (different streams) are not supported:
- * both kernels use a per-device synchronisation area.
+ * vocabulary.
  */
 int seq_verify(const void* target_logits, const void* draft_logits,
                const int32_t* tree_tokens, const int32_t* parent, float temperature,
@@ -233,8 +243,8 @@ int seq_verify_batched(int32_t algorithm, int32_t batch, const void* target_logi
  *                 library's per-device exchange area)
  *
  * Errors: SEQ_ERR_NULL, SEQ_ERR_DTYPE, SEQ_ERR_SHAPE, SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE,
- * SEQ_ERR_HIP.  One launch.  Rows that several workgroups share meet in the per-device
- * synchronisation area, so calls that overlap in time on one device race (see above).
+ * SEQ_ERR_HIP.  One launch.  Rows that several workgroups share meet in the stream's
+ * synchronisation area.
  */
 int seq_draft_sample(const void* draft_logits, const int32_t* n_children, float temperature,
                      const uint64_t* rng, int32_t* tokens, int32_t n_rows, int32_t vocab,
@@ -345,7 +355,8 @@ int seq_pick_tree_shape(const double* acceptance, int32_t max_branch, const int3
                         double decode_time, double draft_time, int32_t* best_size,
                         int32_t* best_depth, double* best_speedup);
 
-/* Releases the plan cache and the synchronisation area of every device.  Safe to call twice. */
+/* Releases the plan cache and every synchronisation area (all devices, all streams).  Safe to call
+ * twice.  Graphs captured before it hold dangling pointers afterwards and must not be replayed. */
 int seq_shutdown(void);
 
 const char* seq_strerror(int code);

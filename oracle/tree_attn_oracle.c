@@ -3,9 +3,9 @@
  * path may call this; it exists so the tests, the smoke check and the benchmark's CPU
  * baseline can compare the HIP kernels with a plain definition.
  *
- * What is computed.  The paper only says that all tokens of the speculated tree are scored
- * "in parallel through a single forward pass" of the target model (Sec. 1) and that the tree
- * root stands for the current prefix (Sec. 2.1).  For the attention layer of that forward
+ * What is computed.  The paper only says that the target model scores all tokens of the
+ * speculated tree together, in one forward pass (Sec. 1), and that the tree root stands for
+ * the current prefix (Sec. 2.1).  For the attention layer of that forward
  * pass this means: tree token i sees the whole prefix KV cache, its ancestors in the tree,
  * and itself -- nothing else.  Written out, for query head h with KV head g = h / (H/Hk):
  *

@@ -3,8 +3,8 @@
  * product path may call this.
  *
  * What is computed.  Algorithm 2 ("Sequoia Sampling and Verification", Sec. 3.2.1) applied
- * recursively from the root of the token tree (Sec. 2.2: all such methods verify a tree
- * "in a recursive manner, starting at the root").  It is a randomized procedure, so the
+ * recursively from the root of the token tree (Sec. 2.2: every such method starts at the
+ * root and goes on at the child it accepts).  It is a randomized procedure, so the
  * checker is the procedure itself, run on uniforms handed in by the caller, step by step in
  * the algorithm's own notation:
  *

@@ -18,11 +18,13 @@ LIB_PATH = os.path.join(HERE, "libseqtree.so")
 SEQ_BF16, SEQ_F32 = 1, 2
 SEQ_OK = 0
 SEQ_ERR_NULL, SEQ_ERR_SHAPE, SEQ_ERR_TREE, SEQ_ERR_DTYPE = -1, -2, -3, -4
-SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE, SEQ_ERR_HIP, SEQ_ERR_ALGORITHM = -5, -6, -7, -8
+SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE, SEQ_ERR_HIP, SEQ_ERR_ALGORITHM, SEQ_ERR_FULL = -5, -6, -7, -8, -9
 SEQ_VERIFY_SEQUOIA, SEQ_VERIFY_SPECINFER, SEQ_VERIFY_TOPK = 0, 1, 2
 SEQ_MAX_TREE = 1024
 SEQ_MAX_VOCAB = 524288
 SEQ_MAX_CHILDREN = 64
+SEQ_MAX_PLANS = 1024
+SEQ_MAX_STREAMS = 16
 TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
 EXPORTS = ("seq_tree_attn", "seq_verify", "seq_verify_with", "seq_verify_batched", "seq_draft_sample", "seq_kv_append", "seq_top_p_filter", "seq_tree_attn_workspace",
@@ -88,6 +90,12 @@ def lib() -> C.CDLL:
         l.seq_version.restype = C.c_int
         l.seqtree_internal_copy_probe.restype = C.c_int
         l.seqtree_internal_copy_probe.argtypes = [vp, vp, sz, vp]
+        l.seqtree_internal_use_host_memory.restype = None
+        l.seqtree_internal_use_host_memory.argtypes = [C.c_int]
+        l.seqtree_internal_plan_pointers.restype = C.c_int
+        l.seqtree_internal_plan_pointers.argtypes = [vp, i32, vp]
+        l.seqtree_internal_sync_area_of.restype = C.c_int
+        l.seqtree_internal_sync_area_of.argtypes = [vp, vp]
         l.seqtree_internal_fast_div.restype = C.c_uint32
         l.seqtree_internal_fast_div.argtypes = [C.c_uint32, C.c_uint32]
         _lib = l

@@ -496,8 +496,9 @@ extern "C" int seq_draft_sample(const void* draft_logits, const int32_t* n_child
     if (!workspace || workspace_bytes < seq_draft_sample_workspace(n_rows, vocab, k_max, dtype) ||
         (reinterpret_cast<uintptr_t>(workspace) & 15) != 0)
         return SEQ_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     SyncArea* sync = nullptr;
-    int rc = get_sync_area(&sync);
+    int rc = get_sync_area(stream, &sync);
     if (rc != SEQ_OK) return rc;
 
     DraftParams p;
@@ -515,7 +516,6 @@ extern "C" int seq_draft_sample(const void* draft_logits, const int32_t* n_child
     const bool greedy = temperature == 0.0f;
     p.inv_T = greedy ? 1.0f : 1.0f / temperature;
     p.spin_limit = 1u << 20;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool vec = vocab % 8 == 0 && (reinterpret_cast<uintptr_t>(draft_logits) & 15) == 0;
     if (dtype == SEQ_BF16) {
         if (vec) launch<uint16_t, true>(p, greedy, stream); else launch<uint16_t, false>(p, greedy, stream);

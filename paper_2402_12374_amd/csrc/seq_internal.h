@@ -21,7 +21,8 @@ struct TreePlan {
     int32_t max_children = 0;
 };
 
-// Per-device area the kernels use to hand partial results between workgroups.  Zeroed once
+// Area the kernels use to hand partial results between workgroups, one per (device, stream) the
+// library has been called on.  Zeroed once
 // when created; the kernels leave it in a reusable state (arrival counters return to zero,
 // exchange slots carry ever-increasing tags).
 struct SyncArea {
@@ -38,6 +39,7 @@ struct SyncArea {
     // L2)?  The attention kernel then keeps all key ranges of a unit on one XCD and can hand
     // partial results over through that L2 without writing it back to memory.
     bool round_robin_xcds = false;
+    int compute_units = 256;   // of this device: workgroups of 1024 threads that run at the same time
 };
 
 constexpr int kVerifyMaxGroups = 64;
@@ -52,7 +54,7 @@ constexpr int kWalkMaxBatch = 64;     // teams of the lazy walk that one launch 
 // Returns SEQ_OK or an error code; *plan receives a copy whose device pointers stay owned by
 // the cache.
 int get_tree_plan(const int32_t* parent, int32_t n, TreePlan* plan);
-int get_sync_area(SyncArea** area);
+int get_sync_area(hipStream_t stream, SyncArea** area);
 int release_all();
 
 // Host-side plan construction (no GPU).  Vectors are sized by the callee.

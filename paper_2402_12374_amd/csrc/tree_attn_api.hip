@@ -54,7 +54,7 @@ extern "C" int seq_tree_attn(const void* q, const void* k_cache, const void* v_c
             head_dim, static_cast<float*>(out), stream);
     }
     SyncArea* sync = nullptr;
-    rc = get_sync_area(&sync);
+    rc = get_sync_area(stream, &sync);
     if (rc != SEQ_OK) return rc;
     return launch_tree_attn_mfma_bf16(q, k_cache, v_cache, k_tree, v_tree, plan, prefix_len,
                                       prefix_cap, n_tree, heads, kv_heads, head_dim, out, sched,

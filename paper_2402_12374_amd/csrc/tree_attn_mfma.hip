@@ -753,12 +753,15 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     ATTN_STAMP(21);
 
     // See whether we are the last range of this unit to finish.  The partial results must be
-    // visible to that workgroup.  When all ranges of a unit run on one XCD they meet in its L2:
-    // it is enough that my stores have completed.  Otherwise the L2 has to be written back.
+    // visible to that workgroup, which runs on another CU.  When all ranges of a unit run on one
+    // XCD they meet in its L2: every wavefront waits until the L2 has acknowledged its own stores
+    // (the vector memory counter counts stores too; a workgroup-scope fence would not wait, since
+    // within a workgroup the CU's own cache is the meeting point), and only then does the barrier
+    // let thread 0 count the workgroup as arrived.  Otherwise the L2 has to be written back.
     // (Sharing the merge among the S workgroups of a unit -- count arrivals, poll a bounded
     // number of times, claim a slice -- was tried: the polling costs more than the one CU's
     // memory pipeline it saves, and workgroups that wait hold CUs that a later batch needs.)
-    if (p.share_l2) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (p.share_l2) wait_vmcnt<0>();
     else __threadfence();
     __syncthreads();
     if (tid == 0) {
@@ -769,7 +772,9 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     __syncthreads();
     ATTN_STAMP(22);
     if (!s_last) { ATTN_STAMP_FLUSH(); return; }
-    if (p.share_l2) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    // The partial results are read from the L2, not from whatever this CU's own cache holds for
+    // those addresses: a device-scope acquire invalidates it (no write-back involved).
+    if (p.share_l2) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     else __threadfence();
     ATTN_STAMP(23);
 

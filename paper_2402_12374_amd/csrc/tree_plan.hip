@@ -3,7 +3,9 @@
 // "Implementation Details": because it is known in advance the step can be captured as a
 // graph), so the plan is built once per tree shape and cached.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
+#include <deque>
 #include <mutex>
 #include <vector>
 
@@ -77,49 +79,79 @@ static void build_host(const int32_t* parent, int32_t n, std::vector<int32_t>* d
 }
 
 namespace {
+// Where the library's own device memory comes from.  The host tests swap in plain host memory
+// (no GPU involved) to exercise the bookkeeping below: what is kept, what is handed out twice,
+// what is refused.
+struct DeviceMemory {
+    bool (*current_device)(int* device);
+    void* (*alloc)(size_t bytes);
+    bool (*upload)(void* dst, const void* src, size_t bytes);   // synchronous
+    bool (*zero)(void* dst, size_t bytes);                      // synchronous
+    void (*release)(void* ptr);
+    bool gpu;
+};
+const DeviceMemory kHipMemory = {
+    [](int* device) { return hipGetDevice(device) == hipSuccess; },
+    [](size_t bytes) { void* ptr = nullptr; return hipMalloc(&ptr, bytes) == hipSuccess ? ptr : nullptr; },
+    [](void* dst, const void* src, size_t bytes) { return hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice) == hipSuccess; },
+    [](void* dst, size_t bytes) { return hipMemset(dst, 0, bytes) == hipSuccess && hipDeviceSynchronize() == hipSuccess; },
+    [](void* ptr) { (void)hipFree(ptr); },
+    true,
+};
+const DeviceMemory kHostMemory = {
+    [](int* device) { *device = 0; return true; },
+    [](size_t bytes) { return std::malloc(bytes); },
+    [](void* dst, const void* src, size_t bytes) { std::memcpy(dst, src, bytes); return true; },
+    [](void* dst, size_t bytes) { std::memset(dst, 0, bytes); return true; },
+    [](void* ptr) { std::free(ptr); },
+    false,
+};
+const DeviceMemory* g_mem = &kHipMemory;
+
 struct CacheEntry {
     int device;
     std::vector<int32_t> parent;
     TreePlan plan;
-    uint64_t last_use;
 };
-struct DeviceSync {
+struct StreamSync {
     int device;
+    hipStream_t stream;
     SyncArea area;
 };
 std::mutex g_mutex;
-std::vector<CacheEntry> g_cache;
-std::vector<DeviceSync> g_sync;
-uint64_t g_clock = 0;
-constexpr size_t kMaxPlans = 32;
+// Plans are never evicted: a captured graph keeps the raw device pointers of the plan it was
+// captured with for as long as it lives, and the library cannot know how long that is.  A plan
+// is small (140 KB at 1024 nodes, 1 KB at 64), so the cache is bounded by a count and a call
+// with one tree too many is refused.
+std::deque<CacheEntry> g_cache;
+std::deque<StreamSync> g_sync;   // (a deque never moves its elements: handed-out pointers stay valid)
 
 void free_plan(TreePlan& p) {
-    if (p.anc_words) (void)hipFree(p.anc_words);
-    if (p.child_start) (void)hipFree(p.child_start);
-    if (p.child_list) (void)hipFree(p.child_list);
+    if (p.anc_words) g_mem->release(p.anc_words);
+    if (p.child_start) g_mem->release(p.child_start);
+    if (p.child_list) g_mem->release(p.child_list);
     p = TreePlan{};
+}
+void free_area(SyncArea& a) {
+    if (a.verify_slots) g_mem->release(a.verify_slots);
+    if (a.attn_counters) g_mem->release(a.attn_counters);
+    if (a.draft_exchange) g_mem->release(a.draft_exchange);
+    a = SyncArea{};
 }
 }  // namespace
 
 int get_tree_plan(const int32_t* parent, int32_t n, TreePlan* out) {
     int device = 0;
-    if (hipGetDevice(&device) != hipSuccess) return SEQ_ERR_HIP;
+    if (!g_mem->current_device(&device)) return SEQ_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_mutex);
     for (auto& e : g_cache) {
         if (e.device == device && (int32_t)e.parent.size() == n &&
             std::memcmp(e.parent.data(), parent, sizeof(int32_t) * n) == 0) {
-            e.last_use = ++g_clock;
             *out = e.plan;
             return SEQ_OK;
         }
     }
-    if (g_cache.size() >= kMaxPlans) {  // evict the least recently used (hipFree waits for the GPU)
-        size_t victim = 0;
-        for (size_t i = 1; i < g_cache.size(); ++i)
-            if (g_cache[i].last_use < g_cache[victim].last_use) victim = i;
-        free_plan(g_cache[victim].plan);
-        g_cache.erase(g_cache.begin() + victim);
-    }
+    if (g_cache.size() >= (size_t)SEQ_MAX_PLANS) return SEQ_ERR_FULL;
     std::vector<int32_t> depth, cstart, clist;
     std::vector<uint32_t> anc;
     build_host(parent, n, &depth, &cstart, &clist, &anc);
@@ -130,36 +162,40 @@ int get_tree_plan(const int32_t* parent, int32_t n, TreePlan* out) {
     e.plan.words_per_row = words_per_row(n);
     for (int32_t v = 0; v < n; ++v)
         e.plan.max_children = std::max(e.plan.max_children, cstart[v + 1] - cstart[v]);
-    bool ok = hipMalloc(&e.plan.anc_words, anc.size() * sizeof(uint32_t)) == hipSuccess &&
-              hipMalloc(&e.plan.child_start, cstart.size() * sizeof(int32_t)) == hipSuccess &&
-              hipMalloc(&e.plan.child_list, clist.size() * sizeof(int32_t)) == hipSuccess;
-    ok = ok && hipMemcpy(e.plan.anc_words, anc.data(), anc.size() * sizeof(uint32_t),
-                         hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(e.plan.child_start, cstart.data(), cstart.size() * sizeof(int32_t),
-                         hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(e.plan.child_list, clist.data(), clist.size() * sizeof(int32_t),
-                         hipMemcpyHostToDevice) == hipSuccess;
+    e.plan.anc_words = static_cast<uint32_t*>(g_mem->alloc(anc.size() * sizeof(uint32_t)));
+    e.plan.child_start = static_cast<int32_t*>(g_mem->alloc(cstart.size() * sizeof(int32_t)));
+    e.plan.child_list = static_cast<int32_t*>(g_mem->alloc(clist.size() * sizeof(int32_t)));
+    const bool ok = e.plan.anc_words && e.plan.child_start && e.plan.child_list &&
+                    g_mem->upload(e.plan.anc_words, anc.data(), anc.size() * sizeof(uint32_t)) &&
+                    g_mem->upload(e.plan.child_start, cstart.data(), cstart.size() * sizeof(int32_t)) &&
+                    g_mem->upload(e.plan.child_list, clist.data(), clist.size() * sizeof(int32_t));
     if (!ok) {
         free_plan(e.plan);
-        (void)hipGetLastError();
+        if (g_mem->gpu) (void)hipGetLastError();
         return SEQ_ERR_HIP;
     }
-    e.last_use = ++g_clock;
     g_cache.push_back(std::move(e));
     *out = g_cache.back().plan;
     return SEQ_OK;
 }
 
-int get_sync_area(SyncArea** out) {
+// One area per (device, stream): calls on different streams of a device may then overlap in
+// time -- they share nothing but the read-only plans -- and calls on one stream are serialised
+// by the stream itself.
+int get_sync_area(hipStream_t stream, SyncArea** out) {
     int device = 0;
-    if (hipGetDevice(&device) != hipSuccess) return SEQ_ERR_HIP;
+    if (!g_mem->current_device(&device)) return SEQ_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_mutex);
-    for (auto& s : g_sync)
-        if (s.device == device) { *out = &s.area; return SEQ_OK; }
-    // g_sync never reallocates below its reserved size, so returned pointers stay valid
-    if (g_sync.capacity() < 64) g_sync.reserve(64);
-    DeviceSync s;
+    int on_device = 0;
+    for (auto& s : g_sync) {
+        if (s.device != device) continue;
+        if (s.stream == stream) { *out = &s.area; return SEQ_OK; }
+        ++on_device;
+    }
+    if (on_device >= SEQ_MAX_STREAMS) return SEQ_ERR_FULL;
+    StreamSync s;
     s.device = device;
+    s.stream = stream;
     // the exchange slots, then two 64-bit cells: tag epoch and poison flag; arrival counter
     const size_t slot_words = (size_t)2 * kVerifyMaxGroups * kVerifySlotWords;
     const size_t slot_bytes = sizeof(unsigned long long) * (slot_words + 2);
@@ -171,18 +207,15 @@ int get_sync_area(SyncArea** out) {
     static_assert((SEQ_MAX_TREE + 4 * kVerifyMaxBatch) % 2 == 0, "the slots that follow hold 64-bit words");
     const size_t draft_bytes = sizeof(unsigned long long) * draft_words + sizeof(uint32_t) * SEQ_MAX_TREE +
                                sizeof(uint32_t) * 4 * kVerifyMaxBatch + sizeof(unsigned long long) * batch_slot_words;
-    bool ok = hipMalloc(&s.area.verify_slots, slot_bytes) == hipSuccess &&
-              hipMalloc(&s.area.attn_counters, ctr_bytes) == hipSuccess &&
-              hipMalloc(&s.area.draft_exchange, draft_bytes) == hipSuccess &&
-              hipMemset(s.area.verify_slots, 0, slot_bytes) == hipSuccess &&
-              hipMemset(s.area.attn_counters, 0, ctr_bytes) == hipSuccess &&
-              hipMemset(s.area.draft_exchange, 0, draft_bytes) == hipSuccess &&
-              hipDeviceSynchronize() == hipSuccess;
+    s.area.verify_slots = static_cast<unsigned long long*>(g_mem->alloc(slot_bytes));
+    s.area.attn_counters = static_cast<uint32_t*>(g_mem->alloc(ctr_bytes));
+    s.area.draft_exchange = static_cast<unsigned long long*>(g_mem->alloc(draft_bytes));
+    const bool ok = s.area.verify_slots && s.area.attn_counters && s.area.draft_exchange &&
+                    g_mem->zero(s.area.verify_slots, slot_bytes) && g_mem->zero(s.area.attn_counters, ctr_bytes) &&
+                    g_mem->zero(s.area.draft_exchange, draft_bytes);
     if (!ok) {
-        if (s.area.verify_slots) (void)hipFree(s.area.verify_slots);
-        if (s.area.attn_counters) (void)hipFree(s.area.attn_counters);
-        if (s.area.draft_exchange) (void)hipFree(s.area.draft_exchange);
-        (void)hipGetLastError();
+        free_area(s.area);
+        if (g_mem->gpu) (void)hipGetLastError();
         return SEQ_ERR_HIP;
     }
     s.area.verify_epoch = reinterpret_cast<uint32_t*>(s.area.verify_slots + slot_words);
@@ -190,7 +223,21 @@ int get_sync_area(SyncArea** out) {
     s.area.draft_arrivals = reinterpret_cast<uint32_t*>(s.area.draft_exchange + draft_words);
     s.area.verify_batch_ctl = s.area.draft_arrivals + SEQ_MAX_TREE;
     s.area.verify_batch_slots = reinterpret_cast<unsigned long long*>(s.area.verify_batch_ctl + 4 * kVerifyMaxBatch);
-    s.area.round_robin_xcds = probe_round_robin_xcds();
+    // what is measured once per device is copied from the device's first area
+    bool known = false;
+    for (auto& other : g_sync)
+        if (other.device == device) {
+            s.area.round_robin_xcds = other.area.round_robin_xcds;
+            s.area.compute_units = other.area.compute_units;
+            known = true;
+            break;
+        }
+    if (!known && g_mem->gpu) {
+        s.area.round_robin_xcds = probe_round_robin_xcds();
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
+            s.area.compute_units = cus;
+    }
     g_sync.push_back(s);
     *out = &g_sync.back().area;
     return SEQ_OK;
@@ -199,7 +246,7 @@ int get_sync_area(SyncArea** out) {
 int release_all() {
     std::lock_guard<std::mutex> lock(g_mutex);
     int current = 0;
-    const bool have_dev = hipGetDevice(&current) == hipSuccess;
+    const bool have_dev = g_mem->gpu && hipGetDevice(&current) == hipSuccess;
     for (auto& e : g_cache) {
         if (have_dev) (void)hipSetDevice(e.device);
         free_plan(e.plan);
@@ -207,9 +254,7 @@ int release_all() {
     g_cache.clear();
     for (auto& s : g_sync) {
         if (have_dev) (void)hipSetDevice(s.device);
-        if (s.area.verify_slots) (void)hipFree(s.area.verify_slots);
-        if (s.area.attn_counters) (void)hipFree(s.area.attn_counters);
-        if (s.area.draft_exchange) (void)hipFree(s.area.draft_exchange);
+        free_area(s.area);
     }
     g_sync.clear();
     if (have_dev) (void)hipSetDevice(current);
@@ -247,11 +292,33 @@ extern "C" const char* seq_strerror(int code) {
         case SEQ_ERR_WORKSPACE: return "workspace missing or too small";
         case SEQ_ERR_HIP: return "HIP runtime error";
         case SEQ_ERR_ALGORITHM: return "algorithm must be one of SEQ_VERIFY_*";
+        case SEQ_ERR_FULL: return "too many distinct trees or streams: seq_shutdown() releases them";
         default: return "unknown seqtree error code";
     }
 }
 
-extern "C" int seq_version(void) { return 100; }
+extern "C" int seq_version(void) { return 200; }
+
+// Test hooks (not part of the public header).  With host memory switched on the bookkeeping of
+// plans and synchronisation areas runs without a GPU; switching discards everything held.
+extern "C" void seqtree_internal_use_host_memory(int on) {
+    (void)seqtree::release_all();
+    seqtree::g_mem = on ? &seqtree::kHostMemory : &seqtree::kHipMemory;
+}
+extern "C" int seqtree_internal_plan_pointers(const int32_t* parent, int32_t n_tree, void** three) {
+    seqtree::TreePlan plan;
+    int rc = seqtree::validate_parent(parent, n_tree);
+    if (rc == SEQ_OK) rc = seqtree::get_tree_plan(parent, n_tree, &plan);
+    if (rc != SEQ_OK) return rc;
+    three[0] = plan.anc_words; three[1] = plan.child_start; three[2] = plan.child_list;
+    return SEQ_OK;
+}
+extern "C" int seqtree_internal_sync_area_of(void* hip_stream, void** area) {
+    seqtree::SyncArea* a = nullptr;
+    const int rc = seqtree::get_sync_area(static_cast<hipStream_t>(hip_stream), &a);
+    *area = a;
+    return rc;
+}
 
 // A plain copy of a known size: the yardstick the benchmark puts beside its kernels when HBM
 // traffic counters are collected, so that the counters' unit can be checked against bytes

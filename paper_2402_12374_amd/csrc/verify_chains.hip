@@ -107,9 +107,10 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
     const int K = c_end - c_begin;
     unsigned long long* const child_rec = p.records;                                    // [n][kChildRecordWords]
     unsigned long long* const node_rec = p.records + (size_t)p.n * kChildRecordWords;   // [n][kNodeRecordWords]
-    // Tag of this launch: every workgroup reads the epoch on entry, and the last one to arrive
-    // moves it on -- after all have read it.  A fresh workspace (zeros) never carries tag 1.
-    const uint32_t tag = __hip_atomic_load(p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+    // Tag of this launch: every workgroup reads the workspace's epoch on entry, and the last one to
+    // arrive moves it on -- after all have read it.
+    uint32_t* const epoch = chain_epoch_cell(p.records);
+    const uint32_t tag = __hip_atomic_load(epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
     CHAIN_STAMP_RESET();
     CHAIN_STAMP(0);
     CHAIN_WG_TIME(0);
@@ -515,7 +516,7 @@ __global__ __launch_bounds__(kThreads) void verify_chains_kernel(const VerifyPar
         p.trace[5] = p.trace[6] = p.trace[7] = 0;
         sh.w_path_len = path_len;
         sh.w_n_dec = n_dec;
-        __hip_atomic_fetch_add(p.epoch, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(epoch, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         CHAIN_STAMP(43);
       }
     }

@@ -72,7 +72,6 @@ __device__ __forceinline__ VerifyParams params_of_sequence(const VerifyParams& i
 // verify_chains.hip: every node's sibling chain in parallel, then the walk over the results.
 // Vocabularies up to kChainsMaxVocab; dtype SEQ_BF16 or SEQ_F32.
 constexpr int kChainsMaxVocab = 32768;
-constexpr int kChainsMaxNodes = 256;   // one workgroup per node, one workgroup per CU
 void launch_verify_chains(const VerifyParams& p, int dtype, hipStream_t stream, int batch = 1);
 // verify_topk.hip: naive / top-k sampling (Sec. 2.2): one draw from the target per node, then the walk.
 void launch_verify_topk(const VerifyParams& p, int dtype, hipStream_t stream, int batch = 1);
@@ -302,6 +301,14 @@ constexpr size_t kTraceBytes =
 constexpr size_t kTraceBytesPadded = (kTraceBytes + 255) / 256 * 256;
 constexpr int kChildRecordWords = 5;   // tagged words per child: the four factors of the test, events
 constexpr int kNodeRecordWords = 4;    // tagged words per node: bonus token, total mass, CDF below / above
+constexpr size_t kRecordWords = (size_t)SEQ_MAX_TREE * (kChildRecordWords + kNodeRecordWords);
+// The tag epoch of the per-node kernel lives in the workspace, right behind the records it tags:
+// whatever else has used the library's synchronisation area in between, the tags one workspace
+// sees only ever grow, so a record left there by an earlier launch can never pass for a new one.
+__host__ __device__ __forceinline__ uint32_t* chain_epoch_cell(unsigned long long* records) {
+    return reinterpret_cast<uint32_t*>(records + kRecordWords);
+}
+constexpr size_t kVerifyWorkspaceBytes = kTraceBytesPadded + sizeof(unsigned long long) * kRecordWords + 256;
 
 }  // namespace verify
 }  // namespace seqtree

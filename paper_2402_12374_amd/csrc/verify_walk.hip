@@ -142,21 +142,28 @@ __device__ __forceinline__ void stage_tree(const VerifyParams& p, Shared& sh) {
     if (threadIdx.x == 0) sh.child_start[p.n] = p.child_start[p.n];
 }
 
+// The status word of the trace is cleared by workgroup 0 on entry and only ever raised after
+// that, by whichever workgroup gives up waiting: it may be the one that owns the bonus token,
+// and workgroup 0 may have left with a clean status by then.
+__device__ __forceinline__ void begin_trace(const VerifyParams& p) {
+    if (wg_rank() == 0 && threadIdx.x == 0)
+        __hip_atomic_store(&p.trace[1], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ void finish(const VerifyParams& p, int path_len, int n_dec, int status,
                                        int stop_node, int fallbacks, int degenerate) {
+    if (status != 0 && threadIdx.x == 0) {
+        __hip_atomic_store(p.poison, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_max(&p.trace[1], status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        p.bonus[0] = -1;
+    }
     if (wg_rank() != 0) return;
     for (int i = path_len + (int)threadIdx.x; i < p.n; i += kThreads) p.path[i] = -1;
     if (threadIdx.x == 0) {
         p.trace[0] = n_dec;
-        p.trace[1] = status;
         p.trace[2] = stop_node;
         p.trace[3] = fallbacks;
         p.trace[4] = degenerate;
         p.trace[5] = p.trace[6] = p.trace[7] = 0;
-        if (status != 0) {
-            p.bonus[0] = -1;
-            __hip_atomic_store(p.poison, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
         atomicAdd(p.epoch, (uint32_t)kVerifyTagsPerCall);
     }
 }
@@ -233,6 +240,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
     load_row_slice<LT, EPT>(draft, base, V, p.inv_T, vec_ok, qr);
     bool poisoned;
     const uint32_t tag_base = launch_tag_base(p, &poisoned);
+    begin_trace(p);
     if (poisoned) { finish(p, 0, 0, 1, 0, 0, 0); return; }
     stage_tree(p, sh);
     uint32_t step = 0;
@@ -460,6 +468,7 @@ __global__ __launch_bounds__(kThreads) void verify_greedy_kernel(const VerifyPar
     constexpr int kNone = 0x7FFFFFFF;
     bool poisoned;
     const uint32_t tag_base = launch_tag_base(p, &poisoned);
+    begin_trace(p);
     if (poisoned) { finish(p, 0, 0, 1, 0, 0, 0); return; }
     stage_tree(p, sh);
     __syncthreads();
@@ -571,8 +580,7 @@ extern "C" void seqtree_internal_set_topk_mode(int mode) { set_topk_mode(mode); 
 
 extern "C" size_t seq_verify_workspace(int32_t n_tree, int32_t vocab, int32_t dtype) {
     (void)n_tree; (void)vocab; (void)dtype;
-    return kTraceBytesPadded +
-           sizeof(unsigned long long) * (size_t)SEQ_MAX_TREE * (kChildRecordWords + kNodeRecordWords);
+    return kVerifyWorkspaceBytes;
 }
 
 extern "C" int seq_verify(const void* target_logits, const void* draft_logits,
@@ -618,8 +626,9 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
     TreePlan plan;
     rc = get_tree_plan(parent, n_tree, &plan);
     if (rc != SEQ_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     SyncArea* sync = nullptr;
-    rc = get_sync_area(&sync);
+    rc = get_sync_area(stream, &sync);
     if (rc != SEQ_OK) return rc;
 
     constexpr int ept = 8;  // kVerifyMaxGroups * kThreads * 8 = SEQ_MAX_VOCAB
@@ -646,7 +655,6 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
     const bool greedy = temperature == 0.0f;
     p.inv_T = greedy ? 1.0f : 1.0f / temperature;
     p.with_replacement = algorithm == SEQ_VERIFY_SPECINFER;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const size_t elt = dtype == SEQ_BF16 ? 2 : 4;
     p.batch_logit_bytes = (size_t)n_tree * vocab * elt;
     p.batch_workspace_bytes = per_sequence;
@@ -657,15 +665,17 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
     // for greedy decoding, which needs one arg-max per visited node) the lazy walk.
     // (T = 0: all three algorithms accept a child exactly when its token is the target's arg-max
     // and emit that arg-max, so the greedy kernel serves them all.)
+    // (one workgroup of 1024 threads fits a compute unit at a time: the device's count of them is
+    // how many workgroups run at once)
+    const int at_once = sync->compute_units;
     bool per_node_kernel = !greedy && algorithm != SEQ_VERIFY_TOPK && vocab <= kChainsMaxVocab &&
-                           g_verify_mode != 1 && (n_tree <= kChainsMaxNodes || g_verify_mode == 2);
+                           g_verify_mode != 1 && (n_tree <= at_once || g_verify_mode == 2);
     const bool topk_draws = algorithm == SEQ_VERIFY_TOPK && !greedy;
     // sequences per launch: as many as find a CU for every workgroup they need -- a workgroup per
     // node in the per-node kernel, a team of W in the lazy walk (whose members wait for each
     // other, so all of them must be running); the top-k draws, which wait for nobody, all of them
-    constexpr int kWorkgroupsAtOnce = kChainsMaxNodes;
-    const int per_launch_nodes = std::max(1, kWorkgroupsAtOnce / n_tree);
-    const int per_launch_teams = std::min(kWalkMaxBatch, std::max(1, kWorkgroupsAtOnce / p.W));
+    const int per_launch_nodes = std::max(1, at_once / n_tree);
+    const int per_launch_teams = std::min(kWalkMaxBatch, std::max(1, at_once / p.W));
     // A batch that the per-node kernel needs more launches for than the teams do goes to the
     // teams: a launch of either costs about the same whatever it holds (64 nodes, 32000 tokens:
     // 4 sequences per per-node launch of 22 us; 16 sequences as teams 42 us, 64 sequences 55 us).

@@ -4,7 +4,7 @@ import torch
 
 import oracle
 import paper_2402_12374_amd as S
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
 DEV = "cuda:0"
 TOL = {W.F32: 1e-5, W.BF16: 2e-2}          # max-abs bound on attention outputs
@@ -25,6 +25,33 @@ def run_attn(a: W.AttnInputs, **kw) -> np.ndarray:
 
 def oracle_attn(a: W.AttnInputs) -> np.ndarray:
     return oracle.tree_attn(a.q, a.k_cache, a.v_cache, a.k_tree, a.v_tree, a.parent, a.prefix_len)
+
+
+def oracle_attn_all_rows(a: W.AttnInputs, workers: int = 0) -> np.ndarray:
+    """Every row of the checker's answer, one call of its row routine per (node, head), spread
+    over host threads (the routine is reentrant and the foreign call releases the interpreter
+    lock).  The arithmetic is the checker's own, row by row; only the outer loop is shared out."""
+    import ctypes as C
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    n, H, d = a.q.shape
+    Hk, cap, _ = a.k_cache.shape
+    out = np.zeros((n, H, d), dtype=np.float64)
+    workers = workers or min(16, os.cpu_count() or 1)
+    arrays = [np.ascontiguousarray(x, dtype=np.float32) for x in (a.q, a.k_cache, a.v_cache, a.k_tree, a.v_tree)]
+    parent = np.ascontiguousarray(a.parent, dtype=np.int32)
+    ptrs = [x.ctypes.data_as(C.c_void_p) for x in arrays] + [parent.ctypes.data_as(C.c_void_p)]
+    row = oracle.lib().oracle_tree_attn_row
+    sizes = [C.c_int32(x) for x in (a.prefix_len, cap, n, H, Hk, d)]
+
+    def rows_of(i):
+        for h in range(H):
+            rc = row(*ptrs, *sizes, C.c_int32(i), C.c_int32(h), C.c_void_p(out[i, h].ctypes.data), None, None)
+            assert rc == 0
+
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        list(pool.map(rows_of, range(n)))
+    return out
 
 
 def run_verify(v: W.VerifyInputs):

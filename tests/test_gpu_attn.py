@@ -4,9 +4,9 @@ import pytest
 import torch
 
 import oracle
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
-from gpu_util import TOL, oracle_attn, run_attn
+from gpu_util import TOL, oracle_attn, oracle_attn_all_rows, run_attn
 
 pytestmark = pytest.mark.gpu
 
@@ -44,22 +44,16 @@ def test_full_config_all_rows(key):
     assert err <= TOL[a.dtype], err
 
 
-@pytest.mark.parametrize("key,samples", [("C4", 96), ("C5", 64)])
-def test_full_config_sampled_rows(key, samples):
+@pytest.mark.parametrize("key", ["C4", "C5"])
+def test_largest_configs_all_rows(key):
+    """Every one of the 13 312 (C4) and 49 152 (C5) output rows against the checker, whose rows
+    are shared out over the host's cores (about 6 s and 45 s of work for one core)."""
     a = W.attn_inputs_for(key)
     got = run_attn(a)
     assert np.isfinite(got).all()
-    rng = np.random.default_rng(7)
-    n, H, _ = a.q.shape
-    rows = {(0, 0), (n - 1, H - 1), (n - 1, 0), (0, H - 1)}
-    while len(rows) < samples:
-        rows.add((int(rng.integers(n)), int(rng.integers(H))))
-    worst = 0.0
-    for i, h in sorted(rows):
-        want = oracle.tree_attn_row(a.q, a.k_cache, a.v_cache, a.k_tree, a.v_tree, a.parent,
-                                    a.prefix_len, i, h)
-        worst = max(worst, float(np.abs(got[i, h] - want).max()))
-    assert worst <= TOL[a.dtype], worst
+    want = oracle_attn_all_rows(a)
+    err = np.abs(got - want).max()
+    assert err <= TOL[a.dtype], err
 
 
 @pytest.mark.parametrize("dtype", [W.BF16, W.F32])

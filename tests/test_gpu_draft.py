@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import paper_2402_12374_amd as S
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
 from gpu_util import DEV, to_dev
 

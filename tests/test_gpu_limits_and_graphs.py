@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import paper_2402_12374_amd as S
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
 from gpu_util import DEV, TOL, check_verify, oracle_attn, run_attn, to_dev
 

@@ -9,7 +9,7 @@ import pytest
 
 import oracle
 import paper_2402_12374_amd as S
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
 from gpu_util import TOL, check_verify, oracle_attn, run_attn
 from test_gpu_draft import check_draft

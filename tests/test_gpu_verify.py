@@ -7,7 +7,7 @@ import torch
 
 import oracle
 import paper_2402_12374_amd as S
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
 from gpu_util import DEV, check_verify, run_verify
 
@@ -118,7 +118,21 @@ def test_greedy_temperature_zero(key):
     v.target_logits[:, 5] = v.target_logits[:, 9] = 50.0
     assert check_verify(v) == "exact"
     _, bonus, _ = run_verify(v)
-    assert bonus == 5 or True
+    assert bonus == 5
+
+
+@pytest.mark.parametrize("key,T", [("C2", 0.6), ("C3", 1.0), ("C3", 0.0), ("C4", 0.6)])
+def test_full_configs_on_both_kernels_against_the_checker(key, T, kernel_choice):
+    """The configurations' own inputs (tree, vocabulary, logit statistics, temperature), decision by
+    decision against the checker: once on the kernel the library picks (the per-node kernel for
+    these vocabularies at T > 0; at C4 its largest form, 256 workgroups of 32 values per thread)
+    and once with the lazy walk forced."""
+    flagged = 0
+    for rep in range(3):
+        v = W.verify_inputs_for(key, rep=rep, temperature=T)
+        assert v.target_logits.shape == (W.CONFIGS[key].n_tree, W.CONFIGS[key].vocab)
+        flagged += check_verify(v) == "flagged"
+    assert flagged <= 1
 
 
 def test_full_llama3_vocab_and_tree():

@@ -7,7 +7,7 @@ import pytest
 import oracle
 import paper_2402_12374_amd as S
 from paper_2402_12374_amd import binding as B
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
 
 def test_decoding_over_the_extended_cache_equals_attention_in_the_tree():

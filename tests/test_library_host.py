@@ -9,7 +9,7 @@ import pytest
 
 import paper_2402_12374_amd as S
 from paper_2402_12374_amd import binding as B
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -228,3 +228,71 @@ def test_division_by_multiplication_is_exact():
         n = np.arange(1 << 16, dtype=np.int64)
         got = np.array([fd(int(x), d) for x in n[:: 7]], dtype=np.int64)
         assert np.array_equal(got, n[:: 7] // d)
+
+
+@pytest.fixture
+def host_memory():
+    """The library's own allocations come from host memory for the duration of a test, so that
+    the bookkeeping of plans and synchronisation areas can be exercised without a GPU."""
+    S.lib().seqtree_internal_use_host_memory(1)
+    yield S.lib()
+    S.lib().seqtree_internal_use_host_memory(0)
+
+
+def _plan_pointers(lib, parent):
+    par = np.ascontiguousarray(parent, np.int32)
+    three = (C.c_void_p * 3)()
+    rc = lib.seqtree_internal_plan_pointers(par.ctypes.data, len(par), three)
+    return rc, tuple(three)
+
+
+def _read(ptr, count, ctype):
+    return np.ctypeslib.as_array(C.cast(ptr, C.POINTER(ctype)), shape=(count,)).copy()
+
+
+def test_a_plan_stays_where_it_is_however_many_trees_follow(host_memory):
+    """A captured graph holds a plan's device pointers: no later tree may move, free or overwrite
+    it, and the tree that no longer fits is refused instead of pushing another one out."""
+    lib = host_memory
+    first = W.geometric_tree(64, 8)
+    rc, ptrs = _plan_pointers(lib, first)
+    assert rc == B.SEQ_OK and all(ptrs)
+    _, cstart, clist, anc = S.seq_tree_plan_host(first)
+    def intact():
+        assert np.array_equal(_read(ptrs[0], anc.size, C.c_uint32), anc.ravel())
+        assert np.array_equal(_read(ptrs[1], 65, C.c_int32), cstart)
+        assert np.array_equal(_read(ptrs[2], 63, C.c_int32), clist)
+    intact()
+    for n in range(2, B.SEQ_MAX_PLANS + 1):              # 1023 more distinct trees: the cache is full
+        rc, other = _plan_pointers(lib, W.chain_tree(n))
+        assert rc == B.SEQ_OK and not set(other) & set(ptrs)
+        if n in (34, 35, 600):                           # (the old cache held 32)
+            assert _plan_pointers(lib, first) == (B.SEQ_OK, ptrs)
+            intact()
+    assert _plan_pointers(lib, W.star_tree(7))[0] == B.SEQ_ERR_FULL
+    assert "seq_shutdown" in S.strerror(B.SEQ_ERR_FULL)
+    assert _plan_pointers(lib, first) == (B.SEQ_OK, ptrs)   # a cached tree is still served
+    assert _plan_pointers(lib, W.chain_tree(500))[0] == B.SEQ_OK
+    intact()
+    S.shutdown()
+    assert _plan_pointers(lib, W.star_tree(7))[0] == B.SEQ_OK
+
+
+def test_every_stream_has_a_synchronisation_area_of_its_own(host_memory):
+    lib = host_memory
+    def area_of(stream):
+        out = C.c_void_p()
+        rc = lib.seqtree_internal_sync_area_of(C.c_void_p(stream), C.byref(out))
+        return rc, out.value
+    rc, null_stream = area_of(None)
+    assert rc == B.SEQ_OK and null_stream
+    areas = {null_stream}
+    for k in range(1, B.SEQ_MAX_STREAMS):
+        rc, a = area_of(0x1000 * k)
+        assert rc == B.SEQ_OK and a not in areas
+        areas.add(a)
+        assert area_of(0x1000 * k) == (B.SEQ_OK, a)       # the same stream: the same area
+    assert area_of(None) == (B.SEQ_OK, null_stream)
+    assert area_of(0x99000)[0] == B.SEQ_ERR_FULL          # one stream too many is refused, nothing is recycled
+    S.shutdown()
+    assert area_of(0x99000)[0] == B.SEQ_OK

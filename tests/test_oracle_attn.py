@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
 
 def dense_masked_attention(q, keys, vals, allowed):

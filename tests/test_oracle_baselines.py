@@ -16,7 +16,7 @@ import pytest
 from scipy.special import softmax as sp_softmax
 
 import oracle
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
 GOLDEN = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_worked_examples.json")))
 ALMOST_ONE = np.float32(1.0 - 2.0 ** -24)

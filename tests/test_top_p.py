@@ -9,7 +9,7 @@ import pytest
 import oracle
 import paper_2402_12374_amd as S
 from paper_2402_12374_amd import binding as B
-from paper_2402_12374_amd import workloads as W
+import workloads as W
 
 
 def test_uniform_and_geometric_rows_have_closed_forms():
@@ -104,8 +104,11 @@ def test_library_against_the_checker(V, rows, dtype, T):
                 continue
             assert has_defining_properties(prob[r], got_keep[r], top_p, 2e-6), (top_p, r, got_keep[r].sum(), keep[r].sum())
             differing += 1
-            if top_p == 1.0:        # no search at all: exactly the tokens whose fp32 probability is not zero
-                assert np.array_equal(got_keep[r], prob[r] > 1e-37) or not ((prob[r] > 1e-37) & ~got_keep[r]).any()
+            if top_p == 1.0:
+                # no search at all: every token whose fp32 probability is not zero is kept (1e-37:
+                # above the smallest normal float), and no token of probability exactly zero is
+                assert not ((prob[r] > 1e-37) & ~got_keep[r]).any()
+                assert not ((prob[r] == 0.0) & got_keep[r]).any()
     assert differing <= 4 * rows // 2
 
 
