@@ -31,8 +31,12 @@
  *     SEQ_MAX_PLANS distinct trees and SEQ_MAX_STREAMS streams per device can be in use between
  *     two seq_shutdown() calls; one more is refused with SEQ_ERR_FULL.
  *   - The first call for a tree, and the first call on a stream, allocates device memory and
- *     copies synchronously: make it outside stream capture.  Every later call with that tree on
- *     that stream allocates nothing, copies nothing and never synchronises with the host.
+ *     copies synchronously.  Every later call with that tree on that stream allocates nothing,
+ *     copies nothing and never synchronises with the host.  Under stream capture nothing can be
+ *     allocated: a call with a tree that is not cached yet is refused (SEQ_ERR_CAPTURE), and a
+ *     capturing stream that has no area yet records its calls with the area of the first stream
+ *     the library was called on for this device (SEQ_ERR_CAPTURE if there is none): make one
+ *     call with the tree outside capture first.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
  *     stream); outputs are valid once the caller has synchronised that stream.
  *   - Return value: SEQ_OK (0) or a negative SEQ_ERR_* code.  Nothing is thrown or printed.
@@ -40,9 +44,9 @@
  *     reported even on a machine without a GPU.
  *   - Calls on different streams may overlap in time: each stream has its own synchronisation
  *     area, and calls on one stream are ordered by the stream.  A captured graph keeps the area
- *     of the stream it was captured on wherever it is replayed: do not replay it while other
- *     work that uses that area (eager calls on the capture stream, another graph captured on
- *     it) may be running.  seq_shutdown() must not run while any call or graph is in flight.
+ *     it was recorded with wherever it is replayed: do not replay it while other work that uses
+ *     that area (eager calls on the stream the area belongs to, another graph recorded with it)
+ *     may be running.  seq_shutdown() must not run while any call or graph is in flight.
  */
 #ifndef SEQTREE_H
 #define SEQTREE_H
@@ -69,6 +73,7 @@ extern "C" {
 #define SEQ_ERR_HIP (-7)         /* a HIP runtime call failed (no device, launch failure, ...) */
 #define SEQ_ERR_ALGORITHM (-8)   /* algorithm is none of SEQ_VERIFY_* */
 #define SEQ_ERR_FULL (-9)        /* SEQ_MAX_PLANS distinct trees or SEQ_MAX_STREAMS streams are already in use */
+#define SEQ_ERR_CAPTURE (-10)    /* under stream capture: first call for this tree, or first call on this device */
 
 #define SEQ_MAX_TREE 1024
 #define SEQ_MAX_VOCAB 524288

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libseqtree.so")
 SEQ_BF16, SEQ_F32 = 1, 2
 SEQ_OK = 0
 SEQ_ERR_NULL, SEQ_ERR_SHAPE, SEQ_ERR_TREE, SEQ_ERR_DTYPE = -1, -2, -3, -4
-SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE, SEQ_ERR_HIP, SEQ_ERR_ALGORITHM, SEQ_ERR_FULL = -5, -6, -7, -8, -9
+SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE, SEQ_ERR_HIP, SEQ_ERR_ALGORITHM, SEQ_ERR_FULL, SEQ_ERR_CAPTURE = -5, -6, -7, -8, -9, -10
 SEQ_VERIFY_SEQUOIA, SEQ_VERIFY_SPECINFER, SEQ_VERIFY_TOPK = 0, 1, 2
 SEQ_MAX_TREE = 1024
 SEQ_MAX_VOCAB = 524288
@@ -93,7 +93,7 @@ def lib() -> C.CDLL:
         l.seqtree_internal_use_host_memory.restype = None
         l.seqtree_internal_use_host_memory.argtypes = [C.c_int]
         l.seqtree_internal_plan_pointers.restype = C.c_int
-        l.seqtree_internal_plan_pointers.argtypes = [vp, i32, vp]
+        l.seqtree_internal_plan_pointers.argtypes = [vp, i32, vp, vp]
         l.seqtree_internal_sync_area_of.restype = C.c_int
         l.seqtree_internal_sync_area_of.argtypes = [vp, vp]
         l.seqtree_internal_fast_div.restype = C.c_uint32

@@ -53,7 +53,7 @@ constexpr int kWalkMaxBatch = 64;     // teams of the lazy walk that one launch 
 // Looks up (or builds and uploads) the plan for this parent array on the current device.
 // Returns SEQ_OK or an error code; *plan receives a copy whose device pointers stay owned by
 // the cache.
-int get_tree_plan(const int32_t* parent, int32_t n, TreePlan* plan);
+int get_tree_plan(const int32_t* parent, int32_t n, hipStream_t stream, TreePlan* plan);
 int get_sync_area(hipStream_t stream, SyncArea** area);
 int release_all();
 

@@ -44,7 +44,7 @@ extern "C" int seq_tree_attn(const void* q, const void* k_cache, const void* v_c
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     TreePlan plan;
-    rc = get_tree_plan(parent, n_tree, &plan);
+    rc = get_tree_plan(parent, n_tree, stream, &plan);
     if (rc != SEQ_OK) return rc;
     if (dtype == SEQ_F32) {
         return launch_tree_attn_rowwise_f32(

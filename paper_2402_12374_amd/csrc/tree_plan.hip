@@ -88,6 +88,7 @@ struct DeviceMemory {
     bool (*upload)(void* dst, const void* src, size_t bytes);   // synchronous
     bool (*zero)(void* dst, size_t bytes);                      // synchronous
     void (*release)(void* ptr);
+    bool (*capturing)(hipStream_t stream);   // work enqueued on the stream is being recorded, not run
     bool gpu;
 };
 const DeviceMemory kHipMemory = {
@@ -96,6 +97,10 @@ const DeviceMemory kHipMemory = {
     [](void* dst, const void* src, size_t bytes) { return hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice) == hipSuccess; },
     [](void* dst, size_t bytes) { return hipMemset(dst, 0, bytes) == hipSuccess && hipDeviceSynchronize() == hipSuccess; },
     [](void* ptr) { (void)hipFree(ptr); },
+    [](hipStream_t stream) {
+        hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+        return hipStreamIsCapturing(stream, &status) == hipSuccess && status != hipStreamCaptureStatusNone;
+    },
     true,
 };
 const DeviceMemory kHostMemory = {
@@ -104,6 +109,7 @@ const DeviceMemory kHostMemory = {
     [](void* dst, const void* src, size_t bytes) { std::memcpy(dst, src, bytes); return true; },
     [](void* dst, size_t bytes) { std::memset(dst, 0, bytes); return true; },
     [](void* ptr) { std::free(ptr); },
+    [](hipStream_t stream) { return (reinterpret_cast<uintptr_t>(stream) & 1) != 0; },   // odd handles play "capturing"
     false,
 };
 const DeviceMemory* g_mem = &kHipMemory;
@@ -140,7 +146,7 @@ void free_area(SyncArea& a) {
 }
 }  // namespace
 
-int get_tree_plan(const int32_t* parent, int32_t n, TreePlan* out) {
+int get_tree_plan(const int32_t* parent, int32_t n, hipStream_t stream, TreePlan* out) {
     int device = 0;
     if (!g_mem->current_device(&device)) return SEQ_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_mutex);
@@ -152,6 +158,8 @@ int get_tree_plan(const int32_t* parent, int32_t n, TreePlan* out) {
         }
     }
     if (g_cache.size() >= (size_t)SEQ_MAX_PLANS) return SEQ_ERR_FULL;
+    // a new plan means allocations and synchronous copies, which would invalidate a capture
+    if (g_mem->capturing(stream)) return SEQ_ERR_CAPTURE;
     std::vector<int32_t> depth, cstart, clist;
     std::vector<uint32_t> anc;
     build_host(parent, n, &depth, &cstart, &clist, &anc);
@@ -181,16 +189,25 @@ int get_tree_plan(const int32_t* parent, int32_t n, TreePlan* out) {
 
 // One area per (device, stream): calls on different streams of a device may then overlap in
 // time -- they share nothing but the read-only plans -- and calls on one stream are serialised
-// by the stream itself.
+// by the stream itself.  A stream that is being captured cannot be given an area (that takes
+// allocations and a synchronous clear): if it has none yet, its calls are recorded with the
+// area of the first stream the library was called on for this device.
 int get_sync_area(hipStream_t stream, SyncArea** out) {
     int device = 0;
     if (!g_mem->current_device(&device)) return SEQ_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_mutex);
     int on_device = 0;
+    SyncArea* first = nullptr;
     for (auto& s : g_sync) {
         if (s.device != device) continue;
         if (s.stream == stream) { *out = &s.area; return SEQ_OK; }
+        if (!first) first = &s.area;
         ++on_device;
+    }
+    if (g_mem->capturing(stream)) {
+        if (!first) return SEQ_ERR_CAPTURE;
+        *out = first;
+        return SEQ_OK;
     }
     if (on_device >= SEQ_MAX_STREAMS) return SEQ_ERR_FULL;
     StreamSync s;
@@ -293,6 +310,7 @@ extern "C" const char* seq_strerror(int code) {
         case SEQ_ERR_HIP: return "HIP runtime error";
         case SEQ_ERR_ALGORITHM: return "algorithm must be one of SEQ_VERIFY_*";
         case SEQ_ERR_FULL: return "too many distinct trees or streams: seq_shutdown() releases them";
+        case SEQ_ERR_CAPTURE: return "first call for this tree or device made under stream capture: make it once outside";
         default: return "unknown seqtree error code";
     }
 }
@@ -305,10 +323,10 @@ extern "C" void seqtree_internal_use_host_memory(int on) {
     (void)seqtree::release_all();
     seqtree::g_mem = on ? &seqtree::kHostMemory : &seqtree::kHipMemory;
 }
-extern "C" int seqtree_internal_plan_pointers(const int32_t* parent, int32_t n_tree, void** three) {
+extern "C" int seqtree_internal_plan_pointers(const int32_t* parent, int32_t n_tree, void* hip_stream, void** three) {
     seqtree::TreePlan plan;
     int rc = seqtree::validate_parent(parent, n_tree);
-    if (rc == SEQ_OK) rc = seqtree::get_tree_plan(parent, n_tree, &plan);
+    if (rc == SEQ_OK) rc = seqtree::get_tree_plan(parent, n_tree, static_cast<hipStream_t>(hip_stream), &plan);
     if (rc != SEQ_OK) return rc;
     three[0] = plan.anc_words; three[1] = plan.child_start; three[2] = plan.child_list;
     return SEQ_OK;

@@ -623,10 +623,10 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
         (reinterpret_cast<uintptr_t>(workspace) & 15) != 0)
         return SEQ_ERR_WORKSPACE;
 
-    TreePlan plan;
-    rc = get_tree_plan(parent, n_tree, &plan);
-    if (rc != SEQ_OK) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    TreePlan plan;
+    rc = get_tree_plan(parent, n_tree, stream, &plan);
+    if (rc != SEQ_OK) return rc;
     SyncArea* sync = nullptr;
     rc = get_sync_area(stream, &sync);
     if (rc != SEQ_OK) return rc;

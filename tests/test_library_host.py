@@ -239,10 +239,10 @@ def host_memory():
     S.lib().seqtree_internal_use_host_memory(0)
 
 
-def _plan_pointers(lib, parent):
+def _plan_pointers(lib, parent, stream=None):
     par = np.ascontiguousarray(parent, np.int32)
     three = (C.c_void_p * 3)()
-    rc = lib.seqtree_internal_plan_pointers(par.ctypes.data, len(par), three)
+    rc = lib.seqtree_internal_plan_pointers(par.ctypes.data, len(par), C.c_void_p(stream), three)
     return rc, tuple(three)
 
 
@@ -296,3 +296,25 @@ def test_every_stream_has_a_synchronisation_area_of_its_own(host_memory):
     assert area_of(0x99000)[0] == B.SEQ_ERR_FULL          # one stream too many is refused, nothing is recycled
     S.shutdown()
     assert area_of(0x99000)[0] == B.SEQ_OK
+
+
+def test_nothing_is_allocated_under_stream_capture(host_memory):
+    """With host memory standing in, odd stream handles count as capturing.  A capturing stream
+    gets no area of its own (that would allocate): it records with the device's first area, and
+    a tree that is not cached yet is refused instead of being uploaded."""
+    lib = host_memory
+    def area_of(stream):
+        out = C.c_void_p()
+        rc = lib.seqtree_internal_sync_area_of(C.c_void_p(stream), C.byref(out))
+        return rc, out.value
+    tree = W.geometric_tree(40, 6)
+    assert area_of(0x2001)[0] == B.SEQ_ERR_CAPTURE             # no area on this device yet
+    assert _plan_pointers(lib, tree, stream=0x2001)[0] == B.SEQ_ERR_CAPTURE
+    rc, first = area_of(0x1000)
+    assert rc == B.SEQ_OK
+    assert area_of(0x3000)[0] == B.SEQ_OK
+    assert area_of(0x2001) == (B.SEQ_OK, first)                # recorded with the first stream's area
+    rc, ptrs = _plan_pointers(lib, tree)                       # one call outside capture ...
+    assert rc == B.SEQ_OK
+    assert _plan_pointers(lib, tree, stream=0x2001) == (B.SEQ_OK, ptrs)   # ... and the capture finds the plan
+    assert "capture" in S.strerror(B.SEQ_ERR_CAPTURE)
