@@ -298,6 +298,32 @@ int seq_kv_append(const void* k_tree, const void* v_tree, const int32_t* accepte
 int seq_top_p_filter(const void* logits, void* filtered, float top_p, float temperature,
                      int32_t n_rows, int32_t vocab, int32_t dtype, int32_t* kept, void* hip_stream);
 
+/*
+ * seq_tree_attn for callers that cannot allocate device memory: code under stream capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments (no workspace), same kernels,
+ * same results bit for bit.  The call allocates nothing, frees nothing, copies nothing between
+ * host and device and looks nothing up: the ancestor bitset is rebuilt on the device at every call
+ * from parent[], which travels as a kernel argument, and bitset, arrival counters and partial
+ * results live in one static device array of 192 KiB + SEQ_NOALLOC_MAX_PARTIAL_BYTES that every
+ * GPU the library runs on holds until the process ends.
+ *
+ * Limits: n_tree <= SEQ_MAX_TREE as everywhere; a shape whose key ranges need more than
+ * SEQ_NOALLOC_MAX_PARTIAL_BYTES of partial results (seq_tree_attn_workspace(...) says how much) is
+ * refused with SEQ_ERR_WORKSPACE.  Other errors as for seq_tree_attn.
+ *
+ * All calls on one GPU share that GPU's array, whatever their stream: calls that overlap in time
+ * on one GPU race; order them (one stream, or events).  The array keeps the last call's contents;
+ * what a call needs cleared it clears itself, on its stream.  The first call on each GPU finds the
+ * array's address and measures how the GPU places workgroups (a small kernel on the null stream
+ * and a synchronous read-back): make it outside stream capture (SEQ_ERR_CAPTURE otherwise).
+ */
+#define SEQ_NOALLOC_MAX_PARTIAL_BYTES (32u << 20)
+int seq_tree_attn_noalloc(const void* q, const void* k_cache, const void* v_cache,
+                          const void* k_tree, const void* v_tree, const int32_t* parent,
+                          int32_t prefix_len, int32_t n_tree, int32_t heads, int32_t kv_heads,
+                          int32_t head_dim, void* out, int32_t prefix_cap, int32_t dtype,
+                          void* hip_stream);
+
 /* Scratch sizes in bytes for the calls above (0 is never returned; at least 256). */
 size_t seq_tree_attn_workspace(int32_t prefix_len, int32_t n_tree, int32_t heads,
                                int32_t kv_heads, int32_t head_dim, int32_t dtype);

@@ -27,7 +27,7 @@ SEQ_MAX_PLANS = 1024
 SEQ_MAX_STREAMS = 16
 TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
-EXPORTS = ("seq_tree_attn", "seq_verify", "seq_verify_with", "seq_verify_batched", "seq_draft_sample", "seq_kv_append", "seq_top_p_filter", "seq_tree_attn_workspace",
+EXPORTS = ("seq_tree_attn", "seq_tree_attn_noalloc", "seq_verify", "seq_verify_with", "seq_verify_batched", "seq_draft_sample", "seq_kv_append", "seq_top_p_filter", "seq_tree_attn_workspace",
            "seq_verify_workspace", "seq_draft_sample_workspace", "seq_tree_plan_host",
            "seq_build_tree", "seq_tree_expected_tokens", "seq_pick_tree_shape",
            "seq_shutdown", "seq_strerror", "seq_version")
@@ -52,6 +52,8 @@ def lib() -> C.CDLL:
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         l.seq_tree_attn.restype = C.c_int
         l.seq_tree_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, i32, vp, sz, vp]
+        l.seq_tree_attn_noalloc.restype = C.c_int
+        l.seq_tree_attn_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, i32, vp]
         l.seq_verify.restype = C.c_int
         l.seq_verify.argtypes = [vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
         l.seq_verify_batched.restype = C.c_int
@@ -218,6 +220,24 @@ def seq_tree_attn(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len: int, 
                              workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     if rc != SEQ_OK:
         raise SeqTreeError(rc, "seq_tree_attn")
+    return out
+
+
+def seq_tree_attn_noalloc(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len: int, out, stream=None):
+    """seq_tree_attn through the entry point that allocates nothing: `out` [n,H,d] comes from the
+    caller, there is no workspace.  Returns out.  Asynchronous on the current stream."""
+    par = _parent_array(parent)
+    n, H, d = q.shape
+    Hk, cap = k_cache.shape[0], k_cache.shape[1]
+    code = _dtype_code(q)
+    for t in (q, k_cache, v_cache, k_tree, v_tree, out):
+        if not t.is_contiguous() or not t.is_cuda or t.dtype != q.dtype:
+            raise SeqTreeError(SEQ_ERR_SHAPE, "seq_tree_attn_noalloc (tensors must be contiguous GPU tensors of one dtype)")
+    rc = lib().seq_tree_attn_noalloc(q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), k_tree.data_ptr(),
+                                     v_tree.data_ptr(), par.ctypes.data, int(prefix_len), n, H, Hk, d,
+                                     out.data_ptr(), cap, code, _stream_ptr(stream))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_tree_attn_noalloc")
     return out
 
 

@@ -60,4 +60,8 @@ int release_all();
 // Host-side plan construction (no GPU).  Vectors are sized by the callee.
 int validate_parent(const int32_t* parent, int32_t n);
 
+constexpr int kXcdProbeBlocks = 1024;
+bool probe_round_robin_xcds_into(int* device_ints);
+bool stream_is_capturing(hipStream_t stream);
+
 }  // namespace seqtree

@@ -23,28 +23,36 @@ __global__ void xcd_probe_kernel(int* out) {
     }
 }
 
-// True iff workgroup b runs on the XCD of workgroup b % 8 and those eight are distinct.
 bool probe_round_robin_xcds() {
-    constexpr int kBlocks = 1024;
     int* dev = nullptr;
-    if (hipMalloc(&dev, sizeof(int) * kBlocks) != hipSuccess) return false;
-    std::vector<int> host(kBlocks, -1);
-    bool ok = hipMemset(dev, 0xFF, sizeof(int) * kBlocks) == hipSuccess;
-    if (ok) {
-        hipLaunchKernelGGL(xcd_probe_kernel, dim3(kBlocks), dim3(64), 0, 0, dev);
-        ok = hipGetLastError() == hipSuccess &&
-             hipMemcpy(host.data(), dev, sizeof(int) * kBlocks, hipMemcpyDeviceToHost) == hipSuccess;
-    }
+    if (hipMalloc(&dev, sizeof(int) * kXcdProbeBlocks) != hipSuccess) return false;
+    const bool answer = probe_round_robin_xcds_into(dev);
     (void)hipFree(dev);
-    if (!ok) return false;
+    return answer;
+}
+}  // namespace
+
+// True iff workgroup b runs on the XCD of workgroup b % 8 and those eight are distinct.  Runs a
+// small kernel on the null stream and reads its output back (synchronous); `device_ints` is
+// device memory for kXcdProbeBlocks ints that the caller lends.
+bool probe_round_robin_xcds_into(int* device_ints) {
+    std::vector<int> host(kXcdProbeBlocks, -1);
+    hipLaunchKernelGGL(xcd_probe_kernel, dim3(kXcdProbeBlocks), dim3(64), 0, 0, device_ints);
+    if (hipGetLastError() != hipSuccess ||
+        hipMemcpy(host.data(), device_ints, sizeof(int) * kXcdProbeBlocks, hipMemcpyDeviceToHost) != hipSuccess)
+        return false;
     for (int b = 0; b < 8; ++b)
         for (int c = 0; c < b; ++c)
             if (host[b] == host[c]) return false;
-    for (int b = 8; b < kBlocks; ++b)
+    for (int b = 8; b < kXcdProbeBlocks; ++b)
         if (host[b] != host[b % 8]) return false;
     return true;
 }
-}  // namespace
+
+bool stream_is_capturing(hipStream_t stream) {
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    return hipStreamIsCapturing(stream, &status) == hipSuccess && status != hipStreamCaptureStatusNone;
+}
 
 int validate_parent(const int32_t* parent, int32_t n) {
     if (n < 1 || n > SEQ_MAX_TREE) return SEQ_ERR_SHAPE;
@@ -97,10 +105,7 @@ const DeviceMemory kHipMemory = {
     [](void* dst, const void* src, size_t bytes) { return hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice) == hipSuccess; },
     [](void* dst, size_t bytes) { return hipMemset(dst, 0, bytes) == hipSuccess && hipDeviceSynchronize() == hipSuccess; },
     [](void* ptr) { (void)hipFree(ptr); },
-    [](hipStream_t stream) {
-        hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
-        return hipStreamIsCapturing(stream, &status) == hipSuccess && status != hipStreamCaptureStatusNone;
-    },
+    [](hipStream_t stream) { return stream_is_capturing(stream); },
     true,
 };
 const DeviceMemory kHostMemory = {

@@ -230,6 +230,26 @@ def test_division_by_multiplication_is_exact():
         assert np.array_equal(got, n[:: 7] // d)
 
 
+def test_noalloc_attn_argument_errors_and_size_limit_need_no_gpu():
+    good = np.asarray([-1, 0, 0, 1], np.int32)
+    def call(parent=good, prefix_len=4, n=None, heads=2, kv_heads=2, head_dim=64, cap=8, dtype=B.SEQ_BF16, q=0x1000, out=0x1000):
+        par = np.asarray(parent, np.int32)
+        return S.lib().seq_tree_attn_noalloc(q, 0x1000, 0x1000, 0x1000, 0x1000, par.ctypes.data, prefix_len,
+                                             len(par) if n is None else n, heads, kv_heads, head_dim, out, cap, dtype, None)
+    assert call(q=None) == B.SEQ_ERR_NULL
+    assert call(out=None) == B.SEQ_ERR_NULL
+    assert call(head_dim=96) == B.SEQ_ERR_SHAPE
+    assert call(heads=3, kv_heads=2) == B.SEQ_ERR_SHAPE
+    assert call(prefix_len=9, cap=8) == B.SEQ_ERR_SHAPE
+    assert call(n=B.SEQ_MAX_TREE + 1) == B.SEQ_ERR_SHAPE
+    assert call(dtype=7) == B.SEQ_ERR_DTYPE
+    assert call(parent=[-1, 0, 2, 1]) == B.SEQ_ERR_TREE
+    # more partial results than the static array holds: refused before anything touches a GPU
+    par = W.geometric_tree(256, 12)
+    assert S.seq_tree_attn_workspace(131072, 256, 16, 8, 128, B.SEQ_BF16) > 32 << 20
+    assert call(parent=par, prefix_len=131072, cap=131072, heads=16, kv_heads=8, head_dim=128) == B.SEQ_ERR_WORKSPACE
+
+
 @pytest.fixture
 def host_memory():
     """The library's own allocations come from host memory for the duration of a test, so that
