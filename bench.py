@@ -30,10 +30,23 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
-# HBM bytes per launch of the attention kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
-# scaled by a copy kernel of known size (profiles/tree_verify_step_C2_hbm_traffic.md gives the commands and
-# the raw counters).  Counters cannot be read from inside this process, so the figure is carried here.
-MEASURED_ATTN_TRAFFIC_BYTES = {"C2": 23.9e6 + 5.9e6}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "tree_attn_mfma_hbm_traffic_per_config.md")
+
+
+def load_traffic_table():
+    """HBM bytes per launch of the attention kernel for each configuration, as measured with rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE and scaled by a copy kernel of known size.  Counters cannot be read from inside
+    this process: the committed summary (which gives the commands and the raw counters) is the source, its
+    table rows read `| C5 | ... | <total bytes> |`.  A configuration without a row reports null."""
+    table = {}
+    try:
+        for row in open(TRAFFIC_TABLE):
+            cells = [c.strip() for c in row.strip().strip("|").split("|")]
+            if len(cells) >= 3 and cells[0] in ("C1", "C2", "C3", "C4", "C5") and cells[-1].replace(" ", "").isdigit():
+                table[cells[0]] = int(cells[-1].replace(" ", ""))
+    except OSError:
+        pass
+    return table
 
 
 def attn_alg_bytes(cfg, n=None, P=None):
@@ -75,6 +88,258 @@ def graph_time_us(torch, fn, count, reps):
     stop.record()
     torch.cuda.synchronize()
     return start.elapsed_time(stop) * 1e3 / (reps * count)
+
+
+def capture(torch, fn, indices):
+    """fn(i) for i in indices as a HIP graph.  (The workload has made one eager call already: the tree's plan
+    and the stream's synchronisation area exist, so nothing is allocated while recording.)"""
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in indices:
+            fn(i)
+    return graph
+
+
+def percentiles(values):
+    v = sorted(values)
+    pick = lambda q: round(v[min(len(v) - 1, int(q * len(v)))], 3)
+    return {"p10": pick(0.10), "p50": pick(0.50), "p90": pick(0.90), "blocks": len(v)}
+
+
+def timed_replays(torch, graph, launches_per_replay, blocks):
+    """Replays a graph `blocks` times with a HIP event (on the launching stream) between every two replays.
+    Returns (average us per launch over all blocks, spread of the per-block averages)."""
+    for _ in range(2):
+        graph.replay()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(blocks + 1)]
+    torch.cuda.synchronize()
+    marks[0].record()
+    for b in range(blocks):
+        graph.replay()
+        marks[b + 1].record()
+    torch.cuda.synchronize()
+    per_block = [marks[b].elapsed_time(marks[b + 1]) * 1e3 / launches_per_replay for b in range(blocks)]
+    total = marks[0].elapsed_time(marks[blocks]) * 1e3 / (launches_per_replay * blocks)
+    return total, percentiles(per_block)
+
+
+class Workload:
+    """One configuration's synthetic inputs, resident in HBM: as many K/V/Q sets as the model has layers (so
+    that no call finds its inputs in a cache left by the one before) and as many logit sets as 2 GiB hold."""
+
+    def __init__(self, key, torch, dev, sets=0):
+        import paper_2402_12374_amd as S
+        import workloads as W
+        self.S, self.W, self.torch, self.key = S, W, torch, key
+        cfg = self.cfg = W.CONFIGS[key]
+        idx = list(W.CONFIGS).index(key) + 1
+        self.tdt = tdt = torch.bfloat16 if cfg.dtype == W.BF16 else torch.float32
+        self.code = 1 if tdt == torch.bfloat16 else 2
+        self.T = T = cfg.temperatures[0]
+        self.sets = sets = sets or cfg.layers
+        self.parent = parent = W.make_tree(cfg, W.seed_for(idx))
+        self.n, self.V = n, V = cfg.n_tree, cfg.vocab
+        H, Hk, d, P = cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.prefix_len
+        g = torch.Generator(device=dev)
+        g.manual_seed(W.seed_for(idx))
+
+        def randn(*shape, scale=1.0):
+            return (torch.randn(*shape, generator=g, device=dev, dtype=torch.float32) * scale).to(tdt).contiguous()
+
+        self.attn_sets = [dict(q=randn(n, H, d), kc=randn(Hk, P, d), vc=randn(Hk, P, d), kt=randn(n, Hk, d), vt=randn(n, Hk, d),
+                               out=torch.empty(n, H, d, device=dev, dtype=tdt)) for _ in range(sets)]
+        e = 2 if tdt == torch.bfloat16 else 4
+        self.n_vsets = max(1, min(sets, 32, (2 << 30) // (2 * n * V * e)))
+        self.host0 = W.verify_inputs_for(key)  # set 0 comes from the seeded host generator
+        children = [(node, ch) for node, ch in enumerate(W.children_lists(parent)) if ch]
+        self.verify_sets = []
+        for s in range(self.n_vsets):
+            if s == 0:
+                tl = torch.from_numpy(self.host0.target_logits).to(dev).to(tdt)
+                dl = torch.from_numpy(self.host0.draft_logits).to(dev).to(tdt)
+                tok = torch.from_numpy(self.host0.tree_tokens).to(dev)
+                un = torch.from_numpy(self.host0.uniforms).to(dev)
+            else:
+                tl = randn(n, V, scale=cfg.sigma_target)
+                dl = (tl.float() + torch.randn(n, V, generator=g, device=dev) * cfg.sigma_draft).to(tdt)
+                # ordered children without replacement: Gumbel-top-k on the tempered draft logits
+                tok = torch.zeros(n, dtype=torch.int32, device=dev)
+                for node, ch in children:
+                    u = torch.rand(V, generator=g, device=dev).clamp_(1e-20, 1.0)
+                    gumbel_key = dl[node].float() / max(T, 1e-6) - torch.log(-torch.log(u))
+                    tok[torch.tensor(ch, device=dev)] = torch.topk(gumbel_key, len(ch)).indices.to(torch.int32)
+                un = torch.rand(n, generator=g, device=dev, dtype=torch.float32).clamp_(0.0, 1.0 - 2.0 ** -24)
+            self.verify_sets.append(dict(tl=tl.contiguous(), dl=dl.contiguous(), tok=tok, un=un,
+                                         path=torch.empty(n, dtype=torch.int32, device=dev),
+                                         bonus=torch.empty(1, dtype=torch.int32, device=dev),
+                                         ws=torch.empty(S.seq_verify_workspace(n, V, self.code), dtype=torch.uint8, device=dev)))
+        self.attn_ws = torch.empty(S.seq_tree_attn_workspace(P, n, H, Hk, d, self.code), dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        self.step(0)   # builds the tree plan and the stream's synchronisation area (the library's only allocations)
+        torch.cuda.synchronize()
+
+    def attn_call(self, i):
+        a = self.attn_sets[i % self.sets]
+        self.S.seq_tree_attn(a["q"], a["kc"], a["vc"], a["kt"], a["vt"], self.parent, self.cfg.prefix_len, out=a["out"],
+                             workspace=self.attn_ws)
+
+    def verify_call(self, i, temperature=None):
+        v = self.verify_sets[i % self.n_vsets]
+        self.S.seq_verify(v["tl"], v["dl"], v["tok"], self.parent, self.T if temperature is None else temperature, v["un"],
+                          accepted_path=v["path"], bonus_token=v["bonus"], workspace=v["ws"])
+
+    def step(self, i):
+        self.attn_call(i)
+        self.verify_call(i)
+
+    def describe(self):
+        c, W = self.cfg, self.W
+        return (f"{c.name}: H{c.heads}/Hk{c.kv_heads}/d{c.head_dim} {c.dtype}, prefix {c.prefix_len}, tree {self.n} "
+                f"(geometric, depth {int(W.depths(self.parent).max())}), vocab {self.V}, T={self.T}")
+
+    def release(self):
+        self.attn_sets = self.verify_sets = self.attn_ws = None
+        self.torch.cuda.empty_cache()
+
+    def check_results(self):
+        """The last verification of set 0 (the seeded, host-generated one) ended normally."""
+        trace = self.S.read_verify_trace(self.verify_sets[0]["ws"])
+        assert trace["status"] == 0
+        self.path0 = [int(x) for x in self.verify_sets[0]["path"].cpu().numpy() if x >= 0]
+
+    def measure_kernels(self, blocks, traffic):
+        """Each kernel alone on the stream: one graph holding one launch per input set, replayed `blocks` times
+        with an event between replays.  Returns the step time and a roofline object per kernel."""
+        torch, cfg, W, n, V = self.torch, self.cfg, self.W, self.n, self.V
+        idx = range(self.sets)
+        attn_us, attn_spread = timed_replays(torch, capture(torch, self.attn_call, idx), self.sets, blocks)
+        verify_us, verify_spread = timed_replays(torch, capture(torch, self.verify_call, idx), self.sets, blocks)
+        step_us, step_spread = timed_replays(torch, capture(torch, self.step, idx), self.sets, blocks)
+        self.check_results()
+
+        bytes_alg, flops_alg = attn_alg_bytes(cfg), attn_alg_flops(cfg, self.parent)
+        gbs = bytes_alg / (attn_us * 1e-6) / 1e9
+        tflops = flops_alg / (attn_us * 1e-6) / 1e12
+        hbm_bound = bytes_alg / (HBM_PEAK_GBS * 1e9) >= flops_alg / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+        sched_kernel = "tree_attn_mfma_kernel" if self.code == 1 else "tree_attn_rowwise_f32"
+        common = {"kernel": sched_kernel, "traffic": traffic.get(self.key), "alg_bytes_per_launch": bytes_alg,
+                  "alg_flops_per_launch": flops_alg, "avg_launch_us": round(attn_us, 3), "launch_us_spread": attn_spread,
+                  "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "mfma_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
+        if hbm_bound:
+            attn = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(gbs / HBM_PEAK_GBS, 4), **common}
+        else:
+            attn = {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), **common}
+
+        # The verification walk: two figures, never merged.  (1) The logit bytes the kernel that ran really reads
+        # against the HBM peak; (2) the bytes of the method's minimum -- only the rows of the nodes the walk visits.
+        e = 2 if self.tdt == torch.bfloat16 else 4
+        lazy_bytes = (len(self.path0) + 1) * 2 * V * e
+        per_node = self.T > 0 and V <= 32768 and n <= 256   # the library's own choice of kernel (include/seqtree.h)
+        kids = W.children_lists(self.parent)
+        leaves = sum(1 for ch in kids if not ch)
+        moved = ((n - leaves) * 2 + leaves) * V * e if per_node else lazy_bytes
+        moved_gbs = moved / (verify_us * 1e-6) / 1e9
+        verify = {"kernel": "verify_chains_kernel" if per_node else "verify_walk_kernel",
+                  "bound": "hbm", "achieved": round(moved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                  "frac": round(moved_gbs / HBM_PEAK_GBS, 5), "traffic": None,
+                  "logit_bytes_read_per_launch": moved, "avg_launch_us": round(verify_us, 3), "launch_us_spread": verify_spread,
+                  "alg_bytes_lazy_set0": lazy_bytes, "accepted_path_len_set0": len(self.path0),
+                  "frac_lazy_set0": round(lazy_bytes / (verify_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 5)}
+        if per_node:
+            # bound by the vector unit of the ONE compute unit that holds the node with the longest sibling chain:
+            # per vocabulary entry 2 x 8 instruction slots for the two softmaxes and 2 per rejection, on 64 lanes per
+            # clock (4 SIMDs x 16 lanes) at 2.4 GHz -- a modelled figure, given beside the measured ones
+            k_max = max(len(ch) for ch in kids)
+            chain_us = V * (16 + 2 * k_max) / 64.0 / 2.4e9 * 1e6
+            verify["note"] = ("one workgroup per node reads every row the tree can visit; limited by one compute unit's vector "
+                              "rate over its node's sibling chain (modelled %.1f us for %d children), not by HBM" % (chain_us, k_max))
+        else:
+            verify["note"] = "reads only the rows of visited nodes: a chain of dependent steps, latency-bound by construction"
+        report = {"step_us": round(step_us, 3), "step_us_spread": step_spread, "attn": attn, "verify": verify}
+        if len(cfg.temperatures) > 1 and 0.0 in cfg.temperatures:
+            greedy = lambda i: self.verify_call(i, temperature=0.0)
+            greedy(0)
+            report["verify_greedy_us"] = round(timed_replays(torch, capture(torch, greedy, idx), self.sets, blocks)[0], 3)
+        return report
+
+
+def yardstick_copy(torch, S, dev, mib):
+    """Four launches of a plain copy kernel of known size: the reference HBM traffic counters are scaled by."""
+    nbytes = mib << 20
+    src = torch.full((nbytes,), 1, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(4):
+        rc = S.lib().seqtree_internal_copy_probe(src.data_ptr(), dst.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
+    torch.cuda.synchronize()
+    assert bool((dst == 1).all())
+    return nbytes
+
+
+def cpu_baseline(w, seconds):
+    """The CPU checker as it stands on a bounded sample of the same workload: attention rows one by one (one
+    thread, then one thread per host core -- the routine is reentrant and the foreign call releases the
+    interpreter lock), and whole verification walks.  Scaled to one step; a baseline, not a target."""
+    import ctypes as C
+    from concurrent.futures import ThreadPoolExecutor
+
+    import numpy as np
+
+    import oracle
+    W, cfg = w.W, w.cfg
+    a0 = W.attn_inputs_for(w.key)
+    n, H, d = a0.q.shape
+    Hk, cap, _ = a0.k_cache.shape
+    rows_per_step = n * H
+    arrays = [np.ascontiguousarray(x, dtype=np.float32) for x in (a0.q, a0.k_cache, a0.v_cache, a0.k_tree, a0.v_tree)]
+    parent = np.ascontiguousarray(a0.parent, dtype=np.int32)
+    ptrs = [x.ctypes.data_as(C.c_void_p) for x in arrays] + [parent.ctypes.data_as(C.c_void_p)]
+    sizes = [C.c_int32(x) for x in (a0.prefix_len, cap, n, H, Hk, d)]
+    row_fn = oracle.lib().oracle_tree_attn_row
+
+    def run_rows(rows):
+        out = np.zeros(d, dtype=np.float64)
+        for i, h in rows:
+            assert row_fn(*ptrs, *sizes, C.c_int32(i), C.c_int32(h), C.c_void_p(out.ctypes.data), None, None) == 0
+
+    rng = np.random.default_rng(0)
+    t0 = time.perf_counter()
+    run_rows([(0, 0)])
+    row_s = max(time.perf_counter() - t0, 1e-6)
+    cores = os.cpu_count() or 1
+
+    def sample(count):
+        if count >= rows_per_step:
+            return [(r // H, r % H) for r in range(rows_per_step)]
+        return [(int(rng.integers(n)), int(rng.integers(H))) for _ in range(count)]
+
+    one = sample(int(max(8, seconds * 0.3 / row_s)))
+    t0 = time.perf_counter()
+    run_rows(one)
+    attn_one_s = (time.perf_counter() - t0) * rows_per_step / len(one)
+    many = sample(int(max(8 * cores, seconds * 0.5 * cores / row_s)))
+    shares = [many[k::cores] for k in range(cores)]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        list(pool.map(run_rows, shares))
+    attn_all_s = (time.perf_counter() - t0) * rows_per_step / len(many)
+    h0 = w.host0
+    t0, reps = time.perf_counter(), 0
+    while reps < 3 or (time.perf_counter() - t0 < seconds * 0.2 and reps < 50):
+        oracle.verify(h0.target_logits, h0.draft_logits, h0.tree_tokens, h0.parent, w.T, h0.uniforms)
+        reps += 1
+    verify_s = (time.perf_counter() - t0) / reps
+    return {"value": round((attn_all_s + verify_s) * 1e6, 1), "unit": "us/step", "cores": cores, "kind": "oracle",
+            "sample": f"{len(many)} of {rows_per_step} attention rows of {cfg.name} on {cores} threads (the checker's row routine, "
+                      f"one row per call; scaled to all rows) + {reps} whole verification walks on one thread; fp64",
+            "attn_us": round(attn_all_s * 1e6, 1), "verify_us": round(verify_s * 1e6, 1),
+            "single_thread": {"value": round((attn_one_s + verify_s) * 1e6, 1), "unit": "us/step", "cores": 1,
+                              "sample": f"{len(one)} of {rows_per_step} attention rows (scaled) + the same walks",
+                              "attn_us": round(attn_one_s * 1e6, 1)}}
 
 
 def run_sweep(args) -> int:
@@ -341,13 +606,20 @@ def run_rejection_curve(args) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=4000)
-    ap.add_argument("--warmup", type=int, default=400)
-    ap.add_argument("--config", default="C2", help="workload (C2 is the one the metric is quoted on)")
+    ap.add_argument("--steps", type=int, default=2000, help="steps timed (exactly this many)")
+    ap.add_argument("--warmup", type=int, default=200, help="untimed steps before them")
+    ap.add_argument("--config", default="C5",
+                    help="workload of the headline figure (C5, the largest configuration that one GPU holds, unless told otherwise)")
+    ap.add_argument("--also", default="C2,C3,C4",
+                    help="configurations reported beside the headline, each with its own rooflines (empty: none)")
+    ap.add_argument("--blocks", type=int, default=20,
+                    help="replays (at least 20) of the per-kernel graphs that the kernel durations and their spread come from")
     ap.add_argument("--sets", type=int, default=0, help="distinct input sets to rotate over (0 = layer count)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of a HIP graph")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--eager", action="store_true",
+                    help="for profilers: launch --warmup + --steps steps of --config from Python, no HIP graph, print a short "
+                         "line and stop (per-dispatch counters and kernel traces then see one dispatch per call)")
+    ap.add_argument("--cpu-seconds", type=float, default=16.0)
     ap.add_argument("--yardstick-mib", type=int, default=0,
                     help="after the timed region, also launch a plain copy kernel of this many MiB four times "
                          "(the known-size reference for HBM traffic counters collected with rocprofv3 --pmc)")
@@ -390,243 +662,94 @@ def main() -> int:
     if args.verify_batch:
         return run_verify_batch(args)
 
-    import numpy as np
     import torch
 
     import paper_2402_12374_amd as S
-    import workloads as W
 
-    cfg = W.CONFIGS[args.config]
-    cfg_index = list(W.CONFIGS).index(args.config) + 1
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    tdt = torch.bfloat16 if cfg.dtype == W.BF16 else torch.float32
-    T = cfg.temperatures[0]
-    sets = args.sets or cfg.layers
-    parent = W.make_tree(cfg, W.seed_for(cfg_index))
-    n, H, Hk, d, P, V = cfg.n_tree, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.prefix_len, cfg.vocab
+    traffic = load_traffic_table()
+    blocks = max(20, args.blocks)
 
-    # ---- inputs, resident in HBM ---------------------------------------------------------
-    g = torch.Generator(device=dev)
-    g.manual_seed(W.seed_for(cfg_index))
-
-    def randn(*shape, scale=1.0):
-        return (torch.randn(*shape, generator=g, device=dev, dtype=torch.float32) * scale).to(tdt).contiguous()
-
-    attn_sets, verify_sets = [], []
-    host0 = W.verify_inputs_for(args.config)  # set 0 comes from the seeded host generator
-    for s in range(sets):
-        attn_sets.append(dict(q=randn(n, H, d), kc=randn(Hk, P, d), vc=randn(Hk, P, d),
-                              kt=randn(n, Hk, d), vt=randn(n, Hk, d), out=torch.empty(n, H, d, device=dev, dtype=tdt)))
-    per_set_bytes = 2 * n * V * (2 if tdt == torch.bfloat16 else 4)
-    n_vsets = max(1, min(sets, 32, (2 << 30) // per_set_bytes))
-    for s in range(n_vsets):
-        if s == 0:
-            tl = torch.from_numpy(host0.target_logits).to(dev).to(tdt)
-            dl = torch.from_numpy(host0.draft_logits).to(dev).to(tdt)
-            tok = torch.from_numpy(host0.tree_tokens).to(dev)
-            un = torch.from_numpy(host0.uniforms).to(dev)
-        else:
-            tl = randn(n, V, scale=cfg.sigma_target)
-            dl = (tl.float() + torch.randn(n, V, generator=g, device=dev) * cfg.sigma_draft).to(tdt)
-            # ordered children without replacement: Gumbel-top-k on the tempered draft logits
-            tok = torch.zeros(n, dtype=torch.int32, device=dev)
-            for node, ch in enumerate(W.children_lists(parent)):
-                if ch:
-                    u = torch.rand(V, generator=g, device=dev).clamp_(1e-20, 1.0)
-                    key = dl[node].float() / max(T, 1e-6) - torch.log(-torch.log(u))
-                    tok[torch.tensor(ch, device=dev)] = torch.topk(key, len(ch)).indices.to(torch.int32)
-            un = torch.rand(n, generator=g, device=dev, dtype=torch.float32).clamp_(0.0, 1.0 - 2.0 ** -24)
-        verify_sets.append(dict(tl=tl.contiguous(), dl=dl.contiguous(), tok=tok, un=un,
-                                path=torch.empty(n, dtype=torch.int32, device=dev),
-                                bonus=torch.empty(1, dtype=torch.int32, device=dev),
-                                ws=torch.empty(S.seq_verify_workspace(n, V, 1), dtype=torch.uint8, device=dev)))
-    code = 1 if tdt == torch.bfloat16 else 2
-    attn_ws = torch.empty(S.seq_tree_attn_workspace(P, n, H, Hk, d, code), dtype=torch.uint8, device=dev)
-    torch.cuda.synchronize()
-
-    def attn_call(i):
-        a = attn_sets[i % sets]
-        S.seq_tree_attn(a["q"], a["kc"], a["vc"], a["kt"], a["vt"], parent, P, out=a["out"], workspace=attn_ws)
-
-    def verify_call(i):
-        v = verify_sets[i % n_vsets]
-        S.seq_verify(v["tl"], v["dl"], v["tok"], parent, T, v["un"], accepted_path=v["path"],
-                     bonus_token=v["bonus"], workspace=v["ws"])
-
-    def step(i):
-        attn_call(i)
-        verify_call(i)
-
-    # one eager pass builds the tree plan and the library's sync area (the only allocations)
-    step(0)
-    torch.cuda.synchronize()
-
-    # ---- the step, captured once as a HIP graph of `sets` consecutive steps --------------
-    use_graph = not args.no_graph
-
-    def capture(fn, count):
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            for i in range(count):
-                fn(i)
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for i in range(count):
-                fn(i)
-        return graph
-
-    def timed(run_block, blocks):
-        """HIP events on the launching stream around `blocks` executions of run_block."""
-        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # ---- the headline workload: exactly --steps steps after --warmup steps ------------------
+    head = Workload(args.config, torch, dev, sets=args.sets)
+    if args.eager:
+        for i in range(args.warmup):
+            head.step(i)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        start.record()
-        for b in range(blocks):
-            run_block(b)
-        stop.record()
+        for i in range(args.steps):
+            head.step(args.warmup + i)
         torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        return start.elapsed_time(stop) * 1e-3, wall
-
-    if use_graph:
-        g_step = capture(step, sets)
-        g_attn = capture(attn_call, sets)
-        g_verify = capture(verify_call, sets)
-        per_block = sets
-        run_step = lambda b: g_step.replay()
-        run_attn = lambda b: g_attn.replay()
-        run_verify = lambda b: g_verify.replay()
-    else:
-        per_block = 1
-        run_step, run_attn, run_verify = step, attn_call, verify_call
-
-    warm_blocks = max(1, -(-args.warmup // per_block))
-    blocks = max(1, -(-args.steps // per_block))
-    steps = blocks * per_block
-    for b in range(warm_blocks):
-        run_step(b)
+        line = {"eager": True, "workload": head.describe(), "steps": args.steps,
+                "us_per_step_from_python": round((time.perf_counter() - t0) / args.steps * 1e6, 2)}
+        head.check_results()
+        if args.yardstick_mib > 0:
+            line["yardstick_copy_bytes"] = yardstick_copy(torch, S, dev, args.yardstick_mib)
+        print(json.dumps(line))
+        S.shutdown()
+        return 0
+    step_graphs = [capture(torch, head.step, [i]) for i in range(head.sets)]   # one graph per step and input set
+    for i in range(args.warmup):
+        step_graphs[i % head.sets].replay()
     torch.cuda.synchronize()
-    ev_s, wall_s = timed(run_step, blocks)
-    step_us = wall_s / steps * 1e6
-    # per-kernel durations over the same number of launches, each kernel alone on the stream
-    attn_ev_s, _ = timed(run_attn, blocks)
-    verify_ev_s, _ = timed(run_verify, blocks)
-    attn_us = attn_ev_s / steps * 1e6
-    verify_us = verify_ev_s / steps * 1e6
-    # spread of the step latency: a few blocks timed one by one (outside the timed region above)
-    per_block_us = sorted(timed(run_step, 1)[0] / per_block * 1e6 for _ in range(min(20, blocks)))
-    pct = lambda q: round(per_block_us[min(len(per_block_us) - 1, int(q * len(per_block_us)))], 3)
-    spread = {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90), "blocks": len(per_block_us),
-              "steps_per_block": per_block}
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for i in range(args.steps):
+        step_graphs[(args.warmup + i) % head.sets].replay()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t0
+    step_us = wall_s / args.steps * 1e6
+    event_step_us = start.elapsed_time(stop) * 1e3 / args.steps
+    # spread of the step latency: at least 20 consecutive steps, an event between every two
+    n_spread = max(20, min(args.steps, 400))
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_spread + 1)]
+    marks[0].record()
+    for i in range(n_spread):
+        step_graphs[i % head.sets].replay()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    spread = percentiles([marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(n_spread)])
+    spread["timed_one_by_one"] = n_spread
+    del step_graphs
+    head_report = head.measure_kernels(blocks, traffic)
+    head.check_results()
 
-    # ---- results still right?  (set 0 is the seeded host-generated one) -------------------
-    v0 = verify_sets[0]
-    path0 = [int(x) for x in v0["path"].cpu().numpy() if x >= 0]
-    trace0 = S.read_verify_trace(v0["ws"])
-    assert trace0["status"] == 0
-
-    bytes_alg = attn_alg_bytes(cfg)
-    flops_alg = attn_alg_flops(cfg, parent)
-    gbs = bytes_alg / (attn_us * 1e-6) / 1e9
-    tflops = flops_alg / (attn_us * 1e-6) / 1e12
-    hbm_bound = bytes_alg / (HBM_PEAK_GBS * 1e9) >= flops_alg / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-    if hbm_bound:
-        roofline = {"kernel": "tree_attn_mfma_kernel" if code == 1 else "tree_attn_rowwise_f32",
-                    "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(args.config),
-                    "alg_bytes_per_launch": bytes_alg, "avg_launch_us": round(attn_us, 3)}
-    else:
-        roofline = {"kernel": "tree_attn_mfma_kernel", "bound": "mfma", "achieved": round(tflops, 1),
-                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(args.config),
-                    "alg_flops_per_launch": flops_alg, "avg_launch_us": round(attn_us, 3)}
-    e = 2 if tdt == torch.bfloat16 else 4
-    verify_bytes = (len(path0) + 1) * 2 * V * e
-    per_node = T > 0 and V <= 32768 and n <= 256   # the library's own choice of kernel (see include/seqtree.h)
-    leaves = int(sum(1 for ch in W.children_lists(parent) if not ch))
-    moved = ((n - leaves) * 2 + leaves) * V * e if per_node else verify_bytes
-    # The per-node kernel is bound by the vector unit of the ONE compute unit that holds the node with
-    # the longest sibling chain: per vocabulary entry 2 x 8 instruction slots for the two softmaxes
-    # (conversion, maximum, fma, exponential at half rate, sum, scaling) and 2 per rejection (clamped fma,
-    # add), on 64 lanes per clock (4 SIMDs x 16 lanes) at 2.4 GHz.
-    k_max = max(len(ch) for ch in W.children_lists(parent))
-    chain_slots = V * (16 + 2 * k_max)
-    chain_us = chain_slots / 64.0 / 2.4e9 * 1e6
-    verify_info = {"kernel": "verify_chains_kernel" if per_node else "verify_walk_kernel",
-                   "avg_launch_us": round(verify_us, 3),
-                   "bound": "alu (one compute unit, longest sibling chain)" if per_node else "latency",
-                   "critical_chain_children": k_max if per_node else None,
-                   "critical_cu_alu_us": round(chain_us, 3) if per_node else None,
-                   "critical_cu_alu_frac": round(chain_us / verify_us, 4) if per_node else None,
-                   "accepted_path_len_set0": len(path0), "alg_bytes_lazy_set0": verify_bytes,
-                   "hbm_frac_lazy_set0": round(verify_bytes / (verify_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 5),
-                   "logit_bytes_read": moved,
-                   "hbm_frac_read": round(moved / (verify_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 5),
-                   "note": ("one workgroup per node reads every row the tree can visit; bound by one compute "
-                            "unit's ALU rate over its node's sibling chain, not by HBM") if per_node else
-                           "latency-bound: reads only the rows of visited nodes"}
-
-    # ---- CPU baseline: the checker as it stands, one thread, same workload ----------------
     cpu = None
     if not args.no_cpu_baseline:
-        import oracle
-        a0 = W.attn_inputs_for(args.config)
-        done, t0 = 0, time.perf_counter()
-        rows_per_step = n * H
-        # whole steps if they are short; otherwise a bounded sample of attention rows
-        t_probe = time.perf_counter()
-        oracle.tree_attn_row(a0.q, a0.k_cache, a0.v_cache, a0.k_tree, a0.v_tree, a0.parent, P, 0, 0)
-        row_s = time.perf_counter() - t_probe
-        sample_rows = int(min(rows_per_step, max(8, args.cpu_seconds * 0.8 / max(row_s, 1e-6))))
-        rng = np.random.default_rng(0)
-        t_a = time.perf_counter()
-        for r in range(sample_rows):
-            i, h = (r // H, r % H) if sample_rows == rows_per_step else (int(rng.integers(n)), int(rng.integers(H)))
-            oracle.tree_attn_row(a0.q, a0.k_cache, a0.v_cache, a0.k_tree, a0.v_tree, a0.parent, P, i, h)
-        attn_cpu_s = (time.perf_counter() - t_a) * rows_per_step / sample_rows
-        t_v = time.perf_counter()
-        reps = 0
-        while reps < 3 or (time.perf_counter() - t_v < args.cpu_seconds * 0.2 and reps < 50):
-            oracle.verify(host0.target_logits, host0.draft_logits, host0.tree_tokens, host0.parent, T, host0.uniforms)
-            reps += 1
-        verify_cpu_s = (time.perf_counter() - t_v) / reps
-        cpu = {"value": round((attn_cpu_s + verify_cpu_s) * 1e6, 1), "unit": "us/step", "cores": 1,
-               "kind": "oracle",
-               "sample": f"{sample_rows} of {rows_per_step} attention rows of {cfg.name} (scaled to all rows) + "
-                         f"{reps} full verification walks; fp64, single thread; host has {os.cpu_count()} cpus",
-               "attn_us": round(attn_cpu_s * 1e6, 1), "verify_us": round(verify_cpu_s * 1e6, 1)}
+        cpu = cpu_baseline(head, args.cpu_seconds)
+    head.release()
+
+    # ---- the other configurations of the paper's models, each with its own rooflines --------
+    others = {}
+    for key in [k for k in args.also.split(",") if k and k != args.config]:
+        w = Workload(key, torch, dev)
+        rep = w.measure_kernels(blocks, traffic)
+        w.check_results()
+        others[key] = {"workload": w.describe(), "step_us": rep["step_us"], "tree_tokens_per_s": round(w.n / (rep["step_us"] * 1e-6), 1),
+                       "attn": rep["attn"], "verify": rep["verify"]}
+        if "verify_greedy_us" in rep:
+            others[key]["verify_greedy_us"] = rep["verify_greedy_us"]
+        w.release()
 
     line = {
         "metric": "tree-verify step latency", "value": round(step_us, 3), "unit": "us",
-        "n_gpus": 1, "steps": steps, "warmup": warm_blocks * per_block, "ms_per_step": round(step_us * 1e-3, 6),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(step_us * 1e-3, 6),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if code == 1 else "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: H{H}/Hk{Hk}/d{d} {cfg.dtype}, prefix {P}, tree {n} "
-                               f"(geometric, depth {int(W.depths(parent).max())}), vocab {V}, T={T}",
-                   "step": "1 x seq_tree_attn (one layer) + 1 x seq_verify", "input_sets": sets,
-                   "launch": "HIP graph of %d steps" % sets if use_graph else "eager from Python"},
-        "tree_tokens_per_s": round(n / (step_us * 1e-6), 1),
-        "attn_us_per_layer": round(attn_us, 3), "verify_us": round(verify_us, 3),
-        "gpu_event_us_per_step": round(ev_s / steps * 1e6, 3),
+        "dtype": "bf16" if head.code == 1 else "f32", "data": "synthetic",
+        "config": {"workload": head.describe(), "step": "1 x seq_tree_attn (one layer) + 1 x seq_verify",
+                   "input_sets": head.sets, "launch": "one HIP graph per step, rotating over the input sets"},
+        "tree_tokens_per_s": round(head.n / (step_us * 1e-6), 1),
+        "attn_us_per_layer": head_report["attn"]["avg_launch_us"], "verify_us": head_report["verify"]["avg_launch_us"],
+        "gpu_event_us_per_step": round(event_step_us, 3), "step_us_in_one_graph": head_report["step_us"],
         "step_us_spread": spread,
-        "roofline": roofline, "verify": verify_info, "cpu_baseline": cpu,
+        "roofline": head_report["attn"], "verify": head_report["verify"],
+        "configs": others, "cpu_baseline": cpu,
     }
     if args.yardstick_mib > 0:
-        nbytes = args.yardstick_mib << 20
-        src = torch.full((nbytes,), 1, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        for _ in range(4):
-            rc = S.lib().seqtree_internal_copy_probe(src.data_ptr(), dst.data_ptr(), nbytes,
-                                                     torch.cuda.current_stream().cuda_stream)
-            assert rc == 0
-        torch.cuda.synchronize()
-        assert bool((dst == 1).all())
-        line["yardstick_copy_bytes"] = nbytes
+        line["yardstick_copy_bytes"] = yardstick_copy(torch, S, dev, args.yardstick_mib)
     print(json.dumps(line))
     S.shutdown()
     return 0
