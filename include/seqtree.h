@@ -299,6 +299,34 @@ int seq_top_p_filter(const void* logits, void* filtered, float top_p, float temp
                      int32_t n_rows, int32_t vocab, int32_t dtype, int32_t* kept, void* hip_stream);
 
 /*
+ * seq_tree_attn for a batch of sequences that share the tree but not the prefix length (the
+ * paper's limitations section: serving means batches; sequences of a batch have histories of
+ * different lengths).  Sequence b attends to the first prefix_lens[b] cache rows of its own KV
+ * heads and to the tree; otherwise the definition above, per sequence.
+ *
+ *   q, out       [n_tree, batch, heads, head_dim]
+ *   k_tree, v_tree   [n_tree, batch, kv_heads, head_dim]
+ *   k_cache, v_cache [batch, kv_heads, prefix_cap, head_dim]
+ *   parent       HOST [n_tree], one tree for the whole batch
+ *   prefix_lens  DEVICE [batch] int32.  It is read by the kernel, not by the host, so a captured
+ *                call follows the lengths as the caller updates them between replays.
+ *   max_prefix_len   HOST: a bound on every prefix_lens[b], at most prefix_cap; the work is cut
+ *                for this length (a length beyond it is read as max_prefix_len, a negative one as 0)
+ *   heads, kv_heads  per sequence;  batch 1 .. SEQ_MAX_BATCH
+ *   workspace    at least seq_tree_attn_batched_workspace(...) bytes
+ * Errors as for seq_tree_attn.
+ */
+#define SEQ_MAX_BATCH 4096
+int seq_tree_attn_batched(const void* q, const void* k_cache, const void* v_cache,
+                          const void* k_tree, const void* v_tree, const int32_t* parent,
+                          const int32_t* prefix_lens, int32_t max_prefix_len, int32_t batch,
+                          int32_t n_tree, int32_t heads, int32_t kv_heads, int32_t head_dim,
+                          void* out, int32_t prefix_cap, int32_t dtype,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t seq_tree_attn_batched_workspace(int32_t max_prefix_len, int32_t batch, int32_t n_tree, int32_t heads,
+                                       int32_t kv_heads, int32_t head_dim, int32_t dtype);
+
+/*
  * seq_tree_attn for callers that cannot allocate device memory: code under stream capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments (no workspace), same kernels,
  * same results bit for bit.  The call allocates nothing, frees nothing, copies nothing between

@@ -25,9 +25,10 @@ SEQ_MAX_VOCAB = 524288
 SEQ_MAX_CHILDREN = 64
 SEQ_MAX_PLANS = 1024
 SEQ_MAX_STREAMS = 16
+SEQ_MAX_BATCH = 4096
 TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
-EXPORTS = ("seq_tree_attn", "seq_tree_attn_noalloc", "seq_verify", "seq_verify_with", "seq_verify_batched", "seq_draft_sample", "seq_kv_append", "seq_top_p_filter", "seq_tree_attn_workspace",
+EXPORTS = ("seq_tree_attn", "seq_tree_attn_noalloc", "seq_tree_attn_batched", "seq_tree_attn_batched_workspace", "seq_verify", "seq_verify_with", "seq_verify_batched", "seq_draft_sample", "seq_kv_append", "seq_top_p_filter", "seq_tree_attn_workspace",
            "seq_verify_workspace", "seq_draft_sample_workspace", "seq_tree_plan_host",
            "seq_build_tree", "seq_tree_expected_tokens", "seq_pick_tree_shape",
            "seq_shutdown", "seq_strerror", "seq_version")
@@ -54,6 +55,10 @@ def lib() -> C.CDLL:
         l.seq_tree_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, i32, vp, sz, vp]
         l.seq_tree_attn_noalloc.restype = C.c_int
         l.seq_tree_attn_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, i32, vp]
+        l.seq_tree_attn_batched.restype = C.c_int
+        l.seq_tree_attn_batched.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, i32, i32, vp, sz, vp]
+        l.seq_tree_attn_batched_workspace.restype = sz
+        l.seq_tree_attn_batched_workspace.argtypes = [i32] * 7
         l.seq_verify.restype = C.c_int
         l.seq_verify.argtypes = [vp, vp, vp, vp, C.c_float, vp, vp, vp, i32, i32, i32, vp, sz, vp]
         l.seq_verify_batched.restype = C.c_int
@@ -220,6 +225,34 @@ def seq_tree_attn(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_len: int, 
                              workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     if rc != SEQ_OK:
         raise SeqTreeError(rc, "seq_tree_attn")
+    return out
+
+
+def seq_tree_attn_batched(q, k_cache, v_cache, k_tree, v_tree, parent, prefix_lens, max_prefix_len: int, out=None,
+                          workspace=None, stream=None):
+    """q [n,B,H,d]; k_cache/v_cache [B,Hk,cap,d]; k_tree/v_tree [n,B,Hk,d]; prefix_lens int32 [B] (all torch, on the
+    GPU); parent: host int array.  Returns out [n,B,H,d].  Asynchronous on the current stream."""
+    import torch
+    par = _parent_array(parent)
+    n, B, H, d = q.shape
+    Hk, cap = k_cache.shape[1], k_cache.shape[2]
+    code = _dtype_code(q)
+    for t in (q, k_cache, v_cache, k_tree, v_tree):
+        if not t.is_contiguous() or not t.is_cuda or t.dtype != q.dtype:
+            raise SeqTreeError(SEQ_ERR_SHAPE, "seq_tree_attn_batched (tensors must be contiguous GPU tensors of one dtype)")
+    if prefix_lens.dtype != torch.int32 or prefix_lens.numel() != B or not prefix_lens.is_cuda or not prefix_lens.is_contiguous():
+        raise SeqTreeError(SEQ_ERR_SHAPE, "seq_tree_attn_batched (prefix_lens: int32 [batch] on the GPU)")
+    if out is None:
+        out = torch.empty_like(q)
+    need = int(lib().seq_tree_attn_batched_workspace(int(max_prefix_len), B, n, H, Hk, d, code))
+    if workspace is None or workspace.numel() * workspace.element_size() < need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = lib().seq_tree_attn_batched(q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), k_tree.data_ptr(),
+                                     v_tree.data_ptr(), par.ctypes.data, prefix_lens.data_ptr(), int(max_prefix_len), B, n, H, Hk, d,
+                                     out.data_ptr(), cap, code, workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != SEQ_OK:
+        raise SeqTreeError(rc, "seq_tree_attn_batched")
     return out
 
 

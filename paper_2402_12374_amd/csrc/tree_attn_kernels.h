@@ -8,7 +8,8 @@ namespace seqtree {
 int launch_tree_attn_rowwise_f32(const float* q, const float* k_cache, const float* v_cache,
                                  const float* k_tree, const float* v_tree, const TreePlan& plan,
                                  int P, int cap, int n, int H, int Hk, int D, float* out,
-                                 hipStream_t stream);
+                                 hipStream_t stream, const int32_t* prefix_lens = nullptr,
+                                 int seq_kv_heads = 0);
 
 // How the bf16 kernel cuts the work: query rows of one KV head (all G = H/Hk heads of the
 // group times n tree tokens) in units of 32 * wq rows (one per workgroup; its 8 wavefronts form
@@ -28,6 +29,9 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
                                const void* k_tree, const void* v_tree, const TreePlan& plan,
                                int P, int cap, int n, int H, int Hk, int D, void* out,
                                const AttnSchedule& sched, float* workspace, uint32_t* counters,
-                               bool units_share_l2, hipStream_t stream);
+                               bool units_share_l2, hipStream_t stream,
+                               // a batch whose sequences differ in prefix length: DEVICE [sequences], each
+                               // held to [0, P]; KV head g belongs to sequence g / seq_kv_heads
+                               const int32_t* prefix_lens = nullptr, int seq_kv_heads = 0);
 
 }  // namespace seqtree

@@ -65,9 +65,11 @@ struct MfmaParams {
     uint16_t* out;
     const uint32_t* anc;
     int words_per_row;
-    int P, cap, n, H, Hk, G;
+    int P_bound, cap, n, H, Hk, G;   // P_bound: the prefix length, or its upper bound if prefix_lens is given
     int query_blocks;     // units per KV head
-    int prefix_tiles;     // ceil(P / 32)
+    int prefix_tiles_bound;   // ceil(P_bound / 32)
+    const int32_t* prefix_lens;   // [sequences] or null: a prefix length per sequence of a batch
+    FastDiv by_seq_kv_heads;      // KV heads per sequence (KV head g belongs to sequence g / that)
     int splits;
     float* partials;
     uint32_t* counters;
@@ -343,6 +345,15 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     if (split >= S || unit >= total_units) return;
     const int g = (int)fast_div((uint32_t)unit, p.by_query_blocks);
     const int qb = unit - g * p.query_blocks;
+    // The prefix length: one for the whole launch, or -- a batch whose sequences differ in it --
+    // that of the sequence this KV head belongs to, read from device memory (so that a captured
+    // launch follows the lengths as they change) and held to the bound the host planned with.
+    int P = p.P_bound, prefix_tiles = p.prefix_tiles_bound;
+    if (p.prefix_lens) {
+        const int seq = (int)fast_div((uint32_t)g, p.by_seq_kv_heads);
+        P = __builtin_amdgcn_readfirstlane(min(max(p.prefix_lens[seq], 0), p.P_bound));
+        prefix_tiles = (P + kKeyTile - 1) / kKeyTile;
+    }
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and the compiler knows it
@@ -367,7 +378,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     const int last_row = min(rows - 1, qb * kUnitRows + kUnitRows - 1);
     const int i_max = (int)fast_div((uint32_t)last_row, p.by_G);   // tree rows beyond i_max are masked for all
     const int tree_tiles = i_max / kKeyTile + 1;
-    const int total_tiles = p.prefix_tiles + tree_tiles;
+    const int total_tiles = prefix_tiles + tree_tiles;
     // (at most 2^26 tiles times 16 ranges: below 2^31)
     const int t_begin = (int)fast_div((uint32_t)total_tiles * (uint32_t)split, p.by_splits);
     const int t_end = (int)fast_div((uint32_t)total_tiles * (uint32_t)(split + 1), p.by_splits);
@@ -405,7 +416,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     // the ring the slot is a literal and ends up in the instructions' offset fields.)
     auto issue_round = [&](int rho, int slot) __attribute__((always_inline)) {
         const int j0 = rho * WK;
-        const bool inside = (t_begin + j0 + WK) * kKeyTile <= p.P && t_begin + j0 + WK <= t_end;
+        const bool inside = (t_begin + j0 + WK) * kKeyTile <= P && t_begin + j0 + WK <= t_end;
 #pragma unroll
         for (int c = 0; c < kCopiesPerWave; ++c) {
             const int item = wave + c * kW;
@@ -417,9 +428,9 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
                 const uint16_t* base = (is_v ? p.v_cache : p.k_cache) + ((size_t)g * p.cap + (size_t)t * kKeyTile) * D;
                 async_copy16(cp_lane_off[c], base, dst);
             } else {
-                const bool is_prefix = t < p.prefix_tiles;
-                const int key0 = is_prefix ? t * kKeyTile : (t - p.prefix_tiles) * kKeyTile;
-                const int limit = is_prefix ? p.P : p.n;
+                const bool is_prefix = t < prefix_tiles;
+                const int key0 = is_prefix ? t * kKeyTile : (t - prefix_tiles) * kKeyTile;
+                const int limit = is_prefix ? P : p.n;
                 const uint16_t* base = is_prefix ? (is_v ? p.v_cache : p.k_cache) + (size_t)g * p.cap * D
                                                  : (is_v ? p.v_tree : p.k_tree) + (size_t)g * D;
                 const uint32_t row_bytes = is_prefix ? (uint32_t)kRowBytes : (uint32_t)(p.Hk * kRowBytes);
@@ -431,7 +442,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int t = max(min(t_begin + j0 + wk, t_end - 1), 0);
-            const int word = min(max(t - p.prefix_tiles, 0), p.words_per_row - 1);
+            const int word = min(max(t - prefix_tiles, 0), p.words_per_row - 1);
             const int cell = wk * WQ + wqw * R + r;
             async_copy4(mask_lane_off[r], p.anc + word, m_lds + (uint32_t)(((slot * WK + wk) * kCells + cell) * 256));
         }
@@ -535,13 +546,13 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         }
     };
     // Visibility of the keys of tile t (ring slot `slot`) for the queries of this lane.
-    auto tile_is_full = [&](int t) __attribute__((always_inline)) { return t < p.prefix_tiles && (t + 1) * kKeyTile <= p.P; };
+    auto tile_is_full = [&](int t) __attribute__((always_inline)) { return t < prefix_tiles && (t + 1) * kKeyTile <= P; };
     auto visibility = [&](int t, int slot, int r) __attribute__((always_inline)) -> uint32_t {   // selects only, no branches
-        const int left = p.P - t * kKeyTile;
+        const int left = P - t * kKeyTile;
         const uint32_t in_prefix = left >= 32 ? 0xFFFFFFFFu : (left <= 0 ? 0u : ((1u << left) - 1u));
-        const int word = t - p.prefix_tiles;
+        const int word = t - prefix_tiles;
         const uint32_t in_tree = maddr[r][slot * WK * kCells * 64];
-        return t < p.prefix_tiles ? in_prefix : ((qvalid[r] && word < p.words_per_row) ? in_tree : 0u);
+        return t < prefix_tiles ? in_prefix : ((qvalid[r] && word < p.words_per_row) ? in_tree : 0u);
     };
     // O^T += V^T P^T.  Matrix step m contracts keys (2m+a)*8 + half*4 + 0..3, a = 0,1 -- the
     // keys whose probabilities sit in accumulator elements 8m..8m+7.
@@ -922,7 +933,8 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
                                const void* k_tree, const void* v_tree, const TreePlan& plan,
                                int P, int cap, int n, int H, int Hk, int D, void* out,
                                const AttnSchedule& sched, float* workspace, uint32_t* counters,
-                               bool units_share_l2, hipStream_t stream) {
+                               bool units_share_l2, hipStream_t stream, const int32_t* prefix_lens,
+                               int seq_kv_heads) {
     MfmaParams p;
     p.q = static_cast<const uint16_t*>(q);
     p.k_cache = static_cast<const uint16_t*>(k_cache);
@@ -932,9 +944,11 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
     p.out = static_cast<uint16_t*>(out);
     p.anc = plan.anc_words;
     p.words_per_row = plan.words_per_row;
-    p.P = P; p.cap = cap; p.n = n; p.H = H; p.Hk = Hk; p.G = H / Hk;
+    p.P_bound = P; p.cap = cap; p.n = n; p.H = H; p.Hk = Hk; p.G = H / Hk;
+    p.prefix_lens = prefix_lens;
+    p.by_seq_kv_heads = make_fast_div((uint32_t)(seq_kv_heads > 0 ? seq_kv_heads : Hk));
     p.query_blocks = sched.query_blocks;
-    p.prefix_tiles = (P + kKeyTile - 1) / kKeyTile;
+    p.prefix_tiles_bound = (P + kKeyTile - 1) / kKeyTile;
     p.splits = sched.splits;
     p.partials = workspace;
     p.counters = counters;

@@ -42,8 +42,8 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void tree_attn_rowwise_f32(
     const float* __restrict__ q, const float* __restrict__ k_cache, const float* __restrict__ v_cache,
     const float* __restrict__ k_tree, const float* __restrict__ v_tree,
-    const uint32_t* __restrict__ anc, int words_per_row, int P, int cap, int n, int H, int Hk,
-    float* __restrict__ out) {
+    const uint32_t* __restrict__ anc, int words_per_row, int P_bound, int cap, int n, int H, int Hk,
+    float* __restrict__ out, const int32_t* __restrict__ prefix_lens, int seq_kv_heads) {
     __shared__ float qs[D];
     __shared__ float sc[kChunk];
     __shared__ float red[kThreads / 64];
@@ -52,6 +52,8 @@ __global__ __launch_bounds__(kThreads) void tree_attn_rowwise_f32(
     const int i = blockIdx.x / H;
     const int h = blockIdx.x % H;
     const int g = h / (H / Hk);
+    // (a batch whose sequences differ in prefix length: that of this KV head's sequence)
+    const int P = prefix_lens ? min(max(prefix_lens[g / seq_kv_heads], 0), P_bound) : P_bound;
     const int tid = threadIdx.x;
     const float scale = 1.0f / sqrtf((float)D);
     const uint32_t* anc_row = anc + (size_t)i * words_per_row;
@@ -133,14 +135,15 @@ __global__ __launch_bounds__(kThreads) void tree_attn_rowwise_f32(
 int launch_tree_attn_rowwise_f32(const float* q, const float* k_cache, const float* v_cache,
                                  const float* k_tree, const float* v_tree, const TreePlan& plan,
                                  int P, int cap, int n, int H, int Hk, int D, float* out,
-                                 hipStream_t stream) {
+                                 hipStream_t stream, const int32_t* prefix_lens, int seq_kv_heads) {
+    if (seq_kv_heads <= 0) seq_kv_heads = Hk;
     const dim3 grid((unsigned)(n * H)), block(kThreads);
     if (D == 64)
         hipLaunchKernelGGL(tree_attn_rowwise_f32<64>, grid, block, 0, stream, q, k_cache, v_cache,
-                           k_tree, v_tree, plan.anc_words, plan.words_per_row, P, cap, n, H, Hk, out);
+                           k_tree, v_tree, plan.anc_words, plan.words_per_row, P, cap, n, H, Hk, out, prefix_lens, seq_kv_heads);
     else
         hipLaunchKernelGGL(tree_attn_rowwise_f32<128>, grid, block, 0, stream, q, k_cache, v_cache,
-                           k_tree, v_tree, plan.anc_words, plan.words_per_row, P, cap, n, H, Hk, out);
+                           k_tree, v_tree, plan.anc_words, plan.words_per_row, P, cap, n, H, Hk, out, prefix_lens, seq_kv_heads);
     return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
 }
 

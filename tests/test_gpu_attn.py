@@ -173,3 +173,69 @@ def test_a_batch_of_sequences_is_a_call_with_more_heads():
     for b, s in enumerate(seqs):
         assert np.abs(got[:, b] - oracle_attn(s)).max() <= TOL[W.BF16], b
         assert np.abs(got[:, b] - run_attn(s)).max() <= 2 ** -6, b      # the same numbers up to the schedule's rounding
+
+
+def _batched_case(B, H, Hk, d, cap, n, lens, dtype, seed, tree):
+    """A batch that shares the tree; sequence b uses the first lens[b] rows of its own cache."""
+    import paper_2402_12374_amd as S
+    from gpu_util import DEV, to_dev
+    seqs = [W.make_attn_inputs(H, Hk, d, int(lens[b]), tree, dtype, seed=seed + b, prefix_cap=cap) for b in range(B)]
+    q = np.stack([s.q for s in seqs], axis=1)
+    kt = np.stack([s.k_tree for s in seqs], axis=1)
+    vt = np.stack([s.v_tree for s in seqs], axis=1)
+    kc = np.stack([s.k_cache for s in seqs], axis=0)
+    vc = np.stack([s.v_cache for s in seqs], axis=0)
+    dev_lens = torch.from_numpy(np.asarray(lens, np.int32)).to(DEV)
+    return seqs, (to_dev(q, dtype), to_dev(kc, dtype), to_dev(vc, dtype), to_dev(kt, dtype), to_dev(vt, dtype)), dev_lens
+
+
+@pytest.mark.parametrize("B,H,Hk,d,cap,n,lens,dtype", [
+    (4, 8, 2, 128, 700, 40, [700, 0, 333, 31], W.BF16),          # full, empty, ragged and one-tile prefixes side by side
+    (3, 32, 32, 128, 1100, 64, [1024, 17, 1100], W.BF16),        # C2's head shape: key ranges cut for 1100, one sequence has 17 keys
+    (6, 4, 1, 64, 300, 130, [300, 299, 1, 64, 150, 0], W.BF16),  # d = 64, grouped heads, five bitset words
+    (5, 2, 2, 64, 256, 16, [256, 3, 0, 100, 255], W.F32),        # the fp32 path
+    (2, 64, 8, 128, 2100, 96, [2100, 5], W.BF16),                # many query rows per KV head
+])
+def test_a_batch_whose_sequences_differ_in_prefix_length(B, H, Hk, d, cap, n, lens, dtype):
+    """seq_tree_attn_batched against one checker call per sequence, element by element; then the
+    lengths change in device memory and the same call (same arguments, same plan) must follow."""
+    import paper_2402_12374_amd as S
+    tree = W.geometric_tree(n, 7) if n != 130 else W.random_topological_tree(n, np.random.default_rng(4))
+    seqs, tensors, dev_lens = _batched_case(B, H, Hk, d, cap, n, lens, dtype, seed=31 * B + n, tree=tree)
+    out = S.seq_tree_attn_batched(*tensors, tree, dev_lens, max(lens))
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    for b, s in enumerate(seqs):
+        err = np.abs(got[:, b] - oracle_attn(s)).max()
+        assert err <= TOL[dtype], (b, lens[b], err)
+    # shorter histories in the same buffers: rows at and beyond the new lengths must have no weight
+    shorter = [max(0, x - 7 * (b + 1)) for b, x in enumerate(lens)]
+    dev_lens.copy_(torch.from_numpy(np.asarray(shorter, np.int32)))
+    out = S.seq_tree_attn_batched(*tensors, tree, dev_lens, max(lens))
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    for b, s in enumerate(seqs):
+        s.prefix_len = shorter[b]
+        err = np.abs(got[:, b] - oracle_attn(s)).max()
+        assert err <= TOL[dtype], (b, shorter[b], err)
+
+
+def test_batched_lengths_are_held_to_the_bound_and_equal_lengths_match_the_folded_call():
+    import paper_2402_12374_amd as S
+    B, H, Hk, d, cap, n = 3, 8, 2, 128, 400, 40
+    tree = W.geometric_tree(n, 6)
+    seqs, tensors, dev_lens = _batched_case(B, H, Hk, d, cap, n, [400, 400, 400], W.BF16, seed=77, tree=tree)
+    batched = S.seq_tree_attn_batched(*tensors, tree, dev_lens, 400)
+    q, kc, vc, kt, vt = tensors
+    folded = S.seq_tree_attn(q.view(n, B * H, d), kc.view(B * Hk, cap, d), vc.view(B * Hk, cap, d),
+                             kt.view(n, B * Hk, d), vt.view(n, B * Hk, d), tree, 400)
+    torch.cuda.synchronize()
+    assert torch.equal(batched.view(n, B * H, d), folded)          # same kernel, same schedule, same bits
+    # lengths outside [0, bound] are read as the nearest legal value
+    dev_lens.copy_(torch.tensor([9999, -5, 123], dtype=torch.int32))
+    out = S.seq_tree_attn_batched(*tensors, tree, dev_lens, 400)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    for b, plen in enumerate([400, 0, 123]):
+        seqs[b].prefix_len = plen
+        assert np.abs(got[:, b] - oracle_attn(seqs[b])).max() <= TOL[W.BF16], b

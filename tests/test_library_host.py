@@ -250,6 +250,28 @@ def test_noalloc_attn_argument_errors_and_size_limit_need_no_gpu():
     assert call(parent=par, prefix_len=131072, cap=131072, heads=16, kv_heads=8, head_dim=128) == B.SEQ_ERR_WORKSPACE
 
 
+def test_batched_attn_argument_errors_need_no_gpu():
+    good = np.asarray([-1, 0, 0, 1], np.int32)
+    def call(parent=good, lens=0x1000, bound=4, batch=2, heads=2, kv_heads=2, head_dim=64, cap=8, dtype=B.SEQ_BF16, q=0x1000,
+             ws=0x1000, ws_bytes=1 << 30):
+        par = np.asarray(parent, np.int32)
+        return S.lib().seq_tree_attn_batched(q, 0x1000, 0x1000, 0x1000, 0x1000, par.ctypes.data, lens, bound, batch, len(par),
+                                             heads, kv_heads, head_dim, 0x1000, cap, dtype, ws, ws_bytes, None)
+    assert call(q=None) == B.SEQ_ERR_NULL
+    assert call(lens=None) == B.SEQ_ERR_NULL
+    assert call(batch=0) == B.SEQ_ERR_SHAPE
+    assert call(batch=B.SEQ_MAX_BATCH + 1) == B.SEQ_ERR_SHAPE
+    assert call(bound=9, cap=8) == B.SEQ_ERR_SHAPE
+    assert call(heads=3, kv_heads=2) == B.SEQ_ERR_SHAPE
+    assert call(head_dim=100) == B.SEQ_ERR_SHAPE
+    assert call(dtype=0) == B.SEQ_ERR_DTYPE
+    assert call(parent=[-1, 1, 0]) == B.SEQ_ERR_TREE
+    par = W.geometric_tree(64, 8)
+    need = S.lib().seq_tree_attn_batched_workspace(1024, 2, 64, 16, 16, 128, B.SEQ_BF16)
+    assert need == S.seq_tree_attn_workspace(1024, 64, 32, 32, 128, B.SEQ_BF16) > 256
+    assert call(parent=par, bound=1024, cap=1024, heads=16, kv_heads=16, head_dim=128, ws_bytes=need - 1) == B.SEQ_ERR_WORKSPACE
+
+
 @pytest.fixture
 def host_memory():
     """The library's own allocations come from host memory for the duration of a test, so that
