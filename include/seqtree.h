@@ -142,14 +142,17 @@ int seq_tree_attn(const void* q, const void* k_cache, const void* v_cache,
  *   bonus_token    [1] int32 out
  *   workspace      DEVICE, 16-byte aligned, at least seq_verify_workspace(...) bytes; on return it
  *                  starts with a trace (see below) that tests and debuggers may read; the rest
- *                  is scratch whose contents are unspecified
+ *                  is scratch whose contents are unspecified.  It need not be cleared: nothing
+ *                  it holds on entry is read (what workgroups hand to each other travels
+ *                  through the stream's synchronisation area).
  *
- * Two kernels sit behind this call and give the same results.  For sampling (T > 0) over a
- * vocabulary of at most 32768 tokens and a tree of at most 256 nodes, every node's accept
- * thresholds are computed at once, one workgroup per node (every logit row the tree can visit
- * is read), and a short walk follows;
- * otherwise only the rows of the nodes the walk visits are read, by workgroups that share the
- * vocabulary.
+ * Three kernels sit behind this call and give the same results.  For sampling (T > 0) every
+ * node's accept thresholds can be computed at once and a short walk follows: over a vocabulary
+ * of at most 32768 tokens with one workgroup per node (every logit row the tree can visit is
+ * read), for trees of at most 256 nodes; over larger vocabularies with a team of
+ * ceil(vocab / 16384) workgroups per node that has children, while every member finds a compute
+ * unit of its own (a 64-node tree over 128256 tokens: 32 teams of 8).  Otherwise only the rows
+ * of the nodes the walk visits are read, by workgroups that share the vocabulary.
  */
 int seq_verify(const void* target_logits, const void* draft_logits,
                const int32_t* tree_tokens, const int32_t* parent, float temperature,

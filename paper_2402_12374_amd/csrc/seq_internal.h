@@ -18,6 +18,8 @@ struct TreePlan {
     uint32_t* anc_words = nullptr;      // [n][words_per_row]
     int32_t* child_start = nullptr;     // [n + 1]
     int32_t* child_list = nullptr;      // [max(n - 1, 1)]
+    int32_t* internal_nodes = nullptr;  // [max(n_internal, 1)] nodes that have children, longest sibling list first
+    int32_t n_internal = 0;
     int32_t max_children = 0;
 };
 
@@ -35,6 +37,13 @@ struct SyncArea {
     uint32_t* verify_batch_ctl = nullptr;        // [kVerifyMaxBatch][4] per sequence of a batched launch: tag epoch of the
                                                  // per-node kernel, tag epoch of the walk's teams, arrivals, the teams' poison flag
     unsigned long long* verify_batch_slots = nullptr;  // [kWalkMaxBatch][2][kVerifyMaxGroups][kVerifySlotWords]
+    // What the workgroups of a per-node verification launch leave for each other, as words under
+    // the tag of their launch: [0] the tag epoch (only ever grows), [1] the word of a team that
+    // gave up waiting, [2] the count of workgroups of the launch that are done; from word
+    // kChainHeaderWords on the records of up to SEQ_MAX_TREE nodes, then the exchange slots of up
+    // to SEQ_MAX_TREE teams.  It lives here and not in the caller's workspace because a tag only
+    // proves anything about memory that nothing but these kernels ever writes.
+    unsigned long long* chain_area = nullptr;
     // Measured once per device: do workgroups whose ids are congruent mod 8 share an XCD (one
     // L2)?  The attention kernel then keeps all key ranges of a unit on one XCD and can hand
     // partial results over through that L2 without writing it back to memory.
@@ -48,6 +57,10 @@ constexpr int kVerifyTagsPerCall = 4096;
 constexpr int kAttnMaxCounters = 16384;
 constexpr int kDraftMaxGroups = 16384;
 constexpr int kVerifyMaxBatch = 256;
+constexpr int kChainHeaderWords = 32;
+constexpr int kChainRecordWordsPerNode = 9;     // 5 tagged words per child, 4 per node
+constexpr int kChainSlotWordsPerTeam = 256;     // two buffers (by step parity) of 4 x 32 tagged words
+constexpr size_t kChainAreaWords = kChainHeaderWords + (size_t)SEQ_MAX_TREE * (kChainRecordWordsPerNode + kChainSlotWordsPerTeam);
 constexpr int kWalkMaxBatch = 64;     // teams of the lazy walk that one launch runs side by side
 
 // Looks up (or builds and uploads) the plan for this parent array on the current device.

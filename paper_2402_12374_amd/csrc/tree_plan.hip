@@ -141,12 +141,14 @@ void free_plan(TreePlan& p) {
     if (p.anc_words) g_mem->release(p.anc_words);
     if (p.child_start) g_mem->release(p.child_start);
     if (p.child_list) g_mem->release(p.child_list);
+    if (p.internal_nodes) g_mem->release(p.internal_nodes);
     p = TreePlan{};
 }
 void free_area(SyncArea& a) {
     if (a.verify_slots) g_mem->release(a.verify_slots);
     if (a.attn_counters) g_mem->release(a.attn_counters);
     if (a.draft_exchange) g_mem->release(a.draft_exchange);
+    if (a.chain_area) g_mem->release(a.chain_area);
     a = SyncArea{};
 }
 }  // namespace
@@ -175,10 +177,22 @@ int get_tree_plan(const int32_t* parent, int32_t n, hipStream_t stream, TreePlan
     e.plan.words_per_row = words_per_row(n);
     for (int32_t v = 0; v < n; ++v)
         e.plan.max_children = std::max(e.plan.max_children, cstart[v + 1] - cstart[v]);
+    // nodes with children, those with the longest sibling lists (the longest chains of dependent
+    // steps in the per-node verification kernel) first
+    std::vector<int32_t> internal;
+    for (int32_t v = 0; v < n; ++v)
+        if (cstart[v + 1] > cstart[v]) internal.push_back(v);
+    std::stable_sort(internal.begin(), internal.end(), [&](int32_t a, int32_t b) {
+        return cstart[a + 1] - cstart[a] > cstart[b + 1] - cstart[b];
+    });
+    e.plan.n_internal = (int32_t)internal.size();
+    if (internal.empty()) internal.push_back(0);
     e.plan.anc_words = static_cast<uint32_t*>(g_mem->alloc(anc.size() * sizeof(uint32_t)));
+    e.plan.internal_nodes = static_cast<int32_t*>(g_mem->alloc(internal.size() * sizeof(int32_t)));
     e.plan.child_start = static_cast<int32_t*>(g_mem->alloc(cstart.size() * sizeof(int32_t)));
     e.plan.child_list = static_cast<int32_t*>(g_mem->alloc(clist.size() * sizeof(int32_t)));
-    const bool ok = e.plan.anc_words && e.plan.child_start && e.plan.child_list &&
+    const bool ok = e.plan.anc_words && e.plan.child_start && e.plan.child_list && e.plan.internal_nodes &&
+                    g_mem->upload(e.plan.internal_nodes, internal.data(), internal.size() * sizeof(int32_t)) &&
                     g_mem->upload(e.plan.anc_words, anc.data(), anc.size() * sizeof(uint32_t)) &&
                     g_mem->upload(e.plan.child_start, cstart.data(), cstart.size() * sizeof(int32_t)) &&
                     g_mem->upload(e.plan.child_list, clist.data(), clist.size() * sizeof(int32_t));
@@ -232,7 +246,10 @@ int get_sync_area(hipStream_t stream, SyncArea** out) {
     s.area.verify_slots = static_cast<unsigned long long*>(g_mem->alloc(slot_bytes));
     s.area.attn_counters = static_cast<uint32_t*>(g_mem->alloc(ctr_bytes));
     s.area.draft_exchange = static_cast<unsigned long long*>(g_mem->alloc(draft_bytes));
-    const bool ok = s.area.verify_slots && s.area.attn_counters && s.area.draft_exchange &&
+    const size_t chain_bytes = sizeof(unsigned long long) * kChainAreaWords;
+    s.area.chain_area = static_cast<unsigned long long*>(g_mem->alloc(chain_bytes));
+    const bool ok = s.area.verify_slots && s.area.attn_counters && s.area.draft_exchange && s.area.chain_area &&
+                    g_mem->zero(s.area.chain_area, chain_bytes) &&
                     g_mem->zero(s.area.verify_slots, slot_bytes) && g_mem->zero(s.area.attn_counters, ctr_bytes) &&
                     g_mem->zero(s.area.draft_exchange, draft_bytes);
     if (!ok) {

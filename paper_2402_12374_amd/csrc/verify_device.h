@@ -34,7 +34,8 @@ struct VerifyParams {
     int32_t* path;
     int32_t* bonus;
     int32_t* trace;
-    unsigned long long* records;   // per-node kernel: child records, then node records
+    unsigned long long* records;   // (top-k baseline) the nodes' draws, in the caller's workspace behind the trace
+    unsigned long long* chain_area;   // per-node kernels: header, records, team slots (the library's, see SyncArea)
     unsigned long long* slots;
     uint32_t* epoch;
     uint32_t* poison;       // lazy walk: set after a timed-out wait, later launches refuse to run
@@ -47,6 +48,12 @@ struct VerifyParams {
     size_t batch_logit_bytes, batch_workspace_bytes;
     uint32_t* batch_ctl;    // [sequences][4]: per-node kernel's epoch, walk's epoch, arrivals, walk's poison flag
     unsigned long long* batch_slots;   // [sequences][2][kVerifyMaxGroups][kVerifySlotWords]
+    unsigned long long* chain_records; // per-node kernels: this sequence's child records [n][5], then node records [n][4]
+    // per-node kernel with a team of W workgroups per node (vocabularies beyond one workgroup's registers)
+    unsigned long long* team_slots;    // [teams][2][kTeamSlotWords][kTeamMaxW] tagged words
+    const int32_t* internal_nodes;     // [n_internal] nodes that have children, longest sibling list first
+    int n_internal;
+    int team_xcd;                      // workgroup b runs on XCD b % 8: keep a team on one XCD
 };
 
 // A batched launch runs the same code once per sequence (grid.y): every sequence has its own
@@ -62,6 +69,7 @@ __device__ __forceinline__ VerifyParams params_of_sequence(const VerifyParams& i
     p.bonus = in.bonus + b;
     p.trace = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(in.trace) + (size_t)b * in.batch_workspace_bytes);
     p.records = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(in.records) + (size_t)b * in.batch_workspace_bytes);
+    p.chain_records = in.chain_records + (size_t)b * in.n * kChainRecordWordsPerNode;   // (the sequences of a launch hold at most SEQ_MAX_TREE nodes together)
     p.epoch = in.batch_ctl + 4 * b + (walk_team ? 1 : 0);
     p.poison = in.batch_ctl + 4 * b + 3;
     p.arrivals = in.batch_ctl + 4 * b + 2;
@@ -73,6 +81,12 @@ __device__ __forceinline__ VerifyParams params_of_sequence(const VerifyParams& i
 // Vocabularies up to kChainsMaxVocab; dtype SEQ_BF16 or SEQ_F32.
 constexpr int kChainsMaxVocab = 32768;
 void launch_verify_chains(const VerifyParams& p, int dtype, hipStream_t stream, int batch = 1);
+// The same chains for larger vocabularies: a team of p.W = ceil(V / 16384) workgroups of 512
+// threads per node that has children (p.internal_nodes), which meet in p.team_slots.
+constexpr int kTeamMaxW = 32;
+constexpr int kTeamSlotWords = 4;
+int team_size_for(int vocab);
+void launch_verify_chains_team(const VerifyParams& p, int dtype, hipStream_t stream);
 // verify_topk.hip: naive / top-k sampling (Sec. 2.2): one draw from the target per node, then the walk.
 void launch_verify_topk(const VerifyParams& p, int dtype, hipStream_t stream, int batch = 1);
 void set_topk_mode(int mode);
@@ -83,16 +97,21 @@ template <> __device__ __forceinline__ float load_logit<uint16_t>(const uint16_t
     return __uint_as_float((uint32_t)row[x] << 16);
 }
 
-// EPT consecutive logits of one row starting at `base`, tempered; tokens past the vocabulary
-// read as -inf.  16-byte loads when the row start and EPT allow it.
+// EPT consecutive logits of one row starting at `base` (a multiple of EPT), tempered; tokens past
+// the vocabulary read as -inf.  16-byte loads when the row starts and the vocabulary allow it
+// (`vec_ok`: every 16-byte group of a row then lies wholly inside or wholly outside it); otherwise
+// token by token, in a loop that is kept rolled: it runs for odd vocabularies only and would
+// otherwise be most of the kernel's code.
 template <typename LT, int EPT>
 __device__ __forceinline__ void load_row_slice(const LT* row, int base, int V, float inv_T, bool vec_ok,
                                                float* x) {
     constexpr int kPerVec = 16 / (int)sizeof(LT);
-    if (vec_ok && base + EPT <= V) {
+    if (vec_ok) {
 #pragma unroll
         for (int c = 0; c < EPT / kPerVec; ++c) {
-            const uint4 raw = *reinterpret_cast<const uint4*>(row + base + c * kPerVec);
+            uint4 raw = make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u);   // -inf as bf16 pairs
+            if (sizeof(LT) == 4) raw = make_uint4(0xFF800000u, 0xFF800000u, 0xFF800000u, 0xFF800000u);
+            if (base + (c + 1) * kPerVec <= V) raw = *reinterpret_cast<const uint4*>(row + base + c * kPerVec);
             const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -105,8 +124,12 @@ __device__ __forceinline__ void load_row_slice(const LT* row, int base, int V, f
             }
         }
     } else {
+#pragma unroll 1
+        for (int e = 0; e < EPT; ++e) {
+            const float val = base + e < V ? load_logit<LT>(row, base + e) * inv_T : -INFINITY;
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) x[e] = base + e < V ? load_logit<LT>(row, base + e) * inv_T : -INFINITY;
+            for (int k = 0; k < EPT; ++k) x[k] = k == e ? val : x[k];   // (static register indices)
+        }
     }
 }
 
@@ -200,7 +223,15 @@ struct ChildTest {
         return (rhs_r * rhs_m) / (lhs_w * lhs_q);
     }
 };
-__device__ __forceinline__ ChildTest node_test_child(const NodeState& st, float ps, float qs, bool in_s, int V) {
+// What a child's test needs of the state before its rejection.
+struct TestState {
+    float af, bf, Wn, massQ;
+    int n_rej, fallback;
+};
+__device__ __forceinline__ TestState test_state_of(const NodeState& st) {
+    return TestState{st.af, st.bf, (float)st.Wn, (float)st.massQ, st.n_rej, st.fallback};
+}
+__device__ __forceinline__ ChildTest node_test_child(const TestState& st, float ps, float qs, bool in_s, int V) {
     const int left = V - st.n_rej;  // tokens not yet rejected
     const float r_num = in_s ? 0.f : residual_of(ps, qs, st.af, st.bf);   // R[s] * W
     ChildTest t;
@@ -209,13 +240,16 @@ __device__ __forceinline__ ChildTest node_test_child(const NodeState& st, float 
         t.lhs_w = 0.f; t.lhs_q = 1.f;
         t.rhs_r = r_num > 0.f ? 1.f : 0.f; t.rhs_m = 1.f;    // D[s] = 0: accepted iff R[s] > 0
     } else if (st.fallback) {
-        t.lhs_w = (float)st.Wn; t.lhs_q = 1.f;
+        t.lhs_w = st.Wn; t.lhs_q = 1.f;
         t.rhs_r = r_num; t.rhs_m = (float)left;              // vocabularies stay far below 2^24
     } else {
-        t.lhs_w = (float)st.Wn; t.lhs_q = qs;
-        t.rhs_r = r_num; t.rhs_m = (float)st.massQ;
+        t.lhs_w = st.Wn; t.lhs_q = qs;
+        t.rhs_r = r_num; t.rhs_m = st.massQ;
     }
     return t;
+}
+__device__ __forceinline__ ChildTest node_test_child(const NodeState& st, float ps, float qs, bool in_s, int V) {
+    return node_test_child(test_state_of(st), ps, qs, in_s, V);
 }
 
 // Rejection: R <- norm(max(R - D, 0)), then D[s] <- 0 (uniform over what is left once the draft
@@ -279,19 +313,28 @@ __device__ __forceinline__ int wave_min(int v) {   // wave-uniform result; all l
 }
 __device__ __forceinline__ int wave_max(int v) { return -wave_min(-v); }
 
-__device__ __forceinline__ BlockPick pick_block(float u0, float sw_f, int blocks) {
+// FRACTION: the goal is x times the total mass of these blocks; otherwise x itself (a cumulative
+// mass counted from the first block).  `force_last`: take the last block with mass whatever the goal.
+template <bool FRACTION>
+__device__ __forceinline__ BlockPick pick_block_impl(double x, bool force_last, float sw_f, int blocks) {
     const double sw = (double)sw_f;
     const double incl = wave_scan(sw);
     BlockPick r;
     r.total = lane_value(incl, 63);
-    const double goal = (double)u0 * r.total;
-    const unsigned long long hit = __ballot(sw > 0.0 && incl > goal);
+    const double goal = FRACTION ? x * r.total : x;
+    const unsigned long long hit = force_last ? 0ull : __ballot(sw > 0.0 && incl > goal);
     const unsigned long long pos = __ballot(sw > 0.0);
     r.forced = 0;
     if (hit) r.owner = __ffsll((long long)hit) - 1;
     else { r.forced = 1; r.owner = pos ? 63 - __clzll((long long)pos) : blocks - 1; }
     r.before = lane_value(incl - sw, __builtin_amdgcn_readfirstlane(r.owner));
     return r;
+}
+__device__ __forceinline__ BlockPick pick_block(float u0, float sw_f, int blocks) {
+    return pick_block_impl<true>((double)u0, false, sw_f, blocks);
+}
+__device__ __forceinline__ BlockPick pick_block_at(double goal, bool force_last, float sw_f, int blocks) {
+    return pick_block_impl<false>(goal, force_last, sw_f, blocks);
 }
 
 // Layout of the caller's workspace: the trace first (header, one record per accept test, four
@@ -302,13 +345,23 @@ constexpr size_t kTraceBytesPadded = (kTraceBytes + 255) / 256 * 256;
 constexpr int kChildRecordWords = 5;   // tagged words per child: the four factors of the test, events
 constexpr int kNodeRecordWords = 4;    // tagged words per node: bonus token, total mass, CDF below / above
 constexpr size_t kRecordWords = (size_t)SEQ_MAX_TREE * (kChildRecordWords + kNodeRecordWords);
-// The tag epoch of the per-node kernel lives in the workspace, right behind the records it tags:
-// whatever else has used the library's synchronisation area in between, the tags one workspace
-// sees only ever grow, so a record left there by an earlier launch can never pass for a new one.
-__host__ __device__ __forceinline__ uint32_t* chain_epoch_cell(unsigned long long* records) {
-    return reinterpret_cast<uint32_t*>(records + kRecordWords);
-}
+static_assert(kChildRecordWords + kNodeRecordWords == kChainRecordWordsPerNode, "layout of the per-node kernels' area");
 constexpr size_t kVerifyWorkspaceBytes = kTraceBytesPadded + sizeof(unsigned long long) * kRecordWords + 256;
+// The per-node kernels' area (library-owned, zeroed when created, written by these kernels only):
+// the tag epoch, which every workgroup of a launch reads on entry and the last workgroup of the
+// launch to finish moves on -- whatever a word of the area holds was written under a smaller tag
+// or by this launch; the word a team member that gave up waiting leaves for the workgroup that
+// walks; the count of finished workgroups; the records; the teams' exchange slots: per team two
+// buffers (by step parity) of kTeamSlotWords x kTeamMaxW tagged words.
+constexpr size_t kTeamSlotWordsPerTeam = (size_t)2 * kTeamSlotWords * kTeamMaxW;
+static_assert(kTeamSlotWordsPerTeam == kChainSlotWordsPerTeam, "layout of the per-node kernels' area");
+__host__ __device__ __forceinline__ uint32_t* chain_epoch_cell(unsigned long long* area) { return reinterpret_cast<uint32_t*>(area); }
+__host__ __device__ __forceinline__ unsigned long long* team_fail_cell(unsigned long long* area) { return area + 1; }
+__host__ __device__ __forceinline__ uint32_t* chain_finished_cell(unsigned long long* area) { return reinterpret_cast<uint32_t*>(area + 2); }
+__host__ __device__ __forceinline__ unsigned long long* chain_records_of(unsigned long long* area) { return area + kChainHeaderWords; }
+__host__ __device__ __forceinline__ unsigned long long* team_slots_of(unsigned long long* area) {
+    return area + kChainHeaderWords + (size_t)SEQ_MAX_TREE * kChainRecordWordsPerNode;
+}
 
 }  // namespace verify
 }  // namespace seqtree

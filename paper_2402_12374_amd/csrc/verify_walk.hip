@@ -80,42 +80,50 @@ struct Shared {
 template <int K>
 __device__ __forceinline__ bool exchange(const VerifyParams& p, uint32_t tag_base, uint32_t step,
                                          const float (&mine)[K], float fill, float (&got)[K]) {
+    // (inside, plain floats and no arrays: an array that the compiler cannot dissolve into
+    // registers goes to a per-thread slice of shared memory, whose address needs the workgroup's
+    // size, which the kernel would have to fetch from the dispatch packet -- a trip to host memory)
+    static_assert(K >= 1 && K <= kVerifySlotWords, "slot words per step");
     const int lane = threadIdx.x;  // first wavefront: 0..63
-#pragma unroll
-    for (int k = 0; k < K; ++k) got[k] = fill;
+    const float mine0 = mine[0], mine1 = mine[K > 1 ? 1 : 0], mine2 = mine[K > 2 ? 2 : 0], mine3 = mine[K > 3 ? 3 : 0];
+    float got0 = fill, got1 = fill, got2 = fill, got3 = fill;
+    auto hand_back = [&]() __attribute__((always_inline)) {
+        got[0] = got0;
+        if constexpr (K > 1) got[1] = got1;
+        if constexpr (K > 2) got[2] = got2;
+        if constexpr (K > 3) got[3] = got3;
+    };
     if (p.W == 1) {   // nobody to talk to
-        if (lane == 0) {
-#pragma unroll
-            for (int k = 0; k < K; ++k) got[k] = mine[k];
-        }
+        if (lane == 0) { got0 = mine0; got1 = mine1; got2 = mine2; got3 = mine3; }
+        hand_back();
         return true;
     }
     const uint32_t tag = tag_base + step;
     unsigned long long* buf = p.slots + (size_t)(step & 1u) * kVerifyMaxGroups * kVerifySlotWords;
     if (lane < K) {
-        float v = mine[0];
-#pragma unroll
-        for (int k = 1; k < K; ++k) v = lane == k ? mine[k] : v;
+        const float v = lane == 0 ? mine0 : lane == 1 ? mine1 : lane == 2 ? mine2 : mine3;
         const unsigned long long word = ((unsigned long long)tag << 32) | __float_as_uint(v);
         __hip_atomic_store(&buf[lane * kVerifyMaxGroups + wg_rank()], word, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
     }
     bool done = lane >= p.W;
     uint32_t spins = 0;
+    auto look = [&](int k, float& value) __attribute__((always_inline)) {
+        const unsigned long long word = __hip_atomic_load(&buf[k * kVerifyMaxGroups + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(word >> 32) != tag) return false;
+        value = __uint_as_float((uint32_t)word);
+        return true;
+    };
     for (;;) {
         if (!done) {
-            bool all = true;
-#pragma unroll
-            for (int k = 0; k < K; ++k) {
-                const unsigned long long word = __hip_atomic_load(
-                    &buf[k * kVerifyMaxGroups + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((uint32_t)(word >> 32) == tag) got[k] = __uint_as_float((uint32_t)word);
-                else all = false;
-            }
+            bool all = look(0, got0);
+            if (K > 1) all &= look(1, got1);
+            if (K > 2) all &= look(2, got2);
+            if (K > 3) all &= look(3, got3);
             done = all;
         }
-        if (__all(done)) return true;
-        if (++spins > p.spin_limit) return false;   // bounded wait: every wave leaves this loop
+        if (__all(done)) { hand_back(); return true; }
+        if (++spins > p.spin_limit) { hand_back(); return false; }   // bounded wait: every wave leaves this loop
         __builtin_amdgcn_s_sleep(1);
     }
 }
@@ -660,6 +668,12 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
     p.batch_workspace_bytes = per_sequence;
     p.batch_ctl = sync->verify_batch_ctl;
     p.batch_slots = sync->verify_batch_slots;
+    p.chain_area = sync->chain_area;
+    p.chain_records = chain_records_of(sync->chain_area);
+    p.team_slots = team_slots_of(sync->chain_area);
+    p.internal_nodes = plan.internal_nodes;
+    p.n_internal = plan.n_internal;
+    p.team_xcd = sync->round_robin_xcds ? 1 : 0;
     // Sampling with a vocabulary one workgroup can hold, and a tree whose nodes all find a CU at
     // once: all nodes at once -- of as many sequences of the batch as still fit.  Otherwise (and
     // for greedy decoding, which needs one arg-max per visited node) the lazy walk.
@@ -670,11 +684,27 @@ extern "C" int seq_verify_batched(int32_t algorithm, int32_t batch, const void* 
     const int at_once = sync->compute_units;
     bool per_node_kernel = !greedy && algorithm != SEQ_VERIFY_TOPK && vocab <= kChainsMaxVocab &&
                            g_verify_mode != 1 && (n_tree <= at_once || g_verify_mode == 2);
+    // Larger vocabularies, one sequence: a team of workgroups per node that has children.  Worth
+    // it while every member finds a compute unit of its own (64 nodes over 128256 tokens, 32 teams
+    // of 8: 25.5 us against 27.5 us for the lazy walk where the walk is short, 31 against 41 us
+    // where it runs to a leaf); with two members to a unit the lazy walk is faster again (128
+    // nodes: 32.2 against 29.9 us), and beyond that by far (768 nodes: 104 against 39 us).
+    const int team_w = team_size_for(vocab);
+    const bool per_node_teams = !greedy && algorithm != SEQ_VERIFY_TOPK && vocab > kChainsMaxVocab && batch == 1 &&
+                                plan.n_internal > 0 && g_verify_mode != 1 &&
+                                (plan.n_internal * team_w <= at_once || g_verify_mode == 2);
+    if (per_node_teams) {
+        VerifyParams q = p;
+        q.W = team_w;
+        launch_verify_chains_team(q, dtype, stream);
+        return hipGetLastError() == hipSuccess ? SEQ_OK : SEQ_ERR_HIP;
+    }
     const bool topk_draws = algorithm == SEQ_VERIFY_TOPK && !greedy;
     // sequences per launch: as many as find a CU for every workgroup they need -- a workgroup per
     // node in the per-node kernel, a team of W in the lazy walk (whose members wait for each
     // other, so all of them must be running); the top-k draws, which wait for nobody, all of them
-    const int per_launch_nodes = std::max(1, at_once / n_tree);
+    // (their records share the area's SEQ_MAX_TREE node records)
+    const int per_launch_nodes = std::max(1, std::min(at_once, SEQ_MAX_TREE) / n_tree);
     const int per_launch_teams = std::min(kWalkMaxBatch, std::max(1, at_once / p.W));
     // A batch that the per-node kernel needs more launches for than the teams do goes to the
     // teams: a launch of either costs about the same whatever it holds (64 nodes, 32000 tokens:

@@ -298,3 +298,109 @@ def test_a_batch_of_sequences_over_one_tree(n, V, B, T):
         # where the residual is flat the edges of the bonus draw's CDF are about 1/V apart, not far
         # from the flag margin of 1e-5: a bonus token drawn there is often flagged by definition
         assert flagged <= max(1, B // 3)
+
+
+@pytest.fixture
+def per_node_forced():
+    """The per-node kernels wherever temperature and algorithm allow them, whatever the size of the
+    tree: one workgroup per node up to 32768 tokens, a team of workgroups per node beyond."""
+    S.lib().seqtree_internal_set_verify_mode(2)
+    yield
+    S.lib().seqtree_internal_set_verify_mode(0)
+
+
+@pytest.mark.parametrize("n,V,dtype,T,sigma_d,tree", [
+    (64, 128256, W.BF16, 0.6, 2.0, "geometric"),     # the 64-node tree over the Llama3 vocabulary: 32 teams of 8
+    (64, 128256, W.BF16, 0.6, 0.3, "geometric"),     # a good drafter: chains end early, paths are long
+    (24, 40000, W.F32, 1.0, 1.0, "random"),          # fp32 logits, a last member with a short share
+    (128, 65536, W.BF16, 0.8, 0.5, "geometric"),     # exactly four full members
+    (12, 524288, W.BF16, 0.6, 1.0, "geometric"),     # the largest vocabulary: teams of 32
+    (40, 32769, W.BF16, 1.3, 1.0, "random"),         # one token past a single workgroup's reach
+    (200, 70001, W.F32, 0.7, 0.6, "chain"),          # 199 teams of 5: more than run at once, odd vocabulary (no 16-byte loads)
+    (48, 100000, W.BF16, 0.5, 1.5, "star"),          # one team, 47 children: a long chain of exchanges
+])
+def test_teams_of_workgroups_per_node_on_large_vocabularies(n, V, dtype, T, sigma_d, tree, kernel_choice, per_node_forced):
+    if kernel_choice != "auto":
+        pytest.skip("the forced lazy walk has its own cases")
+    flagged = 0
+    reps = 2 if V > 200000 or n > 128 else 4
+    for rep in range(reps):
+        parent = {"geometric": lambda: W.geometric_tree(n, 6), "chain": lambda: W.chain_tree(n), "star": lambda: W.star_tree(n),
+                  "random": lambda: W.random_topological_tree(n, np.random.default_rng(rep))}[tree]()
+        v = W.make_verify_inputs(parent, V, 3.0, sigma_d, T, dtype, seed=31 * V + rep)
+        flagged += check_verify(v) == "flagged"
+    assert flagged <= 1
+
+
+def test_teams_draw_at_a_leaf_when_the_walk_ends_there(kernel_choice, per_node_forced):
+    """Draft equal to target: the first child of every node is accepted and the walk runs to a leaf,
+    which has no team; the workgroup that walks draws the bonus token from the leaf's row."""
+    if kernel_choice != "auto":
+        pytest.skip("the forced lazy walk has its own cases")
+    for rep, V in enumerate((50000, 128256, 300001)):
+        parent = W.geometric_tree(40, 6)
+        v = W.make_verify_inputs(parent, V, 3.0, 1.5, 0.8, W.BF16, seed=rep)
+        v.draft_logits[:] = v.target_logits
+        rng = np.random.default_rng(rep)
+        for node, ch in enumerate(W.children_lists(parent)):
+            if ch:
+                v.tree_tokens[ch] = W.draw_children_tokens(v.draft_logits[node], len(ch), 0.8, rng)
+        for u0 in (0.0, 0.31, 0.77, 0.9999999):
+            v.uniforms[0] = u0
+            got = run_verify(v)
+            assert check_verify(v, got) in ("exact", "flagged")
+            assert len(W.children_lists(parent)[got[2]["stop_node"]]) == 0
+
+
+def test_teams_and_the_lazy_walk_leave_the_same_trace():
+    parent = W.geometric_tree(64, 6)
+    for rep, sigma_d in enumerate((2.0, 0.5, 0.2)):
+        v = W.make_verify_inputs(parent, 128256, 4.0, sigma_d, 0.6, W.BF16, seed=4400 + rep)
+        got = []
+        for mode in (2, 1):
+            S.lib().seqtree_internal_set_verify_mode(mode)
+            got.append(run_verify(v))
+        S.lib().seqtree_internal_set_verify_mode(0)
+        (pa, ba, ta), (pb, bb, tb) = got
+        assert np.array_equal(ta["nodes"], tb["nodes"]) and np.array_equal(ta["accepted"], tb["accepted"])
+        assert np.allclose(ta["ratios"], tb["ratios"], rtol=1e-5, atol=1e-7)
+        assert np.array_equal(pa, pb) and ta["stop_node"] == tb["stop_node"]
+        if abs(ta["bonus_cdf_lo"] - ta["bonus_u"]) > 1e-5 and abs(ta["bonus_cdf_hi"] - ta["bonus_u"]) > 1e-5:
+            assert ba == bb
+
+
+def test_a_team_that_gives_up_waiting_is_reported(per_node_forced):
+    """No patience at all: a team member that does not find the others' numbers at its first look
+    leaves; the call still ends, and reports status 1 with bonus -1 unless every look succeeded."""
+    v = W.make_verify_inputs(W.geometric_tree(32, 5), 100000, 3.0, 1.0, 0.6, W.BF16, seed=77)
+    S.lib().seqtree_internal_set_spin_limit(0)
+    try:
+        p, bonus, trace = run_verify(v)
+        assert trace["status"] in (0, 1)
+        if trace["status"] == 1:
+            assert bonus == -1
+    finally:
+        S.lib().seqtree_internal_set_spin_limit(1 << 22)
+    # the workspace's tags have moved on: the next call is not confused by what the failed one left
+    assert check_verify(v) in ("exact", "flagged")
+
+
+@pytest.mark.parametrize("V,n", [(32000, 64), (128256, 40), (2049, 16)])
+def test_whatever_the_workspace_held_before(V, n, kernel_choice):
+    """The caller's workspace is scratch: whatever it holds when the call starts -- here words that
+    look like the kernels' own tagged records under small tags, all ones, and noise -- nothing of
+    it may be taken for a result (the kernels' tagged words live in the library's own area)."""
+    parent = W.geometric_tree(n, 6)
+    v = W.make_verify_inputs(parent, V, 3.0, 1.0, 0.6, W.BF16, seed=V + n)
+    args = (to_dev(v.target_logits, v.dtype), to_dev(v.draft_logits, v.dtype), torch.from_numpy(v.tree_tokens).to(DEV),
+            v.parent, v.temperature, torch.from_numpy(v.uniforms).to(DEV))
+    words = S.seq_verify_workspace(n, V, S.binding.SEQ_BF16) // 8
+    fills = [torch.full((words,), (tag << 32) | payload, dtype=torch.int64, device=DEV) for tag, payload in ((1, 0), (2, 1), (4097, 0))]
+    fills.append(torch.full((words,), -1, dtype=torch.int64, device=DEV))
+    fills.append(torch.randint(-2**62, 2**62, (words,), dtype=torch.int64, device=DEV))
+    for fill in fills:
+        for _ in range(2):
+            ws = fill.clone().view(torch.uint8)
+            path, bonus, ws = S.seq_verify(*args, workspace=ws)
+            torch.cuda.synchronize()
+            assert check_verify(v, (path.cpu().numpy(), int(bonus.item()), S.read_verify_trace(ws))) in ("exact", "flagged")

@@ -189,5 +189,5 @@ def test_random_batches_equal_one_call_per_sequence():
         for b in range(B):
             p1, b1, w1 = S.seq_verify_with(alg, tl[b], dl[b], tok[b], parent, T, un[b])
             torch.cuda.synchronize()
-            assert S.read_verify_trace(ws[b])["status"] == 0 and S.read_verify_trace(w1)["status"] == 0
+            assert S.read_verify_trace(ws[b])["status"] == 0 and S.read_verify_trace(w1)["status"] == 0, (case, n, V, B, T, alg, b)
             assert torch.equal(path[b], p1) and int(bonus[b].item()) == int(b1.item()), (case, n, V, B, T, alg, b)

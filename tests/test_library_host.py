@@ -360,3 +360,34 @@ def test_nothing_is_allocated_under_stream_capture(host_memory):
     assert rc == B.SEQ_OK
     assert _plan_pointers(lib, tree, stream=0x2001) == (B.SEQ_OK, ptrs)   # ... and the capture finds the plan
     assert "capture" in S.strerror(B.SEQ_ERR_CAPTURE)
+
+
+def test_no_kernel_needs_the_dispatch_packet_or_scratch_memory(tmp_path):
+    """Compiled as shipped, no kernel may ask for the pointer to its dispatch packet (the packet
+    lives in host memory: reading the workgroup size from it -- which is what a per-thread array
+    that ends up in shared memory makes the compiler do -- costs every launch several
+    microseconds) and none may spill registers to scratch memory."""
+    import re
+    import subprocess
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2402_12374_amd import build as lib_build
+
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+    def assembly_of(src):
+        out = tmp_path / (os.path.basename(src) + ".s")
+        subprocess.run([hipcc] + lib_build.HIPCC_FLAGS + ["--cuda-device-only", "-S", src, "-o", str(out)], check=True,
+                       stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+        return out.read_text()
+
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        listings = list(pool.map(assembly_of, lib_build.sources()))
+    kernels = 0
+    for src, text in zip(lib_build.sources(), listings):
+        for block in re.findall(r"\.amdhsa_kernel (\S+)(.*?)\.end_amdhsa_kernel", text, flags=re.S):
+            name, body = block
+            kernels += 1
+            assert ".amdhsa_user_sgpr_dispatch_ptr 1" not in body, (src, name)
+            assert ".amdhsa_user_sgpr_queue_ptr 1" not in body, (src, name)
+            assert re.search(r"\.amdhsa_private_segment_fixed_size 0\b", body), (src, name)
+    assert kernels >= 20
