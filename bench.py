@@ -237,12 +237,14 @@ class Workload:
         # against the HBM peak; (2) the bytes of the method's minimum -- only the rows of the nodes the walk visits.
         e = 2 if self.tdt == torch.bfloat16 else 4
         lazy_bytes = (len(self.path0) + 1) * 2 * V * e
-        per_node = self.T > 0 and V <= 32768 and n <= 256   # the library's own choice of kernel (include/seqtree.h)
         kids = W.children_lists(self.parent)
         leaves = sum(1 for ch in kids if not ch)
-        moved = ((n - leaves) * 2 + leaves) * V * e if per_node else lazy_bytes
+        # the library's own choice of kernel (include/seqtree.h): a workgroup per node, a team per node with children, or the lazy walk
+        per_node = self.T > 0 and V <= 32768 and n <= 256
+        teams = self.T > 0 and V > 32768 and (n - leaves) * ((V + 16383) // 16384) <= 256 and n > leaves
+        moved = ((n - leaves) * 2 + leaves) * V * e if per_node else (n - leaves) * 2 * V * e if teams else lazy_bytes
         moved_gbs = moved / (verify_us * 1e-6) / 1e9
-        verify = {"kernel": "verify_chains_kernel" if per_node else "verify_walk_kernel",
+        verify = {"kernel": "verify_chains_kernel" if per_node else "verify_chains_kernel (teams)" if teams else "verify_walk_kernel",
                   "bound": "hbm", "achieved": round(moved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                   "frac": round(moved_gbs / HBM_PEAK_GBS, 5), "traffic": None,
                   "logit_bytes_read_per_launch": moved, "avg_launch_us": round(verify_us, 3), "launch_us_spread": verify_spread,
@@ -258,12 +260,80 @@ class Workload:
                               "rate over its node's sibling chain (modelled %.1f us for %d children), not by HBM" % (chain_us, k_max))
         else:
             verify["note"] = "reads only the rows of visited nodes: a chain of dependent steps, latency-bound by construction"
+        if self.T > 0 and V > 32768 and not teams:
+            # Beyond one workgroup's vocabulary the per-node kernel exists too (a team of workgroups per node that
+            # has children); at this tree size the library does not pick it.  Forced here, to put its figure -- the
+            # streaming efficiency on the bytes it really moves -- beside the lazy walk's.
+            internal = n - leaves
+            self.S.lib().seqtree_internal_set_verify_mode(2)
+            try:
+                self.verify_call(0)
+                torch.cuda.synchronize()
+                assert self.S.read_verify_trace(self.verify_sets[0]["ws"])["status"] == 0
+                eager_us, eager_spread = timed_replays(torch, capture(torch, self.verify_call, idx), self.sets, blocks)
+            finally:
+                self.S.lib().seqtree_internal_set_verify_mode(0)
+            eager_bytes = 2 * internal * V * e
+            eager_gbs = eager_bytes / (eager_us * 1e-6) / 1e9
+            verify["eager_per_node_teams"] = {
+                "kernel": "verify_chains_kernel (teams of %d workgroups per node with children)" % ((V + 16383) // 16384),
+                "bound": "hbm", "achieved": round(eager_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(eager_gbs / HBM_PEAK_GBS, 5), "logit_bytes_read_per_launch": eager_bytes,
+                "avg_launch_us": round(eager_us, 3), "launch_us_spread": eager_spread,
+                "note": "forced for this measurement; every row pair of an internal node is read once, then held in registers "
+                        "for the node's chain of dependent steps"}
         report = {"step_us": round(step_us, 3), "step_us_spread": step_spread, "attn": attn, "verify": verify}
         if len(cfg.temperatures) > 1 and 0.0 in cfg.temperatures:
             greedy = lambda i: self.verify_call(i, temperature=0.0)
             greedy(0)
             report["verify_greedy_us"] = round(timed_replays(torch, capture(torch, greedy, idx), self.sets, blocks)[0], 3)
         return report
+
+
+def small_tree_large_vocab(torch, dev, S, W, blocks, vocab, tree_key="C2"):
+    """seq_verify for a small tree over a large vocabulary -- the case the per-node teams are picked for: the
+    library's own choice against the lazy walk forced, on the same rotating inputs, with a drafter like the
+    configurations' (short accepted paths) and with a good one (the walk runs several nodes deep)."""
+    cfg = W.CONFIGS[tree_key]
+    parent = W.make_tree(cfg, W.seed_for(list(W.CONFIGS).index(tree_key) + 1))
+    n, T = len(parent), 0.6
+    internal = sum(1 for ch in W.children_lists(parent) if ch)
+    out = {"tree": "%s's (%d nodes, %d with children)" % (tree_key, n, internal), "vocab": vocab, "temperature": T}
+    path = torch.empty(n, dtype=torch.int32, device=dev)
+    bonus = torch.empty(1, dtype=torch.int32, device=dev)
+    ws = torch.empty(S.seq_verify_workspace(n, vocab, 1), dtype=torch.uint8, device=dev)
+    for label, sigma_d in (("synthetic_drafter", 2.0), ("good_drafter", 0.3)):
+        sets = []
+        for s_ in range(8):
+            v = W.make_verify_inputs(parent, vocab, 4.0, sigma_d, T, W.BF16, seed=4242 + s_)
+            sets.append((torch.from_numpy(v.target_logits).to(dev).to(torch.bfloat16), torch.from_numpy(v.draft_logits).to(dev).to(torch.bfloat16),
+                         torch.from_numpy(v.tree_tokens).to(dev), torch.from_numpy(v.uniforms).to(dev)))
+
+        def call(i):
+            tl, dl, tok, un = sets[i % len(sets)]
+            S.seq_verify(tl, dl, tok, parent, T, un, accepted_path=path, bonus_token=bonus, workspace=ws)
+
+        row = {}
+        for mode, name in ((0, "library_choice_us"), (1, "lazy_walk_us")):
+            S.lib().seqtree_internal_set_verify_mode(mode)
+            try:
+                lengths = []
+                for i in range(len(sets)):
+                    call(i)
+                    torch.cuda.synchronize()
+                    assert S.read_verify_trace(ws)["status"] == 0
+                    lengths.append(int((path >= 0).sum().item()))
+                us, _ = timed_replays(torch, capture(torch, call, range(len(sets))), len(sets), blocks)
+            finally:
+                S.lib().seqtree_internal_set_verify_mode(0)
+            row[name] = round(us, 3)
+        row["mean_accepted_path"] = round(sum(lengths) / len(lengths), 2)
+        eager_bytes = 2 * internal * vocab * 2
+        row["per_node_bytes_read"] = eager_bytes
+        row["per_node_frac_of_hbm_peak"] = round(eager_bytes / (row["library_choice_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 5)
+        out[label] = row
+        del sets
+    return out
 
 
 def yardstick_copy(torch, S, dev, mib):
@@ -716,6 +786,9 @@ def main() -> int:
     del step_graphs
     head_report = head.measure_kernels(blocks, traffic)
     head.check_results()
+    if head.T > 0 and head.V > 32768:
+        import workloads as W
+        head_report["verify"]["small_tree_same_vocab"] = small_tree_large_vocab(torch, dev, S, W, blocks, head.V)
 
     cpu = None
     if not args.no_cpu_baseline:

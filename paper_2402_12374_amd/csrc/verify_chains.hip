@@ -58,7 +58,7 @@ struct ChainShared {
     int ctl_stop;                      // the child before was accepted: the walk leaves this node through it, nothing after it is needed
     int team_fail;                     // (team) a wait for the other members timed out
     NodeState team_ns;                 // (team) the scalar state of thread 0, kept out of its registers
-    TestState team_before;
+    TestState before[2];               // the state before the rejection of child j, for its accept test (by parity of j)
     BlockPick pick;
     double pick_goal;                  // cumulative residual mass the bonus draw looks for
     int pick_is_mine;                  // (team) the bonus token lies in this member's part of the row
@@ -344,15 +344,25 @@ __device__ void leaf_draw(const LT* row, int V, float slope, float u0, bool vec_
     __syncthreads();
 }
 
-// Every workgroup of a launch passes here when it is done (all sequences of a batched launch
-// count together): the last one moves the tag epoch on for the next launch and clears the count.
-__device__ __forceinline__ void launch_member_done(const VerifyParams& p) {
+// Moving the tag epoch on for the next launch, after every workgroup of this one has read it.
+// One sequence per launch: every workgroup reads the epoch before it does anything else, and the
+// workgroup that walks runs only after all of them have been counted as arrived, so it can move
+// the epoch itself, without waiting for the answer.  Several sequences per launch: a sequence's
+// walk may be over before a workgroup of another sequence has started, so every workgroup of
+// the launch passes through a count of its own when it is done, and the last one moves the epoch.
+template <bool BATCHED>
+__device__ __forceinline__ void launch_member_done(const VerifyParams& p, bool walked) {
     if (threadIdx.x != 0) return;
-    uint32_t* const finished = chain_finished_cell(p.chain_area);
-    const uint32_t total = gridDim.x * gridDim.y;
-    if (__hip_atomic_fetch_add(finished, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == total - 1u) {
-        __hip_atomic_store(finished, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_fetch_add(chain_epoch_cell(p.chain_area), (uint32_t)kVerifyTagsPerCall, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if constexpr (!BATCHED) {
+        if (walked)
+            __hip_atomic_fetch_add(chain_epoch_cell(p.chain_area), (uint32_t)kVerifyTagsPerCall, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        uint32_t* const finished = chain_finished_cell(p.chain_area);
+        const uint32_t total = gridDim.x * gridDim.y;
+        if (__hip_atomic_fetch_add(finished, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == total - 1u) {
+            __hip_atomic_store(finished, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(chain_epoch_cell(p.chain_area), (uint32_t)kVerifyTagsPerCall, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
@@ -381,7 +391,7 @@ __global__ __launch_bounds__(TEAM_NT ? TEAM_NT : kThreads, 4) void verify_chains
             rank = b % W;
         }
         if (team >= p.n_internal) {   // (the grid is rounded up to whole groups of 8 teams)
-            launch_member_done(p);
+            launch_member_done<BATCHED>(p, false);
             return;
         }
         v = p.internal_nodes[team];
@@ -406,18 +416,6 @@ __global__ __launch_bounds__(TEAM_NT ? TEAM_NT : kThreads, 4) void verify_chains
     CHAIN_STAMP_RESET();
     CHAIN_STAMP(0);
     CHAIN_WG_TIME(0);
-    // Ask for a word of everything this workgroup will meet the others in before the rows: the
-    // first access of a launch to a page pays for its address translation, and that way the wait
-    // runs beside the rows' instead of at the first exchange.
-    if (tid < 4) {
-        const unsigned long long* touch = tid == 0 ? child_rec + (size_t)(K > 0 ? p.child_list[c_begin] : v) * kChildRecordWords
-                                          : tid == 1 ? node_rec + (size_t)v * kNodeRecordWords
-                                          : tid == 2 ? reinterpret_cast<const unsigned long long*>(p.arrivals)
-                                          : TEAM ? my_slots : team_fail_cell(p.chain_area);
-        (void)__hip_atomic_load(reinterpret_cast<const unsigned long long*>(reinterpret_cast<uintptr_t>(touch) & ~(uintptr_t)7),
-                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // (the value is not looked at)
-    }
-
     const bool vec_ok = (V % (16 / (int)sizeof(LT)) == 0) &&
                         ((reinterpret_cast<uintptr_t>(p.target) | reinterpret_cast<uintptr_t>(p.draft)) & 15) == 0;
     float pr[EPT], qr[EPT];
@@ -553,10 +551,15 @@ __global__ __launch_bounds__(TEAM_NT ? TEAM_NT : kThreads, 4) void verify_chains
     CHAIN_WG_TIME(1);
 
     // ---- the chain: children in order, each taken as rejected ---------------------------------
-    // Thread 0 owns the scalar state (in a team: thread 0 of every member, all taking the same
-    // steps on the same numbers).  Iteration j: it applies the pass that followed child j-1,
-    // writes that child's record, tests child j and publishes the coefficients of the next pass;
-    // iteration K only closes child K-1 and publishes the coefficients of the bonus draw.
+    // Two wavefronts share the scalar work (in a team: of every member, all taking the same steps
+    // on the same numbers).  The first owns the state: at the top of iteration j its thread 0
+    // applies the pass that followed child j-1, rejects child j and publishes the coefficients
+    // of the next pass -- the only thing everybody waits for.  The second works out, at the same
+    // time, the accept test of child j-1 from the state the first left before rejecting it, and
+    // writes that child's record.  The uniforms are inputs: if that test accepts, the walk will
+    // leave this node through child j-1 and never look at the later children or at this node's
+    // bonus token, so the chain ends here (the step the first wavefront took beside it is
+    // dropped).  Iteration K only closes child K-1.
     //
     // The draft mass left after a rejection is the mass before it minus the rejected token's: as
     // long as a twentieth of the mass is left, thread 0 takes that difference (in fp64; its error
@@ -564,20 +567,21 @@ __global__ __launch_bounds__(TEAM_NT ? TEAM_NT : kThreads, 4) void verify_chains
     // less is left the pass sums q again, which is also what finds the mass exactly zero.
     // (a team member has fewer registers to spare: its thread 0 keeps the state in shared memory)
     NodeState ns_regs;
-    TestState before_regs;
     NodeState& ns = TEAM ? sh.team_ns : ns_regs;
-    TestState& before = TEAM ? sh.team_before : before_regs;
-    bool accepted = false, stopped = false;   // (accepted: thread 0 only)
+    bool stopped = false;
     bool failed = TEAM && __builtin_amdgcn_readfirstlane(sh.team_fail) != 0;
     uint32_t events = 0;
     double q_predicted = 1.0;
     bool q_summed = true;
-    if (tid == 0) { node_begin(ns); ns.fallbacks = 0; ns.degenerate = 0; }
+    if (tid == 0) { node_begin(ns); ns.fallbacks = 0; ns.degenerate = 0; sh.ctl_stop = 0; }
     int par = 1;
     for (int j = 0, j_end = failed ? -1 : K; j <= j_end; ++j) {
         if (TEAM && j > 0) ++step;
         if (wave == 0) {
-            bool exchanged = true;
+            // what the step needs of child j, asked for together with the partials
+            const int tok_j = j < K ? sh.child_tok[j] : 0;
+            const float qs_j = j < K ? sh.child_ld[j] : 0.f;
+            const bool dup_j = j < K && sh.child_dup[j] != 0;
             // lanes 0..15 read the per-wavefront partials (the other rows repeat them)
             const bool have = (lane & 15) < NW;
             const float2 part_w = *reinterpret_cast<const float2*>(sh.part[par ^ 1][lane & 15]);
@@ -590,45 +594,46 @@ __global__ __launch_bounds__(TEAM_NT ? TEAM_NT : kThreads, 4) void verify_chains
                                                      got_w, got_q, unused2, unused3);
                     w_new = wave_reduce<kOpSum>(got_w);
                     q_new = wave_reduce<kOpSum>(got_q);
-                    exchanged = ok;
+                    if (!ok && lane == 0) sh.team_fail = 1;
                 }
             }
             if (tid == 0) {
-                // Everybody waits for the coefficients of the next pass, so they go out first; the
-                // test of child j, which needs the state before its rejection, is worked out from
-                // a copy after the barrier, while the pass runs.  The uniforms are inputs: if that
-                // test accepts, the walk will leave this node through child j and never look at
-                // the later children or at this node's bonus token, so the chain ends at the next
-                // step (the pass under way is the price of not waiting for the test here).
-                sh.ctl_stop = !exchanged ? 2 : accepted ? 1 : 0;   // (2: a member is missing, the team gives up)
-                if (accepted) {
-                    sh.w_rec[j - 1][4] = 0.f;   // no rejection followed child j - 1
-                } else if (j > 0) {
+                if (j > 0) {
                     const int fb = ns.fallbacks, dg = ns.degenerate;
                     node_apply_pass(ns, (double)w_new, q_summed ? (double)q_new : q_predicted);
                     events = (uint32_t)(ns.fallbacks - fb) | ((uint32_t)(ns.degenerate - dg) << 1);
                 }
-                if (j < K && !accepted) {
-                    before = test_state_of(ns);
+                if (j < K) {
+                    sh.before[j & 1] = test_state_of(ns);
                     // (SpecInfer: the draft distribution stays what it was -- nothing is struck out)
-                    const bool in_s = !p.with_replacement && sh.child_dup[j] != 0;
+                    const bool in_s = !p.with_replacement && dup_j;
                     const bool strike = !in_s && !p.with_replacement;
                     node_reject_child(ns, in_s, V, p.with_replacement != 0);
-                    sh.ctl_zero = strike ? sh.child_tok[j] : -1;
-                    q_predicted = ns.massQ - (strike ? (double)sh.child_ld[j] : 0.0);
+                    sh.ctl_zero = strike ? tok_j : -1;
+                    q_predicted = ns.massQ - (strike ? (double)qs_j : 0.0);
                     q_summed = ns.fallback || !(q_predicted >= 0.05);
                     sh.ctl_sum_q = q_summed ? 1 : 0;
                 }
                 sh.ctl_a = ns.af;
                 sh.ctl_b = ns.bf;
             }
+        } else if (tid == 64 && j > 0) {
+            const int c = j - 1;
+            const ChildTest t = node_test_child(sh.before[c & 1], sh.child_lt[c], sh.child_ld[c],
+                                                !p.with_replacement && sh.child_dup[c] != 0, V);
+            sh.w_rec[c][0] = t.lhs_w; sh.w_rec[c][1] = t.lhs_q;
+            sh.w_rec[c][2] = t.rhs_r; sh.w_rec[c][3] = t.rhs_m;
+            sh.ctl_stop = t.accepts(sh.child_u[c]) ? 1 : 0;
         }
         __syncthreads();
         CHAIN_STAMP(10);
-        if (const int stop = __builtin_amdgcn_readfirstlane(sh.ctl_stop)) {
-            if (TEAM && stop == 2) {
+        // (one way out of the loop for both reasons: every exit keeps a copy of the rows alive)
+        if (const int stop = __builtin_amdgcn_readfirstlane(sh.ctl_stop) | (TEAM ? __builtin_amdgcn_readfirstlane(sh.team_fail) << 1 : 0)) {
+            if (TEAM && (stop & 2)) {   // a member is missing: the team gives up
                 failed = true;
             } else {
+                // child j-1 was accepted: no rejection followed it, the children after it are never looked at
+                if (tid == 0) sh.w_rec[j - 1][4] = 0.f;
                 for (int k = j + tid; k < K; k += NT) {
 #pragma unroll
                     for (int w = 0; w < kChildRecordWords; ++w) sh.w_rec[k][w] = 0.f;   // 0 < 0: never accepted
@@ -637,17 +642,8 @@ __global__ __launch_bounds__(TEAM_NT ? TEAM_NT : kThreads, 4) void verify_chains
             }
             break;
         }
-        if (tid == 0) {
-            // records wait in shared memory; they leave together once the chain is done
-            if (j > 0) sh.w_rec[j - 1][4] = __uint_as_float(events);
-            if (j < K) {
-                const ChildTest t = node_test_child(before, sh.child_lt[j], sh.child_ld[j],
-                                                    !p.with_replacement && sh.child_dup[j] != 0, V);
-                sh.w_rec[j][0] = t.lhs_w; sh.w_rec[j][1] = t.lhs_q;
-                sh.w_rec[j][2] = t.rhs_r; sh.w_rec[j][3] = t.rhs_m;
-                accepted = t.accepts(sh.child_u[j]);
-            }
-        }
+        // records wait in shared memory; they leave together once the chain is done
+        if (tid == 0 && j > 0) sh.w_rec[j - 1][4] = __uint_as_float(events);
         if (j == K) break;
         const float af = sh.ctl_a, bf = sh.ctl_b;
         // the rejected token leaves both distributions: only the wavefront that holds it looks
@@ -815,7 +811,7 @@ __global__ __launch_bounds__(TEAM_NT ? TEAM_NT : kThreads, 4) void verify_chains
     CHAIN_STAMP(41);
     CHAIN_WG_TIME(3);
     if (!sh.last) {
-        launch_member_done(p);
+        launch_member_done<BATCHED>(p, false);
         return;
     }
     CHAIN_LAST(0);
@@ -947,7 +943,7 @@ __global__ __launch_bounds__(TEAM_NT ? TEAM_NT : kThreads, 4) void verify_chains
         CHAIN_STAMP(43);
         CHAIN_LAST(3);
     }
-    launch_member_done(p);
+    launch_member_done<BATCHED>(p, true);
 }
 
 }  // namespace

@@ -65,10 +65,11 @@ struct Shared {
     float child_lt[SEQ_MAX_TREE];
     float child_ld[SEQ_MAX_TREE];
     unsigned char child_dup[SEQ_MAX_TREE];  // child's token already carried by an earlier sibling
-    // state of Algorithm 2 at the current node; written by thread 0 only, read after a barrier
+    // What the first wavefront, which keeps the state of Algorithm 2 at the current node in its
+    // registers, tells the others after every step (written by its lane 0, read after a barrier).
     struct {
-        NodeState ns;
-        int action, next, zero_token, ci, n_dec;
+        float af, bf;               // coefficients of the residual for the next pass
+        int action, next, zero_token, n_dec, sums_valid, fallbacks, degenerate;
     } st;
 };
 
@@ -187,29 +188,63 @@ __device__ __forceinline__ void record(const VerifyParams& p, int n_dec, int nod
     }
 }
 
-// One step of Algorithm 2 at the current node, taken by thread 0 alone (a dependent chain of a
-// few dozen scalar operations; every other lane would only repeat it).  Applies the result of
-// the previous vocabulary pass if there was one, then tests the next child: accepted, or
-// rejected (a pass over the vocabulary is needed before the next test), or none is left.
-__device__ void leader_step(const VerifyParams& p, Shared& sh, int c_begin, int c_end, int V,
-                            bool have_pass, double w_new, double q_new) {
-    auto& st = sh.st;
-    if (have_pass) node_apply_pass(st.ns, w_new, q_new);
-    if (st.ci == c_end) { st.action = kActExhausted; return; }
-    const int k = st.ci - c_begin;
-    const int c = sh.child_list[st.ci];
-    const float u = sh.uniform[c];
-    // SpecInfer keeps the draft distribution as it is: no token is ever struck out
-    const bool in_s = !p.with_replacement && sh.child_dup[k] != 0;
-    const ChildTest t = node_test_child(st.ns, sh.child_lt[k], sh.child_ld[k], in_s, V);  // probabilities by now
-    const bool accept = t.accepts(u);
-    record(p, st.n_dec, c, accept, t.ratio(), u);
-    ++st.n_dec;
-    if (accept) { st.action = kActAccepted; st.next = c; return; }
-    node_reject_child(st.ns, in_s, V, p.with_replacement != 0);
-    st.zero_token = (in_s || p.with_replacement) ? -1 : sh.token[c];
-    ++st.ci;
-    st.action = kActPass;
+// The scalar side of Algorithm 2 at the current node, kept by the first wavefront in registers
+// (every lane holds the same values; nothing of it waits for shared memory on the path from a
+// vocabulary sum to the next pass's coefficients), and what it knows of the child that will be
+// tested next, fetched ahead -- while the others' partials are still on their way.
+struct NextChild {
+    int node, token;
+    float u, ps, qs;     // the child's uniform, and both rows' probabilities at its token
+    int dup;             // its token was already carried by an earlier sibling
+};
+struct Leader {
+    NodeState ns;
+    int ci, n_dec;
+    NextChild nx;
+};
+__device__ __forceinline__ void fetch_child(const Shared& sh, Leader& ld, int c_begin, int c_end) {
+    if (ld.ci >= c_end) return;
+    const int k = ld.ci - c_begin;
+    const int c = sh.child_list[ld.ci];
+    ld.nx.node = c;
+    ld.nx.token = sh.token[c];
+    ld.nx.u = sh.uniform[c];
+    ld.nx.ps = sh.child_lt[k];   // probabilities by now
+    ld.nx.qs = sh.child_ld[k];
+    ld.nx.dup = sh.child_dup[k];
+}
+// One step: applies the result of the previous vocabulary pass if there was one, then tests the
+// next child: accepted, or rejected (a pass over the vocabulary is needed before the next
+// test), or none is left.  Publishes the outcome (lane 0) for the other wavefronts.
+__device__ __forceinline__ void leader_step(const VerifyParams& p, Shared& sh, Leader& ld, int c_end, int V,
+                                            bool have_pass, double w_new, double q_new) {
+    if (have_pass) node_apply_pass(ld.ns, w_new, q_new);
+    int action, next = -1, zero_token = -1;
+    if (ld.ci == c_end) {
+        action = kActExhausted;
+    } else {
+        // SpecInfer keeps the draft distribution as it is: no token is ever struck out
+        const bool in_s = !p.with_replacement && ld.nx.dup != 0;
+        const ChildTest t = node_test_child(ld.ns, ld.nx.ps, ld.nx.qs, in_s, V);
+        const bool accept = t.accepts(ld.nx.u);
+        record(p, ld.n_dec, ld.nx.node, accept, t.ratio(), ld.nx.u);
+        ++ld.n_dec;
+        if (accept) {
+            action = kActAccepted;
+            next = ld.nx.node;
+        } else {
+            node_reject_child(ld.ns, in_s, V, p.with_replacement != 0);
+            zero_token = (in_s || p.with_replacement) ? -1 : ld.nx.token;
+            ++ld.ci;
+            action = kActPass;
+        }
+    }
+    if (threadIdx.x == 0) {
+        sh.st.af = ld.ns.af; sh.st.bf = ld.ns.bf;
+        sh.st.action = action; sh.st.next = next; sh.st.zero_token = zero_token;
+        sh.st.n_dec = ld.n_dec; sh.st.sums_valid = ld.ns.sums_valid;
+        sh.st.fallbacks = ld.ns.fallbacks; sh.st.degenerate = ld.ns.degenerate;
+    }
 }
 
 // First wavefront: which workgroup holds the token at cumulative residual mass u * total?
@@ -253,7 +288,9 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
     stage_tree(p, sh);
     uint32_t step = 0;
     int par = 0, v = 0, path_len = 0;
-    if (tid == 0) { sh.st.n_dec = 0; sh.st.ns.fallbacks = 0; sh.st.ns.degenerate = 0; }
+    Leader ld;   // (first wavefront)
+    ld.n_dec = 0; ld.ns.fallbacks = 0; ld.ns.degenerate = 0;
+    if (tid == 0) { sh.st.n_dec = 0; sh.st.fallbacks = 0; sh.st.degenerate = 0; }
     __syncthreads();
 
     for (;;) {
@@ -324,18 +361,19 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
             if (lane == 0) {
                 sh.fail = ok ? 0 : 1;
                 sh.stat[0] = mt; sh.stat[1] = md; sh.stat[2] = 1.0f / zt; sh.stat[3] = 1.0f / zd;
-                auto& st = sh.st;
-                node_begin(st.ns);
-                st.ci = c_begin; st.next = -1;
-                if (ok) leader_step(p, sh, c_begin, c_end, V, false, 0.0, 0.0);
             }
+            node_begin(ld.ns);
+            ld.ci = c_begin;
+            fetch_child(sh, ld, c_begin, c_end);   // (the probabilities above were written by this wavefront)
+            leader_step(p, sh, ld, c_end, V, false, 0.0, 0.0);
+            fetch_child(sh, ld, c_begin, c_end);   // the one after, while everybody turns logits into probabilities
         } else {
             ++step;
         }
         par ^= 1;
         __syncthreads();
         SEQ_STAMP(4);
-        if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.ns.fallbacks, sh.st.ns.degenerate); return; }
+        if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
         {
             const float ft = mt_wave == -INFINITY ? 0.f : exp_fast(mt_wave - sh.stat[0]) * sh.stat[2];
             const float fd = md_wave == -INFINITY ? 0.f : exp_fast(md_wave - sh.stat[1]) * sh.stat[3];
@@ -346,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
         // Algorithm 2 at node v: one vocabulary pass + exchange per rejection
         while (sh.st.action == kActPass) {
             const int zero_token = sh.st.zero_token;
-            const float af = sh.st.ns.af, bf = sh.st.ns.bf;
+            const float af = sh.st.af, bf = sh.st.bf;
             float r_loc = 0.f, q_loc = 0.f;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
@@ -367,19 +405,18 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
                 SEQ_STAMP(11);
                 const float w_new = wave_reduce<kOpSum>(got[0]);
                 const float q_new = wave_reduce<kOpSum>(got[1]);
-                if (lane == 0) {
-                    sh.fail = ok ? 0 : 1;
-                    if (ok) leader_step(p, sh, c_begin, c_end, V, true, (double)w_new, (double)q_new);
-                }
-                if (ok && sh.st.action == kActExhausted && sh.st.ns.sums_valid)
-                    find_bonus_owner(p, sh.uniform[0], got[0], sh);
+                if (lane == 0) sh.fail = ok ? 0 : 1;
+                const bool exhausted = ld.ci == c_end;
+                leader_step(p, sh, ld, c_end, V, true, (double)w_new, (double)q_new);
+                if (ok && exhausted && ld.ns.sums_valid) find_bonus_owner(p, sh.uniform[0], got[0], sh);
+                fetch_child(sh, ld, c_begin, c_end);   // for the step after the pass that starts now
             } else {
                 ++step;
             }
             par ^= 1;
             __syncthreads();
             SEQ_STAMP(12);
-            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.ns.fallbacks, sh.st.ns.degenerate); return; }
+            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
         }
         if (sh.st.action == kActAccepted) {
             const int next = sh.st.next;
@@ -391,9 +428,9 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
         }
 
         // no child accepted: bonus token ~ R by inverse CDF with uniforms[0]
-        const float af = sh.st.ns.af, bf = sh.st.ns.bf;
+        const float af = sh.st.af, bf = sh.st.bf;
         const float u0 = sh.uniform[0];
-        if (!sh.st.ns.sums_valid) {   // no pass has left the workgroups' residual masses yet
+        if (!sh.st.sums_valid) {   // no pass has left the workgroups' residual masses yet
             float r_loc = 0.f;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) r_loc += residual_of(pr[e], qr[e], af, bf);
@@ -408,7 +445,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
                 if (ok) find_bonus_owner(p, u0, got[0], sh);
             }
             __syncthreads();
-            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.ns.fallbacks, sh.st.ns.degenerate); return; }
+            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
         }
         const double total = sh.bonus_d[0], before = sh.bonus_d[1];
         const double goal = (double)u0 * total;
@@ -455,7 +492,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
             if (tid == 0) p.bonus[0] = pick;
         }
         SEQ_STAMP(20);
-        finish(p, path_len, sh.st.n_dec, 0, v, sh.st.ns.fallbacks, sh.st.ns.degenerate);
+        finish(p, path_len, sh.st.n_dec, 0, v, sh.st.fallbacks, sh.st.degenerate);
         return;
     }
 }

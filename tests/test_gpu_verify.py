@@ -9,7 +9,7 @@ import oracle
 import paper_2402_12374_amd as S
 import workloads as W
 
-from gpu_util import DEV, check_verify, run_verify
+from gpu_util import DEV, check_verify, run_verify, to_dev
 
 pytestmark = pytest.mark.gpu
 
