@@ -339,10 +339,14 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     // that everything derived from it would be vector arithmetic and every branch on it a
     // divergent one.  All divisors here are fixed per launch: the host supplies multipliers, and
     // a uniform quotient is three scalar instructions.)
-    const int split = (int)fast_div((uint32_t)idx, p.by_units_per_xcd);
-    const int local = idx - split * units_per_xcd;
+    // Dearest first: the last range of a unit holds the tree tiles (masked, so slower per tile),
+    // and the last query blocks of a head see the most of them.  When a launch takes several
+    // batches of workgroups, what is left for the last batch should be the cheap ones.
+    const int turn = (int)fast_div((uint32_t)idx, p.by_units_per_xcd);
+    const int local = units_per_xcd - 1 - (idx - turn * units_per_xcd);
     const int unit = xcd * units_per_xcd + local;
-    if (split >= S || unit >= total_units) return;
+    if (turn >= S || unit >= total_units) return;
+    const int split = S - 1 - turn;
     const int g = (int)fast_div((uint32_t)unit, p.by_query_blocks);
     const int qb = unit - g * p.query_blocks;
     // The prefix length: one for the whole launch, or -- a batch whose sequences differ in it --
