@@ -128,11 +128,12 @@ class Workload:
     """One configuration's synthetic inputs, resident in HBM: as many K/V/Q sets as the model has layers (so
     that no call finds its inputs in a cache left by the one before) and as many logit sets as 2 GiB hold."""
 
-    def __init__(self, key, torch, dev, sets=0):
+    def __init__(self, key, torch, dev, sets=0, vocab=0):
+        import dataclasses
         import paper_2402_12374_amd as S
         import workloads as W
         self.S, self.W, self.torch, self.key = S, W, torch, key
-        cfg = self.cfg = W.CONFIGS[key]
+        cfg = self.cfg = W.CONFIGS[key] if vocab <= 0 else dataclasses.replace(W.CONFIGS[key], vocab=vocab)
         idx = list(W.CONFIGS).index(key) + 1
         self.tdt = tdt = torch.bfloat16 if cfg.dtype == W.BF16 else torch.float32
         self.code = 1 if tdt == torch.bfloat16 else 2
@@ -151,7 +152,9 @@ class Workload:
                                out=torch.empty(n, H, d, device=dev, dtype=tdt)) for _ in range(sets)]
         e = 2 if tdt == torch.bfloat16 else 4
         self.n_vsets = max(1, min(sets, 32, (2 << 30) // (2 * n * V * e)))
-        self.host0 = W.verify_inputs_for(key)  # set 0 comes from the seeded host generator
+        # set 0 comes from the seeded host generator
+        self.host0 = W.verify_inputs_for(key) if vocab <= 0 else W.make_verify_inputs(
+            parent, V, cfg.sigma_target, cfg.sigma_draft, T, cfg.dtype, seed=W.seed_for(idx))
         children = [(node, ch) for node, ch in enumerate(W.children_lists(parent)) if ch]
         self.verify_sets = []
         for s in range(self.n_vsets):
@@ -690,6 +693,9 @@ def main() -> int:
                     help="for profilers: launch --warmup + --steps steps of --config from Python, no HIP graph, print a short "
                          "line and stop (per-dispatch counters and kernel traces then see one dispatch per call)")
     ap.add_argument("--cpu-seconds", type=float, default=16.0)
+    ap.add_argument("--vocab", type=int, default=0, help="vocabulary of the headline workload (0 = the configuration's)")
+    ap.add_argument("--verify-kernel", choices=("auto", "lazy", "per-node"), default="auto",
+                    help="force the lazy walk, or the per-node kernels wherever temperature and algorithm allow them")
     ap.add_argument("--yardstick-mib", type=int, default=0,
                     help="after the timed region, also launch a plain copy kernel of this many MiB four times "
                          "(the known-size reference for HBM traffic counters collected with rocprofv3 --pmc)")
@@ -742,7 +748,9 @@ def main() -> int:
     blocks = max(20, args.blocks)
 
     # ---- the headline workload: exactly --steps steps after --warmup steps ------------------
-    head = Workload(args.config, torch, dev, sets=args.sets)
+    head = Workload(args.config, torch, dev, sets=args.sets, vocab=args.vocab)
+    if args.verify_kernel != "auto":
+        S.lib().seqtree_internal_set_verify_mode({"lazy": 1, "per-node": 2}[args.verify_kernel])
     if args.eager:
         for i in range(args.warmup):
             head.step(i)
