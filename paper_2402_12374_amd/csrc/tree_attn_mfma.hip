@@ -31,8 +31,8 @@
 // are filled with a copy of the last valid row (never with memory outside the valid range).
 //
 // When the key axis is cut into several ranges, every workgroup leaves (max, normaliser,
-// unnormalised output) in the workspace and the last one to arrive for a unit merges them by
-// log-sum-exp; no workgroup ever waits for another.
+// normalised output in fp16) in the workspace and the last one to arrive for a unit merges them
+// by log-sum-exp; no workgroup ever waits for another.
 #include <algorithm>
 #include <type_traits>
 #include <utility>
@@ -49,6 +49,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
@@ -658,8 +659,14 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     //   o[cell][k4][lane][4]   unnormalised output; k4 = b*4 + rq holds features
     //                          b*32 + rq*8 + half*4 .. +3 of query (lane % 32), half = lane / 32
     //   ml[cell][2][64]        running maximum and (per-lane part of the) normaliser
+    // A range's partial result in the workspace has the same shape, but its output is normalised
+    // and kept in fp16 (half the bytes to write, and to pull through one CU at the merge): a convex
+    // combination of V rows is as large as V's entries at most, round-toward-zero conversion
+    // saturates instead of overflowing, and 11 bits of a value that is then weighted and rounded
+    // to bf16's 8 leave the result where fp32 partial results put it (bf16 ones do not).
+    //   part[k4][lane]         4 x fp16;   then [2][64] fp32: reference and the query's normaliser
     constexpr int kK4 = kDBlocks * 4;
-    const size_t block_words = (size_t)kK4 * 256 + 128;            // one (unit, range, query block)
+    const size_t block_words = (size_t)kK4 * 128 + 128;            // one (unit, range, query block)
     float* const my_part = p.partials + ((size_t)unit * S + split) * WQ * block_words;
     // 8-byte store of four consecutive output features of my query (the row block of my wavefront)
     uint16_t* const out_row = p.out + ((size_t)qi[0] * p.H + qh[0]) * D + half * 4;
@@ -679,20 +686,32 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         return make_float4(oacc[0][k4 >> 2][(k4 & 3) * 4], oacc[0][k4 >> 2][(k4 & 3) * 4 + 1],
                            oacc[0][k4 >> 2][(k4 & 3) * 4 + 2], oacc[0][k4 >> 2][(k4 & 3) * 4 + 3]);
     };
-    float* const part_ml = my_part + (size_t)wqw * block_words + (size_t)kK4 * 256;
-    float4* const part_o = reinterpret_cast<float4*>(my_part + (size_t)wqw * block_words) + lane;
+    float* const part_ml = my_part + (size_t)wqw * block_words + (size_t)kK4 * 128;
+    uint2* const part_o = reinterpret_cast<uint2*>(my_part + (size_t)wqw * block_words) + lane;
+    auto store_part = [&](int k4, float4 acc, float inv) __attribute__((always_inline)) {
+        uint2 w;
+        w.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(acc.x * inv, acc.y * inv));
+        w.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(acc.z * inv, acc.w * inv));
+        part_o[k4 * 64] = w;
+    };
+    // (a query whose keys in this range are all masked has normaliser and output 0)
+    auto whole_normaliser = [&](float mine) __attribute__((always_inline)) {
+        const auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(mine), __float_as_uint(mine), false, false);
+        return __uint_as_float(r2[0]) + __uint_as_float(r2[1]);
+    };
     if constexpr (WK == 1) {
         // my row block is in my registers
+        const float l_all = whole_normaliser(l_run[0]);
         if (S == 1) {
-            const auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run[0]), __float_as_uint(l_run[0]), false, false);
-            const float inv = __builtin_amdgcn_rcpf(__uint_as_float(r2[0]) + __uint_as_float(r2[1]));
+            const float inv = __builtin_amdgcn_rcpf(l_all);
 #pragma unroll
             for (int k4 = 0; k4 < kK4; ++k4) store_out(k4, item_of(k4), inv);
         } else {
+            const float inv = l_all > 0.f ? __builtin_amdgcn_rcpf(l_all) : 0.f;
 #pragma unroll
-            for (int k4 = 0; k4 < kK4; ++k4) part_o[k4 * 64] = item_of(k4);
+            for (int k4 = 0; k4 < kK4; ++k4) store_part(k4, item_of(k4), inv);
             part_ml[lane] = m_run[0];
-            part_ml[64 + lane] = l_run[0];
+            part_ml[64 + lane] = l_all;
         }
     } else {
         // Every wavefront drops its cell; wavefront (row block q, key group j) then merges items
@@ -750,17 +769,18 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
             else fold(std::integral_constant<int, 3>{});
         }
         static_assert(WK == 2 || WK == 4, "one fold per key group");
+        const float l_all = whole_normaliser(lsum);
         if (S == 1) {
-            const auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
-            const float inv = __builtin_amdgcn_rcpf(__uint_as_float(r2[0]) + __uint_as_float(r2[1]));
+            const float inv = __builtin_amdgcn_rcpf(l_all);
 #pragma unroll
             for (int i = 0; i < kMine; ++i) store_out(wk * kMine + i, acc[i], inv);
         } else {
+            const float inv = l_all > 0.f ? __builtin_amdgcn_rcpf(l_all) : 0.f;
 #pragma unroll
-            for (int i = 0; i < kMine; ++i) part_o[(wk * kMine + i) * 64] = acc[i];
+            for (int i = 0; i < kMine; ++i) store_part(wk * kMine + i, acc[i], inv);
             if (wk == 0) {
                 part_ml[lane] = big;
-                part_ml[64 + lane] = lsum;
+                part_ml[64 + lane] = l_all;
             }
         }
     }
@@ -811,12 +831,12 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         constexpr int kBatch = kFit < kItems ? kFit : kItems;
         static_assert(kItems % kBatch == 0, "batches");
         // (addresses: a uniform base per range and item, plus the lane)
-        const float4* const src = reinterpret_cast<const float4*>(row_part) + (wk * kItems) * 64;
-        float4 v[2][kBatch][NS];   // two batches: one being summed, one in flight
-        auto request = [&](int k0, float4 (&dst)[kBatch][NS]) __attribute__((always_inline)) {
+        const uint2* const src = reinterpret_cast<const uint2*>(row_part) + (wk * kItems) * 64;
+        uint2 v[2][kBatch][NS];   // two batches: one being summed, one in flight
+        auto request = [&](int k0, uint2 (&dst)[kBatch][NS]) __attribute__((always_inline)) {
 #pragma unroll
             for (int r = 0; r < NS; ++r) {
-                const float4* const src_r = src + (size_t)min(r, S - 1) * (range_words / 4) + k0 * 64;
+                const uint2* const src_r = src + (size_t)min(r, S - 1) * (range_words / 2) + k0 * 64;
 #pragma unroll
                 for (int j = 0; j < kBatch; ++j) dst[j][r] = src_r[j * 64 + lane];
             }
@@ -825,7 +845,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         float f[NS];
         float lsum = 0.f;
         {
-            const float* ml = row_part + (size_t)kK4 * 256;
+            const float* ml = row_part + (size_t)kK4 * 128;
             float mv[NS], lv[NS];
 #pragma unroll
             for (int r = 0; r < NS; ++r) {
@@ -838,21 +858,23 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
             for (int r = 0; r < NS; ++r) big = fmaxf(big, mv[r]);
             const float ref = (big == -INFINITY) ? 0.f : big;
 #pragma unroll
+            // a range's weight: its normaliser brought to the common reference (its output is
+            // normalised already)
             for (int r = 0; r < NS; ++r) {
-                f[r] = r < S ? __builtin_amdgcn_exp2f(mv[r] - ref) : 0.f;
-                lsum = fmaf(lv[r], f[r], lsum);
+                f[r] = r < S ? __builtin_amdgcn_exp2f(mv[r] - ref) * lv[r] : 0.f;
+                lsum += f[r];
             }
         }
-        const auto l2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
-        const float inv = __builtin_amdgcn_rcpf(__uint_as_float(l2[0]) + __uint_as_float(l2[1]));
-        auto sum_up = [&](int k0, const float4 (&src_v)[kBatch][NS]) __attribute__((always_inline)) {
+        const float inv = __builtin_amdgcn_rcpf(lsum);
+        auto sum_up = [&](int k0, const uint2 (&src_v)[kBatch][NS]) __attribute__((always_inline)) {
 #pragma unroll
             for (int j = 0; j < kBatch; ++j) {
                 float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
                 for (int r = 0; r < NS; ++r) {
-                    acc.x = fmaf(src_v[j][r].x, f[r], acc.x); acc.y = fmaf(src_v[j][r].y, f[r], acc.y);
-                    acc.z = fmaf(src_v[j][r].z, f[r], acc.z); acc.w = fmaf(src_v[j][r].w, f[r], acc.w);
+                    const half2_t lo = __builtin_bit_cast(half2_t, src_v[j][r].x), hi = __builtin_bit_cast(half2_t, src_v[j][r].y);
+                    acc.x = fmaf((float)lo[0], f[r], acc.x); acc.y = fmaf((float)lo[1], f[r], acc.y);
+                    acc.z = fmaf((float)hi[0], f[r], acc.z); acc.w = fmaf((float)hi[1], f[r], acc.w);
                 }
                 store_out(wk * kItems + k0 + j, acc, inv);
             }
@@ -927,7 +949,7 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     }
     s.query_blocks = (rows + 32 * s.wq - 1) / (32 * s.wq);
     const int units = Hk * s.query_blocks;
-    const size_t block_words = (size_t)(D / 32) * 4 * 256 + 128;   // one (unit, range, query block)
+    const size_t block_words = (size_t)(D / 32) * 4 * 128 + 128;   // one (unit, range, query block): fp16 output, fp32 statistics
     s.workspace_bytes = s.splits > 1 ? (size_t)units * s.splits * s.wq * block_words * sizeof(float) : 0;
     if (s.workspace_bytes < 256) s.workspace_bytes = 256;
     return s;

@@ -245,9 +245,9 @@ def test_noalloc_attn_argument_errors_and_size_limit_need_no_gpu():
     assert call(dtype=7) == B.SEQ_ERR_DTYPE
     assert call(parent=[-1, 0, 2, 1]) == B.SEQ_ERR_TREE
     # more partial results than the static array holds: refused before anything touches a GPU
-    par = W.geometric_tree(256, 12)
-    assert S.seq_tree_attn_workspace(131072, 256, 16, 8, 128, B.SEQ_BF16) > 32 << 20
-    assert call(parent=par, prefix_len=131072, cap=131072, heads=16, kv_heads=8, head_dim=128) == B.SEQ_ERR_WORKSPACE
+    par = W.geometric_tree(1024, 12)
+    assert S.seq_tree_attn_workspace(131072, 1024, 56, 8, 128, B.SEQ_BF16) > B.SEQ_NOALLOC_MAX_PARTIAL_BYTES
+    assert call(parent=par, prefix_len=131072, cap=131072, heads=56, kv_heads=8, head_dim=128) == B.SEQ_ERR_WORKSPACE
 
 
 def test_batched_attn_argument_errors_need_no_gpu():

@@ -57,11 +57,22 @@ def test_what_exceeds_the_static_array_is_refused_and_the_ordinary_call_goes_on_
     a = W.make_attn_inputs(4, 2, 128, 100, W.geometric_tree(20, 4), W.BF16, seed=9)
     tensors = [to_dev(x, a.dtype) for x in (a.q, a.k_cache, a.v_cache, a.k_tree, a.v_tree)]
     out = torch.empty_like(tensors[0])
-    # 8 KV heads x 512 query rows over a prefix of 131072 keys: 33 MiB of partial results
-    assert S.seq_tree_attn_workspace(131072, 256, 16, 8, 128, S.binding.SEQ_BF16) > 32 << 20
-    parent = np.ascontiguousarray(W.geometric_tree(256, 12), np.int32)
+    # 8 KV heads x 7168 query rows over a prefix of 131072 keys: 119 MiB of partial results
+    assert S.seq_tree_attn_workspace(131072, 1024, 56, 8, 128, S.binding.SEQ_BF16) > S.binding.SEQ_NOALLOC_MAX_PARTIAL_BYTES
+    parent = np.ascontiguousarray(W.geometric_tree(1024, 12), np.int32)
     rc = S.lib().seq_tree_attn_noalloc(tensors[0].data_ptr(), tensors[1].data_ptr(), tensors[2].data_ptr(),
-                                       tensors[3].data_ptr(), tensors[4].data_ptr(), parent.ctypes.data, 131072, 256,
-                                       16, 8, 128, out.data_ptr(), 131072, S.binding.SEQ_BF16, None)
+                                       tensors[3].data_ptr(), tensors[4].data_ptr(), parent.ctypes.data, 131072, 1024,
+                                       56, 8, 128, out.data_ptr(), 131072, S.binding.SEQ_BF16, None)
     assert rc == S.binding.SEQ_ERR_WORKSPACE     # refused on the host: nothing was launched on these small buffers
     assert np.array_equal(run_noalloc(a), run_attn(a))
+
+
+def test_the_largest_configuration_fits_the_static_array():
+    a = W.attn_inputs_for("C5")      # 192 units x 4 key ranges: 51 MiB of partial results
+    need = S.seq_tree_attn_workspace(a.prefix_len, 768, 64, 8, 128, S.binding.SEQ_BF16)
+    assert 32 << 20 < need <= S.binding.SEQ_NOALLOC_MAX_PARTIAL_BYTES
+    small = W.make_attn_inputs(8, 2, 128, 300, W.geometric_tree(24, 5), W.BF16, seed=15, prefix_cap=310)
+    got, got_small = run_noalloc(a), run_noalloc(small)
+    assert np.array_equal(got, run_attn(a))
+    assert np.array_equal(got_small, run_attn(small))
+    assert np.abs(got_small - oracle_attn(small)).max() <= TOL[small.dtype]
