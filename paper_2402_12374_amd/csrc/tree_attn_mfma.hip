@@ -140,13 +140,19 @@ template <int D> __device__ __forceinline__ int v_swizzle(int row) {
 #ifndef SEQTREE_STAMP_THREAD
 #define SEQTREE_STAMP_THREAD 0
 #endif
+#ifndef SEQTREE_STAMP_BLOCK
+#define SEQTREE_STAMP_BLOCK 0
+#endif
+#ifndef SEQTREE_STAMP_WANTED
+#define SEQTREE_STAMP_WANTED(id) true   // e.g. ((id) < 10 || (id) >= 20): everything but the tile loop
+#endif
 __device__ long long g_attn_stamps[128];
 __device__ int g_attn_stamp_count;
 __device__ long long g_attn_wg_times[2 * 4096];   // start and end of every workgroup
 #define ATTN_STAMP_RESET() __shared__ long long s_stamps[128]; int stamp_count = 0; \
-    const bool stamp_on = blockIdx.x == 0 && threadIdx.x == SEQTREE_STAMP_THREAD; \
+    const bool stamp_on = blockIdx.x == SEQTREE_STAMP_BLOCK && threadIdx.x == SEQTREE_STAMP_THREAD; \
     if (threadIdx.x == 0 && blockIdx.x < 4096) { g_attn_wg_times[2 * blockIdx.x] = wall_clock64(); g_attn_wg_times[2 * blockIdx.x + 1] = 0; }
-#define ATTN_STAMP(id) do { if (stamp_on && stamp_count < 63) { \
+#define ATTN_STAMP(id) do { if (stamp_on && stamp_count < 63 && SEQTREE_STAMP_WANTED(id)) { \
     s_stamps[2 * stamp_count] = (id); s_stamps[2 * stamp_count + 1] = wall_clock64(); ++stamp_count; } } while (0)
 #define ATTN_STAMP_FLUSH() do { if (stamp_on) { \
     for (int i = 0; i < 2 * stamp_count; ++i) g_attn_stamps[i] = s_stamps[i]; g_attn_stamp_count = stamp_count; } \
@@ -826,8 +832,10 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     auto merge_ranges = [&](auto ns_c) __attribute__((always_inline)) {
         constexpr int NS = decltype(ns_c)::value;
         constexpr int kItems = kK4 / WK;                                 // per lane
-        // items requested together: the largest power of two with at most 16 requests per lane
-        constexpr int kFit = NS <= 2 ? 8 : (NS <= 4 ? 4 : (NS <= 8 ? 2 : 1));
+        // items requested together: the largest power of two with at most 32 requests (of 8 bytes)
+        // per lane; the partial results were written a long time ago and come from memory, so a
+        // batch is a full round trip
+        constexpr int kFit = NS <= 2 ? 16 : (NS <= 4 ? 8 : (NS <= 8 ? 4 : 2));
         constexpr int kBatch = kFit < kItems ? kFit : kItems;
         static_assert(kItems % kBatch == 0, "batches");
         // (addresses: a uniform base per range and item, plus the lane)
