@@ -348,7 +348,7 @@ size_t seq_tree_attn_batched_workspace(int32_t max_prefix_len, int32_t batch, in
  * array's address and measures how the GPU places workgroups (a small kernel on the null stream
  * and a synchronous read-back): make it outside stream capture (SEQ_ERR_CAPTURE otherwise).
  */
-#define SEQ_NOALLOC_MAX_PARTIAL_BYTES (64u << 20)
+#define SEQ_NOALLOC_MAX_PARTIAL_BYTES (32u << 20)
 int seq_tree_attn_noalloc(const void* q, const void* k_cache, const void* v_cache,
                           const void* k_tree, const void* v_tree, const int32_t* parent,
                           int32_t prefix_len, int32_t n_tree, int32_t heads, int32_t kv_heads,

@@ -26,7 +26,7 @@ SEQ_MAX_CHILDREN = 64
 SEQ_MAX_PLANS = 1024
 SEQ_MAX_STREAMS = 16
 SEQ_MAX_BATCH = 4096
-SEQ_NOALLOC_MAX_PARTIAL_BYTES = 64 << 20
+SEQ_NOALLOC_MAX_PARTIAL_BYTES = 32 << 20
 TRACE_HEADER_INTS, TRACE_RECORD_WORDS = 8, 4
 
 EXPORTS = ("seq_tree_attn", "seq_tree_attn_noalloc", "seq_tree_attn_batched", "seq_tree_attn_batched_workspace", "seq_verify", "seq_verify_with", "seq_verify_batched", "seq_draft_sample", "seq_kv_append", "seq_top_p_filter", "seq_tree_attn_workspace",

@@ -19,6 +19,7 @@ struct AttnSchedule {
     int wq;             // query blocks per workgroup: 2, 4 or 8
     int query_blocks;   // units per KV head
     int splits;
+    int short_ranges, short_weight, long_weight;   // the first short_ranges ranges have weight short_weight, the others long_weight (equal ranges: 0, 1, 1)
     size_t workspace_bytes;
 };
 constexpr int kKeyTile = 32;

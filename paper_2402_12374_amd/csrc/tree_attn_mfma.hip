@@ -72,12 +72,23 @@ struct MfmaParams {
     const int32_t* prefix_lens;   // [sequences] or null: a prefix length per sequence of a batch
     FastDiv by_seq_kv_heads;      // KV heads per sequence (KV head g belongs to sequence g / that)
     int splits;
+    int short_ranges, short_weight, long_weight;   // the first short_ranges key ranges of a unit have weight short_weight, the others long_weight
     float* partials;
     uint32_t* counters;
     float scale_log2;     // log2(e) / sqrt(D)
     int share_l2;         // all workgroups of a unit run on one XCD (checked once per device)
-    FastDiv by_units_per_xcd, by_query_blocks, by_G, by_splits;   // the divisions of the prologue
+    FastDiv by_units_per_xcd, by_query_blocks, by_G, by_weights;   // the divisions of the prologue (by_weights: by the sum of the ranges' weights)
 };
+
+// First tile of key range `range` of a unit with `tiles` tiles.  The first `short_ranges` ranges
+// have weight `short_weight`, the others `long_weight`; `by_weights` divides by the sum of all
+// weights (equal ranges: no short ones, weight 1, the sum is their number).  tiles x sum < 2^31.
+__host__ __device__ __forceinline__ int range_start(int tiles, int range, int short_ranges, int short_weight, int long_weight,
+                                                    const FastDiv& by_weights) {
+    const int before = range <= short_ranges ? range * short_weight
+                                             : short_ranges * short_weight + (range - short_ranges) * long_weight;
+    return (int)fast_div((uint32_t)tiles * (uint32_t)before, by_weights);
+}
 
 // A pointer that is the same in every lane, moved to scalar registers whatever the compiler
 // believes about it.
@@ -330,7 +341,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     // The arguments span four cache lines that nobody has touched yet; left to itself the compiler
     // fetches them in three groups where they are first needed, a trip to memory each.  Asking
     // for one field of every line here puts all of them in flight at once.
-    asm volatile("" :: "s"(p.q), "s"(p.words_per_row), "s"(p.scale_log2), "s"(p.by_splits.one));
+    asm volatile("" :: "s"(p.q), "s"(p.words_per_row), "s"(p.scale_log2), "s"(p.by_weights.one));
     const int S = p.splits;
     const int bid = blockIdx.x;
     // Consecutive workgroup ids go to consecutive XCDs, each with its own L2.  Give every XCD a
@@ -391,8 +402,8 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     const int tree_tiles = i_max / kKeyTile + 1;
     const int total_tiles = prefix_tiles + tree_tiles;
     // (at most 2^26 tiles times 16 ranges: below 2^31)
-    const int t_begin = (int)fast_div((uint32_t)total_tiles * (uint32_t)split, p.by_splits);
-    const int t_end = (int)fast_div((uint32_t)total_tiles * (uint32_t)(split + 1), p.by_splits);
+    const int t_begin = range_start(total_tiles, split, p.short_ranges, p.short_weight, p.long_weight, p.by_weights);
+    const int t_end = range_start(total_tiles, split + 1, p.short_ranges, p.short_weight, p.long_weight, p.by_weights);
     const int n_rounds = (t_end - t_begin + WK - 1) / WK;
 
     const uint32_t k_lds = lds_address(&sm.k[0][0]);
@@ -938,6 +949,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
 
 int g_splits_override = 0;  // tuning hooks, 0 = automatic
 int g_wq_override = 0;
+int g_uneven_override = -1, g_short_weight_override = 1, g_long_weight_override = 1;   // -1 = automatic, 0 = equal ranges only, m > 0 = m short ranges
 
 AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     AttnSchedule s;
@@ -957,6 +969,8 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     long best = -1;
     s.wq = wq_cover;
     s.splits = 1;
+    s.short_ranges = 0;
+    s.short_weight = s.long_weight = 1;
     for (int wq = 2; wq <= wq_cover; wq *= 2) {
         if (g_wq_override > 0 && wq != std::min(g_wq_override, wq_cover)) continue;
         const int wk = kMaxCells / wq;
@@ -968,8 +982,37 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
             const long batches = ((long)units * cand + 255) / 256;
             const long rounds = (tiles + cand * wk - 1) / (cand * wk);
             const long cost = batches * (rounds * round_cost + 100 + (cand > 1 ? 5 * cand * wq / 2 : 0));
-            if (best < 0 || cost < best) { best = cost; s.wq = wq; s.splits = cand; }
+            if (best < 0 || cost < best) { best = cost; s.wq = wq; s.splits = cand; s.short_ranges = 0; s.short_weight = s.long_weight = 1; }
         }
+        // Ranges of two sizes.  When the units leave CUs over but too few for another range each
+        // (192 units: 64), equal ranges either leave those CUs idle or come in several batches,
+        // each workgroup of which pays the fixed part again.  Instead every unit gets `longs`
+        // long ranges, whose workgroups are dispatched first and take a CU each, and one short
+        // range; the short ones run k in a row on the CUs left over, and the weights are chosen so
+        // that both kinds end together.  One prologue, epilogue and partial result per long range instead
+        // of one per batch.
+        if (g_splits_override > 0 || g_uneven_override >= 0) continue;
+        for (int longs = 1; longs * units < 256 && longs + 1 <= kMaxSplits; ++longs) {
+            const int left_over = 256 - longs * units;
+            const long k = (units + left_over - 1) / left_over;
+            if (k < 2) continue;   // (k = 1 is longs + 1 equal ranges in one batch)
+            if (k > 3) break;      // (measured: with more short ranges in a row their fixed parts eat the gain)
+            // the long ranges' share f of a unit's tiles for which a long workgroup takes as long
+            // as k short ones in a row, in 64ths
+            const long all_rounds = (tiles + wk - 1) / wk, fixed = 100, merge = 5 * (longs + 1) * wq / 2;
+            const long num = k * all_rounds * round_cost + (k - 1) * fixed - merge, den = all_rounds * round_cost * (1 + k * longs);
+            const int long_w = (int)((64 * num + den / 2) / den), short_w = 64 - longs * long_w;
+            if (long_w < 1 || short_w < 1) continue;
+            const long rounds_long = ((long)tiles * long_w / 64 + wk) / wk, rounds_short = ((long)tiles * short_w / 64 + wk) / wk;
+            if (rounds_short < 16) continue;   // (measured: short ranges of a few rounds are all fixed part, which the model overrates evenly but not here)
+            const long cost = std::max(rounds_long * round_cost + fixed + merge, k * (rounds_short * round_cost + fixed));
+            if (cost < best) { best = cost; s.wq = wq; s.splits = longs + 1; s.short_ranges = 1; s.short_weight = short_w; s.long_weight = long_w; }
+        }
+    }
+    if (g_uneven_override > 0 && g_uneven_override < s.splits) {
+        s.short_ranges = g_uneven_override;
+        s.short_weight = g_short_weight_override;
+        s.long_weight = g_long_weight_override;
     }
     s.query_blocks = (rows + 32 * s.wq - 1) / (32 * s.wq);
     const int units = Hk * s.query_blocks;
@@ -1008,7 +1051,10 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
     p.by_units_per_xcd = make_fast_div((uint32_t)((units + 7) >> 3));
     p.by_query_blocks = make_fast_div((uint32_t)sched.query_blocks);
     p.by_G = make_fast_div((uint32_t)(H / Hk));
-    p.by_splits = make_fast_div((uint32_t)sched.splits);
+    p.short_ranges = sched.short_ranges;
+    p.short_weight = sched.short_weight;
+    p.long_weight = sched.long_weight;
+    p.by_weights = make_fast_div((uint32_t)(sched.short_ranges * sched.short_weight + (sched.splits - sched.short_ranges) * sched.long_weight));
     if (units > kAttnMaxCounters) return SEQ_ERR_SHAPE;
     const int unit_groups = (units + 7) / 8;
     const dim3 grid((unsigned)(unit_groups * 8 * sched.splits)), block(512);
@@ -1044,5 +1090,19 @@ extern "C" int seqtree_internal_read_attn_stamps(long long* out) {
 #endif
 extern "C" void seqtree_internal_set_attn_splits(int splits) { seqtree::g_splits_override = splits; }
 extern "C" void seqtree_internal_set_attn_wq(int wq) { seqtree::g_wq_override = wq; }
+// The schedule the library would take: {wq, ranges, short ranges, short weight, long weight}.
+extern "C" void seqtree_internal_attn_schedule(int P, int n, int H, int Hk, int D, int* five) {
+    const seqtree::AttnSchedule s = seqtree::plan_attn_schedule(P, n, H, Hk, D);
+    five[0] = s.wq; five[1] = s.splits; five[2] = s.short_ranges; five[3] = s.short_weight; five[4] = s.long_weight;
+}
+extern "C" int seqtree_internal_attn_range_start(int tiles, int range, int ranges, int short_ranges, int short_weight, int long_weight) {
+    const seqtree::FastDiv by = seqtree::make_fast_div((uint32_t)(short_ranges * short_weight + (ranges - short_ranges) * long_weight));
+    return seqtree::range_start(tiles, range, short_ranges, short_weight, long_weight, by);
+}
+extern "C" void seqtree_internal_set_attn_uneven(int short_ranges, int short_weight, int long_weight) {
+    seqtree::g_uneven_override = short_ranges;
+    seqtree::g_short_weight_override = short_weight > 0 ? short_weight : 1;
+    seqtree::g_long_weight_override = long_weight > 0 ? long_weight : 1;
+}
 // the prologue's division by multiplication, evaluated on the host (for the tests)
 extern "C" uint32_t seqtree_internal_fast_div(uint32_t n, uint32_t d) { return seqtree::fast_div(n, seqtree::make_fast_div(d)); }

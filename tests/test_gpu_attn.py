@@ -126,6 +126,44 @@ def test_every_workgroup_shape_and_range_count(d):
         S.lib().seqtree_internal_set_attn_splits(0)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_key_ranges_of_two_sizes(d):
+    """Where the units leave compute units over, the library cuts a unit's keys into long ranges and
+    short ones (several short ones then run in a row on the units left over).  Forced here on a
+    small ragged shape: any number of short ranges, weights from nearly equal to so lopsided that
+    short ranges get a single tile or none."""
+    import paper_2402_12374_amd as S
+    rng = np.random.default_rng(12)
+    a = W.make_attn_inputs(8, 2, d, 1101, W.random_topological_tree(70, rng), W.BF16, seed=d + 1, prefix_cap=1110)
+    ref = oracle_attn(a)
+    try:
+        for wq, splits, shorts, short_w, long_w in ((8, 2, 1, 1, 3), (8, 2, 1, 15, 49), (4, 3, 1, 12, 26), (2, 3, 2, 1, 5),
+                                                    (8, 4, 3, 1, 61), (4, 5, 1, 1, 1), (8, 6, 2, 3, 7), (2, 2, 1, 1, 63),
+                                                    (8, 16, 15, 1, 49), (4, 8, 4, 2, 3)):
+            S.lib().seqtree_internal_set_attn_wq(wq)
+            S.lib().seqtree_internal_set_attn_splits(splits)
+            S.lib().seqtree_internal_set_attn_uneven(shorts, short_w, long_w)
+            err = np.abs(run_attn(a) - ref).max()
+            assert err <= TOL[W.BF16], (wq, splits, shorts, short_w, long_w, err)
+    finally:
+        S.lib().seqtree_internal_set_attn_wq(0)
+        S.lib().seqtree_internal_set_attn_splits(0)
+        S.lib().seqtree_internal_set_attn_uneven(-1, 1, 1)
+
+
+def test_the_shapes_that_take_ranges_of_two_sizes_by_themselves():
+    """Shapes at which the library's own choice is ranges of two sizes (one or two long ranges per
+    unit, workgroups of 8 or 4 row blocks), all rows against the checker."""
+    import ctypes
+    import paper_2402_12374_amd as S
+    five = (ctypes.c_int * 5)()
+    for H, Hk, P, n in ((64, 8, 1024, 640), (64, 8, 2500, 384), (52, 52, 4096, 320)):
+        S.lib().seqtree_internal_attn_schedule(P, n, H, Hk, 128, five)
+        assert five[2] >= 1, (H, Hk, P, n, list(five))
+        a = W.make_attn_inputs(H, Hk, 128, P, W.geometric_tree(n, 10), W.BF16, seed=n)
+        assert np.abs(run_attn(a) - oracle_attn_all_rows(a)).max() <= TOL[W.BF16], (H, Hk, P, n)
+
+
 @pytest.mark.parametrize("H,Hk,P,n", [(4, 4, 700, 40), (16, 2, 1500, 300)])
 @pytest.mark.parametrize("order", ["rising", "falling", "spiky"])
 def test_scores_of_large_and_moving_magnitude(H, Hk, P, n, order):

@@ -391,3 +391,44 @@ def test_no_kernel_needs_the_dispatch_packet_or_scratch_memory(tmp_path):
             assert ".amdhsa_user_sgpr_queue_ptr 1" not in body, (src, name)
             assert re.search(r"\.amdhsa_private_segment_fixed_size 0\b", body), (src, name)
     assert kernels >= 20
+
+
+def test_attention_schedule_takes_ranges_of_two_sizes_where_units_leave_compute_units_over():
+    import ctypes
+    five = (ctypes.c_int * 5)()
+    def schedule(P, n, H, Hk, d=128):
+        S.lib().seqtree_internal_attn_schedule(P, n, H, Hk, d, five)
+        return tuple(five)
+    # the four configurations: equal ranges for the Llama2 and Vicuna shapes; the Llama3-70B one
+    # (192 units on 256 compute units) gets one long and one short range per unit, the long one
+    # about three quarters of the tiles (three short ones run in a row on the 64 units left over)
+    assert schedule(1024, 64, 32, 32)[2:] == (0, 1, 1)
+    assert schedule(2048, 128, 40, 40)[2:] == (0, 1, 1)
+    assert schedule(4096, 256, 52, 52)[2:] == (0, 1, 1)
+    wq, ranges, shorts, short_w, long_w = schedule(8192, 768, 64, 8)
+    assert (wq, ranges, shorts) == (8, 2, 1) and short_w + long_w == 64 and 0.70 <= long_w / 64 <= 0.80
+    # 96 units: two long ranges each (192 compute units) and one short one, two in a row on the other 64
+    wq, ranges, shorts, short_w, long_w = schedule(8192, 384, 64, 8)
+    assert (wq, ranges, shorts) == (8, 3, 1) and short_w + 2 * long_w == 64 and long_w > short_w
+    # short key axes stay with equal ranges: a short range of a few tiles would be all fixed cost
+    assert schedule(512, 768, 64, 8)[2] == 0
+    # a forced number of ranges means equal ranges
+    S.lib().seqtree_internal_set_attn_splits(4)
+    try:
+        assert schedule(8192, 768, 64, 8)[1:] == (4, 0, 1, 1)
+    finally:
+        S.lib().seqtree_internal_set_attn_splits(0)
+
+
+def test_key_ranges_of_either_kind_cut_the_tiles_into_consecutive_pieces():
+    start = S.lib().seqtree_internal_attn_range_start
+    for ranges, shorts, short_w, long_w in ((1, 0, 1, 1), (4, 0, 1, 1), (16, 0, 1, 1), (2, 1, 15, 49), (3, 1, 12, 26),
+                                            (2, 1, 1, 63), (5, 2, 3, 7), (16, 15, 1, 49), (7, 3, 2, 5)):
+        for tiles in list(range(1, 400)) + [1000, 4097, 65536, 1 << 20]:
+            cuts = [start(tiles, r, ranges, shorts, short_w, long_w) for r in range(ranges + 1)]
+            assert cuts[0] == 0 and cuts[-1] == tiles, (ranges, shorts, tiles, cuts)
+            assert all(a <= b for a, b in zip(cuts, cuts[1:])), (ranges, shorts, tiles, cuts)
+            total = shorts * short_w + (ranges - shorts) * long_w
+            for r in range(ranges):   # a range's length is its share of the tiles, to within one tile
+                share = tiles * (short_w if r < shorts else long_w) / total
+                assert abs((cuts[r + 1] - cuts[r]) - share) < 1.0 + 1e-9, (ranges, shorts, tiles, r, cuts)
