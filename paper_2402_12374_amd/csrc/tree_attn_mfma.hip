@@ -73,6 +73,7 @@ struct MfmaParams {
     FastDiv by_seq_kv_heads;      // KV heads per sequence (KV head g belongs to sequence g / that)
     int splits;
     int short_ranges, short_weight, long_weight;   // the first short_ranges key ranges of a unit have weight short_weight, the others long_weight
+    int keep_own;         // a long range's workgroup may keep its partial result in registers (see the end of the tile loop)
     float* partials;
     uint32_t* counters;
     float scale_log2;     // log2(e) / sqrt(D)
@@ -677,8 +678,20 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
 #pragma unroll 1
         for (int rho = 0; rho < n_rounds; ++rho) round(rho, rho % kSlots);
     }
+    // A long range of a two-size schedule ends long after its unit's short range: if every other
+    // range of the unit has been counted as arrived by now, this workgroup is the one that merges,
+    // and its own partial result need not travel through memory.  (One lane asks, beside the
+    // last copies; the answer is shared through the barrier that follows.  Only where the merge
+    // below takes a single batch, so that the kept items are register arrays with literal indices.
+    // Long ranges are what workgroups of eight row blocks get: the kernels for short ranges,
+    // whose epilogue is most of their time, do not carry the code.)
+    constexpr int kKeepUpTo = WK == 1 ? 2 : 0;
+    const bool may_keep = kKeepUpTo > 0 && p.keep_own && p.short_ranges > 0 && split >= p.short_ranges && S <= kKeepUpTo;
+    uint32_t seen_arrived = 0;
+    if (may_keep && tid == 0) seen_arrived = __hip_atomic_load(&p.counters[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     wait_vmcnt<0>();   // nothing of mine may still be landing in LDS when the ring is reused below
     ATTN_STAMP(20);
+    if (tid == 0) s_last = may_keep && seen_arrived == (uint32_t)(S - 1);
 
     // ---- epilogue ---------------------------------------------------------------------------
     // Code that runs once per workgroup is fetched cold, at a small fraction of the speed of a
@@ -712,6 +725,10 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         *reinterpret_cast<uint2*>(out_row + (k4 >> 2) * 32 + (k4 & 3) * 8) = w;
     };
     __syncthreads();
+    const bool keep_mine = may_keep && s_last;   // (the same in every wavefront)
+    constexpr int kKept = kDBlocks * 4 / WK;
+    uint2 kept[kKept];
+    float kept_m = 0.f, kept_l = 0.f;
     float* const lds_f = reinterpret_cast<float*>(&sm_union);
     float* const o_s = lds_f;                                        // [kCells][kK4][64][4]
     float* const ml_s = o_s + (size_t)kCells * kK4 * 256;            // [kCells][2][64]
@@ -721,11 +738,13 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     };
     float* const part_ml = my_part + (size_t)wqw * block_words + (size_t)kK4 * 128;
     uint2* const part_o = reinterpret_cast<uint2*>(my_part + (size_t)wqw * block_words) + lane;
-    auto store_part = [&](int k4, float4 acc, float inv) __attribute__((always_inline)) {
+    // (`mine`: the item's number among those of this wavefront, a literal)
+    auto store_part = [&](int k4, int mine, float4 acc, float inv) __attribute__((always_inline)) {
         uint2 w;
         w.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(acc.x * inv, acc.y * inv));
         w.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(acc.z * inv, acc.w * inv));
-        part_o[k4 * 64] = w;
+        kept[mine] = w;
+        if (!keep_mine) part_o[k4 * 64] = w;
     };
     // (a query whose keys in this range are all masked has normaliser and output 0)
     auto whole_normaliser = [&](float mine) __attribute__((always_inline)) {
@@ -742,9 +761,13 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         } else {
             const float inv = l_all > 0.f ? __builtin_amdgcn_rcpf(l_all) : 0.f;
 #pragma unroll
-            for (int k4 = 0; k4 < kK4; ++k4) store_part(k4, item_of(k4), inv);
-            part_ml[lane] = m_run[0];
-            part_ml[64 + lane] = l_all;
+            for (int k4 = 0; k4 < kK4; ++k4) store_part(k4, k4, item_of(k4), inv);
+            kept_m = m_run[0];
+            kept_l = l_all;
+            if (!keep_mine) {
+                part_ml[lane] = m_run[0];
+                part_ml[64 + lane] = l_all;
+            }
         }
     } else {
         // Every wavefront drops its cell; wavefront (row block q, key group j) then merges items
@@ -810,8 +833,10 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         } else {
             const float inv = l_all > 0.f ? __builtin_amdgcn_rcpf(l_all) : 0.f;
 #pragma unroll
-            for (int i = 0; i < kMine; ++i) store_part(wk * kMine + i, acc[i], inv);
-            if (wk == 0) {
+            for (int i = 0; i < kMine; ++i) store_part(wk * kMine + i, i, acc[i], inv);
+            kept_m = big;
+            kept_l = l_all;
+            if (wk == 0 && !keep_mine) {
                 part_ml[lane] = big;
                 part_ml[64 + lane] = l_all;
             }
@@ -829,17 +854,21 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     // (Sharing the merge among the S workgroups of a unit -- count arrivals, poll a bounded
     // number of times, claim a slice -- was tried: the polling costs more than the one CU's
     // memory pipeline it saves, and workgroups that wait hold CUs that a later batch needs.)
-    if (p.share_l2) wait_vmcnt<0>();
-    else __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t arrived = atomicAdd(&p.counters[unit], 1u);
-        s_last = (arrived == (uint32_t)(S - 1));
-        if (s_last) atomicExch(&p.counters[unit], 0u);  // ready for the next call
+    if (keep_mine) {
+        if (tid == 0) atomicExch(&p.counters[unit], 0u);   // everybody else has been counted: ready for the next call
+    } else {
+        if (p.share_l2) wait_vmcnt<0>();
+        else __threadfence();
+        __syncthreads();
+        if (tid == 0) {
+            const uint32_t arrived = atomicAdd(&p.counters[unit], 1u);
+            s_last = (arrived == (uint32_t)(S - 1));
+            if (s_last) atomicExch(&p.counters[unit], 0u);  // ready for the next call
+        }
+        __syncthreads();
+        ATTN_STAMP(22);
+        if (!s_last) { ATTN_STAMP_FLUSH(); return; }
     }
-    __syncthreads();
-    ATTN_STAMP(22);
-    if (!s_last) { ATTN_STAMP_FLUSH(); return; }
     // The partial results are read from the L2, not from whatever this CU's own cache holds for
     // those addresses: a device-scope acquire invalidates it (no write-back involved).
     if (p.share_l2) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -871,6 +900,11 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         auto request = [&](int k0, uint2 (&dst)[kBatch][NS]) __attribute__((always_inline)) {
 #pragma unroll
             for (int r = 0; r < NS; ++r) {
+                if (keep_mine && r == split) {   // (mine are in `kept`)
+#pragma unroll
+                    for (int j = 0; j < kBatch; ++j) dst[j][r] = make_uint2(0u, 0u);
+                    continue;
+                }
                 const uint2* const src_r = src + (size_t)min(r, S - 1) * (range_words / 2) + k0 * 64;
 #pragma unroll
                 for (int j = 0; j < kBatch; ++j) dst[j][r] = src_r[j * 64 + lane];
@@ -885,8 +919,9 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
 #pragma unroll
             for (int r = 0; r < NS; ++r) {
                 const float* m = ml + (size_t)min(r, S - 1) * range_words;
-                mv[r] = m[lane];
-                lv[r] = m[64 + lane];
+                const bool mine = keep_mine && r == split;
+                mv[r] = mine ? kept_m : m[lane];
+                lv[r] = mine ? kept_l : m[64 + lane];
             }
             float big = -INFINITY;
 #pragma unroll
@@ -907,7 +942,11 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
                 float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
                 for (int r = 0; r < NS; ++r) {
-                    const half2_t lo = __builtin_bit_cast(half2_t, src_v[j][r].x), hi = __builtin_bit_cast(half2_t, src_v[j][r].y);
+                    uint2 item = src_v[j][r];
+                    if constexpr (kItems == kBatch) {
+                        if (keep_mine && r == split) item = kept[j];
+                    }
+                    const half2_t lo = __builtin_bit_cast(half2_t, item.x), hi = __builtin_bit_cast(half2_t, item.y);
                     acc.x = fmaf((float)lo[0], f[r], acc.x); acc.y = fmaf((float)lo[1], f[r], acc.y);
                     acc.z = fmaf((float)hi[0], f[r], acc.z); acc.w = fmaf((float)hi[1], f[r], acc.w);
                 }
@@ -949,6 +988,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
 
 int g_splits_override = 0;  // tuning hooks, 0 = automatic
 int g_wq_override = 0;
+int g_keep_own = 1;   // test hook: 0 = every partial result goes through memory
 int g_uneven_override = -1, g_short_weight_override = 1, g_long_weight_override = 1;   // -1 = automatic, 0 = equal ranges only, m > 0 = m short ranges
 
 AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
@@ -1054,6 +1094,7 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
     p.short_ranges = sched.short_ranges;
     p.short_weight = sched.short_weight;
     p.long_weight = sched.long_weight;
+    p.keep_own = g_keep_own;
     p.by_weights = make_fast_div((uint32_t)(sched.short_ranges * sched.short_weight + (sched.splits - sched.short_ranges) * sched.long_weight));
     if (units > kAttnMaxCounters) return SEQ_ERR_SHAPE;
     const int unit_groups = (units + 7) / 8;
@@ -1099,6 +1140,7 @@ extern "C" int seqtree_internal_attn_range_start(int tiles, int range, int range
     const seqtree::FastDiv by = seqtree::make_fast_div((uint32_t)(short_ranges * short_weight + (ranges - short_ranges) * long_weight));
     return seqtree::range_start(tiles, range, short_ranges, short_weight, long_weight, by);
 }
+extern "C" void seqtree_internal_set_attn_keep_own(int on) { seqtree::g_keep_own = on; }
 extern "C" void seqtree_internal_set_attn_uneven(int short_ranges, int short_weight, int long_weight) {
     seqtree::g_uneven_override = short_ranges;
     seqtree::g_short_weight_override = short_weight > 0 ? short_weight : 1;
