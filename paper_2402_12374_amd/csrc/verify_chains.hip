@@ -215,17 +215,20 @@ __device__ void leaf_draw(const LT* row, int V, float slope, float u0, bool vec_
     constexpr int kDeep = 16 / kVecs;
     for (int first = wave; first < blocks; first += NW * kDeep) {
         if (vec_ok) {
+            // (a group past the end reads the row's first group and is replaced by -inf afterwards:
+            // loads under a condition would go to memory one at a time)
             uint4 raw[kDeep][kVecs];
+            bool inside[kDeep][kVecs];
 #pragma unroll
             for (int d = 0; d < kDeep; ++d) {
                 const int base = (first + d * NW) * kLeafBlock + lane * kChunk;
 #pragma unroll
                 for (int c = 0; c < kVecs; ++c) {
-                    raw[d][c] = sizeof(LT) == 2 ? make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u)
-                                                : make_uint4(0xFF800000u, 0xFF800000u, 0xFF800000u, 0xFF800000u);   // -inf
-                    if (base + (c + 1) * kPerVec <= V) raw[d][c] = *reinterpret_cast<const uint4*>(row + base + c * kPerVec);
+                    inside[d][c] = base + (c + 1) * kPerVec <= V;
+                    raw[d][c] = *reinterpret_cast<const uint4*>(row + (inside[d][c] ? base + c * kPerVec : 0));
                 }
             }
+            const uint32_t gone = sizeof(LT) == 2 ? 0xFF80FF80u : 0xFF800000u;   // -inf (as a bf16 pair)
 #pragma unroll
             for (int d = 0; d < kDeep; ++d) {
                 const int blk = first + d * NW;
@@ -233,7 +236,8 @@ __device__ void leaf_draw(const LT* row, int V, float slope, float u0, bool vec_
                 float x[kChunk];
 #pragma unroll
                 for (int c = 0; c < kVecs; ++c) {
-                    const uint32_t w[4] = {raw[d][c].x, raw[d][c].y, raw[d][c].z, raw[d][c].w};
+                    const bool in = inside[d][c];
+                    const uint32_t w[4] = {in ? raw[d][c].x : gone, in ? raw[d][c].y : gone, in ? raw[d][c].z : gone, in ? raw[d][c].w : gone};
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         if constexpr (sizeof(LT) == 2) {
@@ -419,14 +423,10 @@ __global__ __launch_bounds__(TEAM_NT ? TEAM_NT : kThreads, 4) void verify_chains
     const bool vec_ok = (V % (16 / (int)sizeof(LT)) == 0) &&
                         ((reinterpret_cast<uintptr_t>(p.target) | reinterpret_cast<uintptr_t>(p.draft)) & 15) == 0;
     float pr[EPT], qr[EPT];
-#pragma unroll
-    for (int c = 0; c < CH; ++c)
-        load_row_slice<LT, kChunk>(trow, row_base + (c * NT + tid) * kChunk, V, 1.0f, vec_ok, pr + c * kChunk);
     if (K > 0) {
-#pragma unroll
-        for (int c = 0; c < CH; ++c)
-            load_row_slice<LT, kChunk>(drow, row_base + (c * NT + tid) * kChunk, V, 1.0f, vec_ok, qr + c * kChunk);
+        load_row_slices<LT, kChunk, CH, true>(trow, drow, row_base + tid * kChunk, NT * kChunk, V, 1.0f, vec_ok, pr, qr);
     } else {
+        load_row_slices<LT, kChunk, CH, false>(trow, trow, row_base + tid * kChunk, NT * kChunk, V, 1.0f, vec_ok, pr, pr);
 #pragma unroll
         for (int e = 0; e < EPT; ++e) qr[e] = -INFINITY;   // a leaf has no draft row to read
     }

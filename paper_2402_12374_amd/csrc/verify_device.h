@@ -102,35 +102,70 @@ template <> __device__ __forceinline__ float load_logit<uint16_t>(const uint16_t
 // (`vec_ok`: every 16-byte group of a row then lies wholly inside or wholly outside it); otherwise
 // token by token, in a loop that is kept rolled: it runs for odd vocabularies only and would
 // otherwise be most of the kernel's code.
-template <typename LT, int EPT>
-__device__ __forceinline__ void load_row_slice(const LT* row, int base, int V, float inv_T, bool vec_ok,
-                                               float* x) {
-    constexpr int kPerVec = 16 / (int)sizeof(LT);
+// CH slices of a row -- slice c starts at token base + c * stride -- and, if TWO, the same slices
+// of a second row, all requested before the first is touched: one trip to memory for everything
+// a thread holds.  (Requests written one slice or one row after the other, each under its own
+// condition, come out of the compiler as one trip each: it waits for a load at the end of the
+// block that issued it.)  A vector group past the end of the row reads the row's first group
+// instead and is replaced by -inf.
+template <typename LT, int EPT, int CH, bool TWO>
+__device__ __forceinline__ void load_row_slices(const LT* row_a, const LT* row_b, int base, int stride, int V, float inv_T,
+                                                bool vec_ok, float* xa, float* xb) {
+    constexpr int kPerVec = 16 / (int)sizeof(LT), kVecs = EPT / kPerVec;
     if (vec_ok) {
+        uint4 ra[CH][kVecs], rb[CH][kVecs];
+        bool inside[CH][kVecs];
 #pragma unroll
-        for (int c = 0; c < EPT / kPerVec; ++c) {
-            uint4 raw = make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u);   // -inf as bf16 pairs
-            if (sizeof(LT) == 4) raw = make_uint4(0xFF800000u, 0xFF800000u, 0xFF800000u, 0xFF800000u);
-            if (base + (c + 1) * kPerVec <= V) raw = *reinterpret_cast<const uint4*>(row + base + c * kPerVec);
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+        for (int c = 0; c < CH; ++c)
+#pragma unroll
+            for (int g = 0; g < kVecs; ++g) {
+                const int first = base + c * stride + g * kPerVec;
+                inside[c][g] = first + kPerVec <= V;
+                const int at = inside[c][g] ? first : 0;
+                ra[c][g] = *reinterpret_cast<const uint4*>(row_a + at);
+                if (TWO) rb[c][g] = *reinterpret_cast<const uint4*>(row_b + at);
+            }
+        const uint32_t gone = sizeof(LT) == 4 ? 0xFF800000u : 0xFF80FF80u;   // -inf, or -inf as a bf16 pair
+        auto unpack = [&](const uint4& got, bool in, float* x) __attribute__((always_inline)) {
+            const uint32_t w[4] = {in ? got.x : gone, in ? got.y : gone, in ? got.z : gone, in ? got.w : gone};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 if constexpr (sizeof(LT) == 2) {
-                    x[c * 8 + 2 * k] = __uint_as_float(w[k] << 16) * inv_T;
-                    x[c * 8 + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u) * inv_T;
+                    x[2 * k] = __uint_as_float(w[k] << 16) * inv_T;
+                    x[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u) * inv_T;
                 } else {
-                    x[c * 4 + k] = __uint_as_float(w[k]) * inv_T;
+                    x[k] = __uint_as_float(w[k]) * inv_T;
+                }
+            }
+        };
+#pragma unroll
+        for (int c = 0; c < CH; ++c)
+#pragma unroll
+            for (int g = 0; g < kVecs; ++g) {
+                unpack(ra[c][g], inside[c][g], xa + c * EPT + g * kPerVec);
+                if (TWO) unpack(rb[c][g], inside[c][g], xb + c * EPT + g * kPerVec);
+            }
+    } else {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            float* const xs[2] = {xa + c * EPT, xb + c * EPT};
+            const LT* const rows[2] = {row_a, row_b};
+#pragma unroll
+            for (int w = 0; w < (TWO ? 2 : 1); ++w) {
+#pragma unroll 1
+                for (int e = 0; e < EPT; ++e) {
+                    const int t = base + c * stride + e;
+                    const float val = t < V ? load_logit<LT>(rows[w], t) * inv_T : -INFINITY;
+#pragma unroll
+                    for (int k = 0; k < EPT; ++k) xs[w][k] = k == e ? val : xs[w][k];   // (static register indices)
                 }
             }
         }
-    } else {
-#pragma unroll 1
-        for (int e = 0; e < EPT; ++e) {
-            const float val = base + e < V ? load_logit<LT>(row, base + e) * inv_T : -INFINITY;
-#pragma unroll
-            for (int k = 0; k < EPT; ++k) x[k] = k == e ? val : x[k];   // (static register indices)
-        }
     }
+}
+template <typename LT, int EPT>
+__device__ __forceinline__ void load_row_slice(const LT* row, int base, int V, float inv_T, bool vec_ok, float* x) {
+    load_row_slices<LT, EPT, 1, false>(row, row, base, 0, V, inv_T, vec_ok, x, x);
 }
 
 // e^x on the hardware base-2 exponential, with the rounding error of x * log2(e) carried into

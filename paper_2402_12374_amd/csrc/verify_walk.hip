@@ -279,8 +279,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
                         ((reinterpret_cast<uintptr_t>(p.target) | reinterpret_cast<uintptr_t>(p.draft)) & 15) == 0;
     float pr[EPT], qr[EPT];
     // the root's rows are needed whatever happens: ask for them before anything else
-    load_row_slice<LT, EPT>(target, base, V, p.inv_T, vec_ok, pr);
-    load_row_slice<LT, EPT>(draft, base, V, p.inv_T, vec_ok, qr);
+    load_row_slices<LT, EPT, 1, true>(target, draft, base, 0, V, p.inv_T, vec_ok, pr, qr);
     bool poisoned;
     const uint32_t tag_base = launch_tag_base(p, &poisoned);
     begin_trace(p);
@@ -308,8 +307,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
             sh.child_dup[k] = dup ? 1 : 0;
         }
         if (v != 0) {
-            load_row_slice<LT, EPT>(trow, base, V, p.inv_T, vec_ok, pr);
-            load_row_slice<LT, EPT>(drow, base, V, p.inv_T, vec_ok, qr);
+            load_row_slices<LT, EPT, 1, true>(trow, drow, base, 0, V, p.inv_T, vec_ok, pr, qr);
         }
         SEQ_STAMP(1);
         // softmax statistics: per wavefront first (no barrier), then folded by the first wavefront.
