@@ -431,15 +431,35 @@ __global__ __launch_bounds__(TEAM_NT ? TEAM_NT : kThreads, 4) void verify_chains
         for (int e = 0; e < EPT; ++e) qr[e] = -INFINITY;   // a leaf has no draft row to read
     }
     // both rows at the children's tokens, in flight together with the rows themselves
-    for (int k = tid; k < K; k += NT) {
-        const int s = min(max(p.tokens[p.child_list[c_begin + k]], 0), V - 1);  // stay inside the row
-        sh.child_tok[k] = s;
-        sh.child_u[k] = p.uniforms[p.child_list[c_begin + k]];
-        sh.child_lt[k] = load_logit<LT>(trow, s);   // raw: the temperature is in the exponent's slope
-        sh.child_ld[k] = load_logit<LT>(drow, s);
+    // (up to 64 children: a lane of the first wavefront per child, so that "an earlier sibling has
+    // the same token" is a walk over lanes, not over memory)
+    if (K > 64) {
+        for (int k = tid; k < K; k += NT) {
+            const int s = min(max(p.tokens[p.child_list[c_begin + k]], 0), V - 1);
+            sh.child_tok[k] = s;
+            sh.child_u[k] = p.uniforms[p.child_list[c_begin + k]];
+            sh.child_lt[k] = load_logit<LT>(trow, s);
+            sh.child_ld[k] = load_logit<LT>(drow, s);
+            bool dup = false;
+            for (int j = 0; j < k; ++j) dup |= min(max(p.tokens[p.child_list[c_begin + j]], 0), V - 1) == s;
+            sh.child_dup[k] = dup ? 1 : 0;
+        }
+    } else if (tid < 64 && K > 0) {
+        const int k = tid;
+        const int child = p.child_list[c_begin + min(k, K - 1)];
+        const int s = min(max(p.tokens[child], 0), V - 1);  // stay inside the row
+        const float u = p.uniforms[child];
+        const float lt = load_logit<LT>(trow, s);   // raw: the temperature is in the exponent's slope
+        const float ld = load_logit<LT>(drow, s);
         bool dup = false;
-        for (int j = 0; j < k; ++j) dup |= min(max(p.tokens[p.child_list[c_begin + j]], 0), V - 1) == s;
-        sh.child_dup[k] = dup ? 1 : 0;
+        for (int j = 0; j < K - 1; ++j) dup |= j < k && __builtin_amdgcn_readlane(s, j) == s;
+        if (k < K) {
+            sh.child_tok[k] = s;
+            sh.child_u[k] = u;
+            sh.child_lt[k] = lt;
+            sh.child_ld[k] = ld;
+            sh.child_dup[k] = dup ? 1 : 0;
+        }
     }
     if (TEAM && tid == 0) sh.team_fail = 0;
 #ifdef SEQTREE_STAMPS

@@ -298,13 +298,28 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
         const int c_begin = sh.child_start[v], c_end = sh.child_start[v + 1];
         // both rows at the children's tokens (needed for the accept tests), in flight together
         // with the row slices themselves
-        for (int k = tid; k < c_end - c_begin; k += kThreads) {
-            const int s = sh.token[sh.child_list[c_begin + k]];
-            sh.child_lt[k] = load_logit<LT>(trow, s) * p.inv_T;
-            sh.child_ld[k] = load_logit<LT>(drow, s) * p.inv_T;
+        const int K = c_end - c_begin;
+        if (K > 64) {
+            for (int k = tid; k < K; k += kThreads) {
+                const int s = sh.token[sh.child_list[c_begin + k]];
+                sh.child_lt[k] = load_logit<LT>(trow, s) * p.inv_T;
+                sh.child_ld[k] = load_logit<LT>(drow, s) * p.inv_T;
+                bool dup = false;
+                for (int j = 0; j < k; ++j) dup |= sh.token[sh.child_list[c_begin + j]] == s;
+                sh.child_dup[k] = dup ? 1 : 0;
+            }
+        } else if (tid < 64 && K > 0) {
+            // a lane per child: "an earlier sibling has the same token" is a walk over lanes
+            const int k = tid;
+            const int s = sh.token[sh.child_list[c_begin + min(k, K - 1)]];
+            const float lt = load_logit<LT>(trow, s) * p.inv_T, ld_ = load_logit<LT>(drow, s) * p.inv_T;
             bool dup = false;
-            for (int j = 0; j < k; ++j) dup |= sh.token[sh.child_list[c_begin + j]] == s;
-            sh.child_dup[k] = dup ? 1 : 0;
+            for (int j = 0; j < K - 1; ++j) dup |= j < k && __builtin_amdgcn_readlane(s, j) == s;
+            if (k < K) {
+                sh.child_lt[k] = lt;
+                sh.child_ld[k] = ld_;
+                sh.child_dup[k] = dup ? 1 : 0;
+            }
         }
         if (v != 0) {
             load_row_slices<LT, EPT, 1, true>(trow, drow, base, 0, V, p.inv_T, vec_ok, pr, qr);

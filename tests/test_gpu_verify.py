@@ -89,6 +89,25 @@ def test_long_accepted_paths_when_draft_equals_target():
         assert (p >= 0).sum() >= 3
 
 
+@pytest.mark.parametrize("n_children", [5, 63, 64, 65, 200])
+def test_siblings_with_the_same_token_up_to_and_beyond_a_wavefront_of_children(n_children):
+    """A child whose token an earlier sibling already had is never accepted (its residual is zero
+    by then).  The kernels find such children by walking over lanes when a node has at most 64
+    children and by walking over memory beyond; both sides of that switch, with repeats planted
+    among the root's children and among those of a deeper node."""
+    rng = np.random.default_rng(n_children)
+    parent = np.concatenate([[-1], np.zeros(n_children, np.int64), np.full(7, 3, np.int64)]).astype(np.int32)
+    flagged = 0
+    for rep, V in enumerate((777, 4096)):
+        v = W.make_verify_inputs(parent, V, 2.0, 1.0, 0.9, W.F32 if rep == 0 else W.BF16, seed=1000 * n_children + rep)
+        kids = np.arange(1, n_children + 1)
+        for twin in rng.choice(kids[1:], size=max(1, n_children // 4), replace=False):
+            v.tree_tokens[twin] = v.tree_tokens[rng.integers(1, twin)]      # an earlier sibling's token
+        v.tree_tokens[n_children + 5] = v.tree_tokens[n_children + 2]
+        flagged += check_verify(v) == "flagged"
+    assert flagged <= 1
+
+
 def test_peaked_target_gives_rejection_chains():
     # target concentrated on few tokens the draft ranks low: many rejections at the root
     rng = np.random.default_rng(5)
