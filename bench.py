@@ -7,7 +7,10 @@ call (the verification walk).  Consecutive steps use different input sets (as ma
 the model has layers), so no step finds its K/V or logits in a cache left by the previous one.
 All inputs are in HBM before the timed region starts.
 
-Prints ONE JSON line (see the design doc for how each figure is formed).
+Prints ONE JSON line: `value` is the wall time per step at the largest configuration; `roofline`
+prices that configuration's attention kernel (algorithmic flops over its launch time from HIP
+events around graph replays, against the dense bf16 matrix peak), `verify` the verification kernel,
+`configs` the other configurations, `cpu_baseline` the fp64 checker on the same workload.
 
 Other modes print lines of their own instead of the benchmark line: --sweep (latency of both calls
 over the tree size; --sweep-tree sequoia for trees built by seq_build_tree; --pick-tree for the
