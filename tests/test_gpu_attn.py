@@ -267,6 +267,31 @@ def test_a_batch_whose_sequences_differ_in_prefix_length(B, H, Hk, d, cap, n, le
         assert err <= TOL[dtype], (b, shorter[b], err)
 
 
+def test_a_batch_with_key_ranges_of_two_sizes():
+    """Sequences of different prefix lengths under a long and a short key range per unit: the
+    ranges are shares of each sequence's own tiles, so a sequence with a handful of keys gets a
+    short range that is empty."""
+    import paper_2402_12374_amd as S
+    B, H, Hk, d, cap, n, lens = 3, 16, 2, 128, 1300, 96, [1300, 40, 611]
+    tree = W.geometric_tree(n, 7)
+    seqs, tensors, dev_lens = _batched_case(B, H, Hk, d, cap, n, lens, W.BF16, seed=77, tree=tree)
+    try:
+        for wq, splits, shorts, short_w, long_w in ((8, 2, 1, 15, 49), (4, 3, 1, 12, 26), (8, 2, 1, 1, 63)):
+            S.lib().seqtree_internal_set_attn_wq(wq)
+            S.lib().seqtree_internal_set_attn_splits(splits)
+            S.lib().seqtree_internal_set_attn_uneven(shorts, short_w, long_w)
+            out = S.seq_tree_attn_batched(*tensors, tree, dev_lens, max(lens))
+            torch.cuda.synchronize()
+            got = out.float().cpu().numpy().astype(np.float64)
+            for b, s in enumerate(seqs):
+                err = np.abs(got[:, b] - oracle_attn(s)).max()
+                assert err <= TOL[W.BF16], (wq, splits, short_w, long_w, b, err)
+    finally:
+        S.lib().seqtree_internal_set_attn_wq(0)
+        S.lib().seqtree_internal_set_attn_splits(0)
+        S.lib().seqtree_internal_set_attn_uneven(-1, 1, 1)
+
+
 def test_batched_lengths_are_held_to_the_bound_and_equal_lengths_match_the_folded_call():
     import paper_2402_12374_amd as S
     B, H, Hk, d, cap, n = 3, 8, 2, 128, 400, 40
