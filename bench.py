@@ -66,11 +66,23 @@ def attn_alg_flops(cfg, parent):
     return 4 * cfg.head_dim * cfg.heads * (len(parent) * cfg.prefix_len + visible)
 
 
+_SIDE_STREAM = None
+
+
+def side_stream(torch):
+    """One stream beside the default one for all warm-ups under capture rules: the library keeps a
+    synchronisation area per stream it has been called on, and has room for a few of them."""
+    global _SIDE_STREAM
+    if _SIDE_STREAM is None:
+        _SIDE_STREAM = torch.cuda.Stream()
+    return _SIDE_STREAM
+
+
 def graph_time_us(torch, fn, count, reps):
     """Average duration of one call of fn(i), i = 0..count-1 captured once as a HIP graph."""
     fn(0)
     torch.cuda.synchronize()
-    side = torch.cuda.Stream()
+    side = side_stream(torch)
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
         for i in range(count):
