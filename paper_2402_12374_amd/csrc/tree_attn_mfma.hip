@@ -1000,12 +1000,15 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     // Two choices: row blocks per workgroup (wq; the 8 / wq wavefronts left over share the key
     // tiles of a round) and key ranges per unit.  One workgroup fits on a CU at a time, so a
     // launch runs in batches of 256 workgroups; a workgroup costs its rounds -- dearer the more
-    // tiles a round copies -- plus a fixed prologue/epilogue plus the merge of the ranges
-    // (figures in tenths of a microsecond, fitted to the measured times of every (wq, ranges) pair
-    // at the head shapes of the paper's models and trees of 16 to 768 nodes: the choice is within
-    // 10 % of the best pair everywhere, the best pair itself in 24 of 28 cases).  A wq beyond what the rows of a KV head fill is never considered; a smaller one
-    // is, because it multiplies the units when there are few KV heads.
+    // tiles a round copies -- plus a fixed prologue/epilogue plus, with more than one range, the
+    // hand-over of the partial results and their merge (figures in tenths of a microsecond,
+    // chosen against the measured times of every (wq, ranges) pair at the head shapes of the
+    // paper's models, trees of 16 to 768 nodes and prefixes of 512 to 20000 keys: the pair chosen
+    // is on average 0.8 % slower than the best pair measured, 14 % at worst).  A wq beyond what
+    // the rows of a KV head fill is never considered; a smaller one is, because it multiplies the
+    // units when there are few KV heads.
     const int wq_cover = rows <= 64 ? 2 : (rows <= 128 ? 4 : 8);
+    constexpr long kFixed = 80, kHandOver = 40;   // prologue and epilogue of a workgroup; partial results handed over and merged at all
     long best = -1;
     s.wq = wq_cover;
     s.splits = 1;
@@ -1015,13 +1018,13 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
         if (g_wq_override > 0 && wq != std::min(g_wq_override, wq_cover)) continue;
         const int wk = kMaxCells / wq;
         const int units = Hk * ((rows + 32 * wq - 1) / (32 * wq));
-        const long round_cost = wk == 1 ? 9 : (wk == 2 ? 10 : 13);
+        const long round_cost = wk == 1 ? 9 : (wk == 2 ? 10 : 14);
         const int max_splits = std::min(kMaxSplits, std::max(1, tiles / wk));
         for (int cand = 1; cand <= max_splits; ++cand) {
             if (g_splits_override > 0 && cand != std::min(g_splits_override, max_splits)) continue;
             const long batches = ((long)units * cand + 255) / 256;
             const long rounds = (tiles + cand * wk - 1) / (cand * wk);
-            const long cost = batches * (rounds * round_cost + 100 + (cand > 1 ? 5 * cand * wq / 2 : 0));
+            const long cost = batches * (rounds * round_cost + kFixed + (cand > 1 ? kHandOver + 3 * cand * wq / 2 : 0));
             if (best < 0 || cost < best) { best = cost; s.wq = wq; s.splits = cand; s.short_ranges = 0; s.short_weight = s.long_weight = 1; }
         }
         // Ranges of two sizes.  When the units leave CUs over but too few for another range each
@@ -1039,7 +1042,7 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
             if (k > 3) break;      // (measured: with more short ranges in a row their fixed parts eat the gain)
             // the long ranges' share f of a unit's tiles for which a long workgroup takes as long
             // as k short ones in a row, in 64ths
-            const long all_rounds = (tiles + wk - 1) / wk, fixed = 100, merge = 5 * (longs + 1) * wq / 2;
+            const long all_rounds = (tiles + wk - 1) / wk, fixed = kFixed, merge = kHandOver + 3 * (longs + 1) * wq / 2;
             const long num = k * all_rounds * round_cost + (k - 1) * fixed - merge, den = all_rounds * round_cost * (1 + k * longs);
             const int long_w = (int)((64 * num + den / 2) / den), short_w = 64 - longs * long_w;
             if (long_w < 1 || short_w < 1) continue;
