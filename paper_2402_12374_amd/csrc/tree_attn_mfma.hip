@@ -660,7 +660,17 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         scores(kf, sacc);
         if (kPrefetchK) load_k((slot + 1) % kSlots, kf);   // (past the last tile: a tile nobody needs)
         ATTN_STAMP(12);
-        if (!tile_is_full(t)) mask_scores(sacc[0], visibility(t, slot, 0), half);   // tiles inside the prefix need no mask
+        if (!tile_is_full(t)) {   // tiles inside the prefix need no mask
+            // A tree tile that holds no ancestor of any of my 32 queries adds nothing for them: a
+            // node has at most depth-many ancestors, so most (row block, tree tile) pairs are like
+            // that.  The wavefront leaves the tile out once it has the visibility words, after the
+            // score product (leaving before it as well made the compiler run out of registers and
+            // wait for every V fragment on the spot); the copies and the barrier are the workgroup's
+            // and stay.
+            const uint32_t vis = visibility(t, slot, 0);
+            if (t >= prefix_tiles && !__any(vis != 0u)) return;
+            mask_scores(sacc[0], vis, half);
+        }
         uint32_t pw[1][2][4];
         bool moved;
         const SoftmaxCarry c = softmax_first(sacc[0], p.scale_log2, m_run[0], pw[0], moved);
