@@ -126,6 +126,39 @@ def test_every_workgroup_shape_and_range_count(d):
         S.lib().seqtree_internal_set_attn_splits(0)
 
 
+@pytest.mark.parametrize("shape", ["star", "two_chains", "late_root_children"])
+def test_tree_tiles_without_an_ancestor_of_a_row_block(shape):
+    """A wavefront leaves out a tree tile none of whose 32 keys is an ancestor of any of its
+    queries.  Trees in which that is most tiles, in which a block's only live tiles are the first
+    and its own, and in which live tiles lie far apart; every workgroup shape, with the tree tiles
+    in one key range and spread over several; no prefix at all as well (every tile a tree tile)."""
+    import paper_2402_12374_amd as S
+    n = 300
+    if shape == "star":
+        parent = W.star_tree(n)
+    elif shape == "two_chains":
+        # nodes alternate between two chains hanging off the root: a node's ancestors are every
+        # other node below it, so every tile below it is live for it
+        parent = np.array([-1, 0, 0] + list(range(1, n - 2)), np.int32)
+    else:
+        # the first 200 nodes are a star; the last 100 are children of node 199: their ancestors
+        # sit in tiles 0 and 6 only
+        parent = np.array([-1] + [0] * 199 + [199] * 100, np.int32)
+    for P in (0, 333):
+        a = W.make_attn_inputs(8, 2, 128, P, parent, W.BF16, seed=17 + P, prefix_cap=max(P, 1) + 5)
+        ref = oracle_attn_all_rows(a)
+        try:
+            for wq in (2, 4, 8):
+                for splits in (1, 2, 5):
+                    S.lib().seqtree_internal_set_attn_wq(wq)
+                    S.lib().seqtree_internal_set_attn_splits(splits)
+                    err = np.abs(run_attn(a) - ref).max()
+                    assert err <= TOL[W.BF16], (shape, P, wq, splits, err)
+        finally:
+            S.lib().seqtree_internal_set_attn_wq(0)
+            S.lib().seqtree_internal_set_attn_splits(0)
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_key_ranges_of_two_sizes(d):
     """Where the units leave compute units over, the library cuts a unit's keys into long ranges and
