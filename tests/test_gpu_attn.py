@@ -206,6 +206,33 @@ def test_the_shapes_that_take_ranges_of_two_sizes_by_themselves():
         assert np.array_equal(run_attn(a), got), (H, Hk, P, n)
 
 
+def test_seeded_random_shapes_under_the_library_s_own_schedule():
+    """Heads, group size, head dimension, prefix and tree drawn at random (seeded): whatever
+    workgroup shape, range count and range sizes the library picks for them by itself, every row
+    agrees with the checker.  The draw is checked to exercise several schedules, among them
+    ranges of two sizes, so that a change of the cost figures cannot quietly narrow the test."""
+    import ctypes
+    import paper_2402_12374_amd as S
+    rng, tree_rng = np.random.default_rng(2402), np.random.default_rng(12374)
+    five = (ctypes.c_int * 5)()
+    picks = []
+    for case in range(14):
+        Hk = int(rng.choice([1, 2, 4, 8, 12, 20, 24, 32]))
+        G = int(rng.choice([1, 1, 2, 4, 8]))
+        d = int(rng.choice([64, 128]))
+        n = int(rng.integers(1, 420))
+        P = int(rng.integers(0, 3600))
+        S.lib().seqtree_internal_attn_schedule(P, n, Hk * G, Hk, d, five)
+        picks.append(tuple(five))
+        parent = W.random_topological_tree(n, tree_rng) if case % 2 else W.geometric_tree(n, 9)
+        a = W.make_attn_inputs(Hk * G, Hk, d, P, parent, W.BF16, seed=100 + case, prefix_cap=P + 1 + case)
+        err = np.abs(run_attn(a) - oracle_attn_all_rows(a)).max()
+        assert err <= TOL[W.BF16], (case, (Hk * G, Hk, d, P, n), picks[-1], err)
+    assert sum(1 for k in picks if k[2] > 0) >= 2, picks           # ranges of two sizes
+    assert len({k[:2] for k in picks}) >= 6, picks                  # (row blocks, ranges) pairs
+    assert {k[0] for k in picks} == {2, 4, 8}, picks
+
+
 @pytest.mark.parametrize("H,Hk,P,n", [(4, 4, 700, 40), (16, 2, 1500, 300)])
 @pytest.mark.parametrize("order", ["rising", "falling", "spiky"])
 def test_scores_of_large_and_moving_magnitude(H, Hk, P, n, order):
