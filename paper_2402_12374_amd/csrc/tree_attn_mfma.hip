@@ -864,25 +864,25 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     // (Sharing the merge among the S workgroups of a unit -- count arrivals, poll a bounded
     // number of times, claim a slice -- was tried: the polling costs more than the one CU's
     // memory pipeline it saves, and workgroups that wait hold CUs that a later batch needs.)
-    if (keep_mine) {
-        if (tid == 0) atomicExch(&p.counters[unit], 0u);   // everybody else has been counted: ready for the next call
-    } else {
+    if (!keep_mine) {
         if (p.share_l2) wait_vmcnt<0>();
         else __threadfence();
         __syncthreads();
         if (tid == 0) {
             const uint32_t arrived = atomicAdd(&p.counters[unit], 1u);
             s_last = (arrived == (uint32_t)(S - 1));
-            if (s_last) atomicExch(&p.counters[unit], 0u);  // ready for the next call
         }
         __syncthreads();
         ATTN_STAMP(22);
         if (!s_last) { ATTN_STAMP_FLUSH(); return; }
     }
     // The partial results are read from the L2, not from whatever this CU's own cache holds for
-    // those addresses: a device-scope acquire invalidates it (no write-back involved).
-    if (p.share_l2) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    else __threadfence();
+    // those addresses: every load of the merge is a device-scope atomic load, which goes past the
+    // CU's cache.  (A device-scope acquire fence would do as well, but its invalidate also sweeps
+    // the XCD's L2 for lines of memory that is not kept coherent there: the first load behind it
+    // came back after 5 us, where the same load before it took 0.4, and the K/V tiles of every
+    // workgroup still running on the XCD went with it.)
+    if (!p.share_l2) __threadfence();
     ATTN_STAMP(23);
 
     // Merge the ranges of the unit.  One workgroup pulls S partial results through one CU's memory
@@ -898,6 +898,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     auto merge_ranges = [&](auto ns_c) __attribute__((always_inline)) {
         constexpr int NS = decltype(ns_c)::value;
         constexpr int kItems = kK4 / WK;                                 // per lane
+        const bool keeping = NS <= kKeepUpTo && keep_mine;               // (never, for most numbers of ranges: their copies carry no code for it)
         // items requested together: the largest power of two with at most 32 requests (of 8 bytes)
         // per lane; the partial results were written a long time ago and come from memory, so a
         // batch is a full round trip
@@ -910,17 +911,24 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         auto request = [&](int k0, uint2 (&dst)[kBatch][NS]) __attribute__((always_inline)) {
 #pragma unroll
             for (int r = 0; r < NS; ++r) {
-                if (keep_mine && r == split) {   // (mine are in `kept`)
+                if (keeping && r == split) {   // (mine are in `kept`)
 #pragma unroll
                     for (int j = 0; j < kBatch; ++j) dst[j][r] = make_uint2(0u, 0u);
                     continue;
                 }
-                const uint2* const src_r = src + (size_t)min(r, S - 1) * (range_words / 2) + k0 * 64;
+                // (a base in scalar registers plus the lane: an address pair per range in vector
+                // registers, which is what the compiler makes of an atomic load otherwise, does not fit)
+                const uint2* const src_r = static_cast<const uint2*>(scalar_pointer(src + (size_t)min(r, S - 1) * (range_words / 2) + k0 * 64));
 #pragma unroll
-                for (int j = 0; j < kBatch; ++j) dst[j][r] = src_r[j * 64 + lane];
+                for (int j = 0; j < kBatch; ++j) {
+                    const unsigned long long two = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src_r + j * 64 + lane),
+                                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    dst[j][r] = make_uint2((uint32_t)two, (uint32_t)(two >> 32));
+                }
             }
         };
         request(0, v[0]);
+        ATTN_STAMP(25);
         float f[NS];
         float lsum = 0.f;
         {
@@ -928,10 +936,14 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
             float mv[NS], lv[NS];
 #pragma unroll
             for (int r = 0; r < NS; ++r) {
-                const float* m = ml + (size_t)min(r, S - 1) * range_words;
-                const bool mine = keep_mine && r == split;
-                mv[r] = mine ? kept_m : m[lane];
-                lv[r] = mine ? kept_l : m[64 + lane];
+                const float* m = static_cast<const float*>(scalar_pointer(ml + (size_t)min(r, S - 1) * range_words));
+                const bool mine = keeping && r == split;
+                // (asked for whether mine or not: under a condition every one of these loads
+                // would be a block of its own with a wait at its end)
+                const float m_r = __hip_atomic_load(m + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float l_r = __hip_atomic_load(m + 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                mv[r] = mine ? kept_m : m_r;
+                lv[r] = mine ? kept_l : l_r;
             }
             float big = -INFINITY;
 #pragma unroll
@@ -946,6 +958,25 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
             }
         }
         const float inv = __builtin_amdgcn_rcpf(lsum);
+        ATTN_STAMP(26);
+        // The merged rows leave through LDS (the rings, free by now).  A lane holds four features
+        // of its query per item: stored from there, an instruction writes 16 bytes to each of 32
+        // rows of `out`, and a row is put together from eight such instructions -- one CU's
+        // memory pipeline took 8 us over the 64 KB of a unit that way.  Each wavefront drops its
+        // items into a tile of its own, [32 queries][its 16 * kItems bytes of a row] (rows 16
+        // bytes apart from a multiple of 256: two-way bank conflicts at worst), and writes the
+        // tile out with 16 bytes per lane, whole runs of a row per instruction.
+        constexpr int kSpanBytes = 16 * kItems;
+        constexpr int kStageRow = kSpanBytes + 16;
+        static_assert(8 * 32 * kStageRow <= (int)sizeof(Rings<D, kCells>), "the rows of eight wavefronts fit the rings");
+        char* const stage = reinterpret_cast<char*>(lds_f) + (size_t)wave * 32 * kStageRow;
+        auto stage_out = [&](int item, float4 acc) __attribute__((always_inline)) {
+            f32x2_t lo = {acc.x * inv, acc.y * inv}, hi = {acc.z * inv, acc.w * inv};
+            uint2 w;
+            w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2_t));
+            w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
+            *reinterpret_cast<uint2*>(stage + col * kStageRow + item * 16 + half * 8) = w;
+        };
         auto sum_up = [&](int k0, const uint2 (&src_v)[kBatch][NS]) __attribute__((always_inline)) {
 #pragma unroll
             for (int j = 0; j < kBatch; ++j) {
@@ -954,13 +985,13 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
                 for (int r = 0; r < NS; ++r) {
                     uint2 item = src_v[j][r];
                     if constexpr (kItems == kBatch) {
-                        if (keep_mine && r == split) item = kept[j];
+                        if (keeping && r == split) item = kept[j];
                     }
                     const half2_t lo = __builtin_bit_cast(half2_t, item.x), hi = __builtin_bit_cast(half2_t, item.y);
                     acc.x = fmaf((float)lo[0], f[r], acc.x); acc.y = fmaf((float)lo[1], f[r], acc.y);
                     acc.z = fmaf((float)hi[0], f[r], acc.z); acc.w = fmaf((float)hi[1], f[r], acc.w);
                 }
-                store_out(wk * kItems + k0 + j, acc, inv);
+                stage_out(k0 + j, acc);
             }
         };
         if constexpr (kItems == kBatch) {
@@ -973,6 +1004,22 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
                 sum_up(k0, v[0]);
                 if (k0 + 2 * kBatch < kItems) request(k0 + 2 * kBatch, v[0]);
                 sum_up(k0 + kBatch, v[1]);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // my lanes' items are in the tile (nobody else's are)
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        constexpr int kLanesPerRow = kSpanBytes / 16, kRowsPerPass = 64 / kLanesPerRow, kPasses = 32 / kRowsPerPass;
+        const int chunk = lane % kLanesPerRow;
+#pragma unroll
+        for (int pass = 0; pass < kPasses; ++pass) {
+            const int row = pass * kRowsPerPass + lane / kLanesPerRow;
+            const int qrow = qb * kUnitRows + wqw * 32 + row;
+            if (qrow < rows) {
+                const int node = (int)fast_div((uint32_t)qrow, p.by_G);
+                const uint4 v16 = *reinterpret_cast<const uint4*>(stage + row * kStageRow + chunk * 16);
+                uint16_t* const dst = p.out + ((size_t)node * p.H + (g * p.G + (qrow - node * p.G))) * D;
+                *reinterpret_cast<uint4*>(reinterpret_cast<char*>(dst) + wk * kSpanBytes + chunk * 16) = v16;
             }
         }
     };
@@ -990,6 +1037,7 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
         case 11: case 12: merge_ranges(std::integral_constant<int, 12>{}); break;
         default: merge_ranges(std::integral_constant<int, kMaxSplits>{}); break;
     }
+    if (tid == 0) atomicExch(&p.counters[unit], 0u);   // every range has been counted: ready for the next call
     ATTN_STAMP(24);
     ATTN_STAMP_FLUSH();
 }
