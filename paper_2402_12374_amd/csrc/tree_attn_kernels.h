@@ -20,6 +20,7 @@ struct AttnSchedule {
     int query_blocks;   // units per KV head
     int splits;
     int short_ranges, short_weight, long_weight;   // the first short_ranges ranges have weight short_weight, the others long_weight (equal ranges: 0, 1, 1)
+    int long_tiles;     // > 0: long ranges of this many tiles in every unit; 0: each range its weight's share of its unit's tiles
     size_t workspace_bytes;
 };
 constexpr int kKeyTile = 32;

@@ -73,19 +73,36 @@ struct MfmaParams {
     FastDiv by_seq_kv_heads;      // KV heads per sequence (KV head g belongs to sequence g / that)
     int splits;
     int short_ranges, short_weight, long_weight;   // the first short_ranges key ranges of a unit have weight short_weight, the others long_weight
+    int long_tiles;       // > 0: every long range has this many tiles, whatever its unit's number of tiles (see range_start)
     int keep_own;         // a long range's workgroup may keep its partial result in registers (see the end of the tile loop)
     float* partials;
     uint32_t* counters;
     float scale_log2;     // log2(e) / sqrt(D)
     int share_l2;         // all workgroups of a unit run on one XCD (checked once per device)
     FastDiv by_units_per_xcd, by_query_blocks, by_G, by_weights;   // the divisions of the prologue (by_weights: by the sum of the ranges' weights)
+    FastDiv by_short_ranges;
 };
 
-// First tile of key range `range` of a unit with `tiles` tiles.  The first `short_ranges` ranges
-// have weight `short_weight`, the others `long_weight`; `by_weights` divides by the sum of all
-// weights (equal ranges: no short ones, weight 1, the sum is their number).  tiles x sum < 2^31.
-__host__ __device__ __forceinline__ int range_start(int tiles, int range, int short_ranges, int short_weight, int long_weight,
-                                                    const FastDiv& by_weights) {
+// First tile of key range `range` (of `ranges`) of a unit with `tiles` tiles.  The first
+// `short_ranges` ranges have weight `short_weight`, the others `long_weight`; `by_weights` divides
+// by the sum of all weights (equal ranges: no short ones, weight 1, the sum is their number).
+// tiles x sum < 2^31.
+// With `long_tiles` > 0 the long ranges are the same length in every unit instead, counted from
+// the end of the unit's tiles, and the short ranges share what is left: the units of a KV head
+// differ in their tree tiles (the last row block sees all of them, the first one tile), a long
+// range is a workgroup with a compute unit to itself from the start of the launch to its end,
+// and the launch ends with the longest of them; the short ranges run several in a row, so their
+// differences average out.
+__host__ __device__ __forceinline__ int range_start(int tiles, int range, int ranges, int short_ranges, int short_weight,
+                                                    int long_weight, int long_tiles, const FastDiv& by_weights,
+                                                    const FastDiv& by_short_ranges) {
+    if (long_tiles > 0) {
+        const int shorts_end = tiles - (ranges - short_ranges) * long_tiles;
+        const int short_total = shorts_end > 0 ? shorts_end : 0;
+        if (range <= short_ranges) return (int)fast_div((uint32_t)short_total * (uint32_t)range, by_short_ranges);
+        const int start = tiles - (ranges - range) * long_tiles;
+        return start > short_total ? start : short_total;
+    }
     const int before = range <= short_ranges ? range * short_weight
                                              : short_ranges * short_weight + (range - short_ranges) * long_weight;
     return (int)fast_div((uint32_t)tiles * (uint32_t)before, by_weights);
@@ -403,8 +420,8 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
     const int tree_tiles = i_max / kKeyTile + 1;
     const int total_tiles = prefix_tiles + tree_tiles;
     // (at most 2^26 tiles times 16 ranges: below 2^31)
-    const int t_begin = range_start(total_tiles, split, p.short_ranges, p.short_weight, p.long_weight, p.by_weights);
-    const int t_end = range_start(total_tiles, split + 1, p.short_ranges, p.short_weight, p.long_weight, p.by_weights);
+    const int t_begin = range_start(total_tiles, split, S, p.short_ranges, p.short_weight, p.long_weight, p.long_tiles, p.by_weights, p.by_short_ranges);
+    const int t_end = range_start(total_tiles, split + 1, S, p.short_ranges, p.short_weight, p.long_weight, p.long_tiles, p.by_weights, p.by_short_ranges);
     const int n_rounds = (t_end - t_begin + WK - 1) / WK;
 
     const uint32_t k_lds = lds_address(&sm.k[0][0]);
@@ -1048,6 +1065,7 @@ int g_splits_override = 0;  // tuning hooks, 0 = automatic
 int g_wq_override = 0;
 int g_keep_own = 1;   // test hook: 0 = every partial result goes through memory
 int g_uneven_override = -1, g_short_weight_override = 1, g_long_weight_override = 1;   // -1 = automatic, 0 = equal ranges only, m > 0 = m short ranges
+int g_long_tiles_override = -1;   // -1 = automatic, 0 = long ranges in proportion to their unit's tiles, L > 0 = long ranges of L tiles
 
 AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     AttnSchedule s;
@@ -1066,7 +1084,9 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     // the rows of a KV head fill is never considered; a smaller one is, because it multiplies the
     // units when there are few KV heads.
     const int wq_cover = rows <= 64 ? 2 : (rows <= 128 ? 4 : 8);
-    constexpr long kFixed = 80, kHandOver = 40;   // prologue and epilogue of a workgroup; partial results handed over and merged at all
+    constexpr long kFixed = 70, kHandOver = 20;   // prologue and epilogue of a workgroup; partial results handed over and merged at all
+    constexpr long kFixedShort = 120;             // the same of a short range that runs behind another (measured at the lengths below)
+    double long_share = 0.;                       // of the ranges of two sizes chosen, before rounding to 64ths
     long best = -1;
     s.wq = wq_cover;
     s.splits = 1;
@@ -1082,7 +1102,7 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
             if (g_splits_override > 0 && cand != std::min(g_splits_override, max_splits)) continue;
             const long batches = ((long)units * cand + 255) / 256;
             const long rounds = (tiles + cand * wk - 1) / (cand * wk);
-            const long cost = batches * (rounds * round_cost + kFixed + (cand > 1 ? kHandOver + 3 * cand * wq / 2 : 0));
+            const long cost = batches * (rounds * round_cost + kFixed + (cand > 1 ? kHandOver + 2 * cand * wq : 0));
             if (best < 0 || cost < best) { best = cost; s.wq = wq; s.splits = cand; s.short_ranges = 0; s.short_weight = s.long_weight = 1; }
         }
         // Ranges of two sizes.  When the units leave CUs over but too few for another range each
@@ -1100,22 +1120,46 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
             if (k > 3) break;      // (measured: with more short ranges in a row their fixed parts eat the gain)
             // the long ranges' share f of a unit's tiles for which a long workgroup takes as long
             // as k short ones in a row, in 64ths
-            const long all_rounds = (tiles + wk - 1) / wk, fixed = kFixed, merge = kHandOver + 3 * (longs + 1) * wq / 2;
-            const long num = k * all_rounds * round_cost + (k - 1) * fixed - merge, den = all_rounds * round_cost * (1 + k * longs);
+            const long all_rounds = (tiles + wk - 1) / wk, merge = kHandOver + 2 * (longs + 1) * wq;
+            const long num = k * all_rounds * round_cost + k * kFixedShort - kFixed - merge, den = all_rounds * round_cost * (1 + k * longs);
             const int long_w = (int)((64 * num + den / 2) / den), short_w = 64 - longs * long_w;
             if (long_w < 1 || short_w < 1) continue;
             const long rounds_long = ((long)tiles * long_w / 64 + wk) / wk, rounds_short = ((long)tiles * short_w / 64 + wk) / wk;
             if (rounds_short < 16) continue;   // (measured: short ranges of a few rounds are all fixed part, which the model overrates evenly but not here)
-            const long cost = std::max(rounds_long * round_cost + fixed + merge, k * (rounds_short * round_cost + fixed));
-            if (cost < best) { best = cost; s.wq = wq; s.splits = longs + 1; s.short_ranges = 1; s.short_weight = short_w; s.long_weight = long_w; }
+            const long cost = std::max(rounds_long * round_cost + kFixed + merge, k * (rounds_short * round_cost + kFixedShort));
+            if (cost < best) {
+                best = cost; s.wq = wq; s.splits = longs + 1; s.short_ranges = 1; s.short_weight = short_w; s.long_weight = long_w;
+                long_share = (double)num / (double)den;
+            }
         }
     }
+    if (s.short_ranges == 0) long_share = 0.;   // (an equal candidate of another wq won in the end)
     if (g_uneven_override > 0 && g_uneven_override < s.splits) {
         s.short_ranges = g_uneven_override;
         s.short_weight = g_short_weight_override;
         s.long_weight = g_long_weight_override;
+        long_share = 0.;
     }
     s.query_blocks = (rows + 32 * s.wq - 1) / (32 * s.wq);
+    // Long ranges of one length: the long share of the tiles of the average unit (the units of a
+    // KV head differ in their tree tiles; with one unit per head nothing changes).  Taken by
+    // itself from eight units per head on: the short ranges then differ in length from unit to
+    // unit, workgroups are dispatched in the order of the units, and with few units per head the
+    // same compute unit gets several of the longest short ranges in a row (two units per head,
+    // three short ranges in a row: 12 % slower than shares in proportion).
+    s.long_tiles = 0;
+    if (s.short_ranges > 0 && g_long_tiles_override != 0 && (g_long_tiles_override > 0 || s.query_blocks >= 8)) {
+        long tree_tiles = 0;
+        for (int qb = 0; qb < s.query_blocks; ++qb) {
+            const int last_row = std::min(rows - 1, qb * 32 * s.wq + 32 * s.wq - 1);
+            tree_tiles += last_row / G / kKeyTile + 1;
+        }
+        const double mean_tiles = (double)prefix_tiles + (double)tree_tiles / s.query_blocks;
+        if (long_share <= 0.)
+            long_share = (double)s.long_weight / (double)(s.short_ranges * s.short_weight + (s.splits - s.short_ranges) * s.long_weight);
+        s.long_tiles = g_long_tiles_override > 0 ? g_long_tiles_override : (int)(mean_tiles * long_share + 0.5);
+        if (s.long_tiles < 1) s.long_tiles = 0;
+    }
     const int units = Hk * s.query_blocks;
     const size_t block_words = (size_t)(D / 32) * 4 * 128 + 128;   // one (unit, range, query block): fp16 output, fp32 statistics
     s.workspace_bytes = s.splits > 1 ? (size_t)units * s.splits * s.wq * block_words * sizeof(float) : 0;
@@ -1155,6 +1199,8 @@ int launch_tree_attn_mfma_bf16(const void* q, const void* k_cache, const void* v
     p.short_ranges = sched.short_ranges;
     p.short_weight = sched.short_weight;
     p.long_weight = sched.long_weight;
+    p.long_tiles = prefix_lens ? 0 : sched.long_tiles;   // (lengths that differ by sequence: each unit's own proportion)
+    p.by_short_ranges = make_fast_div((uint32_t)std::max(sched.short_ranges, 1));
     p.keep_own = g_keep_own;
     p.by_weights = make_fast_div((uint32_t)(sched.short_ranges * sched.short_weight + (sched.splits - sched.short_ranges) * sched.long_weight));
     if (units > kAttnMaxCounters) return SEQ_ERR_SHAPE;
@@ -1197,10 +1243,17 @@ extern "C" void seqtree_internal_attn_schedule(int P, int n, int H, int Hk, int 
     const seqtree::AttnSchedule s = seqtree::plan_attn_schedule(P, n, H, Hk, D);
     five[0] = s.wq; five[1] = s.splits; five[2] = s.short_ranges; five[3] = s.short_weight; five[4] = s.long_weight;
 }
-extern "C" int seqtree_internal_attn_range_start(int tiles, int range, int ranges, int short_ranges, int short_weight, int long_weight) {
+extern "C" int seqtree_internal_attn_range_start(int tiles, int range, int ranges, int short_ranges, int short_weight, int long_weight,
+                                                 int long_tiles) {
     const seqtree::FastDiv by = seqtree::make_fast_div((uint32_t)(short_ranges * short_weight + (ranges - short_ranges) * long_weight));
-    return seqtree::range_start(tiles, range, short_ranges, short_weight, long_weight, by);
+    const seqtree::FastDiv by_short = seqtree::make_fast_div((uint32_t)(short_ranges > 0 ? short_ranges : 1));
+    return seqtree::range_start(tiles, range, ranges, short_ranges, short_weight, long_weight, long_tiles, by, by_short);
 }
+// the length the library would give the long ranges (0: in proportion to each unit's tiles)
+extern "C" int seqtree_internal_attn_long_tiles(int P, int n, int H, int Hk, int D) {
+    return seqtree::plan_attn_schedule(P, n, H, Hk, D).long_tiles;
+}
+extern "C" void seqtree_internal_set_attn_long_tiles(int mode) { seqtree::g_long_tiles_override = mode; }
 extern "C" void seqtree_internal_set_attn_keep_own(int on) { seqtree::g_keep_own = on; }
 extern "C" void seqtree_internal_set_attn_uneven(int short_ranges, int short_weight, int long_weight) {
     seqtree::g_uneven_override = short_ranges;

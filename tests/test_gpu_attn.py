@@ -184,15 +184,42 @@ def test_key_ranges_of_two_sizes(d):
         S.lib().seqtree_internal_set_attn_uneven(-1, 1, 1)
 
 
+def test_long_ranges_of_one_length_for_all_units():
+    """Where a KV head has many units the long ranges get one length for all of them, counted from
+    the end of each unit's tiles, and the short ranges what is left (the units differ in their
+    tree tiles).  Forced here on a small shape whose units have 36 to 45 tiles: lengths from one
+    tile to more than a unit has (short ranges, and then long ones, come out empty)."""
+    import paper_2402_12374_amd as S
+    rng = np.random.default_rng(21)
+    a = W.make_attn_inputs(8, 2, 128, 1101, W.random_topological_tree(300, rng), W.BF16, seed=5, prefix_cap=1110)
+    ref = oracle_attn_all_rows(a)
+    try:
+        for wq, splits, shorts in ((2, 2, 1), (4, 3, 1), (8, 3, 2), (8, 5, 1), (2, 4, 3)):
+            S.lib().seqtree_internal_set_attn_wq(wq)
+            S.lib().seqtree_internal_set_attn_splits(splits)
+            S.lib().seqtree_internal_set_attn_uneven(shorts, 1, 3)
+            for length in (1, 7, 18, 30, 1000):
+                S.lib().seqtree_internal_set_attn_long_tiles(length)
+                err = np.abs(run_attn(a) - ref).max()
+                assert err <= TOL[W.BF16], (wq, splits, shorts, length, err)
+    finally:
+        S.lib().seqtree_internal_set_attn_wq(0)
+        S.lib().seqtree_internal_set_attn_splits(0)
+        S.lib().seqtree_internal_set_attn_uneven(-1, 1, 1)
+        S.lib().seqtree_internal_set_attn_long_tiles(-1)
+
+
 def test_the_shapes_that_take_ranges_of_two_sizes_by_themselves():
     """Shapes at which the library's own choice is ranges of two sizes (one or two long ranges per
-    unit, workgroups of 8 or 4 row blocks), all rows against the checker."""
+    unit, workgroups of 8 or 4 row blocks; long ranges of one length where a KV head has many
+    units, in proportion to their unit's tiles where it has few), all rows against the checker."""
     import ctypes
     import paper_2402_12374_amd as S
     five = (ctypes.c_int * 5)()
-    for H, Hk, P, n in ((64, 8, 1024, 640), (64, 8, 2500, 384), (52, 52, 4096, 320)):
+    for H, Hk, P, n, one_length in ((64, 8, 3000, 640, True), (88, 88, 4096, 256, False), (52, 52, 4096, 320, False)):
         S.lib().seqtree_internal_attn_schedule(P, n, H, Hk, 128, five)
         assert five[2] >= 1, (H, Hk, P, n, list(five))
+        assert (S.lib().seqtree_internal_attn_long_tiles(P, n, H, Hk, 128) > 0) == one_length, (H, Hk, P, n)
         a = W.make_attn_inputs(H, Hk, 128, P, W.geometric_tree(n, 10), W.BF16, seed=n)
         got = run_attn(a)
         assert np.abs(got - oracle_attn_all_rows(a)).max() <= TOL[W.BF16], (H, Hk, P, n)
@@ -213,7 +240,7 @@ def test_seeded_random_shapes_under_the_library_s_own_schedule():
     ranges of two sizes, so that a change of the cost figures cannot quietly narrow the test."""
     import ctypes
     import paper_2402_12374_amd as S
-    rng, tree_rng = np.random.default_rng(2402), np.random.default_rng(12374)
+    rng, tree_rng = np.random.default_rng(2436), np.random.default_rng(12374)
     five = (ctypes.c_int * 5)()
     picks = []
     for case in range(14):
@@ -223,12 +250,13 @@ def test_seeded_random_shapes_under_the_library_s_own_schedule():
         n = int(rng.integers(1, 420))
         P = int(rng.integers(0, 3600))
         S.lib().seqtree_internal_attn_schedule(P, n, Hk * G, Hk, d, five)
-        picks.append(tuple(five))
+        picks.append(tuple(five) + (S.lib().seqtree_internal_attn_long_tiles(P, n, Hk * G, Hk, d),))
         parent = W.random_topological_tree(n, tree_rng) if case % 2 else W.geometric_tree(n, 9)
         a = W.make_attn_inputs(Hk * G, Hk, d, P, parent, W.BF16, seed=100 + case, prefix_cap=P + 1 + case)
         err = np.abs(run_attn(a) - oracle_attn_all_rows(a)).max()
         assert err <= TOL[W.BF16], (case, (Hk * G, Hk, d, P, n), picks[-1], err)
     assert sum(1 for k in picks if k[2] > 0) >= 2, picks           # ranges of two sizes
+    assert sum(1 for k in picks if k[5] > 0) >= 1, picks           # long ranges of one length
     assert len({k[:2] for k in picks}) >= 6, picks                  # (row blocks, ranges) pairs
     assert {k[0] for k in picks} == {2, 4, 8}, picks
 

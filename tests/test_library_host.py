@@ -393,12 +393,15 @@ def test_no_kernel_needs_the_dispatch_packet_or_scratch_memory(tmp_path):
     assert kernels >= 20
 
 
-def test_attention_schedule_takes_ranges_of_two_sizes_where_units_leave_compute_units_over():
+def schedule(P, n, H, Hk, d=128):
+    """(row blocks per workgroup, key ranges, short ranges, short weight, long weight) the library would take."""
     import ctypes
     five = (ctypes.c_int * 5)()
-    def schedule(P, n, H, Hk, d=128):
-        S.lib().seqtree_internal_attn_schedule(P, n, H, Hk, d, five)
-        return tuple(five)
+    S.lib().seqtree_internal_attn_schedule(P, n, H, Hk, d, five)
+    return tuple(five)
+
+
+def test_attention_schedule_takes_ranges_of_two_sizes_where_units_leave_compute_units_over():
     # the four configurations: equal ranges for the Llama2 and Vicuna shapes; the Llama3-70B one
     # (192 units on 256 compute units) gets one long and one short range per unit, the long one
     # about three quarters of the tiles (three short ones run in a row on the 64 units left over)
@@ -425,10 +428,46 @@ def test_key_ranges_of_either_kind_cut_the_tiles_into_consecutive_pieces():
     for ranges, shorts, short_w, long_w in ((1, 0, 1, 1), (4, 0, 1, 1), (16, 0, 1, 1), (2, 1, 15, 49), (3, 1, 12, 26),
                                             (2, 1, 1, 63), (5, 2, 3, 7), (16, 15, 1, 49), (7, 3, 2, 5)):
         for tiles in list(range(1, 400)) + [1000, 4097, 65536, 1 << 20]:
-            cuts = [start(tiles, r, ranges, shorts, short_w, long_w) for r in range(ranges + 1)]
+            cuts = [start(tiles, r, ranges, shorts, short_w, long_w, 0) for r in range(ranges + 1)]
             assert cuts[0] == 0 and cuts[-1] == tiles, (ranges, shorts, tiles, cuts)
             assert all(a <= b for a, b in zip(cuts, cuts[1:])), (ranges, shorts, tiles, cuts)
             total = shorts * short_w + (ranges - shorts) * long_w
             for r in range(ranges):   # a range's length is its share of the tiles, to within one tile
                 share = tiles * (short_w if r < shorts else long_w) / total
                 assert abs((cuts[r + 1] - cuts[r]) - share) < 1.0 + 1e-9, (ranges, shorts, tiles, r, cuts)
+    # long ranges of one length for all units, counted from the end; the short ones share the rest
+    for ranges, shorts, length in ((2, 1, 206), (3, 1, 100), (2, 1, 1), (5, 2, 7), (16, 15, 3), (4, 3, 50)):
+        for tiles in list(range(1, 400)) + [1000, 4097, 65536, 1 << 20]:
+            cuts = [start(tiles, r, ranges, shorts, 1, 1, length) for r in range(ranges + 1)]
+            assert cuts[0] == 0 and cuts[-1] == tiles, (ranges, shorts, length, tiles, cuts)
+            assert all(a <= b for a, b in zip(cuts, cuts[1:])), (ranges, shorts, length, tiles, cuts)
+            longs = ranges - shorts
+            if tiles >= longs * length:
+                assert all(cuts[r + 1] - cuts[r] == length for r in range(shorts, ranges)), (ranges, shorts, length, tiles, cuts)
+            else:   # too few tiles for all of them: the last ones are whole, the one before takes what is left
+                assert cuts[shorts] == 0
+                assert all(cuts[r + 1] - cuts[r] in (0, length) or cuts[r] == 0 for r in range(shorts, ranges)), (tiles, cuts)
+            rest = cuts[shorts]
+            assert all(abs((cuts[r + 1] - cuts[r]) - rest / shorts) < 1.0 + 1e-9 for r in range(shorts)), (ranges, shorts, length, tiles, cuts)
+
+
+def test_long_ranges_have_one_length_where_a_kv_head_has_many_units():
+    length = S.lib().seqtree_internal_attn_long_tiles
+    # C5: 24 units per KV head with 256 prefix tiles and 1..24 tree tiles, 268.5 on average; the
+    # long share of that, within a tile or two of 64ths (measured optimum: 207 +- 1 tiles)
+    wq, ranges, shorts, short_w, long_w = schedule(8192, 768, 64, 8)
+    assert (wq, ranges, shorts) == (8, 2, 1)
+    assert abs(length(8192, 768, 64, 8, 128) - 268.5 * long_w / 64) <= 2.5
+    assert 205 <= length(8192, 768, 64, 8, 128) <= 210
+    # few units per KV head: ranges of two sizes, each its share of its own unit's tiles
+    assert schedule(4096, 256, 88, 88)[2] == 1 and length(4096, 256, 88, 88, 128) == 0
+    assert schedule(8192, 640, 32, 32)[2] == 1 and length(8192, 640, 32, 32, 128) == 0
+    # equal ranges: no such thing
+    assert length(1024, 64, 32, 32, 128) == 0
+    S.lib().seqtree_internal_set_attn_long_tiles(0)
+    try:
+        assert length(8192, 768, 64, 8, 128) == 0
+        S.lib().seqtree_internal_set_attn_long_tiles(123)
+        assert length(8192, 768, 64, 8, 128) == 123 and length(4096, 256, 88, 88, 128) == 123
+    finally:
+        S.lib().seqtree_internal_set_attn_long_tiles(-1)
