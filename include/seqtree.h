@@ -74,6 +74,7 @@ extern "C" {
 #define SEQ_ERR_ALGORITHM (-8)   /* algorithm is none of SEQ_VERIFY_* */
 #define SEQ_ERR_FULL (-9)        /* SEQ_MAX_PLANS distinct trees or SEQ_MAX_STREAMS streams are already in use */
 #define SEQ_ERR_CAPTURE (-10)    /* under stream capture: first call for this tree, or first call on this device */
+#define SEQ_ERR_ALIGN (-11)      /* seq_tree_attn*: q, k/v cache, k/v tree or out not 16-byte aligned */
 
 #define SEQ_MAX_TREE 1024
 #define SEQ_MAX_VOCAB 524288
@@ -100,6 +101,8 @@ extern "C" {
  *   dtype    SEQ_BF16 (bf16 MFMA, fp32 accumulation) or SEQ_F32 (fp32 throughout)
  *   workspace, workspace_bytes   scratch of at least seq_tree_attn_workspace(...) bytes
  *
+ * All six tensors are DEVICE memory and 16-byte aligned (the kernels move them 16 bytes at a
+ * time; SEQ_ERR_ALIGN otherwise).
  * prefix_len = 0 (tree only) and n_tree = 1 (plain decode attention) are legal.
  *
  * A batch of B sequences that share the tree and the prefix length is one call with

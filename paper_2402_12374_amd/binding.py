@@ -19,6 +19,7 @@ SEQ_BF16, SEQ_F32 = 1, 2
 SEQ_OK = 0
 SEQ_ERR_NULL, SEQ_ERR_SHAPE, SEQ_ERR_TREE, SEQ_ERR_DTYPE = -1, -2, -3, -4
 SEQ_ERR_TEMPERATURE, SEQ_ERR_WORKSPACE, SEQ_ERR_HIP, SEQ_ERR_ALGORITHM, SEQ_ERR_FULL, SEQ_ERR_CAPTURE = -5, -6, -7, -8, -9, -10
+SEQ_ERR_ALIGN = -11
 SEQ_VERIFY_SEQUOIA, SEQ_VERIFY_SPECINFER, SEQ_VERIFY_TOPK = 0, 1, 2
 SEQ_MAX_TREE = 1024
 SEQ_MAX_VOCAB = 524288

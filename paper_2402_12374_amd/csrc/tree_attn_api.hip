@@ -1,5 +1,6 @@
 // seq_tree_attn: argument checks (host only, before any GPU call), tree plan lookup, dispatch.
 #include <cmath>
+#include <cstdint>
 
 #include "seq_internal.h"
 #include "tree_attn_kernels.h"
@@ -14,6 +15,12 @@ static int check_attn_shape(int32_t prefix_len, int32_t n_tree, int32_t heads, i
     if (heads < 1 || kv_heads < 1 || heads % kv_heads != 0) return SEQ_ERR_SHAPE;
     if (prefix_len < 0 || prefix_len > prefix_cap) return SEQ_ERR_SHAPE;
     return SEQ_OK;
+}
+
+static bool aligned16(const void* a, const void* b, const void* c, const void* d, const void* e, const void* f) {
+    const uintptr_t all = reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | reinterpret_cast<uintptr_t>(c) |
+                          reinterpret_cast<uintptr_t>(d) | reinterpret_cast<uintptr_t>(e) | reinterpret_cast<uintptr_t>(f);
+    return (all & 15u) == 0;   // (a cache that may be NULL counts as aligned)
 }
 
 extern "C" size_t seq_tree_attn_workspace(int32_t prefix_len, int32_t n_tree, int32_t heads,
@@ -33,6 +40,7 @@ extern "C" int seq_tree_attn(const void* q, const void* k_cache, const void* v_c
     int rc = check_attn_shape(prefix_len, n_tree, heads, kv_heads, head_dim, prefix_cap, dtype);
     if (rc != SEQ_OK) return rc;
     if (prefix_len > 0 && (!k_cache || !v_cache)) return SEQ_ERR_NULL;
+    if (!aligned16(q, k_cache, v_cache, k_tree, v_tree, out)) return SEQ_ERR_ALIGN;
     rc = validate_parent(parent, n_tree);
     if (rc != SEQ_OK) return rc;
     AttnSchedule sched{};
@@ -93,6 +101,7 @@ extern "C" int seq_tree_attn_batched(const void* q, const void* k_cache, const v
     if (rc != SEQ_OK) return rc;
     if (heads % kv_heads != 0) return SEQ_ERR_SHAPE;
     if (max_prefix_len > 0 && (!k_cache || !v_cache)) return SEQ_ERR_NULL;
+    if (!aligned16(q, k_cache, v_cache, k_tree, v_tree, out)) return SEQ_ERR_ALIGN;
     rc = validate_parent(parent, n_tree);
     if (rc != SEQ_OK) return rc;
     const int H = batch * heads, Hk = batch * kv_heads;

@@ -117,6 +117,9 @@ extern "C" int seq_tree_attn_noalloc(const void* q, const void* k_cache, const v
     if (heads < 1 || kv_heads < 1 || heads % kv_heads != 0) return SEQ_ERR_SHAPE;
     if (prefix_len < 0 || prefix_len > prefix_cap) return SEQ_ERR_SHAPE;
     if (prefix_len > 0 && (!k_cache || !v_cache)) return SEQ_ERR_NULL;
+    if (((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_cache) | reinterpret_cast<uintptr_t>(v_cache) |
+          reinterpret_cast<uintptr_t>(k_tree) | reinterpret_cast<uintptr_t>(v_tree) | reinterpret_cast<uintptr_t>(out)) & 15u) != 0)
+        return SEQ_ERR_ALIGN;
     int rc = validate_parent(parent, n_tree);
     if (rc != SEQ_OK) return rc;
 

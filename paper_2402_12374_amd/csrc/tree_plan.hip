@@ -333,6 +333,7 @@ extern "C" const char* seq_strerror(int code) {
         case SEQ_ERR_ALGORITHM: return "algorithm must be one of SEQ_VERIFY_*";
         case SEQ_ERR_FULL: return "too many distinct trees or streams: seq_shutdown() releases them";
         case SEQ_ERR_CAPTURE: return "first call for this tree or device made under stream capture: make it once outside";
+        case SEQ_ERR_ALIGN: return "an attention tensor is not 16-byte aligned";
         default: return "unknown seqtree error code";
     }
 }

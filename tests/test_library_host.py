@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported():
 def test_version_and_strerror():
     assert S.version() >= 100
     assert S.strerror(0) == "ok"
-    for code in range(-7, 0):
+    for code in range(-11, 0):
         assert "unknown" not in S.strerror(code)
     assert "unknown" in S.strerror(-99)
 
@@ -51,6 +51,10 @@ def test_attn_argument_errors_need_no_gpu():
     assert _attn(good, n=0) == B.SEQ_ERR_SHAPE
     assert _attn(good, n=B.SEQ_MAX_TREE + 1) == B.SEQ_ERR_SHAPE
     assert _attn(good, dtype=7) == B.SEQ_ERR_DTYPE
+    # the kernels move the tensors 16 bytes at a time
+    assert _attn(good, q=0x1008) == B.SEQ_ERR_ALIGN
+    assert _attn(good, out=0x1004) == B.SEQ_ERR_ALIGN
+    assert _attn(good, ptr=0x1002) == B.SEQ_ERR_ALIGN
     assert _attn([0, 0, 0, 1]) == B.SEQ_ERR_TREE
     assert _attn([-1, 0, 2, 1]) == B.SEQ_ERR_TREE
     assert _attn([-1, 0, -1, 1]) == B.SEQ_ERR_TREE
