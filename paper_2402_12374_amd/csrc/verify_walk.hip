@@ -67,11 +67,29 @@ struct Shared {
     unsigned char child_dup[SEQ_MAX_TREE];  // child's token already carried by an earlier sibling
     // What the first wavefront, which keeps the state of Algorithm 2 at the current node in its
     // registers, tells the others after every step (written by its lane 0, read after a barrier).
-    struct {
+    // The four words everybody needs after every step come first and are read with one 16-byte
+    // load, together with `fail`: read one after the other, behind the branches that use them,
+    // they were three trips to shared memory on the path of every rejection.
+    struct __attribute__((aligned(16))) {
         float af, bf;               // coefficients of the residual for the next pass
-        int action, next, zero_token, n_dec, sums_valid, fallbacks, degenerate;
+        int action, zero_token;
+        int next, n_dec, sums_valid, fallbacks, degenerate;
     } st;
 };
+
+// What a thread takes from the first wavefront's message after a step's barrier.
+struct StepWord {
+    float af, bf;
+    int action, zero_token, fail;
+};
+__device__ __forceinline__ StepWord read_step(const Shared& sh) {
+    const uint4 w = *reinterpret_cast<const uint4*>(&sh.st);
+    const int fail = sh.fail;
+    StepWord s;
+    s.af = __uint_as_float(w.x); s.bf = __uint_as_float(w.y);
+    s.action = (int)w.z; s.zero_token = (int)w.w; s.fail = fail;
+    return s;
+}
 
 // All-to-all of K floats per workgroup, run by the first wavefront only.  mine[k] is this
 // workgroup's value; afterwards lane w of the wavefront holds workgroup w's values in got[]
@@ -386,7 +404,8 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
         par ^= 1;
         __syncthreads();
         SEQ_STAMP(4);
-        if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
+        StepWord sw = read_step(sh);
+        if (sw.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
         {
             const float ft = mt_wave == -INFINITY ? 0.f : exp_fast(mt_wave - sh.stat[0]) * sh.stat[2];
             const float fd = md_wave == -INFINITY ? 0.f : exp_fast(md_wave - sh.stat[1]) * sh.stat[3];
@@ -395,9 +414,9 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
         }
 
         // Algorithm 2 at node v: one vocabulary pass + exchange per rejection
-        while (sh.st.action == kActPass) {
-            const int zero_token = sh.st.zero_token;
-            const float af = sh.st.af, bf = sh.st.bf;
+        while (sw.action == kActPass) {
+            const int zero_token = sw.zero_token;
+            const float af = sw.af, bf = sw.bf;
             float r_loc = 0.f, q_loc = 0.f;
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
@@ -429,9 +448,10 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
             par ^= 1;
             __syncthreads();
             SEQ_STAMP(12);
-            if (sh.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
+            sw = read_step(sh);
+            if (sw.fail) { finish(p, path_len, sh.st.n_dec, 1, v, sh.st.fallbacks, sh.st.degenerate); return; }
         }
-        if (sh.st.action == kActAccepted) {
+        if (sw.action == kActAccepted) {
             const int next = sh.st.next;
             if (wg_rank() == 0 && tid == 0) p.path[path_len] = next;
             ++path_len;
@@ -441,7 +461,7 @@ __global__ __launch_bounds__(kThreads) void verify_walk_kernel(const VerifyParam
         }
 
         // no child accepted: bonus token ~ R by inverse CDF with uniforms[0]
-        const float af = sh.st.af, bf = sh.st.bf;
+        const float af = sw.af, bf = sw.bf;
         const float u0 = sh.uniform[0];
         if (!sh.st.sums_valid) {   // no pass has left the workgroups' residual masses yet
             float r_loc = 0.f;
