@@ -648,11 +648,12 @@ __global__ __launch_bounds__(WQ * WK * 64) void tree_attn_mfma_kernel(const Mfma
             for (int x = 0; x < 16; ++x) oacc[r][b][x] *= alpha;
     };
 
-    // With one key group every wavefront walks every tile, and the K fragments of tile rho + 1
-    // are requested while tile rho is still being worked on: right after a barrier all eight
-    // wavefronts would otherwise ask LDS for their fragments at once and sit out the queue.
-    // Tile rho + 1 therefore has to be in LDS one barrier earlier.
-    constexpr bool kPrefetchK = WK == 1;
+    // The K fragments of a wavefront's next tile are requested while its current tile is still
+    // being worked on: right after a barrier all eight wavefronts would otherwise ask LDS for
+    // their fragments at once and sit out the queue.  That tile therefore has to be in LDS one
+    // barrier earlier, which takes a ring of more than two rounds: one or two key groups (with
+    // two the gain is small, 1 % at the Vicuna shape; with one it is what the long loops need).
+    constexpr bool kPrefetchK = WK <= 2;
     bf16x8_t kf[kKSteps];
     if (kPrefetchK) {
         wait_vmcnt<(kAheadRounds - 1) * kLoadsPerRound>();
