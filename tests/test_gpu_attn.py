@@ -261,6 +261,20 @@ def test_seeded_random_shapes_under_the_library_s_own_schedule():
     assert {k[0] for k in picks} == {2, 4, 8}, picks
 
 
+@pytest.mark.parametrize("H,Hk,d,P,n", [(28, 4, 64, 5648, 593), (30, 6, 128, 2876, 452), (120, 10, 128, 2552, 222),
+                                        (14, 2, 64, 440, 239), (24, 3, 128, 3430, 580), (50, 10, 128, 4227, 387)])
+def test_group_sizes_that_are_not_powers_of_two(H, Hk, d, P, n):
+    """Query heads per KV head of 7, 5, 12, 7, 8 and 5: a row block of 32 query rows then straddles
+    nodes unevenly, and every division by the group size (which node and head a row is, which
+    tree tiles a unit sees, where a merged row goes) is a multiplication prepared on the host.
+    All rows against the checker, under the library's own schedule (the first shape takes four key
+    ranges of two sizes with long ranges of one length)."""
+    rng = np.random.default_rng(n)
+    a = W.make_attn_inputs(H, Hk, d, P, W.random_topological_tree(n, rng), W.BF16, seed=P, prefix_cap=P + 3)
+    err = np.abs(run_attn(a) - oracle_attn_all_rows(a)).max()
+    assert err <= TOL[W.BF16], (H, Hk, d, P, n, err)
+
+
 @pytest.mark.parametrize("H,Hk,P,n", [(4, 4, 700, 40), (16, 2, 1500, 300)])
 @pytest.mark.parametrize("order", ["rising", "falling", "spiky"])
 def test_scores_of_large_and_moving_magnitude(H, Hk, P, n, order):
