@@ -1076,12 +1076,14 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     const int tiles = prefix_tiles + (n + kKeyTile - 1) / kKeyTile;
     // Two choices: row blocks per workgroup (wq; the 8 / wq wavefronts left over share the key
     // tiles of a round) and key ranges per unit.  One workgroup fits on a CU at a time, so a
-    // launch runs in batches of 256 workgroups; a workgroup costs its rounds -- dearer the more
+    // launch runs in batches of 256 workgroups (the compute units of an MI355X, eight XCDs of 32;
+    // the workspace query has no device to ask, and the cost figures below were measured on that
+    // part and no other); a workgroup costs its rounds -- dearer the more
     // tiles a round copies -- plus a fixed prologue/epilogue plus, with more than one range, the
     // hand-over of the partial results and their merge (figures in tenths of a microsecond,
     // chosen against the measured times of every (wq, ranges) pair at the head shapes of the
     // paper's models, trees of 16 to 768 nodes and prefixes of 512 to 20000 keys: the pair chosen
-    // is on average 0.8 % slower than the best pair measured, 14 % at worst).  A wq beyond what
+    // is on average 1 % slower than the best pair measured, 22 % at worst and 7 % next).  A wq beyond what
     // the rows of a KV head fill is never considered; a smaller one is, because it multiplies the
     // units when there are few KV heads.
     const int wq_cover = rows <= 64 ? 2 : (rows <= 128 ? 4 : 8);
