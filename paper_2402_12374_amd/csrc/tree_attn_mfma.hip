@@ -34,6 +34,7 @@
 // normalised output in fp16) in the workspace and the last one to arrive for a unit merges them
 // by log-sum-exp; no workgroup ever waits for another.
 #include <algorithm>
+#include <functional>
 #include <type_traits>
 #include <utility>
 
@@ -1082,10 +1083,11 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
     // tiles a round copies -- plus a fixed prologue/epilogue plus, with more than one range, the
     // hand-over of the partial results and their merge (figures in tenths of a microsecond,
     // chosen against the measured times of every (wq, ranges) pair at the head shapes of the
-    // paper's models, trees of 16 to 768 nodes and prefixes of 512 to 20000 keys: the pair chosen
-    // is on average 1 % slower than the best pair measured, 22 % at worst and 7 % next).  A wq beyond what
-    // the rows of a KV head fill is never considered; a smaller one is, because it multiplies the
-    // units when there are few KV heads.
+    // paper's models: trees of 16 to 768 nodes under prefixes of 512 to 20000 keys, and trees of
+    // 128 to 768 nodes under prefixes of 128 to 1024; the pair chosen is on average 0.7 % slower
+    // than the best pair measured, 16 % at worst and 11 % next).  A wq beyond what the rows of a
+    // KV head fill is never considered; a smaller one is, because it multiplies the units when
+    // there are few KV heads.
     const int wq_cover = rows <= 64 ? 2 : (rows <= 128 ? 4 : 8);
     constexpr long kFixed = 70, kHandOver = 20;   // prologue and epilogue of a workgroup; partial results handed over and merged at all
     constexpr long kFixedShort = 120;             // the same of a short range that runs behind another (measured at the lengths below)
@@ -1105,7 +1107,35 @@ AttnSchedule plan_attn_schedule(int P, int n, int H, int Hk, int D) {
             if (g_splits_override > 0 && cand != std::min(g_splits_override, max_splits)) continue;
             const long batches = ((long)units * cand + 255) / 256;
             const long rounds = (tiles + cand * wk - 1) / (cand * wk);
-            const long cost = batches * (rounds * round_cost + kFixed + (cand > 1 ? kHandOver + 2 * cand * wq : 0));
+            const long apiece = kFixed + (cand > 1 ? kHandOver + 2 * cand * wq : 0);
+            long cost = batches * (rounds * round_cost + apiece);
+            // Where the units of a KV head differ in their tree tiles (short prefixes under large
+            // trees: 5 to 28 tiles) and there are more workgroups than compute units, whole batches
+            // of the longest workgroup are far from what happens: the dispatcher hands the next
+            // workgroup to whichever CU is free.  Then the launch is played through for one XCD
+            // -- its units, in the order the kernel takes them (range-major, last row block
+            // first), on its 32 CUs.
+            const int per_head = (rows + 32 * wq - 1) / (32 * wq), units_per_xcd = (units + 7) / 8;
+            const long jobs = (long)units_per_xcd * cand;
+            if (per_head > 1 && jobs > 32 && jobs <= 160) {
+                long free_at[32] = {};   // a min-heap of the times at which the CUs fall free
+                long end = 0;
+                for (int turn = 0; turn < cand; ++turn) {
+                    const int range = cand - 1 - turn;
+                    for (int local = units_per_xcd - 1; local >= 0; --local) {
+                        if (local >= units) continue;
+                        const int qb = local % per_head;
+                        const int last_row = std::min(rows - 1, qb * 32 * wq + 32 * wq - 1);
+                        const long unit_tiles = prefix_tiles + last_row / G / kKeyTile + 1;
+                        const long length = unit_tiles * (range + 1) / cand - unit_tiles * range / cand;
+                        std::pop_heap(free_at, free_at + 32, std::greater<long>());
+                        free_at[31] += (length + wk - 1) / wk * round_cost + apiece;
+                        end = std::max(end, free_at[31]);
+                        std::push_heap(free_at, free_at + 32, std::greater<long>());
+                    }
+                }
+                cost = end;
+            }
             if (best < 0 || cost < best) { best = cost; s.wq = wq; s.splits = cand; s.short_ranges = 0; s.short_weight = s.long_weight = 1; }
         }
         // Ranges of two sizes.  When the units leave CUs over but too few for another range each
