@@ -13,8 +13,8 @@ events around graph replays, against the dense bf16 matrix peak), `verify` the v
 `configs` the other configurations, `cpu_baseline` the fp64 checker on the same workload.
 
 Other modes print lines of their own instead of the benchmark line: --sweep (latency of both calls
-over the tree size; --sweep-tree sequoia for trees built by seq_build_tree; --pick-tree for the
-hardware-aware choice fed with the measured times), --draft-sample (seq_draft_sample per
+over the tree size; --sweep-tree sequoia for trees built by seq_build_tree; --sweep-prefix for another
+prefix length than the configurations'; --pick-tree for the hardware-aware choice fed with the measured times), --draft-sample (seq_draft_sample per
 configuration), --rejection-curve (rejection rate against the number of children for the three
 verification algorithms), --verify-batch (seq_verify_batched over the batch size).
 """
@@ -447,6 +447,8 @@ def run_sweep(args) -> int:
         cfg = W.CONFIGS[key]
         # a batch of sequences (same tree, same prefix length) is a call with more heads
         H, Hk, d, P, V = cfg.heads * args.sweep_batch, cfg.kv_heads * args.sweep_batch, cfg.head_dim, cfg.prefix_len, cfg.vocab
+        if args.sweep_prefix > 0:
+            P = args.sweep_prefix
         tdt = torch.bfloat16 if cfg.dtype == W.BF16 else torch.float32
         code = 1 if tdt == torch.bfloat16 else 2
         T = cfg.temperatures[0]
@@ -740,6 +742,8 @@ def main() -> int:
     ap.add_argument("--verify-batch-vocab", type=int, default=0, help="vocabulary for --verify-batch (0 = the configuration's)")
     ap.add_argument("--verify-batch-temperature", type=float, default=-1.0, help="temperature for --verify-batch (< 0 = the configuration's)")
     ap.add_argument("--sweep-configs", default="C2,C3,C4,C5")
+    ap.add_argument("--sweep-prefix", type=int, default=0,
+                    help="with --sweep: this prefix length instead of each configuration's (the paper's prompts are 128 tokens)")
     ap.add_argument("--sweep-sizes", default="16,32,64,128,256,512,768")
     args = ap.parse_args()
     if args.gpus != 1:
