@@ -6,7 +6,7 @@ import torch
 import oracle
 import workloads as W
 
-from gpu_util import TOL, oracle_attn, oracle_attn_all_rows, run_attn
+from gpu_util import TOL, oracle_attn, oracle_attn_all_rows, run_attn, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -86,6 +86,31 @@ def test_repeated_calls_are_bit_identical_and_cached_plan_is_reused():
     first = run_attn(a)
     for _ in range(3):
         assert np.array_equal(run_attn(a), first)
+
+
+@pytest.mark.parametrize("H,Hk,P,n", [(32, 32, 1024, 64), (64, 8, 3000, 640), (52, 52, 4096, 320)])
+def test_launches_on_changing_inputs_share_a_workspace_without_reading_each_other(H, Hk, P, n):
+    """The partial results of the key ranges go through one workspace, call after call, and the
+    workgroup that merges them learns from a counter that they have arrived.  If it could read
+    them before they had landed it would merge the previous call's: 300 launches back to back on
+    three input sets in turn, each set's output bit for bit what it was the first time.  (Five
+    equal ranges; a long and a short one with the long ones of one length; two of two sizes.)"""
+    import torch
+    import paper_2402_12374_amd as S
+    dev = torch.device("cuda:0")
+    parent = W.geometric_tree(n, 9)
+    sets = []
+    for k in range(3):
+        a = W.make_attn_inputs(H, Hk, 128, P, parent, W.BF16, seed=50 + k)
+        sets.append([to_dev(x, a.dtype) for x in (a.q, a.k_cache, a.v_cache, a.k_tree, a.v_tree)])
+    ws = torch.empty(S.seq_tree_attn_workspace(P, n, H, Hk, 128, 1), dtype=torch.uint8, device=dev)
+    outs = [torch.empty(n, H, 128, dtype=torch.bfloat16, device=dev) for _ in range(300)]
+    for i, out in enumerate(outs):
+        S.seq_tree_attn(*sets[i % 3], parent, P, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    for i, out in enumerate(outs):
+        assert torch.equal(out, outs[i % 3]), i
+    assert not torch.equal(outs[0], outs[1])
 
 
 def test_chain_tree_matches_torch_causal_attention():
